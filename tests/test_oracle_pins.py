@@ -1,0 +1,350 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, computed
+here by independent means (integer brute force, float64 numpy closed forms,
+the paper's ray/sphere formulation), never by calling the oracle twice.
+
+Note on one requested invariant: with the clamp r_m^2 for entries outside the
+radius (reading R1 in the oracle header) a filtered entry has d2 > r_m^2 and is
+replaced by the SMALLER value, so thresholded distances are <= the
+unthresholded ones, not >=.  The tests below assert the direction that is
+mathematically true for this clamp; the deviation from the wording of the build
+target is deliberate.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_01712_amd import workloads as wl
+
+
+# ----------------------------------------------------------------------------
+# helpers (independent of the oracle)
+# ----------------------------------------------------------------------------
+
+def identity_index(rng, N=1500, D=12, nlist=6):
+    """Hand-built index that reconstructs every point exactly: integer data,
+    integer centroids, M = D (dsub = 1), codebook[m] = {-128..127},
+    code = residual + 128.  All arithmetic on it is exact in fp32."""
+    base = rng.integers(0, 128, size=(N, D)).astype(np.int64)
+    cent = rng.integers(0, 128, size=(nlist, D)).astype(np.int64)
+    d = ((base[:, None, :] - cent[None, :, :]) ** 2).sum(-1)
+    labels = d.argmin(1)
+    order = np.argsort(labels, kind="stable")
+    res = base - cent[labels]
+    codes = (res + 128).astype(np.uint8)
+    offs = np.zeros(nlist + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(np.bincount(labels, minlength=nlist))
+    cb = np.tile((np.arange(256) - 128).astype(np.float32)[None, :, None], (D, 1, 1))
+    idx = wl.Index(N=N, D=D, nlist=nlist, M=D, centroids=cent.astype(np.float32),
+                   codebooks=np.ascontiguousarray(cb), list_offsets=offs,
+                   codes=np.ascontiguousarray(codes[order]), ids=order.astype(np.int64))
+    return base, idx
+
+
+def brute_knn_int(base, queries, k):
+    d = ((base[None, :, :] - queries[:, None, :]) ** 2).sum(-1)        # int64, exact
+    ids = np.empty((queries.shape[0], k), dtype=np.int64)
+    dist = np.empty((queries.shape[0], k), dtype=np.int64)
+    for q in range(queries.shape[0]):
+        o = np.lexsort((np.arange(base.shape[0]), d[q]))[:k]
+        ids[q], dist[q] = o, d[q][o]
+    return ids, dist
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    out = {}
+    for name in ("T_gauss", "T_sift", "T_deep", "T_tti"):
+        w = wl.WORKLOADS[name]
+        idx, centres = wl.train_index(w)
+        q = wl.queries(w, centres).numpy()
+        out[name] = (w, idx, centres, q)
+    return out
+
+
+def reconstruct(idx):
+    """cent[list(x)] + concat_m codebook[m][code_m], float64, in stored row order."""
+    labels = np.repeat(np.arange(idx.nlist), np.diff(idx.list_offsets))
+    rec = idx.centroids[labels].astype(np.float64)
+    ent = idx.codebooks.astype(np.float64)[np.arange(idx.M)[None, :], idx.codes.astype(np.int64)]  # [N][M][dsub]
+    return rec + ent.reshape(idx.N, idx.D), labels
+
+
+def per_subspace_d2(idx, q, c):
+    """float64 squared distances between the residual projections of query q
+    w.r.t. list c and the entries coded by each point of list c: [n_c][M]."""
+    b, e = idx.list_offsets[c], idx.list_offsets[c + 1]
+    res = (q.astype(np.float32) - idx.centroids[c]).astype(np.float64).reshape(idx.M, idx.dsub)
+    ent = idx.codebooks.astype(np.float64)[np.arange(idx.M)[None, :], idx.codes[b:e].astype(np.int64)]
+    return ((ent - res[None]) ** 2).sum(-1)
+
+
+# ----------------------------------------------------------------------------
+# 1. whole path == exact kNN on identity-codebook indexes (paper Sec. 6.4:
+#    probing every list is a Flat index; with lossless codes the search is exact)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_identity_codebook_equals_bruteforce(seed):
+    rng = np.random.default_rng(seed)
+    base, idx = identity_index(rng)
+    Q, k = 20, 15
+    queries = rng.integers(0, 128, size=(Q, idx.D)).astype(np.int64)
+    radii = np.full(idx.M, np.inf, dtype=np.float32)
+    ids, dist = oracle.search(queries.astype(np.float32), idx, idx.nlist, k, radii)
+    ref_ids, ref_dist = brute_knn_int(base, queries, k)
+    assert np.array_equal(ids, ref_ids)
+    assert np.array_equal(dist.astype(np.int64), ref_dist) and np.all(dist == np.floor(dist))
+    # recall is 1 by construction; the double-precision reference agrees too
+    eid, edist = oracle.exact_knn(base.astype(np.float32), queries.astype(np.float32), k)
+    assert np.array_equal(eid, ref_ids) and np.array_equal(edist, ref_dist.astype(np.float64))
+
+
+def test_identity_codebook_partial_probe_is_subset_exact():
+    """With nprobe < nlist the result is the exact kNN restricted to the probed lists."""
+    rng = np.random.default_rng(7)
+    base, idx = identity_index(rng, N=900, D=8, nlist=5)
+    queries = rng.integers(0, 128, size=(10, idx.D)).astype(np.int64)
+    nprobe, k = 2, 12
+    radii = np.full(idx.M, np.inf, dtype=np.float32)
+    ids, dist = oracle.search(queries.astype(np.float32), idx, nprobe, k, radii)
+    cent = idx.centroids.astype(np.int64)
+    labels = np.empty(idx.N, dtype=np.int64)
+    labels[idx.ids] = np.repeat(np.arange(idx.nlist), np.diff(idx.list_offsets))
+    for q in range(queries.shape[0]):
+        dc = ((cent - queries[q]) ** 2).sum(-1)
+        probes = np.lexsort((np.arange(idx.nlist), dc))[:nprobe]
+        members = np.nonzero(np.isin(labels, probes))[0]
+        d = ((base[members] - queries[q]) ** 2).sum(-1)
+        o = np.lexsort((members, d))[:k]
+        assert np.array_equal(ids[q], members[o])
+        assert np.array_equal(dist[q].astype(np.int64), d[o])
+
+
+# ----------------------------------------------------------------------------
+# 2. coarse stage
+# ----------------------------------------------------------------------------
+
+def test_coarse_full_permutation_and_argmin(tiny):
+    for name, (w, idx, _, q) in tiny.items():
+        ids, dist = oracle.coarse(q, idx.centroids, idx.nlist)
+        d64 = ((q.astype(np.float64)[:, None, :] - idx.centroids.astype(np.float64)[None]) ** 2).sum(-1)
+        for i in range(q.shape[0]):
+            assert sorted(ids[i].tolist()) == list(range(idx.nlist))          # a permutation
+            assert np.all(np.diff(dist[i]) >= 0)                               # ascending
+            np.testing.assert_allclose(dist[i], d64[i][ids[i]], rtol=1e-5)     # fp32 chain vs double
+            ref = np.argsort(d64[i], kind="stable")
+            gaps = np.diff(d64[i][ref]) > 1e-5 * d64[i][ref][1:]
+            # wherever the double distances are clearly separated the order must agree
+            same = ids[i] == ref
+            assert np.all(same[:-1][gaps & np.r_[True, gaps[:-1]]])
+        ids1, _ = oracle.coarse(q, idx.centroids, 1)
+        assert np.array_equal(ids1[:, 0], ids[:, 0])
+        well = np.sort(d64, 1)[:, 1] - np.sort(d64, 1)[:, 0] > 1e-5 * np.sort(d64, 1)[:, 1]
+        assert np.array_equal(ids1[well, 0], d64.argmin(1)[well])
+        idsp, distp = oracle.coarse(q, idx.centroids, w.nprobe)
+        assert np.array_equal(idsp, ids[:, :w.nprobe]) and np.array_equal(distp, dist[:, :w.nprobe])
+
+
+def test_coarse_tie_break_by_list_id():
+    cent = np.array([[1.0, 0.0], [0.0, 1.0], [-1.0, 0.0], [0.0, -1.0], [3.0, 3.0]], dtype=np.float32)
+    ids, dist = oracle.coarse(np.zeros((1, 2), np.float32), cent, 5)
+    assert ids[0].tolist() == [0, 1, 2, 3, 4] and dist[0].tolist() == [1, 1, 1, 1, 18]
+
+
+# ----------------------------------------------------------------------------
+# 3. unthresholded table + ADC == ||q - reconstruct(x)||^2 (paper Sec. 2.1, B-D)
+# ----------------------------------------------------------------------------
+
+def test_adc_equals_reconstruction_distance(tiny):
+    for name, (w, idx, _, q) in tiny.items():
+        probes, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+        radii = np.full(idx.M, np.inf, dtype=np.float32)
+        offs, dist, ids = oracle.scan_all(q, idx, probes, radii)
+        rec, _ = reconstruct(idx)
+        row_of = np.empty(idx.N, dtype=np.int64)
+        row_of[idx.ids] = np.arange(idx.N)
+        for i in range(q.shape[0]):
+            sl = slice(offs[i], offs[i + 1])
+            expect_rows = np.concatenate([np.arange(idx.list_offsets[c], idx.list_offsets[c + 1]) for c in probes[i]])
+            assert np.array_equal(row_of[ids[sl]], expect_rows)                # candidate set and order
+            ref = ((rec[expect_rows] - q[i].astype(np.float64)) ** 2).sum(-1)
+            np.testing.assert_allclose(dist[sl], ref, rtol=1e-4, atol=1e-30)
+
+
+# ----------------------------------------------------------------------------
+# 4. thresholded table / ADC: closed form and invariants
+# ----------------------------------------------------------------------------
+
+def test_thresholded_adc_closed_form_and_invariants(tiny):
+    for name, (w, idx, centres, q) in tiny.items():
+        probes, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+        inf = np.full(idx.M, np.inf, dtype=np.float32)
+        r25 = wl.calibrate_radii(w, idx, centres, 0.25)
+        r50 = np.maximum(wl.calibrate_radii(w, idx, centres, 0.50), r25)
+        offs, d_inf, ids_inf = oracle.scan_all(q, idx, probes, inf)
+        _, d_25, ids_25 = oracle.scan_all(q, idx, probes, r25)
+        _, d_50, _ = oracle.scan_all(q, idx, probes, r50)
+        _, d_big, _ = oracle.scan_all(q, idx, probes, np.full(idx.M, 1e18, np.float32))
+        _, d_zero, _ = oracle.scan_all(q, idx, probes, np.zeros(idx.M, np.float32))
+        assert np.array_equal(ids_inf, ids_25)
+        # (i) thresholded <= unthresholded, (iv) monotone in the radii
+        assert np.all(d_25 <= d_50) and np.all(d_50 <= d_inf)
+        # (iii) bounded by the saturation value sum r_m^2 (same fp32 order)
+        sat = np.float32(0.0)
+        for m in range(idx.M):
+            sat = np.float32(sat + np.float32(r25[m] * r25[m]))
+        assert np.all(d_25 <= sat)
+        # (v) a huge finite radius equals +inf; radius 0 gives 0 everywhere
+        assert np.array_equal(d_big, d_inf)
+        assert np.all(d_zero == 0.0)
+        # (ii) closed form: sum_m min(d2_m, r_m^2) in float64; equality of thr and
+        # unthr exactly where every subspace was kept
+        r2 = (r25.astype(np.float64)) ** 2
+        n_sat = 0
+        for i in range(q.shape[0]):
+            pos = offs[i]
+            for c in probes[i]:
+                d2 = per_subspace_d2(idx, q[i], c)
+                n = d2.shape[0]
+                ref = np.minimum(d2, r2[None]).sum(-1)
+                np.testing.assert_allclose(d_25[pos:pos + n], ref, rtol=2e-5, atol=1e-30)
+                all_kept = np.all(d2 < r2[None] * (1 - 1e-5), axis=1)
+                assert np.array_equal(d_25[pos:pos + n][all_kept], d_inf[pos:pos + n][all_kept])
+                some_cut = np.any(d2 > r2[None] * (1 + 1e-5), axis=1)
+                assert np.all(d_25[pos:pos + n][some_cut] < d_inf[pos:pos + n][some_cut])
+                none_kept = np.all(d2 > r2[None] * (1 + 1e-5), axis=1)
+                assert np.all(d_25[pos:pos + n][none_kept] == sat)
+                n_sat += int(none_kept.sum())
+                pos += n
+            assert pos == offs[i + 1]
+
+
+def test_lut_values_mask_and_keep_fraction(tiny):
+    for name, (w, idx, centres, q) in tiny.items():
+        probes, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+        for frac in (0.10, 0.25, 0.50):
+            radii = wl.calibrate_radii(w, idx, centres, frac)
+            lut, mask = oracle.build_lut(q, idx.centroids, idx.codebooks, probes, radii)
+            res = (q[:, None, :] - idx.centroids[probes]).astype(np.float64)             # [Q][P][D]
+            res = res.reshape(q.shape[0], w.nprobe, idx.M, 1, idx.dsub)
+            d2 = ((res - idx.codebooks.astype(np.float64)[None, None]) ** 2).sum(-1)      # [Q][P][M][256]
+            r2 = (radii.astype(np.float64) ** 2)[None, None, :, None]
+            np.testing.assert_allclose(lut, np.minimum(d2, r2), rtol=1e-5, atol=1e-30)
+            bits = ((mask[..., None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(bool)
+            bits = bits.reshape(q.shape[0], w.nprobe, idx.M, 256)
+            clear = np.abs(d2 - r2) > 1e-5 * r2
+            assert np.array_equal(bits[clear], (d2 <= r2)[clear])
+            assert abs(bits.mean() - frac) < 0.05, (name, frac, bits.mean())
+        lut_inf, mask_inf = oracle.build_lut(q, idx.centroids, idx.codebooks, probes,
+                                             np.full(idx.M, np.inf, np.float32))
+        assert np.all(mask_inf == np.uint64(0xFFFFFFFFFFFFFFFF))
+
+
+# ----------------------------------------------------------------------------
+# 5. the paper's ray/sphere formulation of the keep rule (Sec. 4.2; Algorithm 2)
+# ----------------------------------------------------------------------------
+
+def _ray_sphere(R, thr_scaled, d):
+    """A ray starts on the plane z = 2s at planar distance d from a sphere of
+    radius R centred on the plane z = 2s+1 and travels along +z.  It meets the
+    sphere after t_hit = 1 - sqrt(R^2 - d^2) (if d <= R) and is cut off at
+    t_max = 1 - sqrt(R^2 - thr_scaled^2)."""
+    t_max = 1.0 - math.sqrt(R * R - thr_scaled * thr_scaled)
+    if d > R:
+        return False, None, t_max
+    t_hit = 1.0 - math.sqrt(R * R - d * d)
+    return t_hit <= t_max, t_hit, t_max
+
+
+def test_paper_tmax_example(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "tmax_example.txt")) if l.strip() and l[0] != "#"]
+    R, thr, scale, tmax = map(float, rows[0])
+    assert _ray_sphere(R, thr * scale, 0.0)[2] == pytest.approx(tmax, abs=1e-12)
+
+
+def test_keep_rule_matches_ray_sphere_hits(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "tmax_example.txt")) if l.strip() and l[0] != "#"]
+    R, thr, scale, tmax = map(float, rows[0])
+    rng = np.random.default_rng(3)
+    nlist, M, D = 3, 2, 4
+    cent = rng.uniform(-0.2, 0.2, size=(nlist, D)).astype(np.float32)
+    cb = rng.uniform(-0.7, 0.7, size=(M, 256, 2)).astype(np.float32)
+    q = rng.uniform(-0.3, 0.3, size=(5, D)).astype(np.float32)
+    probes = np.tile(np.arange(nlist, dtype=np.int32), (5, 1))
+    radii = np.full(M, thr * scale, dtype=np.float32)
+    lut, mask = oracle.build_lut(q, cent, cb, probes, radii)
+    n_hit = 0
+    for qi in range(5):
+        for c in range(nlist):
+            for m in range(M):
+                o = (q[qi, 2 * m:2 * m + 2] - cent[c, 2 * m:2 * m + 2]).astype(np.float64)  # ray origin (x, y)
+                for e in range(256):
+                    d = float(np.hypot(*(cb[m, e].astype(np.float64) - o)))
+                    hit, t_hit, t_max = _ray_sphere(R, thr * scale, d)
+                    assert t_max == pytest.approx(tmax, abs=1e-7)
+                    if abs(d - thr * scale) < 1e-5:
+                        continue
+                    kept = bool((int(mask[qi, c, m, e >> 6]) >> (e & 63)) & 1)
+                    assert kept == hit
+                    if hit:
+                        n_hit += 1
+                        # hit-shader distance: L2^2 = R^2 - (1 - t_hit)^2
+                        assert lut[qi, c, m, e] == pytest.approx(R * R - (1.0 - t_hit) ** 2, rel=1e-4, abs=1e-9)
+                    else:
+                        assert lut[qi, c, m, e] == np.float32(radii[m] * radii[m])
+    assert n_hit > 100
+
+
+# ----------------------------------------------------------------------------
+# 6. top-k
+# ----------------------------------------------------------------------------
+
+def test_topk_against_sort_padding_and_ties():
+    rng = np.random.default_rng(5)
+    d = rng.integers(0, 50, size=4000).astype(np.float32)      # many ties
+    ids = rng.permutation(4000).astype(np.int64)
+    oi, od = oracle.topk(d, ids, 100)
+    o = np.lexsort((ids, d))[:100]
+    assert np.array_equal(oi, ids[o]) and np.array_equal(od, d[o])
+    oi, od = oracle.topk(d[:7], ids[:7], 10)
+    o = np.lexsort((ids[:7], d[:7]))
+    assert np.array_equal(oi[:7], ids[:7][o]) and np.all(oi[7:] == -1) and np.all(np.isinf(od[7:]))
+    oi, od = oracle.topk(np.full(500, 2.5, np.float32), ids[:500], 20)
+    assert np.array_equal(oi, np.sort(ids[:500])[:20]) and np.all(od == 2.5)
+    oi, od = oracle.topk(np.zeros(0, np.float32), np.zeros(0, np.int64), 3)
+    assert np.all(oi == -1) and np.all(np.isinf(od))
+
+
+# ----------------------------------------------------------------------------
+# 7. the fused routine is the composition of its stages; threads do not matter
+# ----------------------------------------------------------------------------
+
+def test_search_is_composition_of_stages(tiny):
+    for name, (w, idx, centres, q) in tiny.items():
+        radii = wl.calibrate_radii(w, idx, centres, 0.25)
+        ids, dist = oracle.search(q, idx, w.nprobe, w.k, radii)
+        probes, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+        offs, cd, ci = oracle.scan_all(q, idx, probes, radii)
+        for i in range(q.shape[0]):
+            o = np.lexsort((ci[offs[i]:offs[i + 1]], cd[offs[i]:offs[i + 1]]))[:w.k]
+            assert np.array_equal(ids[i], ci[offs[i]:offs[i + 1]][o])
+            assert np.array_equal(dist[i], cd[offs[i]:offs[i + 1]][o])
+        ids_t, dist_t = oracle.search(q, idx, w.nprobe, w.k, radii, threads=3)
+        assert np.array_equal(ids, ids_t) and np.array_equal(dist, dist_t)
+
+
+def test_recall_sane_and_monotone(tiny):
+    """Recall on synthetic data is unpinned (the paper's numbers are for datasets
+    that are absent); only its direction is checked."""
+    w, idx, centres, q = tiny["T_gauss"]
+    base = wl.base_vectors(w, centres).numpy()
+    truth, _ = oracle.exact_knn(base, q, w.k)
+    inf = np.full(idx.M, np.inf, np.float32)
+    r_all = wl.recall_at_k(oracle.search(q, idx, idx.nlist, w.k, inf)[0], truth)[0]
+    r_few = wl.recall_at_k(oracle.search(q, idx, 1, w.k, inf)[0], truth)[0]
+    r_thr = wl.recall_at_k(oracle.search(q, idx, idx.nlist, w.k, wl.calibrate_radii(w, idx, centres, 0.10))[0], truth)[0]
+    assert r_all >= r_few and r_all >= r_thr and r_all > 0.3
