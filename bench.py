@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the IVF-PQ search hot path on one MI355X.
+
+One step = one pass of the whole hot path (filtering, thresholded tables, ADC
+scan, top-k) over one batch of Q synthetic queries, through the C ABI, with the
+index and the queries resident in HBM.  Prints ONE JSON line:
+
+  metric/value  queries per second over the timed steps (whole path)
+  roofline      the fused table+scan+top-k kernel against the HBM roofline:
+                algorithmic code bytes per launch / its mean duration (HIP events
+                recorded on the launch stream inside the timed region)
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample of the
+                same queries (reported, not a target)
+
+The step issues ivfpq_coarse then ivfpq_scan_topk (the two launches
+ivfpq_search makes) so that an event can sit between them.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", help="C1..C5, C5_10M (default C2: 1M x 128, nprobe 32)")
+    ap.add_argument("--keep", type=float, default=0.25, help="fraction of codebook entries inside the radius")
+    ap.add_argument("--scan-waves", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-recall", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2312_01712_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    torch.cuda.set_device(0)
+    binding.load_library()
+    if args.scan_waves:
+        binding.set_option("scan_waves", args.scan_waves)
+    w = wl.WORKLOADS[args.workload]
+
+    t0 = time.time()
+    idx, centres = wl.train_index(w, device="cuda", progress=log)
+    radii = wl.calibrate_radii(w, idx, centres, args.keep)
+    q = wl.queries(w, centres)
+    gi = binding.IvfPqIndex.from_index(idx)
+    log(f"[{w.name}] index built in {time.time() - t0:.1f}s; code bytes on device {gi.info()['code_bytes']}")
+
+    Q, nprobe, k = w.Q, w.nprobe, w.k
+    ws = gi.workspace(Q, nprobe, k)
+    pid = torch.empty((Q, nprobe), dtype=torch.int32, device="cuda")
+    out_ids = torch.empty((Q, k), dtype=torch.int64, device="cuda")
+    out_dist = torch.empty((Q, k), dtype=torch.float32, device="cuda")
+    lib = binding.load_library()
+    stream = torch.cuda.current_stream().cuda_stream
+    rptr = radii.ctypes.data
+
+    def step(ev=None):
+        binding._check(lib.ivfpq_coarse(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), None, ws.data_ptr(),
+                                        ws.numel(), stream))
+        if ev:
+            ev[0].record()
+        binding._check(lib.ivfpq_scan_topk(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, rptr,
+                                           out_ids.data_ptr(), out_dist.data_ptr(), ws.data_ptr(), ws.numel(),
+                                           stream))
+        if ev:
+            ev[1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    start = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    scan_ms = [a.elapsed_time(b) for a, b in events]
+    coarse_ms = [start.elapsed_time(events[0][0])] + [events[i - 1][1].elapsed_time(events[i][0]) for i in range(1, args.steps)]
+    scan_avg_ms = float(np.mean(scan_ms))
+
+    # algorithmic bytes of one scan launch: one code byte per (probed point, subspace)
+    sizes = torch.from_numpy(np.diff(idx.list_offsets)).cuda()
+    scanned_points = int(sizes[pid.long()].sum().item())
+    algo_bytes = scanned_points * w.M
+    achieved = algo_bytes / (scan_avg_ms * 1e-3) / 1e9
+
+    # the one-call entry point gives the same answer
+    ids2, dist2 = gi.search(q, nprobe, k, radii, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ids2, out_ids) and torch.equal(dist2, out_dist)
+
+    recall = r1 = None
+    if not args.no_recall:
+        truth = wl.exact_knn(w, centres, q, k)
+        recall, r1 = wl.recall_at_k(out_ids.cpu().numpy(), truth)
+
+    result = {
+        "metric": "queries/sec at recall@100 (1M x 128, nprobe=32)" if w.name == "C2" else f"queries/sec at recall@{k}",
+        "value": Q * args.steps / elapsed, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} D={w.D} nlist={w.nlist} M={w.M} Q={Q} nprobe={nprobe} k={k}",
+                   "family": w.family, "keep_fraction": args.keep, "recall_at_k": recall, "r1_at_k": r1,
+                   "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms},
+        "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": scan_avg_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        qh = q.cpu().numpy()
+        threads = min(os.cpu_count() or 1, 16)
+        t = time.perf_counter()
+        probe_n = min(Q, 2 * threads)
+        o_ids, o_dist = oracle.search(qh[:probe_n], idx, nprobe, k, radii, threads=threads)
+        per_q = (time.perf_counter() - t) / probe_n          # wall seconds per query with all threads
+        n = int(max(probe_n, min(Q, args.cpu_seconds / max(per_q, 1e-9))))
+        t = time.perf_counter()
+        o_ids, o_dist = oracle.search(qh[:n], idx, nprobe, k, radii, threads=threads)
+        dt = time.perf_counter() - t
+        same = bool(np.array_equal(o_ids, out_ids.cpu().numpy()[:n]) and
+                    np.array_equal(o_dist.view(np.uint32), out_dist.cpu().numpy()[:n].view(np.uint32)))
+        n1 = int(max(1, min(n, 3.0 / max(per_q * threads, 1e-9))))
+        t = time.perf_counter()
+        oracle.search(qh[:n1], idx, nprobe, k, radii, threads=1)
+        dt1 = time.perf_counter() - t
+        result["cpu_baseline"] = {"value": n / dt, "unit": "queries/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"first {n} of {Q} queries, {threads} threads over disjoint query ranges",
+                                  "value_1thread": n1 / dt1, "sample_1thread": f"first {n1} queries",
+                                  "gpu_matches_oracle_on_sample": same}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,154 @@
+/*
+ * ivfpq.h -- C ABI of the MI355X (gfx950) search path of sparsity-aware IVF-PQ
+ * (JUNO, arxiv 2312.01712).
+ *
+ * Notation.  The paper's Table 1 writes M for the subspace DIMENSION and D/M
+ * for the number of subspaces.  This interface writes M for the NUMBER of
+ * subspaces and dsub = D / M for their dimension; ksub (the paper's E) is fixed
+ * at 256 so that a code is one byte; nlist is the paper's C, nprobe its nprobs.
+ *
+ * One query batch runs four stages (paper Sec. 2.1 "Online Search", Sec. 4.1,
+ * Sec. 5.3):
+ *   1. filtering: squared L2 distance from each query to the nlist IVF
+ *      centroids, the nprobe nearest lists are probed;
+ *   2. selective L2-LUT construction: for every probed list and subspace, a
+ *      codebook entry is kept only if it lies within the subspace's radius of
+ *      the query residual's projection; a kept entry stores its squared
+ *      distance, any other entry stores the clamp r_m^2;
+ *   3. distance calculation: the distance of an encoded point is the sum over
+ *      subspaces of the table value of its code;
+ *   4. top-k over all points of the probed lists, by (distance, id).
+ *
+ * Conventions for every call
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory on the current device.  Nothing passed in is retained
+ *     except by ivfpq_index_create, which copies what it needs.
+ *   - Search-side calls allocate nothing and never synchronise: they enqueue
+ *     kernels on `hip_stream` (a hipStream_t, NULL = the default stream) and
+ *     return.  Results are valid once the stream has reached that point.
+ *   - Return value: IVFPQ_OK or a negative ivfpq_status.  On an argument error
+ *     nothing is enqueued and no output is written.  ivfpq_last_error() gives a
+ *     text for the last failure on the calling thread.
+ *   - Limits: ksub == 256; D % M == 0; M <= 128; 1 <= k <= 128;
+ *     1 <= nprobe <= min(nlist, 1024); N < 2^32; radii finite >= 0 or +inf.
+ *   - NaN in queries or in the index gives unspecified (but in-bounds) results.
+ */
+#ifndef IVFPQ_H
+#define IVFPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  IVFPQ_OK = 0,
+  IVFPQ_ERR_INVALID_ARGUMENT = -1, /* null pointer, size out of range, bad offsets, bad radius */
+  IVFPQ_ERR_UNSUPPORTED = -2,      /* a shape outside the stated limits                          */
+  IVFPQ_ERR_WORKSPACE = -3,        /* workspace missing, misaligned or too small                 */
+  IVFPQ_ERR_HIP = -4,              /* a HIP runtime call failed (text in ivfpq_last_error)       */
+  IVFPQ_ERR_NO_MEMORY = -5         /* host or device allocation failed in index_create           */
+} ivfpq_status;
+
+#define IVFPQ_KSUB 256
+#define IVFPQ_MAX_M 128
+#define IVFPQ_MAX_K 128
+#define IVFPQ_MAX_NPROBE 1024
+
+typedef struct ivfpq_index ivfpq_index; /* opaque; owns its device copies */
+
+/* A trained index as the offline phase leaves it (paper Sec. 2.1, Algorithm 1:
+ * IVF centroids and labels, residual codebooks, encoded points).  All pointers
+ * are caller-owned and read-only; they may be host or device pointers. */
+typedef struct {
+  int64_t N;                   /* number of encoded points                                  */
+  int32_t D;                   /* vector dimension                                          */
+  int32_t nlist;               /* number of inverted lists                                  */
+  int32_t M;                   /* number of subspaces, D % M == 0                           */
+  int32_t ksub;                /* entries per subspace, must be 256                         */
+  const float *centroids;      /* [nlist][D] row-major                                      */
+  const float *codebooks;      /* [M][256][dsub], trained on residuals                      */
+  const int64_t *list_offsets; /* [nlist+1], non-decreasing, [0] = 0, [nlist] = N           */
+  const uint8_t *codes;        /* [N][M]; rows list_offsets[c] .. list_offsets[c+1] are list c */
+  const int64_t *ids;          /* [N] result ids in the same row order; NULL = row number   */
+} ivfpq_index_desc;
+
+/* Copies the index to the current device, re-laid out for the scan (codes in
+ * blocks of 64 points, interleaved so that one wavefront load is contiguous).
+ * Synchronous; allocates device memory that *out owns until destroy. */
+int ivfpq_index_create(const ivfpq_index_desc *desc, ivfpq_index **out);
+void ivfpq_index_destroy(ivfpq_index *index);
+
+/* Bytes of device workspace the search-side calls need for a batch of Q
+ * queries (0 on invalid arguments).  The workspace must be 256-byte aligned. */
+size_t ivfpq_search_workspace_bytes(const ivfpq_index *index, int64_t Q, int32_t nprobe, int32_t k);
+
+/* The whole search path (stages 1-4) for a batch.
+ *   d_queries   device [Q][D] fp32 row-major
+ *   radii       host   [M] fp32, per-subspace radius r_m shared by the batch
+ *               (paper Sec. 4.1: user-set threshold); +inf keeps every entry
+ *   d_out_ids   device [Q][k] int64, ascending by (distance, id); -1 when the
+ *               probed lists hold fewer than k points
+ *   d_out_dist  device [Q][k] fp32, +inf where the id is -1
+ *   d_workspace device, at least ivfpq_search_workspace_bytes(...) bytes
+ * Q == 0 is a no-op. */
+int ivfpq_search(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                 int32_t k, const float *radii, int64_t *d_out_ids, float *d_out_dist,
+                 void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Stage 1 alone (paper Sec. 2.1 step A; Sec. 5.3 on computing it as a matrix
+ * product): d_probe_ids device [Q][nprobe] int32 ordered by (distance, list
+ * id); d_probe_dist device [Q][nprobe] fp32 or NULL.  Distances are
+ * sum_i fmaf(t_i, t_i, .) with t_i = q_i - c_i, i ascending. */
+int ivfpq_coarse(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                 int32_t *d_probe_ids, float *d_probe_dist, void *d_workspace,
+                 size_t workspace_bytes, void *hip_stream);
+
+/* Stage 2 alone (paper Sec. 4.1; Algorithm 2), materialised for inspection:
+ * d_lut device [Q][nprobe][M][256] fp32; d_mask device [Q][nprobe][M][4]
+ * uint64 (bit e%64 of word e/64 set when entry e is kept) or NULL. */
+int ivfpq_build_lut(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                    const int32_t *d_probe_ids, const float *radii, float *d_lut,
+                    uint64_t *d_mask, void *hip_stream);
+
+/* Stages 2-4 for given probe lists (device [Q][nprobe] int32, every id in
+ * [0, nlist)).  Same outputs as ivfpq_search. */
+int ivfpq_scan_topk(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                    const int32_t *d_probe_ids, int32_t k, const float *radii, int64_t *d_out_ids,
+                    float *d_out_dist, void *d_workspace, size_t workspace_bytes,
+                    void *hip_stream);
+
+/* Stages 2-3 with every candidate's distance written out (paper Sec. 5.3: the
+ * list of search points and distances handed to top-k).  d_cand_offsets device
+ * [Q+1] int64: query q's candidates occupy [off[q], off[q+1]) in probe order
+ * then list order, so off[q+1]-off[q] must equal the summed sizes of its probed
+ * lists (checked on the device: a mismatching query is skipped and counted in
+ * *d_errors, device int32, which the call first sets to 0).  Meant for small
+ * inputs. */
+int ivfpq_scan_all(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                   const int32_t *d_probe_ids, const float *radii, const int64_t *d_cand_offsets,
+                   float *d_all_dist, int64_t *d_all_ids, int32_t *d_errors, void *hip_stream);
+
+/* Shape of an index and of its device layout. */
+typedef struct {
+  int64_t N;
+  int32_t D, nlist, M, dsub;
+  int64_t code_bytes;   /* bytes of the interleaved code array on the device   */
+  int64_t max_list_len; /* longest inverted list                                */
+} ivfpq_index_info;
+int ivfpq_index_get_info(const ivfpq_index *index, ivfpq_index_info *info);
+
+/* Tuning knob for measurements, process-wide, not thread-safe against running
+ * searches.  "scan_waves": wavefronts per workgroup of the fused scan kernel,
+ * 0 (default: chosen from the shape), 4, 8 or 16.  Results do not depend on it. */
+int ivfpq_set_option(const char *name, int value);
+
+/* Text for the most recent failure on this thread ("" if none). */
+const char *ivfpq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVFPQ_H */

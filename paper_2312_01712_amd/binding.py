@@ -1,0 +1,231 @@
+"""Thin ctypes binding of the C-ABI library (include/ivfpq.h).
+
+Argument marshalling only: torch supplies device memory (`data_ptr()`) and the
+current stream; every step of the search path runs in the HIP kernels of
+`libivfpq_hip.so`.  There is no fallback: if the library is missing and cannot
+be built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libivfpq_hip.so")
+_lib = None
+
+# every symbol include/ivfpq.h declares
+SYMBOLS = [
+    "ivfpq_index_create", "ivfpq_index_destroy", "ivfpq_search_workspace_bytes", "ivfpq_search",
+    "ivfpq_coarse", "ivfpq_build_lut", "ivfpq_scan_topk", "ivfpq_scan_all", "ivfpq_index_get_info",
+    "ivfpq_set_option", "ivfpq_last_error",
+]
+
+OK, ERR_INVALID_ARGUMENT, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5
+
+
+class IvfpqError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"ivfpq status {status}: {text}")
+        self.status = status
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("D", ctypes.c_int32), ("nlist", ctypes.c_int32),
+                ("M", ctypes.c_int32), ("ksub", ctypes.c_int32), ("centroids", ctypes.c_void_p),
+                ("codebooks", ctypes.c_void_p), ("list_offsets", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("D", ctypes.c_int32), ("nlist", ctypes.c_int32),
+                ("M", ctypes.c_int32), ("dsub", ctypes.c_int32), ("code_bytes", ctypes.c_int64),
+                ("max_list_len", ctypes.c_int64)]
+
+
+def load_library():
+    """Load libivfpq_hip.so, building it first only if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.ivfpq_index_create.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp)]
+    lib.ivfpq_index_destroy.argtypes = [vp]
+    lib.ivfpq_index_destroy.restype = None
+    lib.ivfpq_search_workspace_bytes.argtypes = [vp, i64, i32, i32]
+    lib.ivfpq_search_workspace_bytes.restype = sz
+    lib.ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.ivfpq_coarse.argtypes = [vp, vp, i64, i32, vp, vp, vp, sz, vp]
+    lib.ivfpq_build_lut.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp, vp]
+    lib.ivfpq_scan_topk.argtypes = [vp, vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.ivfpq_scan_all.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.ivfpq_index_get_info.argtypes = [vp, ctypes.POINTER(_Info)]
+    lib.ivfpq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
+    lib.ivfpq_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise IvfpqError(rc, load_library().ivfpq_last_error().decode())
+
+
+def last_error() -> str:
+    return load_library().ivfpq_last_error().decode()
+
+
+def set_option(name: str, value: int):
+    _check(load_library().ivfpq_set_option(name.encode(), int(value)))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+    return t
+
+
+def _radii(radii, M: int) -> np.ndarray:
+    r = np.ascontiguousarray(radii, dtype=np.float32)
+    if r.shape != (M,):
+        raise ValueError(f"radii must have shape ({M},)")
+    return r
+
+
+class IvfPqIndex:
+    """Device-resident index.  `ivfpq_index_create` copies and re-lays out the
+    arrays; the numpy inputs are not kept."""
+
+    def __init__(self, centroids, codebooks, list_offsets, codes, ids=None):
+        lib = load_library()
+        cent = np.ascontiguousarray(centroids, dtype=np.float32)
+        cb = np.ascontiguousarray(codebooks, dtype=np.float32)
+        offs = np.ascontiguousarray(list_offsets, dtype=np.int64)
+        if isinstance(codes, torch.Tensor):
+            codes_ref, codes_ptr, N = codes, codes.data_ptr(), codes.shape[0]
+            assert codes.dtype == torch.uint8 and codes.is_contiguous()
+        else:
+            codes_ref = np.ascontiguousarray(codes, dtype=np.uint8)
+            codes_ptr, N = codes_ref.ctypes.data, codes_ref.shape[0]
+        if ids is None:
+            ids_ref, ids_ptr = None, None
+        elif isinstance(ids, torch.Tensor):
+            assert ids.dtype == torch.int64 and ids.is_contiguous()
+            ids_ref, ids_ptr = ids, ids.data_ptr()
+        else:
+            ids_ref = np.ascontiguousarray(ids, dtype=np.int64)
+            ids_ptr = ids_ref.ctypes.data
+        nlist, D = cent.shape
+        M = cb.shape[0]
+        desc = _Desc(N=N, D=D, nlist=nlist, M=M, ksub=cb.shape[1], centroids=cent.ctypes.data,
+                     codebooks=cb.ctypes.data, list_offsets=offs.ctypes.data,
+                     codes=codes_ptr if N > 0 else (codes_ptr or None), ids=ids_ptr)
+        handle = ctypes.c_void_p()
+        self._h = None
+        _check(lib.ivfpq_index_create(ctypes.byref(desc), ctypes.byref(handle)))
+        self._h = handle
+        self.N, self.D, self.nlist, self.M = N, D, nlist, M
+        del codes_ref, ids_ref
+
+    @classmethod
+    def from_index(cls, idx) -> "IvfPqIndex":
+        return cls(idx.centroids, idx.codebooks, idx.list_offsets, idx.codes, idx.ids)
+
+    def info(self) -> dict:
+        i = _Info()
+        _check(load_library().ivfpq_index_get_info(self._h, ctypes.byref(i)))
+        return {f: getattr(i, f) for f, _ in _Info._fields_}
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().ivfpq_index_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- search-side calls -------------------------------------------------
+    def workspace_bytes(self, Q: int, nprobe: int, k: int) -> int:
+        return int(load_library().ivfpq_search_workspace_bytes(self._h, Q, nprobe, k))
+
+    def workspace(self, Q: int, nprobe: int, k: int) -> torch.Tensor:
+        n = max(256, self.workspace_bytes(Q, nprobe, k))
+        return torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def search(self, queries: torch.Tensor, nprobe: int, k: int, radii, workspace: Optional[torch.Tensor] = None,
+               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+        q = _dev(queries, torch.float32)
+        Q = q.shape[0]
+        r = _radii(radii, self.M)
+        ws = workspace if workspace is not None else self.workspace(Q, nprobe, k)
+        ids, dist = out if out is not None else (torch.empty((Q, k), dtype=torch.int64, device=q.device),
+                                                 torch.empty((Q, k), dtype=torch.float32, device=q.device))
+        _check(load_library().ivfpq_search(self._h, q.data_ptr(), Q, nprobe, k, r.ctypes.data, ids.data_ptr(),
+                                           dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        return ids, dist
+
+    def coarse(self, queries: torch.Tensor, nprobe: int, workspace: Optional[torch.Tensor] = None):
+        q = _dev(queries, torch.float32)
+        Q = q.shape[0]
+        ws = workspace if workspace is not None else self.workspace(Q, nprobe, 1)
+        pid = torch.empty((Q, nprobe), dtype=torch.int32, device=q.device)
+        pd = torch.empty((Q, nprobe), dtype=torch.float32, device=q.device)
+        _check(load_library().ivfpq_coarse(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), pd.data_ptr(),
+                                           ws.data_ptr(), ws.numel(), _stream()))
+        return pid, pd
+
+    def build_lut(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii):
+        q = _dev(queries, torch.float32)
+        pid = _dev(probe_ids, torch.int32)
+        Q, nprobe = pid.shape
+        r = _radii(radii, self.M)
+        lut = torch.empty((Q, nprobe, self.M, 256), dtype=torch.float32, device=q.device)
+        mask = torch.zeros((Q, nprobe, self.M, 4), dtype=torch.int64, device=q.device)
+        _check(load_library().ivfpq_build_lut(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), r.ctypes.data,
+                                              lut.data_ptr(), mask.data_ptr(), _stream()))
+        return lut, mask
+
+    def scan_topk(self, queries: torch.Tensor, probe_ids: torch.Tensor, k: int, radii,
+                  workspace: Optional[torch.Tensor] = None):
+        q = _dev(queries, torch.float32)
+        pid = _dev(probe_ids, torch.int32)
+        Q, nprobe = pid.shape
+        r = _radii(radii, self.M)
+        ws = workspace if workspace is not None else self.workspace(Q, nprobe, k)
+        ids = torch.empty((Q, k), dtype=torch.int64, device=q.device)
+        dist = torch.empty((Q, k), dtype=torch.float32, device=q.device)
+        _check(load_library().ivfpq_scan_topk(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, r.ctypes.data,
+                                              ids.data_ptr(), dist.data_ptr(), ws.data_ptr(), ws.numel(),
+                                              _stream()))
+        return ids, dist
+
+    def scan_all(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, cand_offsets: torch.Tensor):
+        """Every candidate's (distance, id); cand_offsets [Q+1] int64 on the device."""
+        q = _dev(queries, torch.float32)
+        pid = _dev(probe_ids, torch.int32)
+        offs = _dev(cand_offsets, torch.int64)
+        Q, nprobe = pid.shape
+        r = _radii(radii, self.M)
+        total = int(offs[-1].item()) if Q > 0 else 0
+        dist = torch.empty(max(total, 1), dtype=torch.float32, device=q.device)
+        ids = torch.empty(max(total, 1), dtype=torch.int64, device=q.device)
+        err = torch.empty(1, dtype=torch.int32, device=q.device)
+        _check(load_library().ivfpq_scan_all(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), r.ctypes.data,
+                                             offs.data_ptr(), dist.data_ptr(), ids.data_ptr(), err.data_ptr(),
+                                             _stream()))
+        return dist[:total], ids[:total], err

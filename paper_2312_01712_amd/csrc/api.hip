@@ -1,0 +1,370 @@
+// C ABI of the library: argument validation, index construction, workspace
+// planning and the entry points declared in include/ivfpq.h.  No kernel lives
+// here; every step of the search path runs in coarse.hip / scan.hip.
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "ivfpq_internal.h"
+
+namespace ivfpq {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what) {
+  set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+  return IVFPQ_ERR_HIP;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k) {
+  (void)k;
+  Workspace w;
+  memset(&w, 0, sizeof w);
+  w.nlist_pad = (ix->nlist + 63) & ~63;
+  int64_t qc = ((int64_t)1 << 30) / ((int64_t)w.nlist_pad * 4);
+  qc &= ~(int64_t)127;
+  if (qc < 128) qc = 128;
+  if (qc > Q) qc = Q;
+  w.q_chunk = qc < 1 ? 1 : qc;
+  // enough workgroups to fill 256 CUs a few times over when the batch is small
+  int64_t ns = Q > 0 ? (2048 + Q - 1) / Q : 1;
+  if (ns > nprobe) ns = nprobe;
+  if (ns > 64) ns = 64;
+  if (ns < 1) ns = 1;
+  w.nsplit = (int32_t)ns;
+  size_t off = 0;
+  w.coarse_dist = off; off += align256((size_t)w.q_chunk * w.nlist_pad * 4);
+  w.probe_ids = off;   off += align256((size_t)Q * nprobe * 4);
+  w.probe_dist = off;  off += align256((size_t)Q * nprobe * 4);
+  if (w.nsplit > 1) {
+    w.part_d = off;    off += align256((size_t)Q * w.nsplit * 128 * 4);
+    w.part_id = off;   off += align256((size_t)Q * w.nsplit * 128 * 8);
+  }
+  w.total = off;
+  return w;
+}
+
+static int check_common(const ivfpq_index *ix, const void *q, int64_t Q, int32_t nprobe, const char *fn) {
+  if (!ix) { set_error("%s: index is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (Q < 0) { set_error("%s: Q = %lld is negative", fn, (long long)Q); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (Q > 0 && !q) { set_error("%s: queries pointer is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (nprobe < 1 || nprobe > ix->nlist) {
+    set_error("%s: nprobe = %d outside [1, nlist = %d]", fn, nprobe, ix->nlist);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (nprobe > IVFPQ_MAX_NPROBE) {
+    set_error("%s: nprobe = %d above the limit %d", fn, nprobe, IVFPQ_MAX_NPROBE);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  return IVFPQ_OK;
+}
+
+static int check_k(int32_t k, const char *fn) {
+  if (k < 1) { set_error("%s: k = %d must be positive", fn, k); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (k > IVFPQ_MAX_K) { set_error("%s: k = %d above the limit %d", fn, k, IVFPQ_MAX_K); return IVFPQ_ERR_UNSUPPORTED; }
+  return IVFPQ_OK;
+}
+
+static int make_radii(const ivfpq_index *ix, const float *radii, RadiiSq *out, const char *fn) {
+  if (!radii) { set_error("%s: radii pointer is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  memset(out, 0, sizeof *out);
+  for (int m = 0; m < ix->M; ++m) {
+    const float r = radii[m];
+    if (!(r >= 0.0f)) {  // catches NaN and negatives
+      set_error("%s: radii[%d] = %g must be >= 0 (or +inf)", fn, m, (double)r);
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+    out->v[m] = r * r;  // fp32 product; +inf stays +inf
+  }
+  return IVFPQ_OK;
+}
+
+static int check_workspace(const Workspace &w, const void *ws, size_t bytes, const char *fn) {
+  if (w.total == 0) return IVFPQ_OK;
+  if (!ws) { set_error("%s: workspace pointer is NULL (%zu bytes needed)", fn, w.total); return IVFPQ_ERR_WORKSPACE; }
+  if ((uintptr_t)ws % 256) { set_error("%s: workspace must be 256-byte aligned", fn); return IVFPQ_ERR_WORKSPACE; }
+  if (bytes < w.total) { set_error("%s: workspace has %zu bytes, %zu needed", fn, bytes, w.total); return IVFPQ_ERR_WORKSPACE; }
+  return IVFPQ_OK;
+}
+
+}  // namespace ivfpq
+
+using namespace ivfpq;
+
+extern "C" {
+
+const char *ivfpq_last_error(void) { return g_err; }
+
+int ivfpq_set_option(const char *name, int value) {
+  if (name && !strcmp(name, "scan_waves")) {
+    if (value != 0 && value != 4 && value != 8 && value != 16) {
+      set_error("set_option: scan_waves must be 0, 4, 8 or 16");
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+    set_scan_waves(value);
+    return IVFPQ_OK;
+  }
+  set_error("set_option: unknown option");
+  return IVFPQ_ERR_INVALID_ARGUMENT;
+}
+
+void ivfpq_index_destroy(ivfpq_index *ix) {
+  if (!ix) return;
+  (void)hipFree(ix->d_centroids);
+  (void)hipFree(ix->d_cnorm);
+  (void)hipFree(ix->d_codebooks);
+  (void)hipFree(ix->d_list_offsets);
+  (void)hipFree(ix->d_list_blocks);
+  (void)hipFree(ix->d_codes);
+  (void)hipFree(ix->d_ids);
+  delete ix;
+}
+
+int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
+  const char *fn = "index_create";
+  if (!d || !out) { set_error("%s: NULL argument", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  *out = nullptr;
+  if (d->ksub != IVFPQ_KSUB) { set_error("%s: ksub = %d, only 256 is supported", fn, d->ksub); return IVFPQ_ERR_UNSUPPORTED; }
+  if (d->N < 0 || d->D < 1 || d->nlist < 1 || d->M < 1) {
+    set_error("%s: N, D, nlist, M must be positive (N may be 0)", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (d->D % d->M) { set_error("%s: D = %d is not a multiple of M = %d", fn, d->D, d->M); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (d->M > IVFPQ_MAX_M) { set_error("%s: M = %d above the limit %d", fn, d->M, IVFPQ_MAX_M); return IVFPQ_ERR_UNSUPPORTED; }
+  if (d->N >= ((int64_t)1 << 32)) { set_error("%s: N = %lld must be below 2^32", fn, (long long)d->N); return IVFPQ_ERR_UNSUPPORTED; }
+  if (!d->centroids || !d->codebooks || !d->list_offsets || (d->N > 0 && !d->codes)) {
+    set_error("%s: NULL array in the description", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  // list offsets: host copy (works for host and device sources once a device exists;
+  // a plain host pointer is read directly so that bad input is caught without a GPU)
+  std::vector<int64_t> offs((size_t)d->nlist + 1);
+  hipPointerAttribute_t attr;
+  bool on_device = false;
+  if (hipPointerGetAttributes(&attr, d->list_offsets) == hipSuccess)
+    on_device = attr.type == hipMemoryTypeDevice;
+  else
+    (void)hipGetLastError();
+  if (on_device) {
+    IVFPQ_HIP_TRY(hipMemcpy(offs.data(), d->list_offsets, offs.size() * 8, hipMemcpyDeviceToHost));
+  } else {
+    memcpy(offs.data(), d->list_offsets, offs.size() * 8);
+  }
+  if (offs[0] != 0 || offs[d->nlist] != d->N) {
+    set_error("%s: list_offsets must start at 0 and end at N", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  std::vector<int64_t> blocks((size_t)d->nlist + 1);
+  blocks[0] = 0;
+  int64_t max_len = 0;
+  for (int c = 0; c < d->nlist; ++c) {
+    const int64_t len = offs[c + 1] - offs[c];
+    if (len < 0) { set_error("%s: list_offsets decrease at list %d", fn, c); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    if (len > 0x7FFFFFC0ll) { set_error("%s: list %d longer than 2^31 points", fn, c); return IVFPQ_ERR_UNSUPPORTED; }
+    if (len > max_len) max_len = len;
+    blocks[c + 1] = blocks[c] + (len + 63) / 64;
+  }
+
+  ivfpq_index *ix = new (std::nothrow) ivfpq_index;
+  if (!ix) { set_error("%s: out of host memory", fn); return IVFPQ_ERR_NO_MEMORY; }
+  memset(ix, 0, sizeof *ix);
+  ix->N = d->N; ix->D = d->D; ix->nlist = d->nlist; ix->M = d->M; ix->dsub = d->D / d->M;
+  ix->Mp = (d->M + 3) & ~3;
+  ix->total_blocks = blocks[d->nlist];
+  ix->code_bytes = ix->total_blocks * ivfpq_block_bytes(ix->Mp);
+  ix->max_list_len = max_len;
+
+  int rc = IVFPQ_OK;
+  uint8_t *d_rows = nullptr;
+  bool rows_owned = false;
+  std::vector<float> cent_h, cnorm;
+#define TRY_OR_FAIL(expr)                                   \
+  do {                                                      \
+    hipError_t _e = (expr);                                 \
+    if (_e != hipSuccess) {                                 \
+      rc = _e == hipErrorOutOfMemory ? IVFPQ_ERR_NO_MEMORY : IVFPQ_ERR_HIP; \
+      set_error("%s: HIP error %d (%s) in %s", fn, (int)_e, hipGetErrorString(_e), #expr); \
+      goto fail;                                            \
+    }                                                       \
+  } while (0)
+  TRY_OR_FAIL(hipGetDevice(&ix->device));
+  {
+    const size_t cb = (size_t)d->nlist * d->D * 4, kb = (size_t)d->M * 256 * ix->dsub * 4;
+    TRY_OR_FAIL(hipMalloc(&ix->d_centroids, cb));
+    TRY_OR_FAIL(hipMalloc(&ix->d_cnorm, (size_t)d->nlist * 4));
+    TRY_OR_FAIL(hipMalloc(&ix->d_codebooks, kb));
+    TRY_OR_FAIL(hipMalloc(&ix->d_list_offsets, offs.size() * 8));
+    TRY_OR_FAIL(hipMalloc(&ix->d_list_blocks, blocks.size() * 8));
+    TRY_OR_FAIL(hipMalloc(&ix->d_codes, ix->code_bytes > 0 ? (size_t)ix->code_bytes : 256));
+    TRY_OR_FAIL(hipMalloc(&ix->d_ids, d->N > 0 ? (size_t)d->N * 8 : 256));
+    TRY_OR_FAIL(hipMemcpy(ix->d_centroids, d->centroids, cb, hipMemcpyDefault));
+    TRY_OR_FAIL(hipMemcpy(ix->d_codebooks, d->codebooks, kb, hipMemcpyDefault));
+    TRY_OR_FAIL(hipMemcpy(ix->d_list_offsets, offs.data(), offs.size() * 8, hipMemcpyHostToDevice));
+    TRY_OR_FAIL(hipMemcpy(ix->d_list_blocks, blocks.data(), blocks.size() * 8, hipMemcpyHostToDevice));
+    // squared centroid norms: only rank proposals in the filtering stage
+    cent_h.resize((size_t)d->nlist * d->D);
+    TRY_OR_FAIL(hipMemcpy(cent_h.data(), ix->d_centroids, cb, hipMemcpyDeviceToHost));
+    cnorm.resize(d->nlist);
+    float mx = 0.0f;
+    for (int c = 0; c < d->nlist; ++c) {
+      double s = 0.0;
+      for (int i = 0; i < d->D; ++i) s += (double)cent_h[(size_t)c * d->D + i] * cent_h[(size_t)c * d->D + i];
+      cnorm[c] = (float)s;
+      if (cnorm[c] > mx) mx = cnorm[c];
+    }
+    ix->max_cnorm = mx;
+    TRY_OR_FAIL(hipMemcpy(ix->d_cnorm, cnorm.data(), (size_t)d->nlist * 4, hipMemcpyHostToDevice));
+    if (d->N > 0) {
+      bool codes_dev = false;
+      if (hipPointerGetAttributes(&attr, d->codes) == hipSuccess) codes_dev = attr.type == hipMemoryTypeDevice;
+      else (void)hipGetLastError();
+      if (codes_dev) {
+        d_rows = const_cast<uint8_t *>(d->codes);
+      } else {
+        TRY_OR_FAIL(hipMalloc(&d_rows, (size_t)d->N * d->M));
+        rows_owned = true;
+        TRY_OR_FAIL(hipMemcpy(d_rows, d->codes, (size_t)d->N * d->M, hipMemcpyHostToDevice));
+      }
+      rc = launch_relayout(ix, d_rows, nullptr);
+      if (rc != IVFPQ_OK) goto fail;
+      if (d->ids) TRY_OR_FAIL(hipMemcpy(ix->d_ids, d->ids, (size_t)d->N * 8, hipMemcpyDefault));
+      else {
+        rc = launch_iota(ix->d_ids, d->N, nullptr);
+        if (rc != IVFPQ_OK) goto fail;
+      }
+      TRY_OR_FAIL(hipDeviceSynchronize());
+    }
+  }
+  if (rows_owned) (void)hipFree(d_rows);
+  *out = ix;
+  return IVFPQ_OK;
+fail:
+  if (rows_owned) (void)hipFree(d_rows);
+  ivfpq_index_destroy(ix);
+  return rc;
+#undef TRY_OR_FAIL
+}
+
+int ivfpq_index_get_info(const ivfpq_index *ix, ivfpq_index_info *info) {
+  if (!ix || !info) { set_error("index_get_info: NULL argument"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  info->N = ix->N; info->D = ix->D; info->nlist = ix->nlist; info->M = ix->M; info->dsub = ix->dsub;
+  info->code_bytes = ix->code_bytes; info->max_list_len = ix->max_list_len;
+  return IVFPQ_OK;
+}
+
+size_t ivfpq_search_workspace_bytes(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k) {
+  if (!ix || Q < 0 || nprobe < 1 || nprobe > ix->nlist || k < 1) return 0;
+  const Workspace w = plan_workspace(ix, Q, nprobe, k);
+  return w.total < 256 ? 256 : w.total;
+}
+
+int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                 int32_t *d_probe_ids, float *d_probe_dist, void *ws, size_t ws_bytes, void *stream) {
+  const char *fn = "coarse";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  if (Q == 0) return IVFPQ_OK;
+  if (!d_probe_ids) { set_error("%s: output pointer is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  const Workspace w = plan_workspace(ix, Q, nprobe, 1);
+  if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
+  char *base = static_cast<char *>(ws);
+  return launch_coarse(ix, d_queries, Q, nprobe, d_probe_ids, d_probe_dist,
+                       reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad,
+                       static_cast<hipStream_t>(stream));
+}
+
+int ivfpq_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                    const int32_t *d_probe_ids, const float *radii, float *d_lut, uint64_t *d_mask,
+                    void *stream) {
+  const char *fn = "build_lut";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  RadiiSq r2;
+  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  if (Q == 0) return IVFPQ_OK;
+  if (!d_probe_ids || !d_lut) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  return launch_build_lut(ix, d_queries, Q, nprobe, d_probe_ids, r2, d_lut, d_mask,
+                          static_cast<hipStream_t>(stream));
+}
+
+int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                    const int32_t *d_probe_ids, int32_t k, const float *radii, int64_t *d_out_ids,
+                    float *d_out_dist, void *ws, size_t ws_bytes, void *stream) {
+  const char *fn = "scan_topk";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  if ((rc = check_k(k, fn))) return rc;
+  RadiiSq r2;
+  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  if (Q == 0) return IVFPQ_OK;
+  if (!d_probe_ids || !d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  const Workspace w = plan_workspace(ix, Q, nprobe, k);
+  if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
+  char *base = static_cast<char *>(ws);
+  return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, w.nsplit,
+                     reinterpret_cast<uint32_t *>(base + w.part_d),
+                     reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
+                     nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
+                 const float *radii, int64_t *d_out_ids, float *d_out_dist, void *ws, size_t ws_bytes,
+                 void *stream) {
+  const char *fn = "search";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  if ((rc = check_k(k, fn))) return rc;
+  RadiiSq r2;
+  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  if (Q == 0) return IVFPQ_OK;
+  if (!d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  const Workspace w = plan_workspace(ix, Q, nprobe, k);
+  if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
+  char *base = static_cast<char *>(ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
+  rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr,
+                     reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad, s);
+  if (rc) return rc;
+  return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
+                     reinterpret_cast<uint32_t *>(base + w.part_d),
+                     reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
+                     nullptr, nullptr, nullptr, s);
+}
+
+int ivfpq_scan_all(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                   const int32_t *d_probe_ids, const float *radii, const int64_t *d_cand_offsets,
+                   float *d_all_dist, int64_t *d_all_ids, int32_t *d_errors, void *stream) {
+  const char *fn = "scan_all";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  RadiiSq r2;
+  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  if (!d_errors) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (Q > 0 && (!d_probe_ids || !d_cand_offsets || !d_all_dist || !d_all_ids)) {
+    set_error("%s: NULL pointer", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = launch_fill_i32(d_errors, 1, 0, s);
+  if (rc || Q == 0) return rc;
+  // the dump variant of the scan kernel keeps no top-k, so k and the result pointers are unused
+  return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, 0, r2, 1, nullptr, nullptr, nullptr, nullptr,
+                     d_cand_offsets, d_all_dist, d_all_ids, d_errors, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,299 @@
+// Filtering stage (paper Sec. 2.1 "Online Search" step A; Sec. 5.3, last
+// paragraph): squared L2 distance from each query to every IVF centroid, the
+// nprobe nearest lists are probed.
+//
+// The paper computes ||x||^2 - 2 x q^T + ||q||^2 with one matrix product on
+// tensor cores.  Here the product runs on the MFMA units (fp32 inputs, fp32
+// accumulate).  Its rounding differs from the reference order of operations
+// (t = q_i - c_i; acc = fmaf(t, t, acc), i ascending), so the product only
+// PROPOSES nprobe + slack lists per query; their distances are then recomputed
+// in the reference order and the final (distance, list id) selection is made
+// on those.  A proposal is accepted only if the slack window is provably wide
+// enough under a rounding-error bound; otherwise that query falls back to
+// reference-order distances for all lists.  The result is therefore identical
+// to a plain scan in the reference order, whatever the matrix unit rounds.
+
+#include "ivfpq_internal.h"
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;  // queries per tile
+constexpr int BN = 128;  // lists per tile
+constexpr int BK = 16;   // depth per LDS stage
+constexpr int LDT = BM + 4;
+
+__device__ inline void load4(const float *base, bool row_ok, int64_t off, int k, int D, bool vec,
+                             float out[4]) {
+  out[0] = out[1] = out[2] = out[3] = 0.0f;
+  if (!row_ok) return;
+  if (vec) {
+    if (k < D) {
+      const float4 v = *reinterpret_cast<const float4 *>(base + off);
+      out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+      if (k + x < D) out[x] = base[off + x];
+  }
+}
+
+// out[q][c] = ||c||^2 - 2 q.c  (the ||q||^2 term is constant per query and does
+// not change the ranking).  One workgroup of 4 wavefronts computes a 128 x 128
+// tile; each wavefront owns a 64 x 64 quadrant as 2 x 2 MFMA 32x32x2 blocks.
+__global__ __launch_bounds__(256) void coarse_gemm_kernel(const float *__restrict__ Qm,
+                                                          const float *__restrict__ Cm,
+                                                          const float *__restrict__ cnorm,
+                                                          float *__restrict__ out, int Qn, int nlist,
+                                                          int D, int ldo, int vec) {
+  __shared__ float sA[BK][LDT];
+  __shared__ float sB[BK][LDT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int q0 = blockIdx.y * BM, c0 = blockIdx.x * BN;
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  for (int k0 = 0; k0 < D; k0 += BK) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int f = tid + 256 * r;
+      const int row = f >> 2, kq = (f & 3) * 4;
+      float va[4], vb[4];
+      load4(Qm, q0 + row < Qn, (int64_t)(q0 + row) * D + k0 + kq, k0 + kq, D, vec != 0, va);
+      load4(Cm, c0 + row < nlist, (int64_t)(c0 + row) * D + k0 + kq, k0 + kq, D, vec != 0, vb);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        sA[kq + x][row] = va[x];
+        sB[kq + x][row] = vb[x];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      const int kr = kk + (lane >> 5), l31 = lane & 31;
+      const float a0 = sA[kr][wm * 64 + l31], a1 = sA[kr][wm * 64 + 32 + l31];
+      const float b0 = sB[kr][wn * 64 + l31], b1 = sB[kr][wn * 64 + 32 + l31];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  // accumulator layout of the 32x32 block: column = lane % 32,
+  // row = 8 * (v / 4) + 4 * (lane / 32) + v % 4
+#pragma unroll
+  for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj) {
+      const int c = c0 + wn * 64 + bj * 32 + (lane & 31);
+      const float cn = c < nlist ? cnorm[c] : 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int q = q0 + wm * 64 + bi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (q < Qn && c < nlist) out[(int64_t)q * ldo + c] = cn - 2.0f * acc[bi][bj][v];
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------
+
+constexpr int SEL_THREADS = 256;
+constexpr int MAX_PROPOSE = 2048;
+
+__device__ inline uint32_t orderable(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float unorderable(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// Reference-order distance (see header).
+__device__ inline float exact_dist(const float *sq, const float *__restrict__ cen, int D) {
+  float acc = 0.0f;
+  for (int i = 0; i < D; ++i) {
+    const float t = sq[i] - cen[i];
+    acc = fmaf(t, t, acc);
+  }
+  return acc;
+}
+
+// inclusive prefix sum over the 256 threads of the workgroup (tmp: 2 x 256)
+__device__ inline uint32_t scan256(uint32_t v, uint32_t *tmp, int tid) {
+  int cur = 0;
+  tmp[tid] = v;
+  __syncthreads();
+  for (int off = 1; off < SEL_THREADS; off <<= 1) {
+    uint32_t x = tmp[cur * SEL_THREADS + tid];
+    if (tid >= off) x += tmp[cur * SEL_THREADS + tid - off];
+    cur ^= 1;
+    tmp[cur * SEL_THREADS + tid] = x;
+    __syncthreads();
+  }
+  const uint32_t r = tmp[cur * SEL_THREADS + tid];
+  __syncthreads();
+  return r;
+}
+
+// One workgroup per query: pick the kprop smallest (value, list) pairs of the
+// proposal row by radix select on 64-bit keys, recompute their distances in the
+// reference order, sort by (distance, list id), emit the first nprobe.
+__global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
+    float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int nlist,
+    int D, int ldo, int nprobe, int kprop, int psort, float err_scale, float max_cnorm,
+    int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
+  extern __shared__ float sq[];  // [D]
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t tmp[2 * SEL_THREADS];
+  __shared__ unsigned long long keys[MAX_PROPOSE];
+  __shared__ uint32_t sel[2];
+  __shared__ uint32_t count;
+  __shared__ float red[SEL_THREADS / 64];
+
+  const int tid = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  float *row = rows + q * ldo;
+  const float *qv = Qm + q * D;
+
+  float part = 0.0f;
+  for (int i = tid; i < D; i += SEL_THREADS) {
+    const float x = qv[i];
+    sq[i] = x;
+    part += x * x;
+  }
+  for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+  if ((tid & 63) == 0) red[tid >> 6] = part;
+  __syncthreads();
+  const float qq = red[0] + red[1] + red[2] + red[3];
+
+  const int idx_bits = 32 - __clz(nlist > 1 ? nlist - 1 : 1);  // bits of a list id
+  const int low_passes = (idx_bits + 7) / 8;
+
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    if (attempt == 1) {
+      // fallback: reference-order distances for every list
+      for (int c = tid; c < nlist; c += SEL_THREADS) row[c] = exact_dist(sq, cent + (int64_t)c * D, D);
+      __syncthreads();
+    }
+    // ---- radix select of the kprop-th smallest key (value bits : list id) ----
+    unsigned long long prefix = 0, mask = 0;
+    uint32_t remaining = kprop;
+    for (int pass = 0; pass < 4 + low_passes; ++pass) {
+      const int shift = pass < 4 ? 56 - 8 * pass : 8 * (low_passes - 1 - (pass - 4));
+      hist[tid] = 0;
+      __syncthreads();
+      for (int c = tid; c < nlist; c += SEL_THREADS) {
+        const unsigned long long key = ((unsigned long long)orderable(row[c]) << 32) | (uint32_t)c;
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
+      }
+      __syncthreads();
+      const uint32_t h = hist[tid];
+      const uint32_t incl = scan256(h, tmp, tid);
+      if (incl >= remaining && incl - h < remaining) {
+        sel[0] = tid;
+        sel[1] = incl - h;
+      }
+      __syncthreads();
+      prefix |= (unsigned long long)sel[0] << shift;
+      mask |= 0xFFull << shift;
+      remaining -= sel[1];
+      __syncthreads();
+    }
+    // prefix is now the kprop-th smallest key; keys are distinct
+    if (tid == 0) count = 0;
+    for (int i = tid; i < psort; i += SEL_THREADS) keys[i] = ~0ull;
+    __syncthreads();
+    for (int c = tid; c < nlist; c += SEL_THREADS) {
+      const unsigned long long key = ((unsigned long long)orderable(row[c]) << 32) | (uint32_t)c;
+      if (key <= prefix) {
+        const uint32_t slot = atomicAdd(&count, 1u);
+        if (slot < (uint32_t)kprop) {
+          const float d = attempt == 1 ? row[c] : exact_dist(sq, cent + (int64_t)c * D, D);
+          keys[slot] = ((unsigned long long)__float_as_uint(d) << 32) | (uint32_t)c;
+        }
+      }
+    }
+    __syncthreads();
+    // ---- sort the proposals by (reference distance, list id) ----
+    for (int k2 = 2; k2 <= psort; k2 <<= 1)
+      for (int j = k2 >> 1; j > 0; j >>= 1) {
+        for (int t = tid; t < (psort >> 1); t += SEL_THREADS) {
+          const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+          const int p = i + j;
+          const unsigned long long a = keys[i], b = keys[p];
+          const bool up = (i & k2) == 0;
+          if (up ? (b < a) : (a < b)) {
+            keys[i] = b;
+            keys[p] = a;
+          }
+        }
+        __syncthreads();
+      }
+    if (attempt == 1 || kprop >= nlist) break;
+    // every list outside the window has a proposal value >= the kprop-th one;
+    // accept if that lower bound clears the nprobe-th reference distance by
+    // more than the rounding-error bound of the matrix product
+    const float t_prop = unorderable((uint32_t)(prefix >> 32)) + qq;
+    const float tau = __uint_as_float((uint32_t)(keys[nprobe - 1] >> 32));
+    const float bound = err_scale * (qq + max_cnorm);
+    const bool ok = (t_prop - tau) > bound;  // false for NaN
+    __syncthreads();
+    if (ok) break;
+  }
+  for (int p = tid; p < nprobe; p += SEL_THREADS) {
+    const unsigned long long key = keys[p];
+    out_ids[q * nprobe + p] = (int32_t)(uint32_t)key;
+    if (out_dist) out_dist[q * nprobe + p] = __uint_as_float((uint32_t)(key >> 32));
+  }
+}
+
+int pow2ceil(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+}  // namespace
+
+namespace ivfpq {
+
+int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                  int32_t *d_probe_ids, float *d_probe_dist, float *d_scratch, int64_t q_chunk,
+                  int32_t nlist_pad, hipStream_t s) {
+  const int D = ix->D, nlist = ix->nlist;
+  int slack = nprobe / 4;
+  if (slack < 16) slack = 16;
+  int kprop = nprobe + slack;
+  if (kprop > nlist) kprop = nlist;
+  if (kprop > MAX_PROPOSE) {
+    set_error("coarse: nprobe %d too large", nprobe);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  const int psort = pow2ceil(kprop < 2 ? 2 : kprop);
+  const float err_scale = 4.0f * (float)D * 1.1920929e-07f;
+  const int vec = (D % 4 == 0) && (((uintptr_t)d_queries | (uintptr_t)ix->d_centroids) % 16 == 0);
+  for (int64_t q0 = 0; q0 < Q; q0 += q_chunk) {
+    const int qn = (int)((Q - q0) < q_chunk ? (Q - q0) : q_chunk);
+    const float *qm = d_queries + q0 * D;
+    dim3 grid((nlist + BN - 1) / BN, (qn + BM - 1) / BM);
+    hipLaunchKernelGGL(coarse_gemm_kernel, grid, dim3(256), 0, s, qm, ix->d_centroids, ix->d_cnorm,
+                       d_scratch, qn, nlist, D, nlist_pad, vec);
+    hipLaunchKernelGGL(coarse_select_kernel, dim3(qn), dim3(SEL_THREADS), (size_t)D * sizeof(float), s,
+                       d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe, kprop, psort,
+                       err_scale, ix->max_cnorm, d_probe_ids + q0 * nprobe,
+                       d_probe_dist ? d_probe_dist + q0 * nprobe : nullptr);
+  }
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+}  // namespace ivfpq

@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of the HIP library.
+// Not part of the public interface (see include/ivfpq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ivfpq.h"
+
+// Device-side image of an index.
+struct ivfpq_index {
+  int64_t N;
+  int32_t D, nlist, M, dsub;
+  int32_t Mp;               // code bytes per point in the device layout, M rounded up to 4
+  int device;
+  float *d_centroids;       // [nlist][D]
+  float *d_cnorm;           // [nlist] squared norms (only used to propose probe lists)
+  float *d_codebooks;       // [M][256][dsub]
+  int64_t *d_list_offsets;  // [nlist+1] in points
+  int64_t *d_list_blocks;   // [nlist+1] in 64-point blocks of the interleaved layout
+  uint8_t *d_codes;         // interleaved blocks, see layout note below
+  int64_t *d_ids;           // [N]
+  int64_t code_bytes;
+  int64_t total_blocks;
+  int64_t max_list_len;
+  float max_cnorm;
+};
+
+// Device layout of the codes.  Every inverted list is padded to a multiple of 64
+// points; a block of 64 points occupies 64*Mp bytes and is stored chunk-major:
+// first Mp/16 chunks of 16 bytes per point ([chunk][lane][16 B]), then
+// (Mp%16)/4 chunks of 4 bytes per point ([chunk][lane][4 B]).  A wavefront that
+// assigns lane l to point l of the block therefore reads 1 KiB (or 256 B)
+// contiguous per load instruction.  Padding bytes and padding points are 0.
+__host__ __device__ inline int64_t ivfpq_block_bytes(int Mp) { return (int64_t)64 * Mp; }
+
+// r_m^2 for every subspace, passed to kernels by value (kernel-argument
+// segment), so that a search needs no device copy of the radii.
+struct RadiiSq {
+  float v[IVFPQ_MAX_M];
+};
+
+namespace ivfpq {
+
+void set_error(const char *fmt, ...);
+int hip_fail(hipError_t e, const char *what);
+
+#define IVFPQ_HIP_TRY(expr)                              \
+  do {                                                   \
+    hipError_t _e = (expr);                              \
+    if (_e != hipSuccess) return ivfpq::hip_fail(_e, #expr); \
+  } while (0)
+
+// ---- workspace carving (all offsets 256-byte aligned) -----------------------
+struct Workspace {
+  size_t coarse_dist;   // [Qc][nlist_pad] fp32 approximate distances of one query chunk
+  size_t probe_ids;     // [Q][nprobe] int32
+  size_t probe_dist;    // [Q][nprobe] fp32
+  size_t part_d;        // [Q][nsplit][128] uint32 (only when nsplit > 1)
+  size_t part_id;       // [Q][nsplit][128] int64
+  size_t total;
+  int64_t q_chunk;      // queries per coarse chunk
+  int32_t nlist_pad;    // row stride of coarse_dist
+  int32_t nsplit;       // probe groups per query in the scan
+};
+Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k);
+
+// ---- launchers (enqueue only) -------------------------------------------------
+int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                  int32_t *d_probe_ids, float *d_probe_dist, float *d_scratch, int64_t q_chunk,
+                  int32_t nlist_pad, hipStream_t s);
+int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                     const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
+                     hipStream_t s);
+int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
+                uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
+                const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
+                int32_t *d_errors, hipStream_t s);
+int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
+int launch_iota(int64_t *d, int64_t n, hipStream_t s);
+int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);
+void set_scan_waves(int nw);  // wavefronts per scan workgroup: 0 (auto), 4, 8 or 16
+
+}  // namespace ivfpq

@@ -1,0 +1,633 @@
+// Selective L2-LUT construction, distance calculation and top-k, fused
+// (paper Sec. 4.1 and Algorithm 2 for the table; Sec. 2.1 step D and Sec. 5.3
+// for the accumulation; Sec. 2.1 for the final selection).
+//
+// One workgroup serves one (query, probe group).  For each probed list it
+//   1. builds the thresholded table for (query, list) in LDS: entry e of
+//      subspace m stores d2 = ||res_m - codebook[m][e]||^2 if d2 <= r_m^2 and
+//      the clamp r_m^2 otherwise (res = query - list centroid);
+//   2. streams the list's codes from HBM, one point per lane, 16 bytes per load,
+//      and sums the table values of the point's codes in subspace order (fp32,
+//      the same order as a plain loop, so sums are reproducible bit for bit);
+//   3. keeps, per wavefront, the 128 best (distance, id) pairs seen so far as a
+//      sorted list spread over the lanes' registers; candidates that beat the
+//      current k-th best are queued in LDS and folded in 64 at a time with a
+//      bitonic merge.
+// At the end the wavefronts' lists are merged and the first k written out.
+//
+// The paper builds the table on RT cores (a ray per (query, list, subspace)
+// against one sphere per entry) and accumulates on tensor cores.  CDNA4 has
+// neither RT cores nor a reason to turn a byte-indexed gather into a matrix
+// product: the radius test is a compare on the vector ALU and the accumulation
+// is bound by HBM and LDS gather rates.
+
+#include <limits.h>
+
+#include "ivfpq_internal.h"
+
+namespace {
+
+constexpr int KP = 128;                    // capacity of a wavefront's sorted list
+constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
+constexpr int64_t SENT_ID = LLONG_MAX;
+
+struct Key {
+  uint32_t d;  // distance bits (distances are >= 0, so bits order like values)
+  int64_t id;
+};
+
+__device__ inline bool kless(const Key &a, const Key &b) {
+  return a.d < b.d || (a.d == b.d && a.id < b.id);
+}
+
+__device__ inline Key shfl_xor_key(const Key &a, int m) {
+  Key o;
+  o.d = (uint32_t)__shfl_xor((int)a.d, m);
+  const int lo = __shfl_xor((int)(uint32_t)a.id, m);
+  const int hi = __shfl_xor((int)(uint32_t)((uint64_t)a.id >> 32), m);
+  o.id = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+  return o;
+}
+
+// compare-exchange with lane ^ j; this lane keeps the smaller key iff keep_small
+__device__ inline void cx_lane(Key &a, int j, bool keep_small) {
+  const Key o = shfl_xor_key(a, j);
+  const bool take = keep_small ? kless(o, a) : kless(a, o);
+  if (take) a = o;
+}
+
+// Sort 64 keys (one per lane) in DESCENDING lane order.
+__device__ inline void wave_sort_desc(Key &a, int lane) {
+#pragma unroll
+  for (int k2 = 2; k2 <= 64; k2 <<= 1) {
+    const bool desc_block = (lane & k2) == 0 || k2 == 64;  // block sorted descending
+#pragma unroll
+    for (int j = k2 >> 1; j > 0; j >>= 1) {
+      const bool lower = (lane & j) == 0;
+      cx_lane(a, j, desc_block ? !lower : lower);
+    }
+  }
+}
+
+// L0/L1 hold a sorted list of 128 keys (element i lives in lane i%64, register
+// i/64).  qd holds 64 keys sorted descending by lane.  Afterwards L0/L1 hold the
+// 128 smallest of the 192, sorted ascending.
+__device__ inline void wave_merge(Key &L0, Key &L1, const Key &qd, int lane) {
+  // element 64+l against the l-th largest queued key: the 128 survivors form a
+  // bitonic sequence
+  if (kless(qd, L1)) L1 = qd;
+  if (kless(L1, L0)) {
+    const Key t = L0;
+    L0 = L1;
+    L1 = t;
+  }
+#pragma unroll
+  for (int j = 32; j > 0; j >>= 1) {
+    const bool lower = (lane & j) == 0;
+    cx_lane(L0, j, lower);
+    cx_lane(L1, j, lower);
+  }
+}
+
+__device__ inline Key bcast_key(const Key &a, int src) {
+  Key o;
+  o.d = (uint32_t)__shfl((int)a.d, src);
+  const int lo = __shfl((int)(uint32_t)a.id, src);
+  const int hi = __shfl((int)(uint32_t)((uint64_t)a.id >> 32), src);
+  o.id = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+  return o;
+}
+
+// One table entry (paper Sec. 4.1; Algorithm 2): squared distance between the
+// residual projection and a codebook entry, thresholded at r2.
+template <int DSUB>
+__device__ inline float lut_entry(const float *sq, const float *__restrict__ cen,
+                                  const float *__restrict__ cb, int dsub_rt, float r2, bool &keep) {
+  const int dsub = DSUB > 0 ? DSUB : dsub_rt;
+  float d2 = 0.0f;
+  if (DSUB == 2) {
+    const float2 e = *reinterpret_cast<const float2 *>(cb);
+    const float t0 = (sq[0] - cen[0]) - e.x;
+    const float t1 = (sq[1] - cen[1]) - e.y;
+    d2 = fmaf(t1, t1, t0 * t0);
+  } else if (DSUB == 4) {
+    const float4 e = *reinterpret_cast<const float4 *>(cb);
+    const float t0 = (sq[0] - cen[0]) - e.x;
+    const float t1 = (sq[1] - cen[1]) - e.y;
+    const float t2 = (sq[2] - cen[2]) - e.z;
+    const float t3 = (sq[3] - cen[3]) - e.w;
+    d2 = fmaf(t3, t3, fmaf(t2, t2, fmaf(t1, t1, t0 * t0)));
+  } else {
+    for (int j = 0; j < dsub; ++j) {
+      const float t = (sq[j] - cen[j]) - cb[j];
+      d2 = j == 0 ? t * t : fmaf(t, t, d2);
+    }
+  }
+  keep = d2 <= r2;
+  return keep ? d2 : r2;
+}
+
+struct ScanArgs {
+  const float *queries;         // [Q][D]
+  const int32_t *probe_ids;     // [Q][nprobe]
+  const float *centroids;       // [nlist][D]
+  const float *codebooks;       // [M][256][dsub]
+  const int64_t *list_offsets;  // [nlist+1]
+  const int64_t *list_blocks;   // [nlist+1]
+  const uint8_t *codes;         // interleaved blocks
+  const int64_t *ids;           // [N]
+  int64_t *out_ids;             // [Q][k]
+  float *out_dist;              // [Q][k]
+  uint32_t *part_d;             // [Q][nsplit][KP] (nsplit > 1)
+  int64_t *part_id;
+  const int64_t *cand_offsets;  // [Q+1] (DUMP)
+  float *all_dist;              // (DUMP)
+  int64_t *all_ids;             // (DUMP)
+  int32_t *errors;              // (DUMP)
+  int32_t D, M, dsub, Mp, nlist, nprobe, k, nsplit;
+};
+
+// Codes of one point (the lane's) in registers.
+template <int NDW>
+struct CodeRegs {
+  uint32_t w[NDW > 0 ? NDW : 1];
+};
+
+template <int MP>
+__device__ inline void load_codes(const uint8_t *__restrict__ blk, int lane, CodeRegs<MP / 4> &r) {
+  constexpr int N16 = MP / 16, N4 = (MP % 16) / 4;
+#pragma unroll
+  for (int j = 0; j < N16; ++j) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(blk + j * 1024 + lane * 16);
+    r.w[4 * j + 0] = v.x;
+    r.w[4 * j + 1] = v.y;
+    r.w[4 * j + 2] = v.z;
+    r.w[4 * j + 3] = v.w;
+  }
+#pragma unroll
+  for (int t = 0; t < N4; ++t)
+    r.w[4 * N16 + t] = *reinterpret_cast<const uint32_t *>(blk + N16 * 1024 + t * 256 + lane * 4);
+}
+
+template <int MT>
+__device__ inline float adc_sum(const float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r) {
+  float dist = 0.0f;
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
+    dist += lut[m * 256 + code];
+  }
+  return dist;
+}
+
+// runtime-M variant: dwords are fetched as they are needed
+__device__ inline float adc_sum_rt(const float *lut, const uint8_t *__restrict__ blk, int lane, int M,
+                                   int Mp) {
+  const int n16 = Mp >> 4;
+  float dist = 0.0f;
+  for (int d = 0; d < (Mp >> 2); ++d) {
+    const uint8_t *p = d < 4 * n16 ? blk + (d >> 2) * 1024 + lane * 16 + (d & 3) * 4
+                                   : blk + n16 * 1024 + (d - 4 * n16) * 256 + lane * 4;
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+    for (int b = 0; b < 4; ++b) {
+      const int m = 4 * d + b;
+      if (m < M) dist += lut[m * 256 + ((w >> (8 * b)) & 0xFFu)];
+    }
+  }
+  return dist;
+}
+
+// Per-wavefront top-k state.
+struct WaveTop {
+  Key L0, L1;       // sorted list, 2 keys per lane
+  Key tau;          // k-th best so far (sentinel while fewer than k are known)
+  int qcount;       // keys waiting in the LDS queue
+};
+
+__device__ inline void wave_flush(WaveTop &st, uint32_t *qd, int64_t *qid, int lane, int k,
+                                  uint32_t *tau_shared) {
+  Key q;
+  q.d = lane < st.qcount ? qd[lane] : SENT_D;
+  q.id = lane < st.qcount ? qid[lane] : SENT_ID;
+  wave_sort_desc(q, lane);
+  wave_merge(st.L0, st.L1, q, lane);
+  st.qcount = 0;
+  const Key t0 = bcast_key(st.L0, (k - 1) & 63), t1 = bcast_key(st.L1, (k - 1) & 63);
+  st.tau = (k - 1) < 64 ? t0 : t1;
+  if (lane == 0 && st.tau.d != SENT_D) atomicMin(tau_shared, st.tau.d);
+}
+
+// Offer this block's distances to the wavefront's top-k.
+__device__ inline void wave_offer(WaveTop &st, float dist, bool valid, int64_t row,
+                                  const int64_t *__restrict__ ids, uint32_t *qd, int64_t *qid,
+                                  int lane, int k, uint32_t *tau_shared) {
+  const uint32_t bits = __float_as_uint(dist);
+  const uint32_t shared = *(volatile uint32_t *)tau_shared;
+  const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
+  bool pass = valid && bits <= pref;
+  if (__ballot(pass) == 0) return;
+  Key c;
+  c.d = bits;
+  c.id = pass ? ids[row] : SENT_ID;
+  pass = pass && kless(c, st.tau);
+  unsigned long long bal = __ballot(pass);
+  int n = __popcll(bal);
+  if (n == 0) return;
+  if (st.qcount + n > 64) {
+    wave_flush(st, qd, qid, lane, k, tau_shared);
+    pass = pass && kless(c, st.tau);
+    bal = __ballot(pass);
+    n = __popcll(bal);
+    if (n == 0) return;
+  }
+  if (pass) {
+    const int slot = st.qcount + __popcll(bal & ((1ull << lane) - 1ull));
+    qd[slot] = c.d;
+    qid[slot] = c.id;
+  }
+  st.qcount += n;
+}
+
+template <int MT, int DSUB, int NW, bool DUMP>
+__global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
+  constexpr int NT = NW * 64;
+  constexpr int MPT = (MT + 3) / 4 * 4;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int M = MT > 0 ? MT : a.M;
+  const int Mp = MT > 0 ? MPT : a.Mp;
+  const int D = a.D;
+  const int dsub = DSUB > 0 ? DSUB : a.dsub;
+  // LDS carve: table | merge staging (aliases the table) | query | queues | tau
+  const int lut_bytes = M * 1024;
+  const int stage_bytes = NW * KP * 12;
+  const int region0 = lut_bytes > stage_bytes ? lut_bytes : stage_bytes;
+  float *lut = reinterpret_cast<float *>(smem);
+  float *sq = reinterpret_cast<float *>(smem + region0);
+  const int sq_bytes = (D * 4 + 15) & ~15;
+  int64_t *queue_id = reinterpret_cast<int64_t *>(smem + region0 + sq_bytes);
+  uint32_t *queue_d = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 8);
+  uint32_t *tau_shared = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 12);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t q = blockIdx.x / a.nsplit;
+  const int split = blockIdx.x % a.nsplit;
+  const int p_begin = (int)((int64_t)a.nprobe * split / a.nsplit);
+  const int p_end = (int)((int64_t)a.nprobe * (split + 1) / a.nsplit);
+  const int32_t *probes = a.probe_ids + q * a.nprobe;
+
+  int64_t dump_pos = 0;
+  if (DUMP) {
+    int64_t total = 0;
+    for (int p = 0; p < a.nprobe; ++p) {
+      const int32_t c = probes[p];
+      if ((uint32_t)c < (uint32_t)a.nlist) total += a.list_offsets[c + 1] - a.list_offsets[c];
+    }
+    if (total != a.cand_offsets[q + 1] - a.cand_offsets[q]) {
+      if (tid == 0) atomicAdd(a.errors, 1);
+      return;
+    }
+    dump_pos = a.cand_offsets[q];
+  }
+
+  for (int i = tid; i < D; i += NT) sq[i] = a.queries[q * D + i];
+  if (tid == 0) *tau_shared = SENT_D;
+
+  WaveTop st;
+  st.L0.d = st.L1.d = SENT_D;
+  st.L0.id = st.L1.id = SENT_ID;
+  st.tau.d = SENT_D;
+  st.tau.id = SENT_ID;
+  st.qcount = 0;
+  uint32_t *qd = queue_d + wave * 64;
+  int64_t *qid = queue_id + wave * 64;
+
+  for (int p = p_begin; p < p_end; ++p) {
+    const int32_t c = probes[p];
+    if ((uint32_t)c >= (uint32_t)a.nlist) continue;  // uniform
+    __syncthreads();  // previous list fully scanned (and sq written) before the table changes
+    // ---- selective table for (query, list c) ----
+    {
+      const float *cen = a.centroids + (int64_t)c * D;
+      const int e = tid & 255;
+      for (int m = tid >> 8; m < M; m += NT >> 8) {
+        const int mu = __builtin_amdgcn_readfirstlane(m);
+        bool keep;
+        lut[mu * 256 + e] = lut_entry<DSUB>(sq + mu * dsub, cen + mu * dsub,
+                                            a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub,
+                                            r2.v[mu], keep);
+      }
+    }
+    __syncthreads();
+    // ---- distance calculation over list c ----
+    const int64_t row0 = a.list_offsets[c];
+    const int len = (int)(a.list_offsets[c + 1] - row0);
+    const int nb = (len + 63) >> 6;
+    const uint8_t *base = a.codes + a.list_blocks[c] * ivfpq_block_bytes(Mp);
+    if (MT > 0) {
+      CodeRegs<MPT / 4> cur, nxt;
+      int b = wave;
+      if (b < nb) load_codes<MPT>(base + (int64_t)b * 64 * MPT, lane, nxt);
+      while (b < nb) {
+        cur = nxt;
+        const int bn = b + NW;
+        if (bn < nb) load_codes<MPT>(base + (int64_t)bn * 64 * MPT, lane, nxt);
+        const float dist = adc_sum<MT>(lut, cur);
+        const int i = b * 64 + lane;
+        const bool valid = i < len;
+        if (DUMP && valid) {
+          a.all_dist[dump_pos + i] = dist;
+          a.all_ids[dump_pos + i] = a.ids[row0 + i];
+        }
+        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, tau_shared);
+        b = bn;
+      }
+    } else {
+      for (int b = wave; b < nb; b += NW) {
+        const float dist = adc_sum_rt(lut, base + (int64_t)b * 64 * Mp, lane, M, Mp);
+        const int i = b * 64 + lane;
+        const bool valid = i < len;
+        if (DUMP && valid) {
+          a.all_dist[dump_pos + i] = dist;
+          a.all_ids[dump_pos + i] = a.ids[row0 + i];
+        }
+        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, tau_shared);
+      }
+    }
+    if (DUMP) dump_pos += len;
+  }
+  if (DUMP) return;
+
+  // ---- fold the queues, then merge the wavefronts' lists through LDS ----
+  if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, tau_shared);
+  __syncthreads();  // table no longer needed: its LDS becomes the staging area
+  uint32_t *stage_d = reinterpret_cast<uint32_t *>(smem);
+  int64_t *stage_id = reinterpret_cast<int64_t *>(smem + NW * KP * 4);
+  if (wave > 0) {
+    stage_d[wave * KP + lane] = st.L0.d;
+    stage_d[wave * KP + 64 + lane] = st.L1.d;
+    stage_id[wave * KP + lane] = st.L0.id;
+    stage_id[wave * KP + 64 + lane] = st.L1.id;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    for (int w = 1; w < NW; ++w)
+      for (int h = 0; h < 2; ++h) {
+        Key qk;  // the half is sorted ascending: read it reversed to get descending
+        qk.d = stage_d[w * KP + h * 64 + (63 - lane)];
+        qk.id = stage_id[w * KP + h * 64 + (63 - lane)];
+        wave_merge(st.L0, st.L1, qk, lane);
+      }
+    if (a.nsplit > 1) {
+      const int64_t o = (q * a.nsplit + split) * KP;
+      a.part_d[o + lane] = st.L0.d;
+      a.part_d[o + 64 + lane] = st.L1.d;
+      a.part_id[o + lane] = st.L0.id;
+      a.part_id[o + 64 + lane] = st.L1.id;
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const Key &e = h ? st.L1 : st.L0;
+        const int i = h * 64 + lane;
+        if (i < a.k) {
+          const bool real = e.d != SENT_D;
+          a.out_ids[q * a.k + i] = real ? e.id : -1;
+          a.out_dist[q * a.k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+        }
+      }
+    }
+  }
+}
+
+// Merge the probe groups' partial lists of a query (one wavefront per query).
+__global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ part_d,
+                                                   const int64_t *__restrict__ part_id, int nsplit,
+                                                   int k, int64_t *__restrict__ out_ids,
+                                                   float *__restrict__ out_dist) {
+  const int lane = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  const int64_t o = q * nsplit * KP;
+  Key L0, L1;
+  L0.d = part_d[o + lane];
+  L0.id = part_id[o + lane];
+  L1.d = part_d[o + 64 + lane];
+  L1.id = part_id[o + 64 + lane];
+  for (int s = 1; s < nsplit; ++s)
+    for (int h = 0; h < 2; ++h) {
+      Key qk;
+      qk.d = part_d[o + s * KP + h * 64 + (63 - lane)];
+      qk.id = part_id[o + s * KP + h * 64 + (63 - lane)];
+      wave_merge(L0, L1, qk, lane);
+    }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const Key &e = h ? L1 : L0;
+    const int i = h * 64 + lane;
+    if (i < k) {
+      const bool real = e.d != SENT_D;
+      out_ids[q * k + i] = real ? e.id : -1;
+      out_dist[q * k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+    }
+  }
+}
+
+// Stand-alone table construction (same entry routine as the fused kernel).
+// One workgroup of 256 threads per (query, probe): thread e handles entry e.
+template <int DSUB>
+__global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ queries,
+                                                  const int32_t *__restrict__ probe_ids,
+                                                  const float *__restrict__ centroids,
+                                                  const float *__restrict__ codebooks, int D, int M,
+                                                  int dsub_rt, int nlist, int nprobe, RadiiSq r2,
+                                                  float *__restrict__ out_lut,
+                                                  uint64_t *__restrict__ out_mask) {
+  extern __shared__ float sqv[];
+  const int dsub = DSUB > 0 ? DSUB : dsub_rt;
+  const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
+  const int64_t qp = blockIdx.x;
+  const int64_t q = qp / nprobe;
+  const int32_t c = probe_ids[qp];
+  if ((uint32_t)c >= (uint32_t)nlist) return;  // uniform
+  for (int i = e; i < D; i += 256) sqv[i] = queries[q * D + i];
+  __syncthreads();
+  const float *cen = centroids + (int64_t)c * D;
+  for (int m = 0; m < M; ++m) {
+    bool keep;
+    const float v = lut_entry<DSUB>(sqv + m * dsub, cen + m * dsub,
+                                    codebooks + ((int64_t)m * 256 + e) * dsub, dsub, r2.v[m], keep);
+    out_lut[(qp * M + m) * 256 + e] = v;
+    const unsigned long long bal = __ballot(keep);
+    if (out_mask && lane == 0) out_mask[(qp * M + m) * 4 + wave] = bal;
+  }
+}
+
+// Index build: raw rows [N][M] -> interleaved 64-point blocks (one wavefront per block).
+__global__ __launch_bounds__(256) void relayout_kernel(const uint8_t *__restrict__ rows,
+                                                       const int64_t *__restrict__ list_offsets,
+                                                       const int64_t *__restrict__ list_blocks,
+                                                       int nlist, int M, int Mp, int64_t total_blocks,
+                                                       uint8_t *__restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t B = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (B >= total_blocks) return;
+  int lo = 0, hi = nlist;  // largest c with list_blocks[c] <= B (skips empty lists)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (list_blocks[mid] <= B) lo = mid; else hi = mid;
+  }
+  const int c = lo;
+  const int64_t i = (B - list_blocks[c]) * 64 + lane;
+  const bool valid = i < list_offsets[c + 1] - list_offsets[c];
+  const uint8_t *src = rows + (list_offsets[c] + i) * M;
+  uint8_t *blk = out + B * ivfpq_block_bytes(Mp);
+  const int n16 = Mp >> 4;
+  for (int d = 0; d < (Mp >> 2); ++d) {
+    uint32_t w = 0;
+    if (valid)
+      for (int b = 0; b < 4; ++b)
+        if (4 * d + b < M) w |= (uint32_t)src[4 * d + b] << (8 * b);
+    uint8_t *p = d < 4 * n16 ? blk + (d >> 2) * 1024 + lane * 16 + (d & 3) * 4
+                             : blk + n16 * 1024 + (d - 4 * n16) * 256 + lane * 4;
+    *reinterpret_cast<uint32_t *>(p) = w;
+  }
+}
+
+__global__ void iota_kernel(int64_t *d, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) d[i] = i;
+}
+
+__global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) d[i] = v;
+}
+
+int g_scan_waves = 0;  // 0 = choose from the shape
+
+template <int MT, int DSUB, int NW>
+int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
+  const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
+  const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) +
+                     (size_t)NW * 64 * 12 + 16;
+  if (lds > 160 * 1024) {
+    ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  auto kern = dump ? scan_kernel<MT, DSUB, NW, true> : scan_kernel<MT, DSUB, NW, false>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) (void)hipGetLastError();  // not fatal: the launch itself reports a real limit
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
+  return IVFPQ_OK;
+}
+
+template <int MT, int DSUB>
+int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
+  int nw = g_scan_waves;
+  if (nw == 0) nw = a.M > 72 ? 16 : 8;
+  if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
+  if (nw >= 8) return launch_scan_t<MT, DSUB, 8>(a, r2, grid, dump, s);
+  return launch_scan_t<MT, DSUB, 4>(a, r2, grid, dump, s);
+}
+
+}  // namespace
+
+namespace ivfpq {
+
+void set_scan_waves(int nw) { g_scan_waves = nw; }
+
+int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
+                uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
+                const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
+                int32_t *d_errors, hipStream_t s) {
+  ScanArgs a;
+  a.queries = d_queries;
+  a.probe_ids = d_probe_ids;
+  a.centroids = ix->d_centroids;
+  a.codebooks = ix->d_codebooks;
+  a.list_offsets = ix->d_list_offsets;
+  a.list_blocks = ix->d_list_blocks;
+  a.codes = ix->d_codes;
+  a.ids = ix->d_ids;
+  a.out_ids = d_out_ids;
+  a.out_dist = d_out_dist;
+  a.part_d = d_part_d;
+  a.part_id = d_part_id;
+  a.cand_offsets = d_cand_offsets;
+  a.all_dist = d_all_dist;
+  a.all_ids = d_all_ids;
+  a.errors = d_errors;
+  a.D = ix->D;
+  a.M = ix->M;
+  a.dsub = ix->dsub;
+  a.Mp = ix->Mp;
+  a.nlist = ix->nlist;
+  a.nprobe = nprobe;
+  a.k = k;
+  a.nsplit = nsplit;
+  const bool dump = d_all_dist != nullptr;
+  const int64_t grid = Q * nsplit;
+  if (grid > 0x7FFFFFFFll) {
+    set_error("scan: %lld workgroups exceed the grid limit", (long long)grid);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  int rc;
+  const int M = ix->M, ds = ix->dsub;
+  if (M == 64 && ds == 2) rc = launch_scan_nw<64, 2>(a, r2, grid, dump, s);
+  else if (M == 48 && ds == 2) rc = launch_scan_nw<48, 2>(a, r2, grid, dump, s);
+  else if (M == 100 && ds == 2) rc = launch_scan_nw<100, 2>(a, r2, grid, dump, s);
+  else if (M == 16 && ds == 4) rc = launch_scan_nw<16, 4>(a, r2, grid, dump, s);
+  else rc = launch_scan_nw<0, 0>(a, r2, grid, dump, s);
+  if (rc != IVFPQ_OK) return rc;
+  if (nsplit > 1 && !dump)
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)Q), dim3(64), 0, s, d_part_d, d_part_id, nsplit, k,
+                       d_out_ids, d_out_dist);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                     const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
+                     hipStream_t s) {
+  const int64_t grid = Q * nprobe;
+  if (grid > 0x7FFFFFFFll) {
+    set_error("build_lut: %lld workgroups exceed the grid limit", (long long)grid);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  const size_t lds = (size_t)ix->D * sizeof(float);
+#define LUT_LAUNCH(DS)                                                                           \
+  hipLaunchKernelGGL(lut_kernel<DS>, dim3((unsigned)grid), dim3(256), lds, s, d_queries,         \
+                     d_probe_ids, ix->d_centroids, ix->d_codebooks, ix->D, ix->M, ix->dsub,      \
+                     ix->nlist, nprobe, r2, d_lut, d_mask)
+  if (ix->dsub == 2) LUT_LAUNCH(2);
+  else if (ix->dsub == 4) LUT_LAUNCH(4);
+  else LUT_LAUNCH(0);
+#undef LUT_LAUNCH
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s) {
+  if (ix->total_blocks == 0) return IVFPQ_OK;
+  const int64_t grid = (ix->total_blocks + 3) / 4;
+  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(256), 0, s, d_rows, ix->d_list_offsets,
+                     ix->d_list_blocks, ix->nlist, ix->M, ix->Mp, ix->total_blocks, ix->d_codes);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s) {
+  if (n == 0) return IVFPQ_OK;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d, n, v);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+int launch_iota(int64_t *d, int64_t n, hipStream_t s) {
+  if (n == 0) return IVFPQ_OK;
+  hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d, n);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+}  // namespace ivfpq

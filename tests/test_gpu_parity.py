@@ -1,0 +1,277 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by
+element on the same seeded inputs.
+
+Bar: probe lists, keep masks, candidate sets and top-k ids are bit-exact; table
+values and distances are compared bit for bit as well, because both sides use
+the same fp32 operation order (the stated tolerance of 1e-4 relative is the
+fallback reported in the assertion message if a bit differs).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2312_01712_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-4
+
+
+def _binding():
+    from paper_2312_01712_amd import binding
+    return binding
+
+
+def _cuda(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def assert_same_float(gpu, ref, what):
+    gpu, ref = np.asarray(gpu), np.asarray(ref)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    same = gpu.view(np.uint32) == ref.view(np.uint32)
+    if not same.all():
+        bad = np.argwhere(~same)
+        rel = np.abs(gpu.astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-30)
+        raise AssertionError(f"{what}: {bad.shape[0]} of {gpu.size} values differ in bits; "
+                             f"max relative difference {np.nanmax(rel[~same]):.3e} "
+                             f"(tolerance {REL_TOL}); first at {bad[0].tolist()}")
+
+
+def cand_offsets(idx, probes):
+    sizes = np.diff(idx.list_offsets)[probes].sum(1)
+    offs = np.zeros(probes.shape[0] + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(sizes)
+    return offs
+
+
+def full_check(w, idx, q, radii, nprobe=None, k=None, stages=True):
+    """All entry points against the oracle for one (index, queries, radii)."""
+    b = _binding()
+    nprobe = w.nprobe if nprobe is None else nprobe
+    k = w.k if k is None else k
+    say(f"  case {w.name}: N={idx.N} D={idx.D} nlist={idx.nlist} M={idx.M} Q={q.shape[0]} nprobe={nprobe} k={k}")
+    gi = b.IvfPqIndex.from_index(idx)
+    dq = _cuda(q)
+    o_pid, o_pd = oracle.coarse(q, idx.centroids, nprobe)
+    if stages:
+        pid, pd = gi.coarse(dq, nprobe)
+        torch.cuda.synchronize()
+        assert np.array_equal(pid.cpu().numpy(), o_pid), "probe lists differ"
+        assert_same_float(pd.cpu().numpy(), o_pd, "probe distances")
+        lut, mask = gi.build_lut(dq, _cuda(o_pid), radii)
+        o_lut, o_mask = oracle.build_lut(q, idx.centroids, idx.codebooks, o_pid, radii)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy().view(np.uint64), o_mask), "keep masks differ"
+        assert_same_float(lut.cpu().numpy(), o_lut, "table values")
+        o_offs, o_cd, o_ci = oracle.scan_all(q, idx, o_pid, radii)
+        assert np.array_equal(o_offs, cand_offsets(idx, o_pid))
+        cd, ci, err = gi.scan_all(dq, _cuda(o_pid), radii, _cuda(o_offs))
+        torch.cuda.synchronize()
+        assert int(err.item()) == 0
+        assert np.array_equal(ci.cpu().numpy(), o_ci), "candidate sets differ"
+        assert_same_float(cd.cpu().numpy(), o_cd, "candidate distances")
+        ids2, dist2 = gi.scan_topk(dq, _cuda(o_pid), k, radii)
+    ids, dist = gi.search(dq, nprobe, k, radii)
+    torch.cuda.synchronize()
+    o_ids, o_dist = oracle.search(q, idx, nprobe, k, radii, threads=8)
+    assert np.array_equal(ids.cpu().numpy(), o_ids), "top-k ids differ"
+    assert_same_float(dist.cpu().numpy(), o_dist, "top-k distances")
+    if stages:
+        assert np.array_equal(ids2.cpu().numpy(), o_ids) and np.array_equal(dist2.cpu().numpy(), dist.cpu().numpy())
+    gi.close()
+    return o_ids
+
+
+@pytest.fixture(scope="module")
+def lib():
+    b = _binding()
+    b.load_library()
+    assert torch.cuda.is_available()
+    return b
+
+
+@pytest.mark.parametrize("name", ["T_gauss", "T_sift", "T_deep", "T_tti"])
+@pytest.mark.parametrize("frac", [0.25, 1.0])
+def test_tiny_workloads(lib, name, frac):
+    w = wl.WORKLOADS[name]
+    idx, centres = wl.train_index(w)
+    q = wl.queries(w, centres).numpy()
+    radii = wl.calibrate_radii(w, idx, centres, frac)
+    full_check(w, idx, q, radii)
+    # every list probed, and a single probe
+    full_check(w, idx, q[:7], radii, nprobe=idx.nlist, k=w.k)
+    full_check(w, idx, q[:7], radii, nprobe=1, k=w.k)
+
+
+def _random_index(rng, N, D, nlist, M, sizes=None):
+    """Untrained random index with a chosen list-size profile."""
+    if sizes is None:
+        sizes = rng.multinomial(N, np.ones(nlist) / nlist)
+    sizes = np.asarray(sizes, dtype=np.int64)
+    N = int(sizes.sum())
+    offs = np.zeros(nlist + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(sizes)
+    return wl.Index(N=N, D=D, nlist=nlist, M=M,
+                    centroids=rng.normal(size=(nlist, D)).astype(np.float32),
+                    codebooks=(0.5 * rng.normal(size=(M, 256, D // M))).astype(np.float32),
+                    list_offsets=offs, codes=rng.integers(0, 256, size=(N, M), dtype=np.uint8),
+                    ids=rng.permutation(N).astype(np.int64) * 3 + 1)
+
+
+@pytest.mark.parametrize("M,D", [(64, 128), (48, 96), (100, 200), (16, 64), (12, 12), (5, 15), (128, 128), (7, 21)])
+def test_shapes_ragged_and_empty_lists(lib, M, D):
+    """Specialised (64/48/100/16 subspaces) and run-time-M kernels; lists that are
+    empty, shorter than a block, exactly a block, and several blocks plus a tail."""
+    rng = np.random.default_rng(M * 1000 + D)
+    sizes = [0, 1, 63, 64, 65, 0, 130, 700, 5, 1500, 64 * 9, 0, 333, 2, 127, 129]
+    idx = _random_index(rng, 0, D, len(sizes), M, sizes)
+    q = rng.normal(size=(33, D)).astype(np.float32)
+    w = wl.Workload(f"rand_M{M}", idx.N, D, idx.nlist, M, 33, 6, 100, "gauss", 1, 1.0)
+    r = np.full(M, 0.9 * np.sqrt(D / M), dtype=np.float32)
+    full_check(w, idx, q, r)
+    full_check(w, idx, q[:5], np.full(M, np.inf, np.float32), nprobe=idx.nlist, k=128)
+    full_check(w, idx, q[:3], r, nprobe=2, k=1)
+
+
+def test_fewer_candidates_than_k_and_empty_probes(lib):
+    rng = np.random.default_rng(11)
+    sizes = [0, 3, 0, 0, 40, 0, 0, 2]
+    idx = _random_index(rng, 0, 32, len(sizes), 8, sizes)
+    q = np.concatenate([idx.centroids[[0, 2, 3, 5, 6]] + 0.01, rng.normal(size=(20, 32)).astype(np.float32)]).astype(np.float32)
+    w = wl.Workload("sparse", idx.N, 32, idx.nlist, 8, q.shape[0], 2, 50, "gauss", 1, 1.0)
+    o_ids = full_check(w, idx, q, np.full(8, np.inf, np.float32))
+    assert (o_ids == -1).any()
+    full_check(w, idx, q, np.full(8, 0.5, np.float32), nprobe=1, k=10)
+
+
+def test_saturated_ties_resolved_by_id(lib):
+    """Radius 0 clamps every entry to 0, so every candidate ties at distance 0 and
+    the k smallest ids must win; small radii saturate most candidates at sum r_m^2."""
+    rng = np.random.default_rng(12)
+    idx = _random_index(rng, 5000, 32, 8, 16)
+    q = rng.normal(size=(9, 32)).astype(np.float32)
+    w = wl.Workload("ties", idx.N, 32, 8, 16, 9, 4, 100, "gauss", 1, 1.0)
+    full_check(w, idx, q, np.zeros(16, np.float32))
+    full_check(w, idx, q, np.full(16, 0.05, np.float32))
+    full_check(w, idx, q, np.full(16, 0.3, np.float32), nprobe=8, k=128)
+
+
+def test_identity_codebook_exact_knn(lib):
+    """The oracle's brute-force pin, run through the HIP path: lossless codes and
+    all lists probed give the exact k nearest neighbours."""
+    from helpers import identity_index, brute_knn_int
+    rng = np.random.default_rng(0)
+    base, idx = identity_index(rng)
+    queries = rng.integers(0, 128, size=(20, idx.D)).astype(np.int64)
+    b = _binding()
+    gi = b.IvfPqIndex.from_index(idx)
+    ids, dist = gi.search(_cuda(queries.astype(np.float32)), idx.nlist, 15, np.full(idx.M, np.inf, np.float32))
+    ref_ids, ref_dist = brute_knn_int(base, queries, 15)
+    assert np.array_equal(ids.cpu().numpy(), ref_ids)
+    assert np.array_equal(dist.cpu().numpy().astype(np.int64), ref_dist)
+
+
+def test_batch_sizes_and_probe_groups(lib):
+    """Q = 1, 2, 100, 3000: small batches split the probes of a query over several
+    workgroups and merge; results must not depend on that."""
+    w = wl.WORKLOADS["T_sift"]
+    idx, centres = wl.train_index(w)
+    radii = wl.calibrate_radii(w, idx, centres, 0.25)
+    b = _binding()
+    gi = b.IvfPqIndex.from_index(idx)
+    q_all = wl.queries(w, centres, 3000).numpy()
+    o_ids, o_dist = oracle.search(q_all, idx, 12, 20, radii, threads=8)
+    for Q in (1, 2, 100, 3000):
+        ids, dist = gi.search(_cuda(q_all[:Q]), 12, 20, radii)
+        assert np.array_equal(ids.cpu().numpy(), o_ids[:Q]), Q
+        assert_same_float(dist.cpu().numpy(), o_dist[:Q], f"Q={Q}")
+    ids, dist = gi.search(_cuda(q_all[:0]), 12, 20, radii)
+    assert ids.shape == (0, 20)
+    for nw in (4, 8, 16, 0):
+        b.set_option("scan_waves", nw)
+        ids, dist = gi.search(_cuda(q_all[:300]), 12, 20, radii)
+        assert np.array_equal(ids.cpu().numpy(), o_ids[:300]), nw
+    # run twice: bitwise identical
+    a1 = gi.search(_cuda(q_all), 12, 20, radii)
+    a2 = gi.search(_cuda(q_all), 12, 20, radii)
+    assert torch.equal(a1[0], a2[0]) and torch.equal(a1[1], a2[1])
+
+
+def test_argument_errors(lib):
+    b = lib
+    w = wl.WORKLOADS["T_gauss"]
+    idx, centres = wl.train_index(w)
+    gi = b.IvfPqIndex.from_index(idx)
+    q = _cuda(wl.queries(w, centres).numpy())
+    ok = np.full(idx.M, 1.0, np.float32)
+    sentinel = torch.full((q.shape[0], 5), -7, dtype=torch.int64, device="cuda")
+    sd = torch.full((q.shape[0], 5), -7.0, dtype=torch.float32, device="cuda")
+    for kwargs, status in [
+        (dict(nprobe=0, k=5, radii=ok), b.ERR_INVALID_ARGUMENT),
+        (dict(nprobe=idx.nlist + 1, k=5, radii=ok), b.ERR_INVALID_ARGUMENT),
+        (dict(nprobe=2, k=0, radii=ok), b.ERR_INVALID_ARGUMENT),
+        (dict(nprobe=2, k=129, radii=ok), b.ERR_UNSUPPORTED),
+        (dict(nprobe=2, k=5, radii=np.full(idx.M, -1.0, np.float32)), b.ERR_INVALID_ARGUMENT),
+        (dict(nprobe=2, k=5, radii=np.full(idx.M, np.nan, np.float32)), b.ERR_INVALID_ARGUMENT),
+        (dict(nprobe=2, k=5, radii=ok, workspace=torch.empty(256, dtype=torch.uint8, device="cuda")), b.ERR_WORKSPACE),
+    ]:
+        with pytest.raises(b.IvfpqError) as e:
+            kw = dict(kwargs)
+            kk = kw.pop("k")
+            if kk == 5:
+                kw["out"] = (sentinel, sd)
+            gi.search(q, kw.pop("nprobe"), kk, kw.pop("radii"), **kw)
+        assert e.value.status == status, (kwargs, e.value)
+        assert b.last_error() != ""
+    torch.cuda.synchronize()
+    assert bool((sentinel == -7).all()) and bool((sd == -7.0).all())   # outputs untouched
+    # scan_all refuses offsets that do not match the probed lists
+    pid, _ = gi.coarse(q, 2)
+    bad = torch.zeros(q.shape[0] + 1, dtype=torch.int64, device="cuda")
+    _, _, err = gi.scan_all(q, pid, ok, bad)
+    torch.cuda.synchronize()
+    assert int(err.item()) > 0
+
+
+def test_c1_full(lib):
+    """The 100k-point configuration end to end, every query, every stage."""
+    w = wl.WORKLOADS["C1"]
+    idx, centres = wl.train_index(w, device="cuda")
+    q = wl.queries(w, centres).cpu().numpy()
+    radii = wl.calibrate_radii(w, idx, centres, w.keep_frac)
+    full_check(w, idx, q[:64], radii)
+    full_check(w, idx, q, radii, stages=False)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+def test_1m_configs_sampled_queries(lib, name):
+    """Full-size 1M-point indexes in the batch shape the benchmark times (all Q
+    queries in one call); the oracle checks a seeded sample of the outputs."""
+    w = wl.WORKLOADS[name]
+    idx, centres = wl.train_index(w, device="cuda", progress=say)
+    q = wl.queries(w, centres).cpu().numpy()
+    b = _binding()
+    gi = b.IvfPqIndex.from_index(idx)
+    dq = _cuda(q)
+    fracs = (0.10, 0.25, 0.50, 1.0) if name == "C2" else (0.25, 1.0)
+    sample = np.random.default_rng(1).choice(w.Q, 48, replace=False)
+    for frac in fracs:
+        radii = wl.calibrate_radii(w, idx, centres, frac)
+        ids, dist = gi.search(dq, w.nprobe, w.k, radii)
+        torch.cuda.synchronize()
+        o_ids, o_dist = oracle.search(q[sample], idx, w.nprobe, w.k, radii, threads=8)
+        assert np.array_equal(ids.cpu().numpy()[sample], o_ids), (name, frac)
+        assert_same_float(dist.cpu().numpy()[sample], o_dist, f"{name} keep={frac}")
+        say(f"  {name} keep={frac}: {len(sample)} sampled queries match the oracle")
+    # properties that hold for every query at full size
+    ids_np, dist_np = ids.cpu().numpy(), dist.cpu().numpy()
+    assert np.all(np.diff(dist_np, axis=1) >= 0) and ids_np.min() >= 0 and ids_np.max() < w.N
+    assert all(len(set(r.tolist())) == w.k for r in ids_np[:500])
+    gi.close()
