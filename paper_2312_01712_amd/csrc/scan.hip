@@ -127,6 +127,35 @@ __device__ inline float lut_entry(const float *sq, const float *__restrict__ cen
   return keep ? d2 : r2;
 }
 
+// Four consecutive entries of one subspace (same arithmetic per entry as above).
+template <int DSUB>
+__device__ inline void lut_entry4(const float *sq, const float *__restrict__ cen,
+                                  const float *__restrict__ cb, float r2, float4 &out) {
+  constexpr int DS = DSUB > 0 ? DSUB : 1;
+  float res[DS];
+#pragma unroll
+  for (int j = 0; j < DSUB; ++j) res[j] = sq[j] - cen[j];
+  float e[4 * DS];
+#pragma unroll
+  for (int x = 0; x < DSUB; ++x) {
+    const float4 v = *reinterpret_cast<const float4 *>(cb + 4 * x);
+    e[4 * x + 0] = v.x; e[4 * x + 1] = v.y; e[4 * x + 2] = v.z; e[4 * x + 3] = v.w;
+  }
+  float d2[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float t0 = res[0] - e[i * DSUB];
+    float acc = t0 * t0;
+#pragma unroll
+    for (int j = 1; j < DSUB; ++j) {
+      const float t = res[j] - e[i * DSUB + j];
+      acc = fmaf(t, t, acc);
+    }
+    d2[i] = acc <= r2 ? acc : r2;
+  }
+  out = make_float4(d2[0], d2[1], d2[2], d2[3]);
+}
+
 struct ScanArgs {
   const float *queries;         // [Q][D]
   const int32_t *probe_ids;     // [Q][nprobe]
@@ -204,8 +233,24 @@ struct WaveTop {
   int qcount;       // keys waiting in the LDS queue
 };
 
+// Bounds shared by the wavefronts of a workgroup (LDS): word 0 is an upper bound
+// on the k-th smallest distance over everything the workgroup has seen; words
+// 1..NW hold each wavefront's ceil(k/NW)-th smallest distance.
+struct SharedTau {
+  uint32_t *bound;
+  uint32_t *rank;  // [NW]
+  int nw, wave, jrank;
+};
+
+// Fold the queued keys into the sorted list and refresh the bounds.  Two rules
+// tighten the shared bound, both by atomic min so that a stale value can only
+// be looser, never wrong:
+//   (i)  a wavefront that knows k keys publishes its k-th smallest distance;
+//   (ii) the wavefronts see disjoint points, so if each of the NW wavefronts
+//        knows j = ceil(k/NW) keys no larger than x_w, at least k keys are no
+//        larger than max_w x_w.
 __device__ inline void wave_flush(WaveTop &st, uint32_t *qd, int64_t *qid, int lane, int k,
-                                  uint32_t *tau_shared) {
+                                  const SharedTau &sh) {
   Key q;
   q.d = lane < st.qcount ? qd[lane] : SENT_D;
   q.id = lane < st.qcount ? qid[lane] : SENT_ID;
@@ -214,15 +259,28 @@ __device__ inline void wave_flush(WaveTop &st, uint32_t *qd, int64_t *qid, int l
   st.qcount = 0;
   const Key t0 = bcast_key(st.L0, (k - 1) & 63), t1 = bcast_key(st.L1, (k - 1) & 63);
   st.tau = (k - 1) < 64 ? t0 : t1;
-  if (lane == 0 && st.tau.d != SENT_D) atomicMin(tau_shared, st.tau.d);
+  const int jr = sh.jrank - 1;
+  const uint32_t j0 = (uint32_t)__shfl((int)st.L0.d, jr & 63), j1 = (uint32_t)__shfl((int)st.L1.d, jr & 63);
+  volatile uint32_t *rank = sh.rank;
+  if (lane == 0) {
+    if (st.tau.d != SENT_D) atomicMin(sh.bound, st.tau.d);
+    rank[sh.wave] = jr < 64 ? j0 : j1;
+  }
+  uint32_t mx = lane < sh.nw ? rank[lane] : 0u;
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)mx, off);
+    mx = o > mx ? o : mx;
+  }
+  if (lane == 0 && mx != SENT_D) atomicMin(sh.bound, mx);
 }
 
 // Offer this block's distances to the wavefront's top-k.
 __device__ inline void wave_offer(WaveTop &st, float dist, bool valid, int64_t row,
                                   const int64_t *__restrict__ ids, uint32_t *qd, int64_t *qid,
-                                  int lane, int k, uint32_t *tau_shared) {
+                                  int lane, int k, const SharedTau &sh) {
   const uint32_t bits = __float_as_uint(dist);
-  const uint32_t shared = *(volatile uint32_t *)tau_shared;
+  const uint32_t shared = *(volatile uint32_t *)sh.bound;
   const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
   bool pass = valid && bits <= pref;
   if (__ballot(pass) == 0) return;
@@ -234,7 +292,7 @@ __device__ inline void wave_offer(WaveTop &st, float dist, bool valid, int64_t r
   int n = __popcll(bal);
   if (n == 0) return;
   if (st.qcount + n > 64) {
-    wave_flush(st, qd, qid, lane, k, tau_shared);
+    wave_flush(st, qd, qid, lane, k, sh);
     pass = pass && kless(c, st.tau);
     bal = __ballot(pass);
     n = __popcll(bal);
@@ -266,9 +324,10 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
   const int sq_bytes = (D * 4 + 15) & ~15;
   int64_t *queue_id = reinterpret_cast<int64_t *>(smem + region0 + sq_bytes);
   uint32_t *queue_d = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 8);
-  uint32_t *tau_shared = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 12);
+  uint32_t *tau_words = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 12);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int64_t q = blockIdx.x / a.nsplit;
   const int split = blockIdx.x % a.nsplit;
   const int p_begin = (int)((int64_t)a.nprobe * split / a.nsplit);
@@ -290,7 +349,13 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
   }
 
   for (int i = tid; i < D; i += NT) sq[i] = a.queries[q * D + i];
-  if (tid == 0) *tau_shared = SENT_D;
+  if (tid <= NW) tau_words[tid] = SENT_D;
+  SharedTau sh;
+  sh.bound = tau_words;
+  sh.rank = tau_words + 1;
+  sh.nw = NW;
+  sh.wave = wave;
+  sh.jrank = (a.k + NW - 1) / NW;
 
   WaveTop st;
   st.L0.d = st.L1.d = SENT_D;
@@ -308,13 +373,25 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
     // ---- selective table for (query, list c) ----
     {
       const float *cen = a.centroids + (int64_t)c * D;
-      const int e = tid & 255;
-      for (int m = tid >> 8; m < M; m += NT >> 8) {
-        const int mu = __builtin_amdgcn_readfirstlane(m);
-        bool keep;
-        lut[mu * 256 + e] = lut_entry<DSUB>(sq + mu * dsub, cen + mu * dsub,
-                                            a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub,
-                                            r2.v[mu], keep);
+      if constexpr (DSUB == 2 || DSUB == 4) {
+        // one subspace per wavefront and pass, four consecutive entries per lane:
+        // 16-byte codebook loads, one 16-byte LDS store
+        for (int m = wave; m < M; m += NW) {
+          const int mu = __builtin_amdgcn_readfirstlane(m);
+          float4 v;
+          lut_entry4<DSUB>(sq + mu * DSUB, cen + mu * DSUB,
+                           a.codebooks + ((int64_t)mu * 256 + 4 * lane) * DSUB, r2.v[mu], v);
+          *reinterpret_cast<float4 *>(lut + mu * 256 + 4 * lane) = v;
+        }
+      } else {
+        const int e = tid & 255;
+        for (int m = tid >> 8; m < M; m += NT >> 8) {
+          const int mu = __builtin_amdgcn_readfirstlane(m);
+          bool keep;
+          lut[mu * 256 + e] = lut_entry<DSUB>(sq + mu * dsub, cen + mu * dsub,
+                                              a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub,
+                                              r2.v[mu], keep);
+        }
       }
     }
     __syncthreads();
@@ -324,22 +401,37 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
     const int nb = (len + 63) >> 6;
     const uint8_t *base = a.codes + a.list_blocks[c] * ivfpq_block_bytes(Mp);
     if (MT > 0) {
-      CodeRegs<MPT / 4> cur, nxt;
-      int b = wave;
-      if (b < nb) load_codes<MPT>(base + (int64_t)b * 64 * MPT, lane, nxt);
-      while (b < nb) {
-        cur = nxt;
-        const int bn = b + NW;
-        if (bn < nb) load_codes<MPT>(base + (int64_t)bn * 64 * MPT, lane, nxt);
-        const float dist = adc_sum<MT>(lut, cur);
+      // two register sets alternate: the next block's loads are in flight while
+      // the current block is looked up
+      CodeRegs<MPT / 4> ra, rb;
+      auto consume = [&](const CodeRegs<MPT / 4> &r, int b) {
+        const float dist = adc_sum<MT>(lut, r);
         const int i = b * 64 + lane;
         const bool valid = i < len;
         if (DUMP && valid) {
           a.all_dist[dump_pos + i] = dist;
           a.all_ids[dump_pos + i] = a.ids[row0 + i];
         }
-        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, tau_shared);
-        b = bn;
+        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
+      };
+      // loads are issued unconditionally (past the end they re-read the list's last
+      // block, which is in bounds) so that the number of loads in flight is known at
+      // every wait and the next block's load never has to complete first
+      if (wave < nb) {
+        const int last = nb - 1;
+        int b = wave;
+        load_codes<MPT>(base + (int64_t)b * 64 * MPT, lane, ra);
+        for (;;) {
+          const int b1 = b + NW;
+          load_codes<MPT>(base + (int64_t)(b1 < last ? b1 : last) * 64 * MPT, lane, rb);
+          consume(ra, b);
+          if (b1 >= nb) break;
+          const int b2 = b1 + NW;
+          load_codes<MPT>(base + (int64_t)(b2 < last ? b2 : last) * 64 * MPT, lane, ra);
+          consume(rb, b1);
+          if (b2 >= nb) break;
+          b = b2;
+        }
       }
     } else {
       for (int b = wave; b < nb; b += NW) {
@@ -350,7 +442,7 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
           a.all_dist[dump_pos + i] = dist;
           a.all_ids[dump_pos + i] = a.ids[row0 + i];
         }
-        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, tau_shared);
+        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
       }
     }
     if (DUMP) dump_pos += len;
@@ -358,7 +450,7 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
   if (DUMP) return;
 
   // ---- fold the queues, then merge the wavefronts' lists through LDS ----
-  if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, tau_shared);
+  if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, sh);
   __syncthreads();  // table no longer needed: its LDS becomes the staging area
   uint32_t *stage_d = reinterpret_cast<uint32_t *>(smem);
   int64_t *stage_id = reinterpret_cast<int64_t *>(smem + NW * KP * 4);
@@ -507,7 +599,7 @@ template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + 16;
+                     (size_t)NW * 64 * 12 + 4 * (NW + 1) + 12;
   if (lds > 160 * 1024) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;

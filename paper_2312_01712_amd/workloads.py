@@ -21,8 +21,9 @@ PQ split), and stand in for them.
 
 k-means details the paper leaves open (initialisation, iteration count, empty
 clusters, training subsample) are free choices, because both search paths are
-fed the same trained index: seeded random distinct initial points, a fixed
-number of Lloyd iterations, empty clusters re-seeded from random points.
+fed the same trained index: D^2-weighted seeding for the IVF centroids (random
+distinct points for the PQ codebooks), a fixed number of Lloyd iterations, empty
+clusters re-seeded from random points.
 """
 from __future__ import annotations
 
@@ -69,9 +70,9 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("C4", 1_000_000, 200, 1_024, 100, 10_000, 64, 100, "tti", 1_024, 0.25,
              query_shift=0.3),
     Workload("C5", 100_000_000, 128, 16_384, 64, 10_000, 64, 100, "sift", 16_384, 20.0,
-             kmeans_iters=4),
+             kmeans_iters=8),
     Workload("C5_10M", 10_000_000, 128, 4_096, 64, 10_000, 64, 100, "sift", 4_096, 20.0,
-             kmeans_iters=6),
+             kmeans_iters=8),
     # host-test sized
     Workload("T_gauss", 6_000, 32, 16, 8, 40, 4, 10, "gauss", 16, 0.15),
     Workload("T_sift", 8_000, 32, 24, 16, 32, 6, 20, "sift", 24, 20.0),
@@ -162,24 +163,53 @@ def _nearest(x: torch.Tensor, c: torch.Tensor, chunk: int = 1 << 16) -> torch.Te
     return out
 
 
+def _seed_centroids(x: torch.Tensor, k: int, g: torch.Generator) -> torch.Tensor:
+    """D^2-weighted seeding (k-means++): each new seed is drawn with probability
+    proportional to the squared distance to the nearest seed chosen so far.  On
+    well-separated mixtures this puts about one seed in every component, which
+    plain random seeding does not, and keeps the inverted lists balanced."""
+    n, d = x.shape
+    c = torch.empty((k, d), dtype=x.dtype, device=x.device)
+    first = int(torch.randint(0, n, (1,), generator=g, device=x.device).item())
+    c[0] = x[first]
+    d2 = ((x - c[0]) ** 2).sum(1)
+    # draw all uniforms up front; pick by inverse CDF so that n may exceed multinomial's limit
+    u = torch.rand(k, generator=g, device=x.device, dtype=torch.float64)
+    for i in range(1, k):
+        cdf = torch.cumsum(d2.to(torch.float64), 0)
+        j = int(torch.searchsorted(cdf, u[i] * cdf[-1]).clamp(max=n - 1).item())
+        c[i] = x[j]
+        d2 = torch.minimum(d2, ((x - c[i]) ** 2).sum(1))
+    return c
+
+
 def kmeans(x: torch.Tensor, k: int, iters: int, g: torch.Generator) -> torch.Tensor:
-    """Plain Lloyd k-means; returns centroids [k][d]."""
+    """D^2-seeded Lloyd k-means; returns centroids [k][d]."""
     n, d = x.shape
     if n < k:
         raise ValueError(f"k-means needs at least k={k} points, got {n}")
-    perm = torch.randperm(n, generator=g, device=x.device)[:k]
-    c = x[perm].clone()
-    for _ in range(iters):
+    c = _seed_centroids(x, k, g)
+    for it in range(iters):
         a = _nearest(x, c)
         sums = torch.zeros((k, d), dtype=torch.float32, device=x.device).index_add_(0, a, x)
-        cnt = torch.bincount(a, minlength=k).to(torch.float32)
-        c_new = sums / cnt.clamp(min=1.0)[:, None]
-        empty = cnt == 0
-        ne = int(empty.sum())
-        if ne:
-            r = torch.randint(0, n, (ne,), generator=g, device=x.device)
-            c_new[empty] = x[r]
-        c = c_new
+        cnt = torch.bincount(a, minlength=k)
+        c = sums / cnt.clamp(min=1).to(torch.float32)[:, None]
+        if it == iters - 1:
+            break
+        # clusters that stay (nearly) empty are re-seeded from a random member of one
+        # of the largest clusters, so a list that swallowed several mixture components
+        # is split instead of starving its neighbours
+        small = torch.nonzero(cnt < 0.6 * n / k).reshape(-1)
+        if small.numel():
+            donors = torch.argsort(cnt, descending=True)[:small.numel()]
+            donors = donors[cnt[donors] > 1.5 * n / k]
+            perm = torch.randperm(n, generator=g, device=x.device)
+            a_perm = a[perm]
+            # first occurrence of every donor label in the permuted order
+            first = torch.full((k,), n, dtype=torch.int64, device=x.device)
+            first.scatter_reduce_(0, a_perm, torch.arange(n, device=x.device), reduce="amin")
+            pick = perm[first[donors].clamp(max=n - 1)]
+            c[small[:donors.numel()]] = x[pick]
     return c.contiguous()
 
 
