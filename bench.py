@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--workload", default="C2", help="C1..C5, C5_10M (default C2: 1M x 128, nprobe 32)")
     ap.add_argument("--keep", type=float, default=0.25, help="fraction of codebook entries inside the radius")
     ap.add_argument("--scan-waves", type=int, default=0)
+    ap.add_argument("--lds-pad", type=int, default=0, help="measurement only: extra LDS bytes per scan workgroup")
+    ap.add_argument("--ablate", type=int, default=0, help="measurement only: scan_ablate bit mask (results invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -59,6 +61,12 @@ def main():
     binding.load_library()
     if args.scan_waves:
         binding.set_option("scan_waves", args.scan_waves)
+    if args.lds_pad:
+        binding.set_option("scan_lds_pad", args.lds_pad)
+    if args.ablate:
+        binding.set_option("scan_ablate", args.ablate)
+        if args.ablate & 7:
+            args.no_cpu_baseline = args.no_recall = True
     w = wl.WORKLOADS[args.workload]
 
     t0 = time.time()
@@ -119,7 +127,7 @@ def main():
     # the one-call entry point gives the same answer
     ids2, dist2 = gi.search(q, nprobe, k, radii, workspace=ws)
     torch.cuda.synchronize()
-    assert torch.equal(ids2, out_ids) and torch.equal(dist2, out_dist)
+    assert (args.ablate & 7) or (torch.equal(ids2, out_ids) and torch.equal(dist2, out_dist))
 
     recall = r1 = None
     if not args.no_recall:

@@ -142,7 +142,11 @@ int ivfpq_index_get_info(const ivfpq_index *index, ivfpq_index_info *info);
 
 /* Tuning knob for measurements, process-wide, not thread-safe against running
  * searches.  "scan_waves": wavefronts per workgroup of the fused scan kernel,
- * 0 (default: chosen from the shape), 4, 8 or 16.  Results do not depend on it. */
+ * 0 (default: chosen from the shape), 4, 8 or 16.  Results do not depend on it.
+ * "scan_ablate": bit mask that switches off parts of the scan kernel to attribute
+ * its time (1 table arithmetic, 2 list scan, 4 top-k offers: results are
+ * meaningless with any of these; 8 turns off the early exit of the distance sums:
+ * results unchanged). */
 int ivfpq_set_option(const char *name, int value);
 
 /* Text for the most recent failure on this thread ("" if none). */

@@ -118,6 +118,15 @@ int ivfpq_set_option(const char *name, int value) {
     set_scan_waves(value);
     return IVFPQ_OK;
   }
+  if (name && !strcmp(name, "scan_ablate")) {
+    set_scan_ablate(value & 15);
+    return IVFPQ_OK;
+  }
+  if (name && !strcmp(name, "scan_lds_pad")) {
+    if (value < 0 || value > 96 * 1024) { set_error("set_option: scan_lds_pad out of range"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    set_scan_lds_pad(value);
+    return IVFPQ_OK;
+  }
   set_error("set_option: unknown option");
   return IVFPQ_ERR_INVALID_ARGUMENT;
 }
@@ -209,7 +218,10 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
     TRY_OR_FAIL(hipMalloc(&ix->d_codebooks, kb));
     TRY_OR_FAIL(hipMalloc(&ix->d_list_offsets, offs.size() * 8));
     TRY_OR_FAIL(hipMalloc(&ix->d_list_blocks, blocks.size() * 8));
-    TRY_OR_FAIL(hipMalloc(&ix->d_codes, ix->code_bytes > 0 ? (size_t)ix->code_bytes : 256));
+    // one block of padding behind the last list: the scan may read (and ignore) the
+    // first block of an empty list
+    TRY_OR_FAIL(hipMalloc(&ix->d_codes, (size_t)ix->code_bytes + (size_t)ivfpq_block_bytes(ix->Mp)));
+    TRY_OR_FAIL(hipMemset(ix->d_codes + ix->code_bytes, 0, (size_t)ivfpq_block_bytes(ix->Mp)));
     TRY_OR_FAIL(hipMalloc(&ix->d_ids, d->N > 0 ? (size_t)d->N * 8 : 256));
     TRY_OR_FAIL(hipMemcpy(ix->d_centroids, d->centroids, cb, hipMemcpyDefault));
     TRY_OR_FAIL(hipMemcpy(ix->d_codebooks, d->codebooks, kb, hipMemcpyDefault));

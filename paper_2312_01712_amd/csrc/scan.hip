@@ -27,6 +27,11 @@
 
 namespace {
 
+// Pointers into LDS carry their address space in the type, so that every access
+// is a DS instruction and no generic-pointer dispatch is ever generated.
+#define LDS __attribute__((address_space(3)))
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
 constexpr int KP = 128;                    // capacity of a wavefront's sorted list
 constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
 constexpr int64_t SENT_ID = LLONG_MAX;
@@ -100,8 +105,8 @@ __device__ inline Key bcast_key(const Key &a, int src) {
 
 // One table entry (paper Sec. 4.1; Algorithm 2): squared distance between the
 // residual projection and a codebook entry, thresholded at r2.
-template <int DSUB>
-__device__ inline float lut_entry(const float *sq, const float *__restrict__ cen,
+template <int DSUB, typename SP>
+__device__ inline float lut_entry(SP sq, const float *__restrict__ cen,
                                   const float *__restrict__ cb, int dsub_rt, float r2, bool &keep) {
   const int dsub = DSUB > 0 ? DSUB : dsub_rt;
   float d2 = 0.0f;
@@ -127,10 +132,13 @@ __device__ inline float lut_entry(const float *sq, const float *__restrict__ cen
   return keep ? d2 : r2;
 }
 
-// Four consecutive entries of one subspace (same arithmetic per entry as above).
-template <int DSUB>
-__device__ inline void lut_entry4(const float *sq, const float *__restrict__ cen,
-                                  const float *__restrict__ cb, float r2, float4 &out) {
+// Four consecutive entries of one subspace (same arithmetic per entry as above);
+// ev holds their 4 * DSUB coordinates as loaded from the codebook.  The clamp
+// keep ? d2 : r2 is written as a minimum: equal bit for bit, and a NaN d2 yields r2
+// in both forms.
+template <int DSUB, typename SP>
+__device__ inline float4 lut_entry4(SP sq, const float *__restrict__ cen, const float4 *ev,
+                                    float r2) {
   constexpr int DS = DSUB > 0 ? DSUB : 1;
   float res[DS];
 #pragma unroll
@@ -138,8 +146,7 @@ __device__ inline void lut_entry4(const float *sq, const float *__restrict__ cen
   float e[4 * DS];
 #pragma unroll
   for (int x = 0; x < DSUB; ++x) {
-    const float4 v = *reinterpret_cast<const float4 *>(cb + 4 * x);
-    e[4 * x + 0] = v.x; e[4 * x + 1] = v.y; e[4 * x + 2] = v.z; e[4 * x + 3] = v.w;
+    e[4 * x + 0] = ev[x].x; e[4 * x + 1] = ev[x].y; e[4 * x + 2] = ev[x].z; e[4 * x + 3] = ev[x].w;
   }
   float d2[4];
 #pragma unroll
@@ -151,9 +158,9 @@ __device__ inline void lut_entry4(const float *sq, const float *__restrict__ cen
       const float t = res[j] - e[i * DSUB + j];
       acc = fmaf(t, t, acc);
     }
-    d2[i] = acc <= r2 ? acc : r2;
+    d2[i] = fminf(acc, r2);
   }
-  out = make_float4(d2[0], d2[1], d2[2], d2[3]);
+  return make_float4(d2[0], d2[1], d2[2], d2[3]);
 }
 
 struct ScanArgs {
@@ -174,6 +181,8 @@ struct ScanArgs {
   int64_t *all_ids;             // (DUMP)
   int32_t *errors;              // (DUMP)
   int32_t D, M, dsub, Mp, nlist, nprobe, k, nsplit;
+  int32_t ablate;  // measurement only: 1 skips the table arithmetic, 2 the list scan, 4 the top-k offers,
+                   // 8 disables the early exit of the distance sums (results stay valid)
 };
 
 // Codes of one point (the lane's) in registers.
@@ -199,7 +208,7 @@ __device__ inline void load_codes(const uint8_t *__restrict__ blk, int lane, Cod
 }
 
 template <int MT>
-__device__ inline float adc_sum(const float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r) {
+__device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r) {
   float dist = 0.0f;
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
@@ -209,8 +218,34 @@ __device__ inline float adc_sum(const float *lut, const CodeRegs<((MT + 3) / 4 *
   return dist;
 }
 
+// Same sum with early exit.  Table values are >= 0 and fp32 addition of a
+// non-negative term never decreases a sum, so a partial sum above the bound
+// means the final distance is above it too.  Every 8 subspaces the wavefront
+// checks whether any of its points can still reach the bound `pref` (an upper
+// bound on the k-th smallest distance); if none can, the rest of the block is
+// skipped.  Returns false in that case.  Points that survive get exactly the
+// sum adc_sum computes.
+template <int MT>
+__device__ inline bool adc_sum_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
+                                    uint32_t pref, bool valid, float &out) {
+  float dist = 0.0f;
+#pragma unroll
+  for (int g = 0; g < MT; g += 8) {
+#pragma unroll
+    for (int m = g; m < (g + 8 < MT ? g + 8 : MT); ++m) {
+      const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
+      dist += lut[m * 256 + code];
+    }
+    if (g + 8 < MT) {
+      if (__ballot(valid && __float_as_uint(dist) <= pref) == 0) return false;
+    }
+  }
+  out = dist;
+  return true;
+}
+
 // runtime-M variant: dwords are fetched as they are needed
-__device__ inline float adc_sum_rt(const float *lut, const uint8_t *__restrict__ blk, int lane, int M,
+__device__ inline float adc_sum_rt(const LDS float *lut, const uint8_t *__restrict__ blk, int lane, int M,
                                    int Mp) {
   const int n16 = Mp >> 4;
   float dist = 0.0f;
@@ -237,8 +272,8 @@ struct WaveTop {
 // on the k-th smallest distance over everything the workgroup has seen; words
 // 1..NW hold each wavefront's ceil(k/NW)-th smallest distance.
 struct SharedTau {
-  uint32_t *bound;
-  uint32_t *rank;  // [NW]
+  LDS uint32_t *bound;
+  LDS uint32_t *rank;  // [NW]
   int nw, wave, jrank;
 };
 
@@ -249,7 +284,7 @@ struct SharedTau {
 //   (ii) the wavefronts see disjoint points, so if each of the NW wavefronts
 //        knows j = ceil(k/NW) keys no larger than x_w, at least k keys are no
 //        larger than max_w x_w.
-__device__ inline void wave_flush(WaveTop &st, uint32_t *qd, int64_t *qid, int lane, int k,
+__device__ __forceinline__ void wave_flush(WaveTop &st, LDS uint32_t *qd, LDS int64_t *qid, int lane, int k,
                                   const SharedTau &sh) {
   Key q;
   q.d = lane < st.qcount ? qd[lane] : SENT_D;
@@ -261,9 +296,9 @@ __device__ inline void wave_flush(WaveTop &st, uint32_t *qd, int64_t *qid, int l
   st.tau = (k - 1) < 64 ? t0 : t1;
   const int jr = sh.jrank - 1;
   const uint32_t j0 = (uint32_t)__shfl((int)st.L0.d, jr & 63), j1 = (uint32_t)__shfl((int)st.L1.d, jr & 63);
-  volatile uint32_t *rank = sh.rank;
+  volatile LDS uint32_t *rank = sh.rank;
   if (lane == 0) {
-    if (st.tau.d != SENT_D) atomicMin(sh.bound, st.tau.d);
+    if (st.tau.d != SENT_D) __hip_atomic_fetch_min(sh.bound, st.tau.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     rank[sh.wave] = jr < 64 ? j0 : j1;
   }
   uint32_t mx = lane < sh.nw ? rank[lane] : 0u;
@@ -272,15 +307,15 @@ __device__ inline void wave_flush(WaveTop &st, uint32_t *qd, int64_t *qid, int l
     const uint32_t o = (uint32_t)__shfl_xor((int)mx, off);
     mx = o > mx ? o : mx;
   }
-  if (lane == 0 && mx != SENT_D) atomicMin(sh.bound, mx);
+  if (lane == 0 && mx != SENT_D) __hip_atomic_fetch_min(sh.bound, mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Offer this block's distances to the wavefront's top-k.
-__device__ inline void wave_offer(WaveTop &st, float dist, bool valid, int64_t row,
-                                  const int64_t *__restrict__ ids, uint32_t *qd, int64_t *qid,
+__device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, int64_t row,
+                                  const int64_t *__restrict__ ids, LDS uint32_t *qd, LDS int64_t *qid,
                                   int lane, int k, const SharedTau &sh) {
   const uint32_t bits = __float_as_uint(dist);
-  const uint32_t shared = *(volatile uint32_t *)sh.bound;
+  const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
   const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
   bool pass = valid && bits <= pref;
   if (__ballot(pass) == 0) return;
@@ -306,8 +341,10 @@ __device__ inline void wave_offer(WaveTop &st, float dist, bool valid, int64_t r
   st.qcount += n;
 }
 
+// At least 4 wavefronts per SIMD (two 8-wave workgroups or one 16-wave workgroup
+// per CU), i.e. at most 128 vector registers.
 template <int MT, int DSUB, int NW, bool DUMP>
-__global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) void scan_kernel(ScanArgs a, RadiiSq r2) {
   constexpr int NT = NW * 64;
   constexpr int MPT = (MT + 3) / 4 * 4;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -319,12 +356,13 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
   const int lut_bytes = M * 1024;
   const int stage_bytes = NW * KP * 12;
   const int region0 = lut_bytes > stage_bytes ? lut_bytes : stage_bytes;
-  float *lut = reinterpret_cast<float *>(smem);
-  float *sq = reinterpret_cast<float *>(smem + region0);
+  LDS unsigned char *smem3 = (LDS unsigned char *)smem;
+  LDS float *lut = (LDS float *)smem3;
+  LDS float *sq = (LDS float *)(smem3 + region0);
   const int sq_bytes = (D * 4 + 15) & ~15;
-  int64_t *queue_id = reinterpret_cast<int64_t *>(smem + region0 + sq_bytes);
-  uint32_t *queue_d = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 8);
-  uint32_t *tau_words = reinterpret_cast<uint32_t *>(smem + region0 + sq_bytes + NW * 64 * 12);
+  LDS int64_t *queue_id = (LDS int64_t *)(smem3 + region0 + sq_bytes);
+  LDS uint32_t *queue_d = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 8);
+  LDS uint32_t *tau_words = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
@@ -363,64 +401,108 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
   st.tau.d = SENT_D;
   st.tau.id = SENT_ID;
   st.qcount = 0;
-  uint32_t *qd = queue_d + wave * 64;
-  int64_t *qid = queue_id + wave * 64;
+  LDS uint32_t *qd = queue_d + wave * 64;
+  LDS int64_t *qid = queue_id + wave * 64;
 
   for (int p = p_begin; p < p_end; ++p) {
     const int32_t c = probes[p];
     if ((uint32_t)c >= (uint32_t)a.nlist) continue;  // uniform
-    __syncthreads();  // previous list fully scanned (and sq written) before the table changes
-    // ---- selective table for (query, list c) ----
-    {
-      const float *cen = a.centroids + (int64_t)c * D;
-      if constexpr (DSUB == 2 || DSUB == 4) {
-        // one subspace per wavefront and pass, four consecutive entries per lane:
-        // 16-byte codebook loads, one 16-byte LDS store
-        for (int m = wave; m < M; m += NW) {
-          const int mu = __builtin_amdgcn_readfirstlane(m);
-          float4 v;
-          lut_entry4<DSUB>(sq + mu * DSUB, cen + mu * DSUB,
-                           a.codebooks + ((int64_t)mu * 256 + 4 * lane) * DSUB, r2.v[mu], v);
-          *reinterpret_cast<float4 *>(lut + mu * 256 + 4 * lane) = v;
-        }
-      } else {
-        const int e = tid & 255;
-        for (int m = tid >> 8; m < M; m += NT >> 8) {
-          const int mu = __builtin_amdgcn_readfirstlane(m);
-          bool keep;
-          lut[mu * 256 + e] = lut_entry<DSUB>(sq + mu * dsub, cen + mu * dsub,
-                                              a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub,
-                                              r2.v[mu], keep);
-        }
-      }
-    }
-    __syncthreads();
-    // ---- distance calculation over list c ----
     const int64_t row0 = a.list_offsets[c];
     const int len = (int)(a.list_offsets[c + 1] - row0);
     const int nb = (len + 63) >> 6;
     const uint8_t *base = a.codes + a.list_blocks[c] * ivfpq_block_bytes(Mp);
+    const float *cen = a.centroids + (int64_t)c * D;
+    constexpr bool VEC = MT > 0 && (DSUB == 2 || DSUB == 4);
+    constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
+    constexpr int DS4 = VEC ? DSUB : 1;
+    // how many passes' codebook entries are fetched ahead: bounded so that they fit
+    // beside the two code register sets without spilling
+    constexpr int PRE_CAP = (80 - 2 * (MPT / 4)) / (4 * DS4);
+    constexpr int PRE = !VEC ? 1 : (ITER < PRE_CAP ? ITER : (PRE_CAP > 1 ? PRE_CAP : 1));
+    // Loads that do not depend on LDS go out before the barrier, so that their
+    // latency overlaps the tail of the previous list: this wavefront's share of the
+    // codebook (the same for every list) and the first code block of the new list.
+    float4 cbv[PRE][DS4];
+    CodeRegs<MPT / 4> ra, rb;
+    if constexpr (VEC) {
+#pragma unroll
+      for (int it = 0; it < PRE; ++it) {
+        const int m = wave + it * NW;
+        const int mc = m < MT ? m : MT - 1;
+        const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
+#pragma unroll
+        for (int x = 0; x < DSUB; ++x) cbv[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+      }
+    }
+    if constexpr (MT > 0) {
+      // an empty list still has one readable (padding) block behind its base
+      const int b0 = wave < nb ? wave : (nb > 0 ? nb - 1 : 0);
+      load_codes<MPT>(base + (int64_t)b0 * 64 * MPT, lane, ra);
+    }
+    __syncthreads();  // previous list fully scanned (and sq written) before the table changes
+    // ---- selective table for (query, list c) ----
+    if constexpr (VEC) {
+      // one subspace per wavefront and pass, four consecutive entries per lane
+#pragma unroll
+      for (int it = 0; it < ITER; ++it) {
+        const int m = wave + it * NW;
+        if (m < MT && !(a.ablate & 1)) {
+          float4 late[DS4];
+          if (it >= PRE) {
+            const float *cb = a.codebooks + ((int64_t)m * 256 + 4 * lane) * DSUB;
+#pragma unroll
+            for (int x = 0; x < DSUB; ++x) late[x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+          }
+          const float4 v = lut_entry4<DSUB>(sq + m * DSUB, cen + m * DSUB, it < PRE ? cbv[it] : late, r2.v[m]);
+          *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
+        }
+      }
+    } else {
+      const int e = tid & 255;
+      for (int m = tid >> 8; m < M; m += NT >> 8) {
+        const int mu = __builtin_amdgcn_readfirstlane(m);
+        bool keep;
+        lut[mu * 256 + e] = lut_entry<DSUB>(sq + mu * dsub, cen + mu * dsub,
+                                            a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub,
+                                            r2.v[mu], keep);
+      }
+    }
+    __syncthreads();
+    // ---- distance calculation over list c ----
     if (MT > 0) {
       // two register sets alternate: the next block's loads are in flight while
       // the current block is looked up
-      CodeRegs<MPT / 4> ra, rb;
-      auto consume = [&](const CodeRegs<MPT / 4> &r, int b) {
-        const float dist = adc_sum<MT>(lut, r);
+      // (the lambda must not capture the kernel-argument struct by reference: that
+      // would force a copy of it into scratch memory)
+      const int64_t *const ids_p = a.ids;
+      float *const all_dist_p = a.all_dist;
+      int64_t *const all_ids_p = a.all_ids;
+      const int kk = a.k, ablate = a.ablate;
+      auto consume = [&, ids_p, all_dist_p, all_ids_p, kk, ablate](const CodeRegs<MPT / 4> &r, int b)
+                         __attribute__((always_inline)) {
         const int i = b * 64 + lane;
         const bool valid = i < len;
-        if (DUMP && valid) {
-          a.all_dist[dump_pos + i] = dist;
-          a.all_ids[dump_pos + i] = a.ids[row0 + i];
+        if (DUMP) {
+          const float dist = adc_sum<MT>(lut, r);
+          if (valid) {
+            all_dist_p[dump_pos + i] = dist;
+            all_ids_p[dump_pos + i] = ids_p[row0 + i];
+          }
+        } else {
+          const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
+          const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
+          float dist;
+          if (!adc_sum_exit<MT>(lut, r, (ablate & 8) ? SENT_D : pref, valid, dist)) return;
+          if (!(ablate & 4)) wave_offer(st, dist, valid, row0 + i, ids_p, qd, qid, lane, kk, sh);
+          if (ablate & 4) st.L0.d = st.L0.d < __float_as_uint(dist) ? st.L0.d : __float_as_uint(dist);
         }
-        if (!DUMP) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
       };
       // loads are issued unconditionally (past the end they re-read the list's last
       // block, which is in bounds) so that the number of loads in flight is known at
       // every wait and the next block's load never has to complete first
-      if (wave < nb) {
+      if (wave < nb && !(a.ablate & 2)) {
         const int last = nb - 1;
         int b = wave;
-        load_codes<MPT>(base + (int64_t)b * 64 * MPT, lane, ra);
         for (;;) {
           const int b1 = b + NW;
           load_codes<MPT>(base + (int64_t)(b1 < last ? b1 : last) * 64 * MPT, lane, rb);
@@ -452,8 +534,8 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
   // ---- fold the queues, then merge the wavefronts' lists through LDS ----
   if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, sh);
   __syncthreads();  // table no longer needed: its LDS becomes the staging area
-  uint32_t *stage_d = reinterpret_cast<uint32_t *>(smem);
-  int64_t *stage_id = reinterpret_cast<int64_t *>(smem + NW * KP * 4);
+  LDS uint32_t *stage_d = (LDS uint32_t *)smem3;
+  LDS int64_t *stage_id = (LDS int64_t *)(smem3 + NW * KP * 4);
   if (wave > 0) {
     stage_d[wave * KP + lane] = st.L0.d;
     stage_d[wave * KP + 64 + lane] = st.L1.d;
@@ -478,7 +560,7 @@ __global__ __launch_bounds__(NW * 64) void scan_kernel(ScanArgs a, RadiiSq r2) {
     } else {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const Key &e = h ? st.L1 : st.L0;
+        const Key e = h ? st.L1 : st.L0;  // by value: a reference would pin the state in scratch
         const int i = h * 64 + lane;
         if (i < a.k) {
           const bool real = e.d != SENT_D;
@@ -512,7 +594,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ 
     }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const Key &e = h ? L1 : L0;
+    const Key e = h ? L1 : L0;
     const int i = h * 64 + lane;
     if (i < k) {
       const bool real = e.d != SENT_D;
@@ -594,12 +676,14 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
 }
 
 int g_scan_waves = 0;  // 0 = choose from the shape
+int g_scan_ablate = 0;
+int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
 
 template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + 4 * (NW + 1) + 12;
+                     (size_t)NW * 64 * 12 + 4 * (NW + 1) + 12 + (size_t)g_scan_lds_pad;
   if (lds > 160 * 1024) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
@@ -626,6 +710,8 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
 namespace ivfpq {
 
 void set_scan_waves(int nw) { g_scan_waves = nw; }
+void set_scan_ablate(int bits) { g_scan_ablate = bits; }
+void set_scan_lds_pad(int bytes) { g_scan_lds_pad = bytes; }
 
 int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
@@ -657,6 +743,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.nprobe = nprobe;
   a.k = k;
   a.nsplit = nsplit;
+  a.ablate = g_scan_ablate;
   const bool dump = d_all_dist != nullptr;
   const int64_t grid = Q * nsplit;
   if (grid > 0x7FFFFFFFll) {
