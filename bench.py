@@ -26,6 +26,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 
+# HBM bytes per scan-kernel launch from rocprofv3 counter runs of this file (FETCH_SIZE and
+# WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for an
+# elementwise pass over 1 GiB: x2.000 and x1.000).  Commands and raw figures: profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    ("C2", 0.25): 9.20115e6 * 1024 * 2.000 + 11875 * 1024 * 1.000,
+    ("C5", 0.25): 2.23839e8 * 1024 * 2.000 + 11875 * 1024 * 1.000,
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -143,7 +151,8 @@ def main():
                    "family": w.family, "keep_fraction": args.keep, "recall_at_k": recall, "r1_at_k": r1,
                    "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms},
         "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.keep)),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": scan_avg_ms},
     }
 
