@@ -119,7 +119,12 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_ablate")) {
-    set_scan_ablate(value & 15);
+    set_scan_ablate(value & 31);
+    return IVFPQ_OK;
+  }
+  if (name && !strcmp(name, "scan_variant")) {
+    if (value < 0 || value > 2) { set_error("set_option: scan_variant must be 0, 1 or 2"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    set_scan_variant(value);
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_lds_pad")) {

@@ -82,6 +82,7 @@ int launch_iota(int64_t *d, int64_t n, hipStream_t s);
 int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);
 void set_scan_ablate(int bits);  // measurement only: skip parts of the scan kernel (results invalid)
 void set_scan_lds_pad(int bytes); // measurement only: extra LDS per scan workgroup
+void set_scan_variant(int v);     // 0 auto, 1 two-barrier scan kernel, 2 double-table scan kernel
 void set_scan_waves(int nw);  // wavefronts per scan workgroup: 0 (auto), 4, 8 or 16
 
 }  // namespace ivfpq

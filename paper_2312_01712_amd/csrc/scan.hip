@@ -32,6 +32,7 @@ namespace {
 #define LDS __attribute__((address_space(3)))
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+constexpr int RES_REGS = 48;  // vector registers a wavefront may devote to resident codebook rows
 constexpr int KP = 128;                    // capacity of a wavefront's sorted list
 constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
 constexpr int64_t SENT_ID = LLONG_MAX;
@@ -137,12 +138,11 @@ __device__ inline float lut_entry(SP sq, const float *__restrict__ cen,
 // keep ? d2 : r2 is written as a minimum: equal bit for bit, and a NaN d2 yields r2
 // in both forms.
 template <int DSUB, typename SP>
-__device__ inline float4 lut_entry4(SP sq, const float *__restrict__ cen, const float4 *ev,
-                                    float r2) {
+__device__ inline float4 lut_entry4(SP res_p, const float4 *ev, float r2) {
   constexpr int DS = DSUB > 0 ? DSUB : 1;
-  float res[DS];
+  float res[DS];  // residual projection q_m - centroid_m, computed once per list
 #pragma unroll
-  for (int j = 0; j < DSUB; ++j) res[j] = sq[j] - cen[j];
+  for (int j = 0; j < DSUB; ++j) res[j] = res_p[j];
   float e[4 * DS];
 #pragma unroll
   for (int x = 0; x < DSUB; ++x) {
@@ -341,6 +341,53 @@ __device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, 
   st.qcount += n;
 }
 
+// End of a workgroup's work: fold the queues, merge the wavefronts' sorted lists
+// through LDS (the table region is free by then) and write the first k keys, or
+// the whole list when the probes of the query were split over several workgroups.
+template <int NW>
+__device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS int64_t *qid, int lane,
+                                            int wave, const SharedTau &sh, LDS unsigned char *smem3,
+                                            const ScanArgs &a, int64_t q, int split) {
+  if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, sh);
+  __syncthreads();  // tables no longer needed: their LDS becomes the staging area
+  LDS uint32_t *stage_d = (LDS uint32_t *)smem3;
+  LDS int64_t *stage_id = (LDS int64_t *)(smem3 + NW * KP * 4);
+  if (wave > 0) {
+    stage_d[wave * KP + lane] = st.L0.d;
+    stage_d[wave * KP + 64 + lane] = st.L1.d;
+    stage_id[wave * KP + lane] = st.L0.id;
+    stage_id[wave * KP + 64 + lane] = st.L1.id;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    for (int w = 1; w < NW; ++w)
+      for (int h = 0; h < 2; ++h) {
+        Key qk;  // the half is sorted ascending: read it reversed to get descending
+        qk.d = stage_d[w * KP + h * 64 + (63 - lane)];
+        qk.id = stage_id[w * KP + h * 64 + (63 - lane)];
+        wave_merge(st.L0, st.L1, qk, lane);
+      }
+    if (a.nsplit > 1) {
+      const int64_t o = (q * a.nsplit + split) * KP;
+      a.part_d[o + lane] = st.L0.d;
+      a.part_d[o + 64 + lane] = st.L1.d;
+      a.part_id[o + lane] = st.L0.id;
+      a.part_id[o + 64 + lane] = st.L1.id;
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const Key e = h ? st.L1 : st.L0;  // by value: a reference would pin the state in scratch
+        const int i = h * 64 + lane;
+        if (i < a.k) {
+          const bool real = e.d != SENT_D;
+          a.out_ids[q * a.k + i] = real ? e.id : -1;
+          a.out_dist[q * a.k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+        }
+      }
+    }
+  }
+}
+
 // At least 4 wavefronts per SIMD (two 8-wave workgroups or one 16-wave workgroup
 // per CU), i.e. at most 128 vector registers.
 template <int MT, int DSUB, int NW, bool DUMP>
@@ -359,10 +406,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   LDS unsigned char *smem3 = (LDS unsigned char *)smem;
   LDS float *lut = (LDS float *)smem3;
   LDS float *sq = (LDS float *)(smem3 + region0);
-  const int sq_bytes = (D * 4 + 15) & ~15;
+  const int sq_bytes = 2 * ((D * 4 + 15) & ~15);  // the query, then the residual of the current list
+  LDS float *sres = sq + (sq_bytes >> 3);
   LDS int64_t *queue_id = (LDS int64_t *)(smem3 + region0 + sq_bytes);
   LDS uint32_t *queue_d = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 8);
   LDS uint32_t *tau_words = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12);
+  // per-probe list metadata of up to META probes, staged once per chunk of probes so
+  // that a probe does not start with a chain of dependent scalar loads
+  constexpr int META = 64;
+  const int tau_bytes = (4 * (NW + 1) + 15) & ~15;
+  LDS int64_t *meta_row0 = (LDS int64_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12 + tau_bytes);
+  LDS int64_t *meta_blk = meta_row0 + META;
+  LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
+  LDS int32_t *meta_c = meta_len + META;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
@@ -404,34 +460,73 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   LDS uint32_t *qd = queue_d + wave * 64;
   LDS int64_t *qid = queue_id + wave * 64;
 
-  for (int p = p_begin; p < p_end; ++p) {
-    const int32_t c = probes[p];
-    if ((uint32_t)c >= (uint32_t)a.nlist) continue;  // uniform
-    const int64_t row0 = a.list_offsets[c];
-    const int len = (int)(a.list_offsets[c + 1] - row0);
-    const int nb = (len + 63) >> 6;
-    const uint8_t *base = a.codes + a.list_blocks[c] * ivfpq_block_bytes(Mp);
-    const float *cen = a.centroids + (int64_t)c * D;
-    constexpr bool VEC = MT > 0 && (DSUB == 2 || DSUB == 4);
-    constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
-    constexpr int DS4 = VEC ? DSUB : 1;
-    // how many passes' codebook entries are fetched ahead: bounded so that they fit
-    // beside the two code register sets without spilling
-    constexpr int PRE_CAP = (80 - 2 * (MPT / 4)) / (4 * DS4);
-    constexpr int PRE = !VEC ? 1 : (ITER < PRE_CAP ? ITER : (PRE_CAP > 1 ? PRE_CAP : 1));
-    // Loads that do not depend on LDS go out before the barrier, so that their
-    // latency overlaps the tail of the previous list: this wavefront's share of the
-    // codebook (the same for every list) and the first code block of the new list.
-    float4 cbv[PRE][DS4];
-    CodeRegs<MPT / 4> ra, rb;
-    if constexpr (VEC) {
+  // Codebook rows of this wavefront (rows wave, wave + NW, ...): the first RES of them
+  // stay in registers for the whole kernel -- the codebook is the same for every list
+  // and re-reading all of it per list costs a quarter of the kernel on short lists --
+  // the remaining STR are streamed per list.  RES is what fits beside the scan's
+  // registers at 4 wavefronts per SIMD.
+  constexpr bool VEC = MT > 0 && (DSUB == 2 || DSUB == 4);
+  constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
+  constexpr int DS4 = VEC ? DSUB : 1;
+  constexpr int RES_CAP = RES_REGS / (4 * DS4);
+  constexpr int RES = !VEC ? 0 : (ITER < RES_CAP ? ITER : RES_CAP);
+  constexpr int STR = VEC ? ITER - RES : 0;
+  float4 cbr[RES > 0 ? RES : 1][DS4];
+  if constexpr (VEC) {
 #pragma unroll
-      for (int it = 0; it < PRE; ++it) {
-        const int m = wave + it * NW;
+    for (int it = 0; it < RES; ++it) {
+      const int m = wave + it * NW;
+      const int mc = m < MT ? m : MT - 1;
+      const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
+#pragma unroll
+      for (int x = 0; x < DSUB; ++x) cbr[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+    }
+  }
+  bool sres_ready = false;
+  for (int p = p_begin; p < p_end; ++p) {
+    const int pm = (p - p_begin) & (META - 1);
+    if (pm == 0) {
+      // every wavefront has passed the second barrier of the previous probe, so nobody
+      // still reads the old entries
+      if (tid < META && p + tid < p_end) {
+        const int32_t cc = probes[p + tid];
+        const bool ok = (uint32_t)cc < (uint32_t)a.nlist;
+        const int64_t r0 = ok ? a.list_offsets[cc] : 0;
+        meta_c[tid] = ok ? cc : 0;  // a probe id outside [0, nlist) becomes an empty list
+        meta_row0[tid] = r0;
+        meta_len[tid] = ok ? (int)(a.list_offsets[cc + 1] - r0) : 0;
+        meta_blk[tid] = ok ? a.list_blocks[cc] : 0;
+      }
+      __syncthreads();
+    }
+    const int32_t c = __builtin_amdgcn_readfirstlane(meta_c[pm]);
+    const int64_t row0 = meta_row0[pm];
+    const int len = __builtin_amdgcn_readfirstlane(meta_len[pm]);
+    const int nb = (len + 63) >> 6;
+    const uint8_t *base = a.codes + meta_blk[pm] * ivfpq_block_bytes(Mp);
+    const float *cen = a.centroids + (int64_t)c * D;
+    // Loads that do not depend on LDS go out before the barrier, so that their
+    // latency overlaps the tail of the previous list: the streamed part of this
+    // wavefront's codebook rows and the first code block of the new list.
+    float4 cbs[STR > 0 ? STR : 1][DS4];
+    CodeRegs<MPT / 4> ra, rb;
+    // The residual q - centroid of a list is formed once, in LDS.  For the list after
+    // this one the centroid is requested now and the residual written after this
+    // list's table is finished, so the next table does not wait for it.
+    const bool next_known = VEC && D <= NT && pm + 1 < META && p + 1 < p_end;
+    float cen_next = 0.0f;
+    if constexpr (VEC) {
+      if (!sres_ready)
+        for (int i = tid; i < D; i += NT) sres[i] = sq[i] - cen[i];
+      if (next_known && tid < D)
+        cen_next = a.centroids[(int64_t)__builtin_amdgcn_readfirstlane(meta_c[pm + 1]) * D + tid];
+#pragma unroll
+      for (int it = 0; it < STR; ++it) {
+        const int m = wave + (RES + it) * NW;
         const int mc = m < MT ? m : MT - 1;
         const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
 #pragma unroll
-        for (int x = 0; x < DSUB; ++x) cbv[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+        for (int x = 0; x < DSUB; ++x) cbs[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
       }
     }
     if constexpr (MT > 0) {
@@ -447,13 +542,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
       for (int it = 0; it < ITER; ++it) {
         const int m = wave + it * NW;
         if (m < MT && !(a.ablate & 1)) {
-          float4 late[DS4];
-          if (it >= PRE) {
-            const float *cb = a.codebooks + ((int64_t)m * 256 + 4 * lane) * DSUB;
-#pragma unroll
-            for (int x = 0; x < DSUB; ++x) late[x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
-          }
-          const float4 v = lut_entry4<DSUB>(sq + m * DSUB, cen + m * DSUB, it < PRE ? cbv[it] : late, r2.v[m]);
+          const float4 v = lut_entry4<DSUB>(sres + m * DSUB, it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0],
+                                            r2.v[m]);
           *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
         }
       }
@@ -468,6 +558,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
       }
     }
     __syncthreads();
+    if constexpr (VEC) {
+      if (next_known && tid < D) sres[tid] = sq[tid] - cen_next;  // this list's table is complete
+      sres_ready = next_known;
+    }
     // ---- distance calculation over list c ----
     if (MT > 0) {
       // two register sets alternate: the next block's loads are in flight while
@@ -531,45 +625,203 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   }
   if (DUMP) return;
 
-  // ---- fold the queues, then merge the wavefronts' lists through LDS ----
-  if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, sh);
-  __syncthreads();  // table no longer needed: its LDS becomes the staging area
-  LDS uint32_t *stage_d = (LDS uint32_t *)smem3;
-  LDS int64_t *stage_id = (LDS int64_t *)(smem3 + NW * KP * 4);
-  if (wave > 0) {
-    stage_d[wave * KP + lane] = st.L0.d;
-    stage_d[wave * KP + 64 + lane] = st.L1.d;
-    stage_id[wave * KP + lane] = st.L0.id;
-    stage_id[wave * KP + 64 + lane] = st.L1.id;
-  }
-  __syncthreads();
-  if (wave == 0) {
-    for (int w = 1; w < NW; ++w)
-      for (int h = 0; h < 2; ++h) {
-        Key qk;  // the half is sorted ascending: read it reversed to get descending
-        qk.d = stage_d[w * KP + h * 64 + (63 - lane)];
-        qk.id = stage_id[w * KP + h * 64 + (63 - lane)];
-        wave_merge(st.L0, st.L1, qk, lane);
-      }
-    if (a.nsplit > 1) {
-      const int64_t o = (q * a.nsplit + split) * KP;
-      a.part_d[o + lane] = st.L0.d;
-      a.part_d[o + 64 + lane] = st.L1.d;
-      a.part_id[o + lane] = st.L0.id;
-      a.part_id[o + 64 + lane] = st.L1.id;
-    } else {
+  finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
+}
+
+// Second organisation of the same work for shapes whose table fits LDS twice
+// (2 * M KiB + queues <= 160 KiB): one workgroup of 16 wavefronts per CU and two
+// table buffers.  While list p is scanned with table p, table p+1 is built into
+// the other buffer, half of the wavefronts building first and scanning second, the
+// other half the other way round, so vector-ALU work (tables) and LDS gathers (scan)
+// overlap instead of alternating; one barrier per probed list instead of two.
+// Each wavefront keeps its rows of the codebook in registers for the whole kernel
+// (the codebook is the same for every list), which removes the per-list codebook
+// traffic from L2.  Blocks of a list are handed out through an LDS counter, so a
+// wavefront that built first simply scans fewer blocks.  Arithmetic, order of
+// operations and results are those of scan_kernel.
+template <int MT, int DSUB>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4))) void scan_kernel_v2(ScanArgs a,
+                                                                                             RadiiSq r2) {
+  constexpr int NW = 16, NT = NW * 64, META = 64;
+  constexpr int MPT = (MT + 3) / 4 * 4;
+  constexpr int ITER = (MT + NW - 1) / NW;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int D = a.D;
+  constexpr int lut_bytes = MT * 1024;
+  constexpr int stage_bytes = NW * KP * 12;
+  constexpr int region0 = 2 * lut_bytes > stage_bytes ? 2 * lut_bytes : stage_bytes;
+  LDS unsigned char *smem3 = (LDS unsigned char *)smem;
+  LDS float *lut0 = (LDS float *)smem3;
+  LDS float *sq = (LDS float *)(smem3 + region0);
+  const int sq_pad = (D * 4 + 15) & ~15;
+  const int sq_bytes = 3 * sq_pad;  // the query, then two buffers of list residuals q - centroid
+  LDS float *sres = sq + (sq_pad >> 2);  // residual of probe r lives in buffer r & 1
+  LDS int64_t *queue_id = (LDS int64_t *)(smem3 + region0 + sq_bytes);
+  LDS uint32_t *queue_d = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 8);
+  LDS uint32_t *tau_words = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12);
+  constexpr int tau_bytes = (4 * (NW + 1) + 15) & ~15;
+  // two sets of list metadata (one per chunk of META probes) and two block counters
+  LDS int64_t *meta_row0 = (LDS int64_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12 + tau_bytes);
+  LDS int64_t *meta_blk = meta_row0 + 2 * META;
+  LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + 2 * META);
+  LDS int32_t *meta_c = meta_len + 2 * META;
+  LDS int32_t *counters = meta_c + 2 * META;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t q = blockIdx.x / a.nsplit;
+  const int split = blockIdx.x % a.nsplit;
+  const int p_begin = (int)((int64_t)a.nprobe * split / a.nsplit);
+  const int p_end = (int)((int64_t)a.nprobe * (split + 1) / a.nsplit);
+  const int32_t *probes = a.probe_ids + q * a.nprobe;
+
+  // metadata of chunk `ch` (probes p_begin + ch*META ...) into set ch & 1; a probe id
+  // outside [0, nlist) becomes an empty list (its table is still built, from list 0)
+  auto stage_meta = [&](int ch) {
+    const int p0 = p_begin + ch * META;
+    if (tid < META && p0 + tid < p_end) {
+      const int32_t cc = probes[p0 + tid];
+      const bool ok = (uint32_t)cc < (uint32_t)a.nlist;
+      const int64_t r0 = ok ? a.list_offsets[cc] : 0;
+      const int o = (ch & 1) * META + tid;
+      meta_c[o] = ok ? cc : 0;
+      meta_row0[o] = r0;
+      meta_len[o] = ok ? (int)(a.list_offsets[cc + 1] - r0) : 0;
+      meta_blk[o] = ok ? a.list_blocks[cc] : 0;
+    }
+  };
+
+  for (int i = tid; i < D; i += NT) sq[i] = a.queries[q * D + i];
+  if (tid <= NW) tau_words[tid] = SENT_D;
+  if (tid < 2) counters[tid] = NW;
+  stage_meta(0);
+  stage_meta(1);
+  SharedTau sh;
+  sh.bound = tau_words;
+  sh.rank = tau_words + 1;
+  sh.nw = NW;
+  sh.wave = wave;
+  sh.jrank = (a.k + NW - 1) / NW;
+  WaveTop st;
+  st.L0.d = st.L1.d = SENT_D;
+  st.L0.id = st.L1.id = SENT_ID;
+  st.tau.d = SENT_D;
+  st.tau.id = SENT_ID;
+  st.qcount = 0;
+  LDS uint32_t *qd = queue_d + wave * 64;
+  LDS int64_t *qid = queue_id + wave * 64;
+
+  // this wavefront's codebook rows, resident for the whole kernel
+  float4 cbv[ITER][DSUB];
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const Key e = h ? st.L1 : st.L0;  // by value: a reference would pin the state in scratch
-        const int i = h * 64 + lane;
-        if (i < a.k) {
-          const bool real = e.d != SENT_D;
-          a.out_ids[q * a.k + i] = real ? e.id : -1;
-          a.out_dist[q * a.k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
-        }
+  for (int it = 0; it < ITER; ++it) {
+    const int m = wave + it * NW;
+    const int mc = m < MT ? m : MT - 1;
+    const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
+#pragma unroll
+    for (int x = 0; x < DSUB; ++x) cbv[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+  }
+  auto build_table = [&](LDS float *lut, LDS float *res) __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int m = wave + it * NW;
+      if (m < MT) {
+        const float4 v = lut_entry4<DSUB>(res + m * DSUB, cbv[it], r2.v[m]);
+        *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
       }
     }
+  };
+
+  const int64_t *const ids_p = a.ids;
+  const int kk = a.k;
+  CodeRegs<MPT / 4> ra, rb;
+  __syncthreads();  // query, metadata and counters are in LDS
+  LDS float *sres1 = sres + (sq_pad >> 2);
+  if (tid < D) {
+    sres[tid] = sq[tid] - a.centroids[(int64_t)meta_c[0] * D + tid];
+    if (p_begin + 1 < p_end) sres1[tid] = sq[tid] - a.centroids[(int64_t)meta_c[1] * D + tid];
   }
+  __syncthreads();
+  if (p_begin < p_end) {
+    build_table(lut0, sres);
+    const int nb0 = (__builtin_amdgcn_readfirstlane(meta_len[0]) + 63) >> 6;
+    const int b0 = wave < nb0 ? wave : (nb0 > 0 ? nb0 - 1 : 0);
+    load_codes<MPT>(a.codes + (meta_blk[0] * 64 + (int64_t)b0 * 64) * MPT, lane, ra);
+  }
+  __syncthreads();
+
+  for (int p = p_begin; p < p_end; ++p) {
+    const int rel = p - p_begin;
+    const int cur = rel & 1, nxt = cur ^ 1;
+    const int mo = ((rel / META) & 1) * META + (rel & (META - 1));
+    const bool has_next = p + 1 < p_end;
+    const int rel1 = rel + 1;
+    const int mo1 = ((rel1 / META) & 1) * META + (rel1 & (META - 1));
+    // stage the chunk after the next one as soon as a chunk starts: its set was last
+    // read two chunks ago, and it is first read META - 1 barriers from now
+    if ((rel & (META - 1)) == 0 && rel > 0) stage_meta(rel / META + 1);
+    if (tid == 0) counters[nxt] = NW;  // not in use: its list was finished before the last barrier
+
+    const int64_t row0 = meta_row0[mo];
+    const int len = __builtin_amdgcn_readfirstlane(meta_len[mo]);
+    const int nb = (len + 63) >> 6;
+    const uint8_t *base = a.codes + meta_blk[mo] * 64 * MPT;
+    LDS float *lut = lut0 + cur * (MT * 256);
+    LDS float *lut_next = lut0 + nxt * (MT * 256);
+    const bool build_first = (wave & 1) == 0;
+    LDS float *res_next = (rel1 & 1) ? sres1 : sres;
+    // centroid of the list after the next one: requested now, its residual is written at
+    // the end of this iteration into the buffer that the current list's residual used
+    const bool has_next2 = p + 2 < p_end;
+    const int rel2 = rel + 2;
+    const int mo2 = ((rel2 / META) & 1) * META + (rel2 & (META - 1));
+    float cen2 = 0.0f;
+    if (has_next2 && tid < D) cen2 = a.centroids[(int64_t)meta_c[mo2] * D + tid];
+
+    if (has_next && build_first) build_table(lut_next, res_next);
+
+    if (wave < nb) {
+      auto consume = [&, ids_p, kk](const CodeRegs<MPT / 4> &r, int b) __attribute__((always_inline)) {
+        const int i = b * 64 + lane;
+        const bool valid = i < len;
+        const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
+        const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
+        float dist;
+        if (!adc_sum_exit<MT>(lut, r, pref, valid, dist)) return;
+        wave_offer(st, dist, valid, row0 + i, ids_p, qd, qid, lane, kk, sh);
+      };
+      auto claim = [&]() __attribute__((always_inline)) {
+        int v = 0;
+        if (lane == 0) v = __hip_atomic_fetch_add(counters + cur, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return __builtin_amdgcn_readfirstlane(v);
+      };
+      const int last = nb - 1;
+      int b = wave;       // the first block was assigned statically and is already in ra
+      int bn = claim();   // further blocks come from the list's counter
+      for (;;) {
+        load_codes<MPT>(base + (int64_t)(bn < last ? bn : last) * 64 * MPT, lane, rb);
+        consume(ra, b);
+        if (bn >= nb) break;
+        b = bn;
+        bn = claim();
+        load_codes<MPT>(base + (int64_t)(bn < last ? bn : last) * 64 * MPT, lane, ra);
+        consume(rb, b);
+        if (bn >= nb) break;
+        b = bn;
+        bn = claim();
+      }
+    }
+
+    if (has_next && !build_first) build_table(lut_next, res_next);
+    if (has_next2 && tid < D) ((rel2 & 1) ? sres1 : sres)[tid] = sq[tid] - cen2;
+    if (has_next) {
+      const int nb1 = (__builtin_amdgcn_readfirstlane(meta_len[mo1]) + 63) >> 6;
+      const int b1 = wave < nb1 ? wave : (nb1 > 0 ? nb1 - 1 : 0);
+      load_codes<MPT>(a.codes + (meta_blk[mo1] * 64 + (int64_t)b1 * 64) * MPT, lane, ra);
+    }
+    __syncthreads();  // list p scanned by everyone, table p+1 complete
+  }
+  finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
 // Merge the probe groups' partial lists of a query (one wavefront per query).
@@ -677,13 +929,14 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
 
 int g_scan_waves = 0;  // 0 = choose from the shape
 int g_scan_ablate = 0;
+int g_scan_variant = 0;  // 0 = choose from the shape, 1 = two-barrier kernel, 2 = double-table kernel
 int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
 
 template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
-  const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + 4 * (NW + 1) + 12 + (size_t)g_scan_lds_pad;
+  const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
+                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 24 + (size_t)g_scan_lds_pad;
   if (lds > 160 * 1024) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
@@ -697,7 +950,28 @@ int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump,
 }
 
 template <int MT, int DSUB>
+int launch_scan_v2(const ScanArgs &a, const RadiiSq &r2, int64_t grid, hipStream_t s) {
+  constexpr int NW = 16;
+  const int two = 2 * MT * 1024, stage = NW * KP * 12;
+  const size_t lds = (size_t)(two > stage ? two : stage) + 3 * ((a.D * 4 + 15) & ~15) + (size_t)NW * 64 * 12 +
+                     ((4 * (NW + 1) + 15) & ~15) + 2 * 64 * 24 + 16;
+  if (lds > 160 * 1024) return 1;  // does not fit: caller falls back to the two-barrier kernel
+  auto kern = scan_kernel_v2<MT, DSUB>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) (void)hipGetLastError();
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
+  return IVFPQ_OK;
+}
+
+template <int MT, int DSUB>
 int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
+  if constexpr (MT > 0 && MT <= 72 && (DSUB == 2 || DSUB == 4)) {
+    if (!dump && g_scan_variant == 2) {
+      const int rc = launch_scan_v2<MT, DSUB>(a, r2, grid, s);
+      if (rc <= 0) return rc;
+    }
+  }
   int nw = g_scan_waves;
   if (nw == 0) nw = a.M > 72 ? 16 : 8;
   if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
@@ -712,6 +986,7 @@ namespace ivfpq {
 void set_scan_waves(int nw) { g_scan_waves = nw; }
 void set_scan_ablate(int bits) { g_scan_ablate = bits; }
 void set_scan_lds_pad(int bytes) { g_scan_lds_pad = bytes; }
+void set_scan_variant(int v) { g_scan_variant = v; }
 
 int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
