@@ -116,6 +116,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    binding.coarse_fallbacks(reset=True)
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     start = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -152,7 +153,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} D={w.D} nlist={w.nlist} M={w.M} Q={Q} nprobe={nprobe} k={k}",
                    "family": w.family, "keep_fraction": args.keep, "recall_at_k": recall, "r1_at_k": r1,
-                   "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms},
+                   "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms,
+                   "coarse_exact_fallbacks_per_step": binding.coarse_fallbacks() / max(1, args.steps + 1)},
         "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.keep)),

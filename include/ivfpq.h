@@ -140,6 +140,13 @@ typedef struct {
 } ivfpq_index_info;
 int ivfpq_index_get_info(const ivfpq_index *index, ivfpq_index_info *info);
 
+/* Diagnostic: number of queries, on the current device since the last reset, whose
+ * probe lists were not accepted from the matrix-product proposal and were instead
+ * computed from reference-order distances to every centroid (the result is the
+ * same either way; the count says how often the slower path ran).  Synchronises
+ * the device.  Negative: an ivfpq_status. */
+int64_t ivfpq_coarse_fallbacks(int reset);
+
 /* Tuning knob for measurements, process-wide, not thread-safe against running
  * searches.  "scan_waves": wavefronts per workgroup of the fused scan kernel,
  * 0 (default: chosen from the shape), 4, 8 or 16.  Results do not depend on it.

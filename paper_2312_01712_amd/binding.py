@@ -22,7 +22,7 @@ _lib = None
 SYMBOLS = [
     "ivfpq_index_create", "ivfpq_index_destroy", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_coarse", "ivfpq_build_lut", "ivfpq_scan_topk", "ivfpq_scan_all", "ivfpq_index_get_info",
-    "ivfpq_set_option", "ivfpq_last_error",
+    "ivfpq_set_option", "ivfpq_coarse_fallbacks", "ivfpq_last_error",
 ]
 
 OK, ERR_INVALID_ARGUMENT, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5
@@ -69,6 +69,8 @@ def load_library():
     lib.ivfpq_scan_all.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.ivfpq_index_get_info.argtypes = [vp, ctypes.POINTER(_Info)]
     lib.ivfpq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
+    lib.ivfpq_coarse_fallbacks.argtypes = [ctypes.c_int]
+    lib.ivfpq_coarse_fallbacks.restype = ctypes.c_int64
     lib.ivfpq_last_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
@@ -85,6 +87,13 @@ def last_error() -> str:
 
 def set_option(name: str, value: int):
     _check(load_library().ivfpq_set_option(name.encode(), int(value)))
+
+
+def coarse_fallbacks(reset: bool = False) -> int:
+    n = int(load_library().ivfpq_coarse_fallbacks(1 if reset else 0))
+    if n < 0:
+        _check(n)
+    return n
 
 
 def _stream() -> int:

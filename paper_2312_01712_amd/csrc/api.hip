@@ -136,6 +136,12 @@ int ivfpq_set_option(const char *name, int value) {
   return IVFPQ_ERR_INVALID_ARGUMENT;
 }
 
+int64_t ivfpq_coarse_fallbacks(int reset) {
+  unsigned int n = 0;
+  const int rc = coarse_fallbacks(reset, &n);
+  return rc == IVFPQ_OK ? (int64_t)n : (int64_t)rc;
+}
+
 void ivfpq_index_destroy(ivfpq_index *ix) {
   if (!ix) return;
   (void)hipFree(ix->d_centroids);

@@ -120,7 +120,21 @@ __device__ inline float unorderable(uint32_t k) {
 // Reference-order distance (see header).
 __device__ inline float exact_dist(const float *sq, const float *__restrict__ cen, int D) {
   float acc = 0.0f;
-  for (int i = 0; i < D; ++i) {
+  int i = 0;
+  if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(cen) & 15) == 0) {
+    for (; i < D; i += 4) {  // same order of operations, 16-byte loads
+      const float4 c4 = *reinterpret_cast<const float4 *>(cen + i);
+      float t = sq[i] - c4.x;
+      acc = fmaf(t, t, acc);
+      t = sq[i + 1] - c4.y;
+      acc = fmaf(t, t, acc);
+      t = sq[i + 2] - c4.z;
+      acc = fmaf(t, t, acc);
+      t = sq[i + 3] - c4.w;
+      acc = fmaf(t, t, acc);
+    }
+  }
+  for (; i < D; ++i) {
     const float t = sq[i] - cen[i];
     acc = fmaf(t, t, acc);
   }
@@ -144,18 +158,32 @@ __device__ inline uint32_t scan256(uint32_t v, uint32_t *tmp, int tid) {
   return r;
 }
 
-// One workgroup per query: pick the kprop smallest (value, list) pairs of the
-// proposal row by radix select on 64-bit keys, recompute their distances in the
-// reference order, sort by (distance, list id), emit the first nprobe.
+// queries that needed the exact fallback since the counter was last reset (diagnostic)
+__device__ unsigned int g_coarse_fallbacks = 0;
+
+constexpr int NBINS = 2048;                       // histogram bins per refinement level
+constexpr int BINS_PER_THREAD = NBINS / SEL_THREADS;
+
+__device__ inline unsigned long long row_key(const float *row, int c) {
+  return ((unsigned long long)orderable(row[c]) << 32) | (uint32_t)c;
+}
+
+// One workgroup per query.  Keys are (proposal value, list id) packed in 64 bits, so
+// they are distinct.  A histogram over equal-width key intervals finds a cut that
+// holds at least kprop and at most MAX_PROPOSE keys below it (refining the interval
+// of the kprop-th key when a level is too coarse; at width 1 a bin holds one key, so
+// the loop ends).  The selected lists get their distances in the reference order,
+// are sorted by (distance, list id), and the first nprobe are emitted.
 __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
     float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int nlist,
-    int D, int ldo, int nprobe, int kprop, int psort, float err_scale, float max_cnorm,
+    int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm,
     int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
   extern __shared__ float sq[];  // [D]
-  __shared__ uint32_t hist[256];
+  __shared__ uint32_t hist[NBINS];
   __shared__ uint32_t tmp[2 * SEL_THREADS];
   __shared__ unsigned long long keys[MAX_PROPOSE];
-  __shared__ uint32_t sel[2];
+  __shared__ unsigned long long red_lo[SEL_THREADS / 64], red_hi[SEL_THREADS / 64];
+  __shared__ uint32_t sel[3];
   __shared__ uint32_t count;
   __shared__ float red[SEL_THREADS / 64];
 
@@ -175,52 +203,108 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
   __syncthreads();
   const float qq = red[0] + red[1] + red[2] + red[3];
 
-  const int idx_bits = 32 - __clz(nlist > 1 ? nlist - 1 : 1);  // bits of a list id
-  const int low_passes = (idx_bits + 7) / 8;
-
   for (int attempt = 0; attempt < 2; ++attempt) {
     if (attempt == 1) {
       // fallback: reference-order distances for every list
+      if (tid == 0) atomicAdd(&g_coarse_fallbacks, 1u);
       for (int c = tid; c < nlist; c += SEL_THREADS) row[c] = exact_dist(sq, cent + (int64_t)c * D, D);
       __syncthreads();
     }
-    // ---- radix select of the kprop-th smallest key (value bits : list id) ----
-    unsigned long long prefix = 0, mask = 0;
-    uint32_t remaining = kprop;
-    for (int pass = 0; pass < 4 + low_passes; ++pass) {
-      const int shift = pass < 4 ? 56 - 8 * pass : 8 * (low_passes - 1 - (pass - 4));
-      hist[tid] = 0;
+    // ---- smallest and largest key of the row ----
+    unsigned long long kmin = ~0ull, kmax = 0ull;
+    for (int c = tid; c < nlist; c += SEL_THREADS) {
+      const unsigned long long k = row_key(row, c);
+      kmin = k < kmin ? k : kmin;
+      kmax = k > kmax ? k : kmax;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+      const unsigned long long a = __shfl_xor(kmin, off), b = __shfl_xor(kmax, off);
+      kmin = a < kmin ? a : kmin;
+      kmax = b > kmax ? b : kmax;
+    }
+    if ((tid & 63) == 0) {
+      red_lo[tid >> 6] = kmin;
+      red_hi[tid >> 6] = kmax;
+    }
+    __syncthreads();
+    for (int w = 0; w < SEL_THREADS / 64; ++w) {
+      kmin = red_lo[w] < kmin ? red_lo[w] : kmin;
+      kmax = red_hi[w] > kmax ? red_hi[w] : kmax;
+    }
+    // ---- histogram levels: window [lo, lo + (NBINS << shift)) ----
+    unsigned long long lo = kmin;
+    int shift = 64 - __clzll((kmax - kmin) | 1ull) - 11;  // (kmax - lo) >> shift < NBINS
+    if (shift < 0) shift = 0;
+    uint32_t need = kprop;   // keys still wanted from the window
+    uint32_t below = 0;      // keys under the window (all selected)
+    unsigned long long cut;  // exclusive upper bound of the selected keys
+    for (;;) {
+      for (int i = tid; i < NBINS; i += SEL_THREADS) hist[i] = 0;
       __syncthreads();
       for (int c = tid; c < nlist; c += SEL_THREADS) {
-        const unsigned long long key = ((unsigned long long)orderable(row[c]) << 32) | (uint32_t)c;
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
-      }
-      __syncthreads();
-      const uint32_t h = hist[tid];
-      const uint32_t incl = scan256(h, tmp, tid);
-      if (incl >= remaining && incl - h < remaining) {
-        sel[0] = tid;
-        sel[1] = incl - h;
-      }
-      __syncthreads();
-      prefix |= (unsigned long long)sel[0] << shift;
-      mask |= 0xFFull << shift;
-      remaining -= sel[1];
-      __syncthreads();
-    }
-    // prefix is now the kprop-th smallest key; keys are distinct
-    if (tid == 0) count = 0;
-    for (int i = tid; i < psort; i += SEL_THREADS) keys[i] = ~0ull;
-    __syncthreads();
-    for (int c = tid; c < nlist; c += SEL_THREADS) {
-      const unsigned long long key = ((unsigned long long)orderable(row[c]) << 32) | (uint32_t)c;
-      if (key <= prefix) {
-        const uint32_t slot = atomicAdd(&count, 1u);
-        if (slot < (uint32_t)kprop) {
-          const float d = attempt == 1 ? row[c] : exact_dist(sq, cent + (int64_t)c * D, D);
-          keys[slot] = ((unsigned long long)__float_as_uint(d) << 32) | (uint32_t)c;
+        const unsigned long long k = row_key(row, c);
+        if (k >= lo) {
+          const unsigned long long bin = (k - lo) >> shift;
+          if (bin < NBINS) atomicAdd(&hist[(uint32_t)bin], 1u);
         }
       }
+      __syncthreads();
+      uint32_t local[BINS_PER_THREAD], sum = 0;
+#pragma unroll
+      for (int i = 0; i < BINS_PER_THREAD; ++i) {
+        local[i] = hist[tid * BINS_PER_THREAD + i];
+        sum += local[i];
+      }
+      const uint32_t incl = scan256(sum, tmp, tid);
+      uint32_t run = incl - sum;
+      if (run < need && incl >= need) {  // the bin of the need-th key is one of this thread's
+#pragma unroll
+        for (int i = 0; i < BINS_PER_THREAD; ++i) {
+          if (run < need && run + local[i] >= need) {
+            sel[0] = tid * BINS_PER_THREAD + i;  // bin
+            sel[1] = run;                        // keys of the window under that bin
+            sel[2] = local[i];                   // keys in that bin
+          }
+          run += local[i];
+        }
+      }
+      __syncthreads();
+      const uint32_t bin = sel[0], under = sel[1], inbin = sel[2];
+      __syncthreads();
+      if (below + under + inbin <= (uint32_t)MAX_PROPOSE || shift == 0) {
+        cut = lo + (((unsigned long long)bin + 1) << shift);
+        if (cut < lo) cut = ~0ull;  // wrapped: the window reaches the top of the key range
+        break;
+      }
+      below += under;
+      need -= under;
+      lo += (unsigned long long)bin << shift;
+      shift = shift > 11 ? shift - 11 : 0;
+    }
+    // ---- collect the selected lists ----
+    if (tid == 0) count = 0;
+    __syncthreads();
+    for (int c = tid; c < nlist; c += SEL_THREADS) {
+      const unsigned long long k = row_key(row, c);
+      if (k < cut || cut == ~0ull) {
+        const uint32_t slot = atomicAdd(&count, 1u);
+        if (slot < (uint32_t)MAX_PROPOSE) keys[slot] = (uint32_t)c;
+      }
+    }
+    __syncthreads();
+    const int nsel = count < (uint32_t)MAX_PROPOSE ? (int)count : MAX_PROPOSE;
+    int psort = 2;
+    while (psort < nsel) psort <<= 1;
+    // reference-order distances, one selected list per thread (dense: the sequential
+    // chain over D runs once per wavefront, not once per selected list)
+    for (int i = tid; i < psort; i += SEL_THREADS) {
+      unsigned long long key = ~0ull;
+      if (i < nsel) {
+        const int c = (int)(uint32_t)keys[i];
+        const float d = attempt == 1 ? row[c] : exact_dist(sq, cent + (int64_t)c * D, D);
+        key = ((unsigned long long)__float_as_uint(d) << 32) | (uint32_t)c;
+      }
+      keys[i] = key;
     }
     __syncthreads();
     // ---- sort the proposals by (reference distance, list id) ----
@@ -238,11 +322,11 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
         }
         __syncthreads();
       }
-    if (attempt == 1 || kprop >= nlist) break;
-    // every list outside the window has a proposal value >= the kprop-th one;
-    // accept if that lower bound clears the nprobe-th reference distance by
-    // more than the rounding-error bound of the matrix product
-    const float t_prop = unorderable((uint32_t)(prefix >> 32)) + qq;
+    if (attempt == 1 || nsel >= nlist) break;
+    // every list that was not selected has a proposal value >= the cut's; accept if
+    // that lower bound clears the nprobe-th reference distance by more than the
+    // rounding-error bound of the matrix product
+    const float t_prop = unorderable((uint32_t)(cut >> 32)) + qq;
     const float tau = __uint_as_float((uint32_t)(keys[nprobe - 1] >> 32));
     const float bound = err_scale * (qq + max_cnorm);
     const bool ok = (t_prop - tau) > bound;  // false for NaN
@@ -266,6 +350,15 @@ int pow2ceil(int v) {
 
 namespace ivfpq {
 
+int coarse_fallbacks(int reset, unsigned int *out) {
+  IVFPQ_HIP_TRY(hipMemcpyFromSymbol(out, HIP_SYMBOL(g_coarse_fallbacks), sizeof(unsigned int)));
+  if (reset) {
+    const unsigned int zero = 0;
+    IVFPQ_HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_coarse_fallbacks), &zero, sizeof zero));
+  }
+  return IVFPQ_OK;
+}
+
 int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                   int32_t *d_probe_ids, float *d_probe_dist, float *d_scratch, int64_t q_chunk,
                   int32_t nlist_pad, hipStream_t s) {
@@ -278,7 +371,6 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
     set_error("coarse: nprobe %d too large", nprobe);
     return IVFPQ_ERR_UNSUPPORTED;
   }
-  const int psort = pow2ceil(kprop < 2 ? 2 : kprop);
   const float err_scale = 4.0f * (float)D * 1.1920929e-07f;
   const int vec = (D % 4 == 0) && (((uintptr_t)d_queries | (uintptr_t)ix->d_centroids) % 16 == 0);
   for (int64_t q0 = 0; q0 < Q; q0 += q_chunk) {
@@ -288,7 +380,7 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
     hipLaunchKernelGGL(coarse_gemm_kernel, grid, dim3(256), 0, s, qm, ix->d_centroids, ix->d_cnorm,
                        d_scratch, qn, nlist, D, nlist_pad, vec);
     hipLaunchKernelGGL(coarse_select_kernel, dim3(qn), dim3(SEL_THREADS), (size_t)D * sizeof(float), s,
-                       d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe, kprop, psort,
+                       d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe, kprop,
                        err_scale, ix->max_cnorm, d_probe_ids + q0 * nprobe,
                        d_probe_dist ? d_probe_dist + q0 * nprobe : nullptr);
   }

@@ -79,6 +79,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 int32_t *d_errors, hipStream_t s);
 int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);
+int coarse_fallbacks(int reset, unsigned int *out);
 int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);
 void set_scan_ablate(int bits);  // measurement only: skip parts of the scan kernel (results invalid)
 void set_scan_lds_pad(int bytes); // measurement only: extra LDS per scan workgroup

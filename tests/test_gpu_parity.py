@@ -189,6 +189,36 @@ def test_identity_codebook_exact_knn(lib):
     assert np.array_equal(dist.cpu().numpy().astype(np.int64), ref_dist)
 
 
+def test_coarse_degenerate_centroids(lib):
+    """Thousands of identical or nearly identical centroids: the proposal's slack window
+    cannot separate them, so the exact fallback and the (distance, list id) tie order
+    decide; and duplicated centroids among ordinary ones."""
+    rng = np.random.default_rng(21)
+    b = _binding()
+    D, M = 16, 4
+    for name, cent in [
+        ("all equal", np.tile(rng.normal(size=(1, D)).astype(np.float32), (5000, 1))),
+        ("two values", np.repeat(rng.normal(size=(2, D)).astype(np.float32), 2500, axis=0)),
+        ("tiny jitter", (rng.normal(size=(1, D)) + 1e-7 * rng.normal(size=(3000, D))).astype(np.float32)),
+        ("duplicates", np.concatenate([rng.normal(size=(300, D)), rng.normal(size=(300, D))[rng.integers(0, 300, 700)]]).astype(np.float32)),
+    ]:
+        nlist = cent.shape[0]
+        sizes = np.full(nlist, 2, dtype=np.int64)
+        idx = _random_index(rng, 0, D, nlist, M, sizes)
+        idx.centroids = np.ascontiguousarray(cent)
+        q = rng.normal(size=(20, D)).astype(np.float32)
+        gi = b.IvfPqIndex.from_index(idx)
+        for nprobe in (1, 10, 200, 1000):
+            nprobe = min(nprobe, nlist)
+            o_pid, o_pd = oracle.coarse(q, idx.centroids, nprobe)
+            pid, pd = gi.coarse(_cuda(q), nprobe)
+            torch.cuda.synchronize()
+            assert np.array_equal(pid.cpu().numpy(), o_pid), (name, nprobe)
+            assert_same_float(pd.cpu().numpy(), o_pd, f"{name} nprobe={nprobe}")
+        gi.close()
+        say(f"  coarse, {name}: ok")
+
+
 def test_batch_sizes_and_probe_groups(lib):
     """Q = 1, 2, 100, 3000: small batches split the probes of a query over several
     workgroups and merge; results must not depend on that."""
