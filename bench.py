@@ -47,7 +47,7 @@ def main():
     ap.add_argument("--workload", default="C2", help="C1..C5, C5_10M (default C2: 1M x 128, nprobe 32)")
     ap.add_argument("--keep", type=float, default=0.25, help="fraction of codebook entries inside the radius")
     ap.add_argument("--scan-waves", type=int, default=0)
-    ap.add_argument("--scan-variant", type=int, default=0, help="0 auto, 1 two-barrier kernel, 2 double-table kernel")
+    ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 adaptive, 1 whole blocks, 2 first half + rest on demand")
     ap.add_argument("--lds-pad", type=int, default=0, help="measurement only: extra LDS bytes per scan workgroup")
     ap.add_argument("--ablate", type=int, default=0, help="measurement only: scan_ablate bit mask (results invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -70,8 +70,8 @@ def main():
     binding.load_library()
     if args.scan_waves:
         binding.set_option("scan_waves", args.scan_waves)
-    if args.scan_variant:
-        binding.set_option("scan_variant", args.scan_variant)
+    if args.scan_loads:
+        binding.set_option("scan_loads", args.scan_loads)
     if args.lds_pad:
         binding.set_option("scan_lds_pad", args.lds_pad)
     if args.ablate:

@@ -122,8 +122,8 @@ int ivfpq_set_option(const char *name, int value) {
     set_scan_ablate(value & 31);
     return IVFPQ_OK;
   }
-  if (name && !strcmp(name, "scan_variant")) {
-    if (value < 0 || value > 2) { set_error("set_option: scan_variant must be 0, 1 or 2"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (name && !strcmp(name, "scan_loads")) {
+    if (value < 0 || value > 2) { set_error("set_option: scan_loads must be 0, 1 or 2"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_scan_variant(value);
     return IVFPQ_OK;
   }
@@ -229,10 +229,10 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
     TRY_OR_FAIL(hipMalloc(&ix->d_codebooks, kb));
     TRY_OR_FAIL(hipMalloc(&ix->d_list_offsets, offs.size() * 8));
     TRY_OR_FAIL(hipMalloc(&ix->d_list_blocks, blocks.size() * 8));
-    // one block of padding behind the last list: the scan may read (and ignore) the
-    // first block of an empty list
-    TRY_OR_FAIL(hipMalloc(&ix->d_codes, (size_t)ix->code_bytes + (size_t)ivfpq_block_bytes(ix->Mp)));
-    TRY_OR_FAIL(hipMemset(ix->d_codes + ix->code_bytes, 0, (size_t)ivfpq_block_bytes(ix->Mp)));
+    // padding behind the last list: for an empty list the scan reads (and ignores) one
+    // 1 KiB chunk at the list's base
+    TRY_OR_FAIL(hipMalloc(&ix->d_codes, (size_t)ix->code_bytes + 4096));
+    TRY_OR_FAIL(hipMemset(ix->d_codes + ix->code_bytes, 0, 4096));
     TRY_OR_FAIL(hipMalloc(&ix->d_ids, d->N > 0 ? (size_t)d->N * 8 : 256));
     TRY_OR_FAIL(hipMemcpy(ix->d_centroids, d->centroids, cb, hipMemcpyDefault));
     TRY_OR_FAIL(hipMemcpy(ix->d_codebooks, d->codebooks, kb, hipMemcpyDefault));

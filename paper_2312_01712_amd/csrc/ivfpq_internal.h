@@ -27,11 +27,14 @@ struct ivfpq_index {
 };
 
 // Device layout of the codes.  Every inverted list is padded to a multiple of 64
-// points; a block of 64 points occupies 64*Mp bytes and is stored chunk-major:
-// first Mp/16 chunks of 16 bytes per point ([chunk][lane][16 B]), then
-// (Mp%16)/4 chunks of 4 bytes per point ([chunk][lane][4 B]).  A wavefront that
-// assigns lane l to point l of the block therefore reads 1 KiB (or 256 B)
-// contiguous per load instruction.  Padding bytes and padding points are 0.
+// points (nb blocks) and occupies nb*64*Mp bytes, stored chunk-major: a point's Mp
+// code bytes are cut into Mp/16 chunks of 16 bytes followed by (Mp%16)/4 chunks of
+// 4 bytes; chunk j of the whole list comes first for j = 0, then j = 1, ...:
+// [chunk][block][lane][16 B], then [chunk][block][lane][4 B].  A wavefront that
+// assigns lane l to point l of a block reads 1 KiB (or 256 B) contiguous per load
+// instruction, consecutive blocks of one chunk are contiguous, and the later
+// chunks of blocks that are abandoned early are never touched.  Padding bytes and
+// padding points are 0; 4 KiB of zero padding follow the last list.
 __host__ __device__ inline int64_t ivfpq_block_bytes(int Mp) { return (int64_t)64 * Mp; }
 
 // r_m^2 for every subspace, passed to kernels by value (kernel-argument
@@ -83,7 +86,7 @@ int coarse_fallbacks(int reset, unsigned int *out);
 int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);
 void set_scan_ablate(int bits);  // measurement only: skip parts of the scan kernel (results invalid)
 void set_scan_lds_pad(int bytes); // measurement only: extra LDS per scan workgroup
-void set_scan_variant(int v);     // 0 auto, 1 two-barrier scan kernel, 2 double-table scan kernel
+void set_scan_variant(int v);     // code loads: 0 adaptive, 1 whole blocks, 2 first half + rest on demand
 void set_scan_waves(int nw);  // wavefronts per scan workgroup: 0 (auto), 4, 8 or 16
 
 }  // namespace ivfpq

@@ -181,6 +181,7 @@ struct ScanArgs {
   int64_t *all_ids;             // (DUMP)
   int32_t *errors;              // (DUMP)
   int32_t D, M, dsub, Mp, nlist, nprobe, k, nsplit;
+  int32_t load_mode;  // 0 adaptive, 1 whole blocks, 2 first half of the chunks, rest on demand
   int32_t ablate;  // measurement only: 1 skips the table arithmetic, 2 the list scan, 4 the top-k offers,
                    // 8 disables the early exit of the distance sums (results stay valid)
 };
@@ -191,20 +192,44 @@ struct CodeRegs {
   uint32_t w[NDW > 0 ? NDW : 1];
 };
 
-template <int MP>
-__device__ inline void load_codes(const uint8_t *__restrict__ blk, int lane, CodeRegs<MP / 4> &r) {
-  constexpr int N16 = MP / 16, N4 = (MP % 16) / 4;
+// A pointer that is the same in every lane, moved to scalar registers so that loads
+// through it use the scalar-base + 32-bit lane-offset addressing form.
+__device__ inline const uint8_t *uniform_ptr(const uint8_t *p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const uint8_t *>(((uint64_t)hi << 32) | lo);
+}
+
+// Chunks [J0, J1) of block b of a list with nb blocks (J counts the 16-byte chunks
+// first, then the 4-byte chunks).  Within a list the layout is chunk-major: chunk j of
+// all blocks is contiguous, so a wavefront that stops needing the later chunks of its
+// blocks leaves whole streams of the list unread.
+template <int MP, int J0, int J1>
+__device__ inline void load_chunks(const uint8_t *__restrict__ list_base, int nb, int b, int lane,
+                                   CodeRegs<MP / 4> &r) {
+  constexpr int N16 = MP / 16;
 #pragma unroll
-  for (int j = 0; j < N16; ++j) {
-    const uint4 v = *reinterpret_cast<const uint4 *>(blk + j * 1024 + lane * 16);
-    r.w[4 * j + 0] = v.x;
-    r.w[4 * j + 1] = v.y;
-    r.w[4 * j + 2] = v.z;
-    r.w[4 * j + 3] = v.w;
+  for (int j = J0; j < J1; ++j) {
+    if (j < N16) {
+      const uint8_t *sp = uniform_ptr(list_base + ((int64_t)j * nb + b) * 1024);
+      const uint4 v = *reinterpret_cast<const uint4 *>(sp + (uint32_t)(lane * 16));
+      r.w[4 * j + 0] = v.x;
+      r.w[4 * j + 1] = v.y;
+      r.w[4 * j + 2] = v.z;
+      r.w[4 * j + 3] = v.w;
+    } else {
+      const int t = j - N16;
+      const uint8_t *sp = uniform_ptr(list_base + (int64_t)N16 * nb * 1024 + ((int64_t)t * nb + b) * 256);
+      r.w[4 * N16 + t] = *reinterpret_cast<const uint32_t *>(sp + (uint32_t)(lane * 4));
+    }
   }
-#pragma unroll
-  for (int t = 0; t < N4; ++t)
-    r.w[4 * N16 + t] = *reinterpret_cast<const uint32_t *>(blk + N16 * 1024 + t * 256 + lane * 4);
+}
+
+template <int MP>
+__device__ inline void load_codes(const uint8_t *__restrict__ list_base, int nb, int b, int lane,
+                                  CodeRegs<MP / 4> &r) {
+  load_chunks<MP, 0, MP / 16 + (MP % 16) / 4>(list_base, nb, b, lane, r);
 }
 
 template <int MT>
@@ -218,44 +243,43 @@ __device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) /
   return dist;
 }
 
-// Same sum with early exit.  Table values are >= 0 and fp32 addition of a
+// Same sum, over subspaces [M0, M1), with early exit.  Table values are >= 0 and fp32 addition of a
 // non-negative term never decreases a sum, so a partial sum above the bound
 // means the final distance is above it too.  Every 8 subspaces the wavefront
 // checks whether any of its points can still reach the bound `pref` (an upper
 // bound on the k-th smallest distance); if none can, the rest of the block is
 // skipped.  Returns false in that case.  Points that survive get exactly the
 // sum adc_sum computes.
-template <int MT>
-__device__ inline bool adc_sum_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
-                                    uint32_t pref, bool valid, float &out) {
-  float dist = 0.0f;
+template <int MT, int M0, int M1>
+__device__ inline bool adc_part_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
+                                     uint32_t pref, bool valid, float &dist) {
 #pragma unroll
-  for (int g = 0; g < MT; g += 8) {
+  for (int g = M0; g < M1; g += 8) {
 #pragma unroll
-    for (int m = g; m < (g + 8 < MT ? g + 8 : MT); ++m) {
+    for (int m = g; m < (g + 8 < M1 ? g + 8 : M1); ++m) {
       const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
       dist += lut[m * 256 + code];
     }
-    if (g + 8 < MT) {
+    if ((g + 8 < M1 ? g + 8 : M1) < MT) {
       if (__ballot(valid && __float_as_uint(dist) <= pref) == 0) return false;
     }
   }
-  out = dist;
   return true;
 }
 
 // runtime-M variant: dwords are fetched as they are needed
-__device__ inline float adc_sum_rt(const LDS float *lut, const uint8_t *__restrict__ blk, int lane, int M,
-                                   int Mp) {
+__device__ inline float adc_sum_rt(const LDS float *lut, const uint8_t *__restrict__ list_base, int nb, int b,
+                                   int lane, int M, int Mp) {
   const int n16 = Mp >> 4;
   float dist = 0.0f;
   for (int d = 0; d < (Mp >> 2); ++d) {
-    const uint8_t *p = d < 4 * n16 ? blk + (d >> 2) * 1024 + lane * 16 + (d & 3) * 4
-                                   : blk + n16 * 1024 + (d - 4 * n16) * 256 + lane * 4;
+    const uint8_t *p = d < 4 * n16
+                           ? list_base + ((int64_t)(d >> 2) * nb + b) * 1024 + lane * 16 + (d & 3) * 4
+                           : list_base + (int64_t)n16 * nb * 1024 + ((int64_t)(d - 4 * n16) * nb + b) * 256 + lane * 4;
     const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
-    for (int b = 0; b < 4; ++b) {
-      const int m = 4 * d + b;
-      if (m < M) dist += lut[m * 256 + ((w >> (8 * b)) & 0xFFu)];
+    for (int bb = 0; bb < 4; ++bb) {
+      const int m = 4 * d + bb;
+      if (m < M) dist += lut[m * 256 + ((w >> (8 * bb)) & 0xFFu)];
     }
   }
   return dist;
@@ -482,6 +506,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
       for (int x = 0; x < DSUB; ++x) cbr[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
     }
   }
+  // Code chunks per point (16-byte chunks, then 4-byte chunks) and how many of them
+  // the "first half" loading mode fetches ahead; that mode exists when it splits the
+  // chunks in two non-empty parts.
+  constexpr int NCH = MPT / 16 + (MPT % 16) / 4;
+  constexpr int HCH = (MPT / 16 + 1) / 2;
+  constexpr int MH = 16 * HCH;  // subspaces covered by the first HCH chunks
+  constexpr bool HALF_OK = MT > 0 && HCH >= 1 && HCH < NCH && MH < MT;
+  bool use_half = HALF_OK && !DUMP && a.load_mode == 2;  // the nearest list is loaded whole
   bool sres_ready = false;
   for (int p = p_begin; p < p_end; ++p) {
     const int pm = (p - p_begin) & (META - 1);
@@ -509,7 +541,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     // latency overlaps the tail of the previous list: the streamed part of this
     // wavefront's codebook rows and the first code block of the new list.
     float4 cbs[STR > 0 ? STR : 1][DS4];
-    CodeRegs<MPT / 4> ra, rb;
+    CodeRegs<MPT / 4> nxt;
     // The residual q - centroid of a list is formed once, in LDS.  For the list after
     // this one the centroid is requested now and the residual written after this
     // list's table is finished, so the next table does not wait for it.
@@ -530,9 +562,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
       }
     }
     if constexpr (MT > 0) {
-      // an empty list still has one readable (padding) block behind its base
+      // an empty list still has readable padding behind its base
       const int b0 = wave < nb ? wave : (nb > 0 ? nb - 1 : 0);
-      load_codes<MPT>(base + (int64_t)b0 * 64 * MPT, lane, ra);
+      if (use_half) load_chunks<MPT, 0, HCH>(base, nb, b0, lane, nxt);
+      else load_codes<MPT>(base, nb, b0, lane, nxt);
     }
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
     // ---- selective table for (query, list c) ----
@@ -564,54 +597,48 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     }
     // ---- distance calculation over list c ----
     if (MT > 0) {
-      // two register sets alternate: the next block's loads are in flight while
-      // the current block is looked up
-      // (the lambda must not capture the kernel-argument struct by reference: that
-      // would force a copy of it into scratch memory)
-      const int64_t *const ids_p = a.ids;
-      float *const all_dist_p = a.all_dist;
-      int64_t *const all_ids_p = a.all_ids;
-      const int kk = a.k, ablate = a.ablate;
-      auto consume = [&, ids_p, all_dist_p, all_ids_p, kk, ablate](const CodeRegs<MPT / 4> &r, int b)
-                         __attribute__((always_inline)) {
-        const int i = b * 64 + lane;
-        const bool valid = i < len;
-        if (DUMP) {
-          const float dist = adc_sum<MT>(lut, r);
-          if (valid) {
-            all_dist_p[dump_pos + i] = dist;
-            all_ids_p[dump_pos + i] = ids_p[row0 + i];
-          }
-        } else {
-          const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
-          const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
-          float dist;
-          if (!adc_sum_exit<MT>(lut, r, (ablate & 8) ? SENT_D : pref, valid, dist)) return;
-          if (!(ablate & 4)) wave_offer(st, dist, valid, row0 + i, ids_p, qd, qid, lane, kk, sh);
-          if (ablate & 4) st.L0.d = st.L0.d < __float_as_uint(dist) ? st.L0.d : __float_as_uint(dist);
-        }
-      };
-      // loads are issued unconditionally (past the end they re-read the list's last
-      // block, which is in bounds) so that the number of loads in flight is known at
-      // every wait and the next block's load never has to complete first
+      // Two register sets: `nxt` receives the loads of the next block while `cur` is
+      // looked up.  Loads are issued for every iteration (past the end they re-read the
+      // list's last block, which is in bounds), so the block in flight never has to
+      // complete before the current one can be used.
       if (wave < nb && !(a.ablate & 2)) {
         const int last = nb - 1;
-        int b = wave;
-        for (;;) {
-          const int b1 = b + NW;
-          load_codes<MPT>(base + (int64_t)(b1 < last ? b1 : last) * 64 * MPT, lane, rb);
-          consume(ra, b);
-          if (b1 >= nb) break;
-          const int b2 = b1 + NW;
-          load_codes<MPT>(base + (int64_t)(b2 < last ? b2 : last) * 64 * MPT, lane, ra);
-          consume(rb, b1);
-          if (b2 >= nb) break;
-          b = b2;
+        int late = 0, blocks = 0;
+        for (int b = wave; b < nb; b += NW) {
+          CodeRegs<MPT / 4> cur = nxt;
+          const int bn = b + NW < last ? b + NW : last;
+          if (use_half) load_chunks<MPT, 0, HCH>(base, nb, bn, lane, nxt);
+          else load_codes<MPT>(base, nb, bn, lane, nxt);
+          const int i = b * 64 + lane;
+          const bool valid = i < len;
+          if (DUMP) {
+            const float dist = adc_sum<MT>(lut, cur);
+            if (valid) {
+              a.all_dist[dump_pos + i] = dist;
+              a.all_ids[dump_pos + i] = a.ids[row0 + i];
+            }
+          } else {
+            const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
+            const uint32_t pref = (a.ablate & 8) ? SENT_D : (shared < st.tau.d ? shared : st.tau.d);
+            float dist = 0.0f;
+            ++blocks;
+            // first half of the chunks; most blocks end here
+            if (HALF_OK && !adc_part_exit<MT, 0, MH>(lut, cur, pref, valid, dist)) continue;
+            ++late;
+            // the rest of the block: already in registers, or fetched now (rare)
+            if (HALF_OK && use_half) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
+            if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, pref, valid, dist)) continue;
+            if (!(a.ablate & 4)) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
+            if (a.ablate & 4) st.L0.d = st.L0.d < __float_as_uint(dist) ? st.L0.d : __float_as_uint(dist);
+          }
         }
+        // how the next list is loaded: whole blocks if more than a quarter of this
+        // list's blocks needed all their chunks, else the first half only
+        if (HALF_OK && !DUMP && a.load_mode == 0) use_half = 4 * late <= blocks;
       }
     } else {
       for (int b = wave; b < nb; b += NW) {
-        const float dist = adc_sum_rt(lut, base + (int64_t)b * 64 * Mp, lane, M, Mp);
+        const float dist = adc_sum_rt(lut, base, nb, b, lane, M, Mp);
         const int i = b * 64 + lane;
         const bool valid = i < len;
         if (DUMP && valid) {
@@ -625,202 +652,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   }
   if (DUMP) return;
 
-  finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
-}
-
-// Second organisation of the same work for shapes whose table fits LDS twice
-// (2 * M KiB + queues <= 160 KiB): one workgroup of 16 wavefronts per CU and two
-// table buffers.  While list p is scanned with table p, table p+1 is built into
-// the other buffer, half of the wavefronts building first and scanning second, the
-// other half the other way round, so vector-ALU work (tables) and LDS gathers (scan)
-// overlap instead of alternating; one barrier per probed list instead of two.
-// Each wavefront keeps its rows of the codebook in registers for the whole kernel
-// (the codebook is the same for every list), which removes the per-list codebook
-// traffic from L2.  Blocks of a list are handed out through an LDS counter, so a
-// wavefront that built first simply scans fewer blocks.  Arithmetic, order of
-// operations and results are those of scan_kernel.
-template <int MT, int DSUB>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4))) void scan_kernel_v2(ScanArgs a,
-                                                                                             RadiiSq r2) {
-  constexpr int NW = 16, NT = NW * 64, META = 64;
-  constexpr int MPT = (MT + 3) / 4 * 4;
-  constexpr int ITER = (MT + NW - 1) / NW;
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int D = a.D;
-  constexpr int lut_bytes = MT * 1024;
-  constexpr int stage_bytes = NW * KP * 12;
-  constexpr int region0 = 2 * lut_bytes > stage_bytes ? 2 * lut_bytes : stage_bytes;
-  LDS unsigned char *smem3 = (LDS unsigned char *)smem;
-  LDS float *lut0 = (LDS float *)smem3;
-  LDS float *sq = (LDS float *)(smem3 + region0);
-  const int sq_pad = (D * 4 + 15) & ~15;
-  const int sq_bytes = 3 * sq_pad;  // the query, then two buffers of list residuals q - centroid
-  LDS float *sres = sq + (sq_pad >> 2);  // residual of probe r lives in buffer r & 1
-  LDS int64_t *queue_id = (LDS int64_t *)(smem3 + region0 + sq_bytes);
-  LDS uint32_t *queue_d = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 8);
-  LDS uint32_t *tau_words = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12);
-  constexpr int tau_bytes = (4 * (NW + 1) + 15) & ~15;
-  // two sets of list metadata (one per chunk of META probes) and two block counters
-  LDS int64_t *meta_row0 = (LDS int64_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12 + tau_bytes);
-  LDS int64_t *meta_blk = meta_row0 + 2 * META;
-  LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + 2 * META);
-  LDS int32_t *meta_c = meta_len + 2 * META;
-  LDS int32_t *counters = meta_c + 2 * META;
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t q = blockIdx.x / a.nsplit;
-  const int split = blockIdx.x % a.nsplit;
-  const int p_begin = (int)((int64_t)a.nprobe * split / a.nsplit);
-  const int p_end = (int)((int64_t)a.nprobe * (split + 1) / a.nsplit);
-  const int32_t *probes = a.probe_ids + q * a.nprobe;
-
-  // metadata of chunk `ch` (probes p_begin + ch*META ...) into set ch & 1; a probe id
-  // outside [0, nlist) becomes an empty list (its table is still built, from list 0)
-  auto stage_meta = [&](int ch) {
-    const int p0 = p_begin + ch * META;
-    if (tid < META && p0 + tid < p_end) {
-      const int32_t cc = probes[p0 + tid];
-      const bool ok = (uint32_t)cc < (uint32_t)a.nlist;
-      const int64_t r0 = ok ? a.list_offsets[cc] : 0;
-      const int o = (ch & 1) * META + tid;
-      meta_c[o] = ok ? cc : 0;
-      meta_row0[o] = r0;
-      meta_len[o] = ok ? (int)(a.list_offsets[cc + 1] - r0) : 0;
-      meta_blk[o] = ok ? a.list_blocks[cc] : 0;
-    }
-  };
-
-  for (int i = tid; i < D; i += NT) sq[i] = a.queries[q * D + i];
-  if (tid <= NW) tau_words[tid] = SENT_D;
-  if (tid < 2) counters[tid] = NW;
-  stage_meta(0);
-  stage_meta(1);
-  SharedTau sh;
-  sh.bound = tau_words;
-  sh.rank = tau_words + 1;
-  sh.nw = NW;
-  sh.wave = wave;
-  sh.jrank = (a.k + NW - 1) / NW;
-  WaveTop st;
-  st.L0.d = st.L1.d = SENT_D;
-  st.L0.id = st.L1.id = SENT_ID;
-  st.tau.d = SENT_D;
-  st.tau.id = SENT_ID;
-  st.qcount = 0;
-  LDS uint32_t *qd = queue_d + wave * 64;
-  LDS int64_t *qid = queue_id + wave * 64;
-
-  // this wavefront's codebook rows, resident for the whole kernel
-  float4 cbv[ITER][DSUB];
-#pragma unroll
-  for (int it = 0; it < ITER; ++it) {
-    const int m = wave + it * NW;
-    const int mc = m < MT ? m : MT - 1;
-    const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
-#pragma unroll
-    for (int x = 0; x < DSUB; ++x) cbv[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
-  }
-  auto build_table = [&](LDS float *lut, LDS float *res) __attribute__((always_inline)) {
-#pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-      const int m = wave + it * NW;
-      if (m < MT) {
-        const float4 v = lut_entry4<DSUB>(res + m * DSUB, cbv[it], r2.v[m]);
-        *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
-      }
-    }
-  };
-
-  const int64_t *const ids_p = a.ids;
-  const int kk = a.k;
-  CodeRegs<MPT / 4> ra, rb;
-  __syncthreads();  // query, metadata and counters are in LDS
-  LDS float *sres1 = sres + (sq_pad >> 2);
-  if (tid < D) {
-    sres[tid] = sq[tid] - a.centroids[(int64_t)meta_c[0] * D + tid];
-    if (p_begin + 1 < p_end) sres1[tid] = sq[tid] - a.centroids[(int64_t)meta_c[1] * D + tid];
-  }
-  __syncthreads();
-  if (p_begin < p_end) {
-    build_table(lut0, sres);
-    const int nb0 = (__builtin_amdgcn_readfirstlane(meta_len[0]) + 63) >> 6;
-    const int b0 = wave < nb0 ? wave : (nb0 > 0 ? nb0 - 1 : 0);
-    load_codes<MPT>(a.codes + (meta_blk[0] * 64 + (int64_t)b0 * 64) * MPT, lane, ra);
-  }
-  __syncthreads();
-
-  for (int p = p_begin; p < p_end; ++p) {
-    const int rel = p - p_begin;
-    const int cur = rel & 1, nxt = cur ^ 1;
-    const int mo = ((rel / META) & 1) * META + (rel & (META - 1));
-    const bool has_next = p + 1 < p_end;
-    const int rel1 = rel + 1;
-    const int mo1 = ((rel1 / META) & 1) * META + (rel1 & (META - 1));
-    // stage the chunk after the next one as soon as a chunk starts: its set was last
-    // read two chunks ago, and it is first read META - 1 barriers from now
-    if ((rel & (META - 1)) == 0 && rel > 0) stage_meta(rel / META + 1);
-    if (tid == 0) counters[nxt] = NW;  // not in use: its list was finished before the last barrier
-
-    const int64_t row0 = meta_row0[mo];
-    const int len = __builtin_amdgcn_readfirstlane(meta_len[mo]);
-    const int nb = (len + 63) >> 6;
-    const uint8_t *base = a.codes + meta_blk[mo] * 64 * MPT;
-    LDS float *lut = lut0 + cur * (MT * 256);
-    LDS float *lut_next = lut0 + nxt * (MT * 256);
-    const bool build_first = (wave & 1) == 0;
-    LDS float *res_next = (rel1 & 1) ? sres1 : sres;
-    // centroid of the list after the next one: requested now, its residual is written at
-    // the end of this iteration into the buffer that the current list's residual used
-    const bool has_next2 = p + 2 < p_end;
-    const int rel2 = rel + 2;
-    const int mo2 = ((rel2 / META) & 1) * META + (rel2 & (META - 1));
-    float cen2 = 0.0f;
-    if (has_next2 && tid < D) cen2 = a.centroids[(int64_t)meta_c[mo2] * D + tid];
-
-    if (has_next && build_first) build_table(lut_next, res_next);
-
-    if (wave < nb) {
-      auto consume = [&, ids_p, kk](const CodeRegs<MPT / 4> &r, int b) __attribute__((always_inline)) {
-        const int i = b * 64 + lane;
-        const bool valid = i < len;
-        const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
-        const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
-        float dist;
-        if (!adc_sum_exit<MT>(lut, r, pref, valid, dist)) return;
-        wave_offer(st, dist, valid, row0 + i, ids_p, qd, qid, lane, kk, sh);
-      };
-      auto claim = [&]() __attribute__((always_inline)) {
-        int v = 0;
-        if (lane == 0) v = __hip_atomic_fetch_add(counters + cur, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        return __builtin_amdgcn_readfirstlane(v);
-      };
-      const int last = nb - 1;
-      int b = wave;       // the first block was assigned statically and is already in ra
-      int bn = claim();   // further blocks come from the list's counter
-      for (;;) {
-        load_codes<MPT>(base + (int64_t)(bn < last ? bn : last) * 64 * MPT, lane, rb);
-        consume(ra, b);
-        if (bn >= nb) break;
-        b = bn;
-        bn = claim();
-        load_codes<MPT>(base + (int64_t)(bn < last ? bn : last) * 64 * MPT, lane, ra);
-        consume(rb, b);
-        if (bn >= nb) break;
-        b = bn;
-        bn = claim();
-      }
-    }
-
-    if (has_next && !build_first) build_table(lut_next, res_next);
-    if (has_next2 && tid < D) ((rel2 & 1) ? sres1 : sres)[tid] = sq[tid] - cen2;
-    if (has_next) {
-      const int nb1 = (__builtin_amdgcn_readfirstlane(meta_len[mo1]) + 63) >> 6;
-      const int b1 = wave < nb1 ? wave : (nb1 > 0 ? nb1 - 1 : 0);
-      load_codes<MPT>(a.codes + (meta_blk[mo1] * 64 + (int64_t)b1 * 64) * MPT, lane, ra);
-    }
-    __syncthreads();  // list p scanned by everyone, table p+1 complete
-  }
   finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
@@ -886,7 +717,8 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
   }
 }
 
-// Index build: raw rows [N][M] -> interleaved 64-point blocks (one wavefront per block).
+// Index build: raw rows [N][M] -> 64-point blocks, chunk-major within each list
+// (one wavefront per block).
 __global__ __launch_bounds__(256) void relayout_kernel(const uint8_t *__restrict__ rows,
                                                        const int64_t *__restrict__ list_offsets,
                                                        const int64_t *__restrict__ list_blocks,
@@ -901,18 +733,20 @@ __global__ __launch_bounds__(256) void relayout_kernel(const uint8_t *__restrict
     if (list_blocks[mid] <= B) lo = mid; else hi = mid;
   }
   const int c = lo;
-  const int64_t i = (B - list_blocks[c]) * 64 + lane;
+  const int64_t b = B - list_blocks[c];
+  const int64_t nb = list_blocks[c + 1] - list_blocks[c];
+  const int64_t i = b * 64 + lane;
   const bool valid = i < list_offsets[c + 1] - list_offsets[c];
   const uint8_t *src = rows + (list_offsets[c] + i) * M;
-  uint8_t *blk = out + B * ivfpq_block_bytes(Mp);
+  uint8_t *list_base = out + list_blocks[c] * ivfpq_block_bytes(Mp);
   const int n16 = Mp >> 4;
   for (int d = 0; d < (Mp >> 2); ++d) {
     uint32_t w = 0;
     if (valid)
-      for (int b = 0; b < 4; ++b)
-        if (4 * d + b < M) w |= (uint32_t)src[4 * d + b] << (8 * b);
-    uint8_t *p = d < 4 * n16 ? blk + (d >> 2) * 1024 + lane * 16 + (d & 3) * 4
-                             : blk + n16 * 1024 + (d - 4 * n16) * 256 + lane * 4;
+      for (int bb = 0; bb < 4; ++bb)
+        if (4 * d + bb < M) w |= (uint32_t)src[4 * d + bb] << (8 * bb);
+    uint8_t *p = d < 4 * n16 ? list_base + ((int64_t)(d >> 2) * nb + b) * 1024 + lane * 16 + (d & 3) * 4
+                             : list_base + (int64_t)n16 * nb * 1024 + ((int64_t)(d - 4 * n16) * nb + b) * 256 + lane * 4;
     *reinterpret_cast<uint32_t *>(p) = w;
   }
 }
@@ -929,7 +763,7 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
 
 int g_scan_waves = 0;  // 0 = choose from the shape
 int g_scan_ablate = 0;
-int g_scan_variant = 0;  // 0 = choose from the shape, 1 = two-barrier kernel, 2 = double-table kernel
+int g_scan_variant = 0;  // code loads: 0 = adaptive, 1 = always whole blocks, 2 = always first half + rest on demand
 int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
 
 template <int MT, int DSUB, int NW>
@@ -950,28 +784,7 @@ int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump,
 }
 
 template <int MT, int DSUB>
-int launch_scan_v2(const ScanArgs &a, const RadiiSq &r2, int64_t grid, hipStream_t s) {
-  constexpr int NW = 16;
-  const int two = 2 * MT * 1024, stage = NW * KP * 12;
-  const size_t lds = (size_t)(two > stage ? two : stage) + 3 * ((a.D * 4 + 15) & ~15) + (size_t)NW * 64 * 12 +
-                     ((4 * (NW + 1) + 15) & ~15) + 2 * 64 * 24 + 16;
-  if (lds > 160 * 1024) return 1;  // does not fit: caller falls back to the two-barrier kernel
-  auto kern = scan_kernel_v2<MT, DSUB>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) (void)hipGetLastError();
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
-  return IVFPQ_OK;
-}
-
-template <int MT, int DSUB>
 int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
-  if constexpr (MT > 0 && MT <= 72 && (DSUB == 2 || DSUB == 4)) {
-    if (!dump && g_scan_variant == 2) {
-      const int rc = launch_scan_v2<MT, DSUB>(a, r2, grid, s);
-      if (rc <= 0) return rc;
-    }
-  }
   int nw = g_scan_waves;
   if (nw == 0) nw = a.M > 72 ? 16 : 8;
   if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
@@ -1019,6 +832,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.k = k;
   a.nsplit = nsplit;
   a.ablate = g_scan_ablate;
+  a.load_mode = g_scan_variant;
   const bool dump = d_all_dist != nullptr;
   const int64_t grid = Q * nsplit;
   if (grid > 0x7FFFFFFFll) {

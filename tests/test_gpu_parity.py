@@ -83,17 +83,17 @@ def full_check(w, idx, q, radii, nprobe=None, k=None, stages=True):
     o_ids, o_dist = oracle.search(q, idx, nprobe, k, radii, threads=8)
     assert np.array_equal(ids.cpu().numpy(), o_ids), "top-k ids differ"
     assert_same_float(dist.cpu().numpy(), o_dist, "top-k distances")
-    # both organisations of the scan kernel (the double-table one only exists for some shapes;
-    # elsewhere the option falls back to the other) must give the same bits
+    # both ways of loading code blocks (whole, or first half with the rest on demand) must
+    # give the same bits as the adaptive default
     for variant in (1, 2):
-        b.set_option("scan_variant", variant)
+        b.set_option("scan_loads", variant)
         try:
             ids_v, dist_v = gi.search(dq, nprobe, k, radii)
             torch.cuda.synchronize()
         finally:
-            b.set_option("scan_variant", 0)
-        assert np.array_equal(ids_v.cpu().numpy(), o_ids), f"top-k ids differ (scan variant {variant})"
-        assert_same_float(dist_v.cpu().numpy(), o_dist, f"top-k distances (scan variant {variant})")
+            b.set_option("scan_loads", 0)
+        assert np.array_equal(ids_v.cpu().numpy(), o_ids), f"top-k ids differ (scan_loads {variant})"
+        assert_same_float(dist_v.cpu().numpy(), o_dist, f"top-k distances (scan_loads {variant})")
     if stages:
         assert np.array_equal(ids2.cpu().numpy(), o_ids) and np.array_equal(dist2.cpu().numpy(), dist.cpu().numpy())
     gi.close()
