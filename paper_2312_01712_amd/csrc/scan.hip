@@ -501,9 +501,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     for (int it = 0; it < RES; ++it) {
       const int m = wave + it * NW;
       const int mc = m < MT ? m : MT - 1;
-      const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
+      const uint8_t *cb = uniform_ptr(reinterpret_cast<const uint8_t *>(a.codebooks + (int64_t)mc * 256 * DSUB));
 #pragma unroll
-      for (int x = 0; x < DSUB; ++x) cbr[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+      for (int x = 0; x < DSUB; ++x)
+        cbr[it][x] = *reinterpret_cast<const float4 *>(cb + (uint32_t)(lane * 16 * DSUB + 16 * x));
     }
   }
   // Code chunks per point (16-byte chunks, then 4-byte chunks) and how many of them
@@ -551,14 +552,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
       if (!sres_ready)
         for (int i = tid; i < D; i += NT) sres[i] = sq[i] - cen[i];
       if (next_known && tid < D)
-        cen_next = a.centroids[(int64_t)__builtin_amdgcn_readfirstlane(meta_c[pm + 1]) * D + tid];
+        cen_next = *reinterpret_cast<const float *>(
+            uniform_ptr(reinterpret_cast<const uint8_t *>(
+                a.centroids + (int64_t)__builtin_amdgcn_readfirstlane(meta_c[pm + 1]) * D)) +
+            (uint32_t)(tid * 4));
 #pragma unroll
       for (int it = 0; it < STR; ++it) {
         const int m = wave + (RES + it) * NW;
         const int mc = m < MT ? m : MT - 1;
-        const float *cb = a.codebooks + ((int64_t)mc * 256 + 4 * lane) * DSUB;
+        const uint8_t *cb = uniform_ptr(reinterpret_cast<const uint8_t *>(a.codebooks + (int64_t)mc * 256 * DSUB));
 #pragma unroll
-        for (int x = 0; x < DSUB; ++x) cbs[it][x] = *reinterpret_cast<const float4 *>(cb + 4 * x);
+        for (int x = 0; x < DSUB; ++x)
+          cbs[it][x] = *reinterpret_cast<const float4 *>(cb + (uint32_t)(lane * 16 * DSUB + 16 * x));
       }
     }
     if constexpr (MT > 0) {
