@@ -6,6 +6,8 @@ values and distances are compared bit for bit as well, because both sides use
 the same fp32 operation order (the stated tolerance of 1e-4 relative is the
 fallback reported in the assertion message if a bit differs).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -291,10 +293,13 @@ def test_c1_full(lib):
     full_check(w, idx, q, radii, stages=False)
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5_10M"] +
+                         (["C5"] if os.environ.get("IVFPQ_TEST_C5") else []))
 def test_1m_configs_sampled_queries(lib, name):
-    """Full-size 1M-point indexes in the batch shape the benchmark times (all Q
-    queries in one call); the oracle checks a seeded sample of the outputs."""
+    """Full-size indexes (1M points; a 10M-point scale model of the 100M configuration
+    with its long lists; the 100M one itself when IVFPQ_TEST_C5 is set -- bench.py
+    checks that one against the oracle on every run) in the batch shape the benchmark
+    times (all Q queries in one call); the oracle checks a seeded sample of the outputs."""
     w = wl.WORKLOADS[name]
     idx, centres = wl.train_index(w, device="cuda", progress=say)
     q = wl.queries(w, centres).cpu().numpy()
