@@ -131,6 +131,51 @@ int ivfpq_scan_all(const ivfpq_index *index, const float *d_queries, int64_t Q, 
                    const int32_t *d_probe_ids, const float *radii, const int64_t *d_cand_offsets,
                    float *d_all_dist, int64_t *d_all_ids, int32_t *d_errors, void *hip_stream);
 
+/* ---- scoring variants --------------------------------------------------------
+ * The calls above rank by distances with one radius per subspace for the whole
+ * batch (the paper's JUNO-H).  The *_ex calls take an ivfpq_scoring that selects
+ *   - per-query radii (paper Sec. 4.1 "Determining Proper Threshold": a threshold
+ *     specific to the query, times a user scale): d_query_radii, device [Q][M] fp32,
+ *     each >= 0 or +inf (not validated: a NaN radius keeps no entry and yields NaN
+ *     sums); when it is non-NULL the host `radii` argument is ignored and may be NULL;
+ *   - hit-count scoring (paper Sec. 5.4), expressed as a penalty that is summed and
+ *     ranked exactly like a distance, smaller is better:
+ *       IVFPQ_SCORE_HIT_COUNT   an entry inside the radius stores 0, any other 1,
+ *                               so the result is M - (number of subspaces hit)
+ *                               (the paper's JUNO-L);
+ *       IVFPQ_SCORE_HIT_REWARD  with the inner sphere of half the radius: 0 inside it
+ *                               (the paper's +1), 1 inside the outer sphere only (0),
+ *                               2 outside both (-1), so the result is M - score
+ *                               (the paper's JUNO-M).
+ *     The returned "distances" are these sums (small integers held in fp32); ties are
+ *     frequent and go to the smaller id.  Keep masks are those of the outer radius.
+ * scoring == NULL means distances and shared radii, i.e. the plain call. */
+typedef enum {
+  IVFPQ_SCORE_DISTANCE = 0,
+  IVFPQ_SCORE_HIT_COUNT = 1,
+  IVFPQ_SCORE_HIT_REWARD = 2
+} ivfpq_score_mode;
+
+typedef struct {
+  int32_t mode;               /* an ivfpq_score_mode                              */
+  const float *d_query_radii; /* device [Q][M], or NULL for the shared host radii */
+} ivfpq_scoring;
+
+int ivfpq_search_ex(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                    int32_t k, const float *radii, const ivfpq_scoring *scoring, int64_t *d_out_ids,
+                    float *d_out_dist, void *d_workspace, size_t workspace_bytes, void *hip_stream);
+int ivfpq_build_lut_ex(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                       const int32_t *d_probe_ids, const float *radii, const ivfpq_scoring *scoring,
+                       float *d_lut, uint64_t *d_mask, void *hip_stream);
+int ivfpq_scan_topk_ex(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                       const int32_t *d_probe_ids, int32_t k, const float *radii,
+                       const ivfpq_scoring *scoring, int64_t *d_out_ids, float *d_out_dist,
+                       void *d_workspace, size_t workspace_bytes, void *hip_stream);
+int ivfpq_scan_all_ex(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                      const int32_t *d_probe_ids, const float *radii, const ivfpq_scoring *scoring,
+                      const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
+                      int32_t *d_errors, void *hip_stream);
+
 /* Shape of an index and of its device layout. */
 typedef struct {
   int64_t N;

@@ -66,7 +66,16 @@ def coarse(queries, centroids, nprobe: int) -> Tuple[np.ndarray, np.ndarray]:
     return ids, dist
 
 
-def build_lut(queries, centroids, codebooks, probe_ids, radii) -> Tuple[np.ndarray, np.ndarray]:
+def _stride(r: np.ndarray, Q: int, M: int) -> int:
+    """radii [M] (shared) -> 0, radii [Q][M] (per query) -> M."""
+    if r.shape == (M,):
+        return 0
+    if r.shape == (Q, M):
+        return M
+    raise ValueError(f"radii must have shape ({M},) or ({Q}, {M})")
+
+
+def build_lut(queries, centroids, codebooks, probe_ids, radii, mode: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     q, c, cb, r = _f32(queries), _f32(centroids), _f32(codebooks), _f32(radii)
     pid = np.ascontiguousarray(probe_ids, dtype=np.int32)
     Q, D = q.shape
@@ -75,13 +84,14 @@ def build_lut(queries, centroids, codebooks, probe_ids, radii) -> Tuple[np.ndarr
     lut = np.empty((Q, nprobe, M, 256), dtype=np.float32)
     mask = np.empty((Q, nprobe, M, 4), dtype=np.uint64)
     rc = _load().oracle_build_lut(ctypes.c_int64(Q), D, M, _p(q, _f32p), _p(c, _f32p), _p(cb, _f32p),
-                                  _p(pid, _i32p), nprobe, _p(r, _f32p), _p(lut, _f32p), _p(mask, _u64p))
+                                  _p(pid, _i32p), nprobe, _p(r, _f32p), _stride(r, Q, M), mode, _p(lut, _f32p),
+                                  _p(mask, _u64p))
     if rc:
         raise ValueError("oracle_build_lut: invalid argument")
     return lut, mask
 
 
-def scan_all(queries, index, probe_ids, radii) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def scan_all(queries, index, probe_ids, radii, mode: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """(cand_offsets [Q+1], dist [total], ids [total]) for every candidate."""
     q, r = _f32(queries), _f32(radii)
     pid = np.ascontiguousarray(probe_ids, dtype=np.int32)
@@ -92,7 +102,7 @@ def scan_all(queries, index, probe_ids, radii) -> Tuple[np.ndarray, np.ndarray, 
     args = lambda d, i: (ctypes.c_int64(Q), D, index.M, _p(q, _f32p), _p(index.centroids, _f32p),
                          _p(index.codebooks, _f32p), _p(index.list_offsets, _i64p),
                          _p(index.codes, _u8p), _p(index.ids, _i64p), _p(pid, _i32p), nprobe,
-                         _p(r, _f32p), _p(offs, _i64p), _p(d, _f32p), _p(i, _i64p))
+                         _p(r, _f32p), _stride(r, Q, index.M), mode, _p(offs, _i64p), _p(d, _f32p), _p(i, _i64p))
     if lib.oracle_scan_all(*args(None, None)):
         raise ValueError("oracle_scan_all: invalid argument")
     total = int(offs[Q])
@@ -113,7 +123,7 @@ def topk(dist, ids, k: int) -> Tuple[np.ndarray, np.ndarray]:
 
 
 def search(queries, index, nprobe: int, k: int, radii, threads: int = 1,
-           q_range: Optional[Tuple[int, int]] = None) -> Tuple[np.ndarray, np.ndarray]:
+           q_range: Optional[Tuple[int, int]] = None, mode: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Whole search path.  threads > 1 runs the same single-threaded routine on
     disjoint query ranges from Python threads (ctypes releases the GIL)."""
     q, r = _f32(queries), _f32(radii)
@@ -127,8 +137,8 @@ def search(queries, index, nprobe: int, k: int, radii, threads: int = 1,
         rc = lib.oracle_search(ctypes.c_int64(a), ctypes.c_int64(b), D, index.nlist, index.M,
                                _p(q, _f32p), _p(index.centroids, _f32p), _p(index.codebooks, _f32p),
                                _p(index.list_offsets, _i64p), _p(index.codes, _u8p),
-                               _p(index.ids, _i64p), nprobe, k, _p(r, _f32p), _p(out_ids, _i64p),
-                               _p(out_dist, _f32p))
+                               _p(index.ids, _i64p), nprobe, k, _p(r, _f32p), _stride(r, Q, index.M), mode,
+                               _p(out_ids, _i64p), _p(out_dist, _f32p))
         if rc:
             raise ValueError("oracle_search: invalid argument")
 

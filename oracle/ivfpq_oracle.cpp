@@ -25,7 +25,20 @@
 //       on residuals, Sec. 2.1 / Algorithm 1);
 //   R6  one (query, probed list, subspace) ray writes one table row only;
 //   R7  radii are per subspace and shared by all queries of a call;
-//   R11 top-k order is (distance, id) lexicographic.
+//   R11 top-k order is (distance, id) lexicographic;
+//   R14 hit-count scoring (Sec. 5.4) is expressed as a penalty that is summed like a
+//       distance, so that smaller is better in every mode: a missed subspace costs 1
+//       (hit count = M - sum); with the half-radius inner sphere of the reward /
+//       penalty model, inside the inner sphere costs 0 (+1 in the paper), inside the
+//       outer sphere only costs 1 (0), outside both costs 2 (-1), i.e. score = M - sum.
+//       Rankings are those of the paper's scores; ties go to the smaller id;
+//   R15 a per-query radius (Sec. 4.1 "Determining Proper Threshold": query-specific
+//       thresholds times a user scale) is an input array radii[Q][M]; how it is
+//       derived from densities is outside the search path.
+//
+// Scoring modes: 0 = distances (the paper's JUNO-H), 1 = hit count (JUNO-L),
+// 2 = reward/penalty hit count (JUNO-M).  radii_stride = 0 means one radii[M] for all
+// queries, radii_stride = M means radii[Q][M].
 //
 // Pins (tests/test_oracle_pins.py): brute-force exact kNN on identity-codebook
 // indexes, reconstruction identity of the unthresholded ADC sum, truncated-sum
@@ -87,8 +100,12 @@ void coarse_one(const float* q, int D, const float* centroids, int nlist, int np
 //                          residual projection; R4, R5)
 //   lut[m][e] = keep ? d2 : r_m^2                                    (R1, R3)
 // mask (optional) gets bit e of word [m][e/64] set when the entry is kept.
+//
+// Hit-count scoring (paper Sec. 5.4, R14): mode 1 stores 0 for a kept entry and 1
+// otherwise; mode 2 stores 0 inside the inner sphere of radius r_m / 2
+// (d2 <= r_m^2 / 4), 1 inside the outer sphere only, 2 outside both.
 void lut_one(const float* q, const float* cen, int D, int M, const float* codebooks,
-             const float* radii, float* lut, uint64_t* mask) {
+             const float* radii, int mode, float* lut, uint64_t* mask) {
   const int dsub = D / M;
   for (int m = 0; m < M; ++m) {
     const float r2 = radii[m] * radii[m];
@@ -102,7 +119,9 @@ void lut_one(const float* q, const float* cen, int D, int M, const float* codebo
         d2 = (j == 0) ? t * t : std::fmaf(t, t, d2);
       }
       const bool keep = d2 <= r2;
-      lut[m * E + e] = keep ? d2 : r2;
+      if (mode == 0) lut[m * E + e] = keep ? d2 : r2;
+      else if (mode == 1) lut[m * E + e] = keep ? 0.0f : 1.0f;
+      else lut[m * E + e] = d2 <= 0.25f * r2 ? 0.0f : (keep ? 1.0f : 2.0f);
       if (mask && keep) mask[m * 4 + (e >> 6)] |= (uint64_t)1 << (e & 63);
     }
   }
@@ -151,13 +170,15 @@ int oracle_coarse(int64_t Q, int32_t D, int32_t nlist, const float* queries,
 // out_mask [Q][nprobe][M][4] uint64 (may be null).
 int oracle_build_lut(int64_t Q, int32_t D, int32_t M, const float* queries, const float* centroids,
                      const float* codebooks, const int32_t* probe_ids, int32_t nprobe,
-                     const float* radii, float* out_lut, uint64_t* out_mask) {
-  if (D % M) return -1;
+                     const float* radii, int32_t radii_stride, int32_t mode, float* out_lut,
+                     uint64_t* out_mask) {
+  if (D % M || mode < 0 || mode > 2 || (radii_stride != 0 && radii_stride != M)) return -1;
   for (int64_t q = 0; q < Q; ++q)
     for (int p = 0; p < nprobe; ++p) {
       const size_t row = (size_t)q * nprobe + p;
-      lut_one(queries + q * D, centroids + (size_t)probe_ids[row] * D, D, M, codebooks, radii,
-              out_lut + row * M * E, out_mask ? out_mask + row * M * 4 : nullptr);
+      lut_one(queries + q * D, centroids + (size_t)probe_ids[row] * D, D, M, codebooks,
+              radii + q * radii_stride, mode, out_lut + row * M * E,
+              out_mask ? out_mask + row * M * 4 : nullptr);
     }
   return 0;
 }
@@ -169,8 +190,9 @@ int oracle_build_lut(int64_t Q, int32_t D, int32_t M, const float* queries, cons
 int oracle_scan_all(int64_t Q, int32_t D, int32_t M, const float* queries, const float* centroids,
                     const float* codebooks, const int64_t* list_offsets, const uint8_t* codes,
                     const int64_t* ids, const int32_t* probe_ids, int32_t nprobe,
-                    const float* radii, int64_t* cand_offsets, float* out_dist, int64_t* out_ids) {
-  if (D % M) return -1;
+                    const float* radii, int32_t radii_stride, int32_t mode, int64_t* cand_offsets,
+                    float* out_dist, int64_t* out_ids) {
+  if (D % M || mode < 0 || mode > 2 || (radii_stride != 0 && radii_stride != M)) return -1;
   std::vector<float> lut((size_t)M * E);
   int64_t pos = 0;
   for (int64_t q = 0; q < Q; ++q) {
@@ -179,8 +201,8 @@ int oracle_scan_all(int64_t Q, int32_t D, int32_t M, const float* queries, const
       const int32_t c = probe_ids[q * nprobe + p];
       const int64_t b = list_offsets[c], e = list_offsets[c + 1];
       if (out_dist) {
-        lut_one(queries + q * D, centroids + (size_t)c * D, D, M, codebooks, radii, lut.data(),
-                nullptr);
+        lut_one(queries + q * D, centroids + (size_t)c * D, D, M, codebooks,
+                radii + q * radii_stride, mode, lut.data(), nullptr);
         for (int64_t i = b; i < e; ++i) {
           out_dist[pos + (i - b)] = adc_one(lut.data(), codes + i * M, M);
           out_ids[pos + (i - b)] = ids ? ids[i] : i;
@@ -209,9 +231,11 @@ int oracle_topk(int64_t n, const float* dist, const int64_t* ids, int32_t k, int
 int oracle_search(int64_t q_begin, int64_t q_end, int32_t D, int32_t nlist, int32_t M,
                   const float* queries, const float* centroids, const float* codebooks,
                   const int64_t* list_offsets, const uint8_t* codes, const int64_t* ids,
-                  int32_t nprobe, int32_t k, const float* radii, int64_t* out_ids,
-                  float* out_dist) {
-  if (D % M || nprobe > nlist || nprobe < 1 || k < 1) return -1;
+                  int32_t nprobe, int32_t k, const float* radii, int32_t radii_stride, int32_t mode,
+                  int64_t* out_ids, float* out_dist) {
+  if (D % M || nprobe > nlist || nprobe < 1 || k < 1 || mode < 0 || mode > 2 ||
+      (radii_stride != 0 && radii_stride != M))
+    return -1;
   std::vector<float> lut((size_t)M * E);
   std::vector<int32_t> probes(nprobe);
   std::vector<Cand> cand;
@@ -221,7 +245,8 @@ int oracle_search(int64_t q_begin, int64_t q_end, int32_t D, int32_t nlist, int3
     cand.clear();
     for (int p = 0; p < nprobe; ++p) {
       const int32_t c = probes[p];
-      lut_one(qv, centroids + (size_t)c * D, D, M, codebooks, radii, lut.data(), nullptr);
+      lut_one(qv, centroids + (size_t)c * D, D, M, codebooks, radii + q * radii_stride, mode,
+              lut.data(), nullptr);
       for (int64_t i = list_offsets[c]; i < list_offsets[c + 1]; ++i)
         cand.push_back({adc_one(lut.data(), codes + i * M, M), ids ? ids[i] : i});
     }

@@ -23,7 +23,10 @@ SYMBOLS = [
     "ivfpq_index_create", "ivfpq_index_destroy", "ivfpq_search_workspace_bytes", "ivfpq_search",
     "ivfpq_coarse", "ivfpq_build_lut", "ivfpq_scan_topk", "ivfpq_scan_all", "ivfpq_index_get_info",
     "ivfpq_set_option", "ivfpq_coarse_fallbacks", "ivfpq_last_error",
+    "ivfpq_search_ex", "ivfpq_build_lut_ex", "ivfpq_scan_topk_ex", "ivfpq_scan_all_ex",
 ]
+
+SCORE_DISTANCE, SCORE_HIT_COUNT, SCORE_HIT_REWARD = 0, 1, 2
 
 OK, ERR_INVALID_ARGUMENT, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5
 
@@ -39,6 +42,10 @@ class _Desc(ctypes.Structure):
                 ("M", ctypes.c_int32), ("ksub", ctypes.c_int32), ("centroids", ctypes.c_void_p),
                 ("codebooks", ctypes.c_void_p), ("list_offsets", ctypes.c_void_p),
                 ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p)]
+
+
+class _Scoring(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("d_query_radii", ctypes.c_void_p)]
 
 
 class _Info(ctypes.Structure):
@@ -67,6 +74,11 @@ def load_library():
     lib.ivfpq_build_lut.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.ivfpq_scan_topk.argtypes = [vp, vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.ivfpq_scan_all.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    sp = ctypes.POINTER(_Scoring)
+    lib.ivfpq_search_ex.argtypes = [vp, vp, i64, i32, i32, vp, sp, vp, vp, vp, sz, vp]
+    lib.ivfpq_build_lut_ex.argtypes = [vp, vp, i64, i32, vp, vp, sp, vp, vp, vp]
+    lib.ivfpq_scan_topk_ex.argtypes = [vp, vp, i64, i32, vp, i32, vp, sp, vp, vp, vp, sz, vp]
+    lib.ivfpq_scan_all_ex.argtypes = [vp, vp, i64, i32, vp, vp, sp, vp, vp, vp, vp, vp]
     lib.ivfpq_index_get_info.argtypes = [vp, ctypes.POINTER(_Info)]
     lib.ivfpq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.ivfpq_coarse_fallbacks.argtypes = [ctypes.c_int]
@@ -111,6 +123,28 @@ def _radii(radii, M: int) -> np.ndarray:
     if r.shape != (M,):
         raise ValueError(f"radii must have shape ({M},)")
     return r
+
+
+def _scoring(mode: int, query_radii: Optional[torch.Tensor], radii, Q: int, M: int):
+    """(host radii pointer or None, ctypes scoring struct or None, objects to keep alive)."""
+    keep = []
+    qr_ptr = None
+    if query_radii is not None:
+        qr = _dev(query_radii, torch.float32)
+        if tuple(qr.shape) != (Q, M):
+            raise ValueError(f"query_radii must have shape ({Q}, {M})")
+        qr_ptr = qr.data_ptr()
+        keep.append(qr)
+    r_ptr = None
+    if radii is not None:
+        r = _radii(radii, M)
+        r_ptr = r.ctypes.data
+        keep.append(r)
+    sc = None
+    if mode != SCORE_DISTANCE or qr_ptr is not None:
+        sc = _Scoring(mode=int(mode), d_query_radii=qr_ptr)
+        keep.append(sc)
+    return r_ptr, (ctypes.byref(sc) if sc is not None else None), keep
 
 
 class IvfPqIndex:
@@ -177,15 +211,22 @@ class IvfPqIndex:
         return torch.empty(n, dtype=torch.uint8, device="cuda")
 
     def search(self, queries: torch.Tensor, nprobe: int, k: int, radii, workspace: Optional[torch.Tensor] = None,
-               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, mode: int = SCORE_DISTANCE,
+               query_radii: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
         q = _dev(queries, torch.float32)
         Q = q.shape[0]
-        r = _radii(radii, self.M)
+        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
         ws = workspace if workspace is not None else self.workspace(Q, nprobe, k)
         ids, dist = out if out is not None else (torch.empty((Q, k), dtype=torch.int64, device=q.device),
                                                  torch.empty((Q, k), dtype=torch.float32, device=q.device))
-        _check(load_library().ivfpq_search(self._h, q.data_ptr(), Q, nprobe, k, r.ctypes.data, ids.data_ptr(),
-                                           dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        lib = load_library()
+        if sc is None:
+            _check(lib.ivfpq_search(self._h, q.data_ptr(), Q, nprobe, k, r_ptr, ids.data_ptr(),
+                                    dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        else:
+            _check(lib.ivfpq_search_ex(self._h, q.data_ptr(), Q, nprobe, k, r_ptr, sc, ids.data_ptr(),
+                                       dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        del keep
         return ids, dist
 
     def coarse(self, queries: torch.Tensor, nprobe: int, workspace: Optional[torch.Tensor] = None):
@@ -198,43 +239,49 @@ class IvfPqIndex:
                                            ws.data_ptr(), ws.numel(), _stream()))
         return pid, pd
 
-    def build_lut(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii):
+    def build_lut(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, mode: int = SCORE_DISTANCE,
+                  query_radii: Optional[torch.Tensor] = None):
         q = _dev(queries, torch.float32)
         pid = _dev(probe_ids, torch.int32)
         Q, nprobe = pid.shape
-        r = _radii(radii, self.M)
+        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
         lut = torch.empty((Q, nprobe, self.M, 256), dtype=torch.float32, device=q.device)
         mask = torch.zeros((Q, nprobe, self.M, 4), dtype=torch.int64, device=q.device)
-        _check(load_library().ivfpq_build_lut(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), r.ctypes.data,
-                                              lut.data_ptr(), mask.data_ptr(), _stream()))
+        _check(load_library().ivfpq_build_lut_ex(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), r_ptr, sc,
+                                                 lut.data_ptr(), mask.data_ptr(), _stream()))
+        del keep
         return lut, mask
 
     def scan_topk(self, queries: torch.Tensor, probe_ids: torch.Tensor, k: int, radii,
-                  workspace: Optional[torch.Tensor] = None):
+                  workspace: Optional[torch.Tensor] = None, mode: int = SCORE_DISTANCE,
+                  query_radii: Optional[torch.Tensor] = None):
         q = _dev(queries, torch.float32)
         pid = _dev(probe_ids, torch.int32)
         Q, nprobe = pid.shape
-        r = _radii(radii, self.M)
+        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
         ws = workspace if workspace is not None else self.workspace(Q, nprobe, k)
         ids = torch.empty((Q, k), dtype=torch.int64, device=q.device)
         dist = torch.empty((Q, k), dtype=torch.float32, device=q.device)
-        _check(load_library().ivfpq_scan_topk(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, r.ctypes.data,
-                                              ids.data_ptr(), dist.data_ptr(), ws.data_ptr(), ws.numel(),
-                                              _stream()))
+        _check(load_library().ivfpq_scan_topk_ex(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, r_ptr, sc,
+                                                 ids.data_ptr(), dist.data_ptr(), ws.data_ptr(), ws.numel(),
+                                                 _stream()))
+        del keep
         return ids, dist
 
-    def scan_all(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, cand_offsets: torch.Tensor):
+    def scan_all(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, cand_offsets: torch.Tensor,
+                 mode: int = SCORE_DISTANCE, query_radii: Optional[torch.Tensor] = None):
         """Every candidate's (distance, id); cand_offsets [Q+1] int64 on the device."""
         q = _dev(queries, torch.float32)
         pid = _dev(probe_ids, torch.int32)
         offs = _dev(cand_offsets, torch.int64)
         Q, nprobe = pid.shape
-        r = _radii(radii, self.M)
+        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
         total = int(offs[-1].item()) if Q > 0 else 0
         dist = torch.empty(max(total, 1), dtype=torch.float32, device=q.device)
         ids = torch.empty(max(total, 1), dtype=torch.int64, device=q.device)
         err = torch.empty(1, dtype=torch.int32, device=q.device)
-        _check(load_library().ivfpq_scan_all(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), r.ctypes.data,
-                                             offs.data_ptr(), dist.data_ptr(), ids.data_ptr(), err.data_ptr(),
-                                             _stream()))
+        _check(load_library().ivfpq_scan_all_ex(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), r_ptr, sc,
+                                                offs.data_ptr(), dist.data_ptr(), ids.data_ptr(), err.data_ptr(),
+                                                _stream()))
+        del keep
         return dist[:total], ids[:total], err

@@ -310,29 +310,60 @@ int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32
                        static_cast<hipStream_t>(stream));
 }
 
-int ivfpq_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
-                    const int32_t *d_probe_ids, const float *radii, float *d_lut, uint64_t *d_mask,
-                    void *stream) {
+// scoring defaults (distances, shared radii) when the caller passes none
+static int unpack_scoring(const ivfpq_index *ix, const ivfpq_scoring *sc, const float *radii, RadiiSq *r2,
+                          int32_t *mode, const float **d_query_radii, const char *fn) {
+  *mode = IVFPQ_SCORE_DISTANCE;
+  *d_query_radii = nullptr;
+  if (sc) {
+    if (sc->mode < IVFPQ_SCORE_DISTANCE || sc->mode > IVFPQ_SCORE_HIT_REWARD) {
+      set_error("%s: scoring mode %d unknown", fn, sc->mode);
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+    *mode = sc->mode;
+    *d_query_radii = sc->d_query_radii;
+  }
+  if (*d_query_radii) {  // per-query radii replace the shared ones
+    memset(r2, 0, sizeof *r2);
+    return IVFPQ_OK;
+  }
+  return make_radii(ix, radii, r2, fn);
+}
+
+int ivfpq_build_lut_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                       const int32_t *d_probe_ids, const float *radii, const ivfpq_scoring *scoring,
+                       float *d_lut, uint64_t *d_mask, void *stream) {
   const char *fn = "build_lut";
   int rc = check_common(ix, d_queries, Q, nprobe, fn);
   if (rc) return rc;
   RadiiSq r2;
-  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  int32_t mode;
+  const float *qr;
+  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn))) return rc;
   if (Q == 0) return IVFPQ_OK;
   if (!d_probe_ids || !d_lut) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
-  return launch_build_lut(ix, d_queries, Q, nprobe, d_probe_ids, r2, d_lut, d_mask,
+  return launch_build_lut(ix, d_queries, Q, nprobe, d_probe_ids, r2, d_lut, d_mask, mode, qr,
                           static_cast<hipStream_t>(stream));
 }
 
-int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
-                    const int32_t *d_probe_ids, int32_t k, const float *radii, int64_t *d_out_ids,
-                    float *d_out_dist, void *ws, size_t ws_bytes, void *stream) {
+int ivfpq_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                    const int32_t *d_probe_ids, const float *radii, float *d_lut, uint64_t *d_mask,
+                    void *stream) {
+  return ivfpq_build_lut_ex(ix, d_queries, Q, nprobe, d_probe_ids, radii, nullptr, d_lut, d_mask, stream);
+}
+
+int ivfpq_scan_topk_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                       const int32_t *d_probe_ids, int32_t k, const float *radii,
+                       const ivfpq_scoring *scoring, int64_t *d_out_ids, float *d_out_dist, void *ws,
+                       size_t ws_bytes, void *stream) {
   const char *fn = "scan_topk";
   int rc = check_common(ix, d_queries, Q, nprobe, fn);
   if (rc) return rc;
   if ((rc = check_k(k, fn))) return rc;
   RadiiSq r2;
-  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  int32_t mode;
+  const float *qr;
+  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn))) return rc;
   if (Q == 0) return IVFPQ_OK;
   if (!d_probe_ids || !d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
@@ -341,18 +372,27 @@ int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
   return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, w.nsplit,
                      reinterpret_cast<uint32_t *>(base + w.part_d),
                      reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                     nullptr, nullptr, nullptr, mode, qr, static_cast<hipStream_t>(stream));
 }
 
-int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
-                 const float *radii, int64_t *d_out_ids, float *d_out_dist, void *ws, size_t ws_bytes,
-                 void *stream) {
+int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                    const int32_t *d_probe_ids, int32_t k, const float *radii, int64_t *d_out_ids,
+                    float *d_out_dist, void *ws, size_t ws_bytes, void *stream) {
+  return ivfpq_scan_topk_ex(ix, d_queries, Q, nprobe, d_probe_ids, k, radii, nullptr, d_out_ids, d_out_dist,
+                            ws, ws_bytes, stream);
+}
+
+int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
+                    const float *radii, const ivfpq_scoring *scoring, int64_t *d_out_ids,
+                    float *d_out_dist, void *ws, size_t ws_bytes, void *stream) {
   const char *fn = "search";
   int rc = check_common(ix, d_queries, Q, nprobe, fn);
   if (rc) return rc;
   if ((rc = check_k(k, fn))) return rc;
   RadiiSq r2;
-  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  int32_t mode;
+  const float *qr;
+  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn))) return rc;
   if (Q == 0) return IVFPQ_OK;
   if (!d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
@@ -366,17 +406,27 @@ int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32
   return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
                      reinterpret_cast<uint32_t *>(base + w.part_d),
                      reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, s);
+                     nullptr, nullptr, nullptr, mode, qr, s);
 }
 
-int ivfpq_scan_all(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
-                   const int32_t *d_probe_ids, const float *radii, const int64_t *d_cand_offsets,
-                   float *d_all_dist, int64_t *d_all_ids, int32_t *d_errors, void *stream) {
+int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
+                 const float *radii, int64_t *d_out_ids, float *d_out_dist, void *ws, size_t ws_bytes,
+                 void *stream) {
+  return ivfpq_search_ex(ix, d_queries, Q, nprobe, k, radii, nullptr, d_out_ids, d_out_dist, ws, ws_bytes,
+                         stream);
+}
+
+int ivfpq_scan_all_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                      const int32_t *d_probe_ids, const float *radii, const ivfpq_scoring *scoring,
+                      const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
+                      int32_t *d_errors, void *stream) {
   const char *fn = "scan_all";
   int rc = check_common(ix, d_queries, Q, nprobe, fn);
   if (rc) return rc;
   RadiiSq r2;
-  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  int32_t mode;
+  const float *qr;
+  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn))) return rc;
   if (!d_errors) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   if (Q > 0 && (!d_probe_ids || !d_cand_offsets || !d_all_dist || !d_all_ids)) {
     set_error("%s: NULL pointer", fn);
@@ -387,7 +437,14 @@ int ivfpq_scan_all(const ivfpq_index *ix, const float *d_queries, int64_t Q, int
   if (rc || Q == 0) return rc;
   // the dump variant of the scan kernel keeps no top-k, so k and the result pointers are unused
   return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, 0, r2, 1, nullptr, nullptr, nullptr, nullptr,
-                     d_cand_offsets, d_all_dist, d_all_ids, d_errors, s);
+                     d_cand_offsets, d_all_dist, d_all_ids, d_errors, mode, qr, s);
+}
+
+int ivfpq_scan_all(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                   const int32_t *d_probe_ids, const float *radii, const int64_t *d_cand_offsets,
+                   float *d_all_dist, int64_t *d_all_ids, int32_t *d_errors, void *stream) {
+  return ivfpq_scan_all_ex(ix, d_queries, Q, nprobe, d_probe_ids, radii, nullptr, d_cand_offsets, d_all_dist,
+                           d_all_ids, d_errors, stream);
 }
 
 }  // extern "C"

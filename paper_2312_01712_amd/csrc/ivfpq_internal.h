@@ -74,12 +74,12 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
                   int32_t nlist_pad, hipStream_t s);
 int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                      const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
-                     hipStream_t s);
+                     int32_t mode, const float *d_query_radii, hipStream_t s);
 int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
                 uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
                 const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
-                int32_t *d_errors, hipStream_t s);
+                int32_t *d_errors, int32_t mode, const float *d_query_radii, hipStream_t s);
 int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);
 int coarse_fallbacks(int reset, unsigned int *out);

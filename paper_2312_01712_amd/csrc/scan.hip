@@ -23,6 +23,8 @@
 
 #include <limits.h>
 
+#include <type_traits>
+
 #include "ivfpq_internal.h"
 
 namespace {
@@ -104,11 +106,27 @@ __device__ inline Key bcast_key(const Key &a, int src) {
   return o;
 }
 
+// What an entry at squared distance d2 stores (r2 = r_m^2).  Mode 0: the distance,
+// clamped at r2 (written as a minimum: equal bit for bit to keep ? d2 : r2, and a NaN
+// d2 yields r2 in both forms).  Modes 1 and 2 are the hit-count scorings of paper
+// Sec. 5.4, expressed as penalties so that smaller is better: mode 1 stores 0 for a hit
+// and 1 for a miss (hit count = M - sum); mode 2 adds the inner sphere of radius
+// r_m / 2: 0 inside it, 1 inside the outer sphere only, 2 outside both (score = M - sum).
+template <int MODE>
+__device__ inline float table_value(float d2, float r2) {
+  if (MODE == 0) return fminf(d2, r2);
+  if (MODE == 1) return d2 <= r2 ? 0.0f : 1.0f;
+  return d2 <= 0.25f * r2 ? 0.0f : (d2 <= r2 ? 1.0f : 2.0f);
+}
+__device__ inline float table_value(float d2, float r2, int mode) {
+  return mode == 0 ? table_value<0>(d2, r2) : (mode == 1 ? table_value<1>(d2, r2) : table_value<2>(d2, r2));
+}
+
 // One table entry (paper Sec. 4.1; Algorithm 2): squared distance between the
 // residual projection and a codebook entry, thresholded at r2.
 template <int DSUB, typename SP>
 __device__ inline float lut_entry(SP sq, const float *__restrict__ cen,
-                                  const float *__restrict__ cb, int dsub_rt, float r2, bool &keep) {
+                                  const float *__restrict__ cb, int dsub_rt, float r2, int mode, bool &keep) {
   const int dsub = DSUB > 0 ? DSUB : dsub_rt;
   float d2 = 0.0f;
   if (DSUB == 2) {
@@ -130,14 +148,12 @@ __device__ inline float lut_entry(SP sq, const float *__restrict__ cen,
     }
   }
   keep = d2 <= r2;
-  return keep ? d2 : r2;
+  return table_value(d2, r2, mode);
 }
 
 // Four consecutive entries of one subspace (same arithmetic per entry as above);
-// ev holds their 4 * DSUB coordinates as loaded from the codebook.  The clamp
-// keep ? d2 : r2 is written as a minimum: equal bit for bit, and a NaN d2 yields r2
-// in both forms.
-template <int DSUB, typename SP>
+// ev holds their 4 * DSUB coordinates as loaded from the codebook.
+template <int DSUB, int MODE, typename SP>
 __device__ inline float4 lut_entry4(SP res_p, const float4 *ev, float r2) {
   constexpr int DS = DSUB > 0 ? DSUB : 1;
   float res[DS];  // residual projection q_m - centroid_m, computed once per list
@@ -158,7 +174,7 @@ __device__ inline float4 lut_entry4(SP res_p, const float4 *ev, float r2) {
       const float t = res[j] - e[i * DSUB + j];
       acc = fmaf(t, t, acc);
     }
-    d2[i] = fminf(acc, r2);
+    d2[i] = table_value<MODE>(acc, r2);
   }
   return make_float4(d2[0], d2[1], d2[2], d2[3]);
 }
@@ -181,6 +197,8 @@ struct ScanArgs {
   int64_t *all_ids;             // (DUMP)
   int32_t *errors;              // (DUMP)
   int32_t D, M, dsub, Mp, nlist, nprobe, k, nsplit;
+  const float *query_radii;     // [Q][M] per-query radii, or NULL: the shared r_m^2 of the call
+  int32_t mode;       // scoring: 0 distances, 1 hit count, 2 reward/penalty hit count
   int32_t load_mode;  // 0 adaptive, 1 whole blocks, 2 first half of the chunks, rest on demand
   int32_t ablate;  // measurement only: 1 skips the table arithmetic, 2 the list scan, 4 the top-k offers,
                    // 8 disables the early exit of the distance sums (results stay valid)
@@ -443,6 +461,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   LDS int64_t *meta_blk = meta_row0 + META;
   LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
   LDS int32_t *meta_c = meta_len + META;
+  LDS float *sr2 = (LDS float *)(meta_c + META);  // [M] r_m^2 of this query
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
@@ -467,6 +486,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   }
 
   for (int i = tid; i < D; i += NT) sq[i] = a.queries[q * D + i];
+  for (int m = tid; m < M; m += NT) {
+    float v = r2.v[m];
+    if (a.query_radii) {
+      const float r = a.query_radii[q * M + m];
+      v = r * r;
+    }
+    sr2[m] = v;
+  }
+  const int mode = a.mode;
   if (tid <= NW) tau_words[tid] = SENT_D;
   SharedTau sh;
   sh.bound = tau_words;
@@ -575,15 +603,24 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
     // ---- selective table for (query, list c) ----
     if constexpr (VEC) {
-      // one subspace per wavefront and pass, four consecutive entries per lane
+      // one subspace per wavefront and pass, four consecutive entries per lane; the
+      // scoring mode is resolved once per list, outside the unrolled passes
+      auto build_rows = [&](auto mode_tag) __attribute__((always_inline)) {
+        constexpr int MODE = decltype(mode_tag)::value;
 #pragma unroll
-      for (int it = 0; it < ITER; ++it) {
-        const int m = wave + it * NW;
-        if (m < MT && !(a.ablate & 1)) {
-          const float4 v = lut_entry4<DSUB>(sres + m * DSUB, it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0],
-                                            r2.v[m]);
-          *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
+        for (int it = 0; it < ITER; ++it) {
+          const int m = wave + it * NW;
+          if (m < MT) {
+            const float4 v = lut_entry4<DSUB, MODE>(
+                sres + m * DSUB, it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0], sr2[m]);
+            *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
+          }
         }
+      };
+      if (!(a.ablate & 1)) {
+        if (mode == 0) build_rows(std::integral_constant<int, 0>{});
+        else if (mode == 1) build_rows(std::integral_constant<int, 1>{});
+        else build_rows(std::integral_constant<int, 2>{});
       }
     } else {
       const int e = tid & 255;
@@ -592,7 +629,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
         bool keep;
         lut[mu * 256 + e] = lut_entry<DSUB>(sq + mu * dsub, cen + mu * dsub,
                                             a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub,
-                                            r2.v[mu], keep);
+                                            sr2[mu], mode, keep);
       }
     }
     __syncthreads();
@@ -700,6 +737,7 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
                                                   const float *__restrict__ centroids,
                                                   const float *__restrict__ codebooks, int D, int M,
                                                   int dsub_rt, int nlist, int nprobe, RadiiSq r2,
+                                                  const float *__restrict__ query_radii, int mode,
                                                   float *__restrict__ out_lut,
                                                   uint64_t *__restrict__ out_mask) {
   extern __shared__ float sqv[];
@@ -714,8 +752,13 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
   const float *cen = centroids + (int64_t)c * D;
   for (int m = 0; m < M; ++m) {
     bool keep;
+    float rm2 = r2.v[m];
+    if (query_radii) {
+      const float r = query_radii[q * M + m];
+      rm2 = r * r;
+    }
     const float v = lut_entry<DSUB>(sqv + m * dsub, cen + m * dsub,
-                                    codebooks + ((int64_t)m * 256 + e) * dsub, dsub, r2.v[m], keep);
+                                    codebooks + ((int64_t)m * 256 + e) * dsub, dsub, rm2, mode, keep);
     out_lut[(qp * M + m) * 256 + e] = v;
     const unsigned long long bal = __ballot(keep);
     if (out_mask && lane == 0) out_mask[(qp * M + m) * 4 + wave] = bal;
@@ -775,7 +818,7 @@ template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 24 + (size_t)g_scan_lds_pad;
+                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 24 + IVFPQ_MAX_M * 4 + (size_t)g_scan_lds_pad;
   if (lds > 160 * 1024) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
@@ -810,7 +853,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
                 uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
                 const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
-                int32_t *d_errors, hipStream_t s) {
+                int32_t *d_errors, int32_t mode, const float *d_query_radii, hipStream_t s) {
   ScanArgs a;
   a.queries = d_queries;
   a.probe_ids = d_probe_ids;
@@ -837,6 +880,8 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.k = k;
   a.nsplit = nsplit;
   a.ablate = g_scan_ablate;
+  a.mode = mode;
+  a.query_radii = d_query_radii;
   a.load_mode = g_scan_variant;
   const bool dump = d_all_dist != nullptr;
   const int64_t grid = Q * nsplit;
@@ -861,7 +906,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
 
 int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                      const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
-                     hipStream_t s) {
+                     int32_t mode, const float *d_query_radii, hipStream_t s) {
   const int64_t grid = Q * nprobe;
   if (grid > 0x7FFFFFFFll) {
     set_error("build_lut: %lld workgroups exceed the grid limit", (long long)grid);
@@ -871,7 +916,7 @@ int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, i
 #define LUT_LAUNCH(DS)                                                                           \
   hipLaunchKernelGGL(lut_kernel<DS>, dim3((unsigned)grid), dim3(256), lds, s, d_queries,         \
                      d_probe_ids, ix->d_centroids, ix->d_codebooks, ix->D, ix->M, ix->dsub,      \
-                     ix->nlist, nprobe, r2, d_lut, d_mask)
+                     ix->nlist, nprobe, r2, d_query_radii, mode, d_lut, d_mask)
   if (ix->dsub == 2) LUT_LAUNCH(2);
   else if (ix->dsub == 4) LUT_LAUNCH(4);
   else LUT_LAUNCH(0);

@@ -191,6 +191,62 @@ def test_identity_codebook_exact_knn(lib):
     assert np.array_equal(dist.cpu().numpy().astype(np.int64), ref_dist)
 
 
+@pytest.mark.parametrize("name", ["T_gauss", "T_sift", "T_tti"])
+def test_hit_count_scoring_and_per_query_radii(lib, name):
+    """The *_ex entry points: hit-count (mode 1) and reward/penalty (mode 2) scoring, and
+    radii given per query on the device, each against the oracle, every stage."""
+    b = _binding()
+    w = wl.WORKLOADS[name]
+    idx, centres = wl.train_index(w)
+    q = wl.queries(w, centres).numpy()
+    shared = wl.calibrate_radii(w, idx, centres, 0.25)
+    rq = wl.dynamic_radii(w, idx, centres, torch.from_numpy(q), 0.25)
+    gi = b.IvfPqIndex.from_index(idx)
+    dq = _cuda(q)
+    o_pid, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+    offs = cand_offsets(idx, o_pid)
+    for mode in (0, 1, 2):
+        for radii, d_rq in ((shared, None), (rq, _cuda(rq))):
+            kw = dict(mode=mode, query_radii=d_rq)
+            host_r = shared if d_rq is None else None
+            lut, mask = gi.build_lut(dq, _cuda(o_pid), host_r, **kw)
+            o_lut, o_mask = oracle.build_lut(q, idx.centroids, idx.codebooks, o_pid, radii, mode=mode)
+            assert np.array_equal(mask.cpu().numpy().view(np.uint64), o_mask), (mode, d_rq is not None)
+            assert_same_float(lut.cpu().numpy(), o_lut, f"table values mode {mode}")
+            cd, ci, err = gi.scan_all(dq, _cuda(o_pid), host_r, _cuda(offs), **kw)
+            _, o_cd, o_ci = oracle.scan_all(q, idx, o_pid, radii, mode=mode)
+            assert int(err.item()) == 0 and np.array_equal(ci.cpu().numpy(), o_ci)
+            assert_same_float(cd.cpu().numpy(), o_cd, f"candidate scores mode {mode}")
+            o_ids, o_dist = oracle.search(q, idx, w.nprobe, w.k, radii, mode=mode)
+            for ids, dist in (gi.search(dq, w.nprobe, w.k, host_r, **kw),
+                              gi.scan_topk(dq, _cuda(o_pid), w.k, host_r, **kw)):
+                assert np.array_equal(ids.cpu().numpy(), o_ids), (mode, d_rq is not None)
+                assert_same_float(dist.cpu().numpy(), o_dist, f"top-k mode {mode}")
+    with pytest.raises(b.IvfpqError) as e:
+        gi.search(dq, w.nprobe, w.k, shared, mode=3)
+    assert e.value.status == b.ERR_INVALID_ARGUMENT
+    gi.close()
+
+
+def test_hit_count_scoring_1m(lib):
+    """Hit-count scoring on the 1M x 128 configuration (specialised kernel, ties en masse)."""
+    b = _binding()
+    w = wl.WORKLOADS["C2"]
+    idx, centres = wl.train_index(w, device="cuda")
+    q = wl.queries(w, centres).cpu().numpy()
+    radii = wl.calibrate_radii(w, idx, centres, 0.25)
+    rq = wl.dynamic_radii(w, idx, centres, torch.from_numpy(q).cuda(), 0.25)
+    gi = b.IvfPqIndex.from_index(idx)
+    sample = np.random.default_rng(2).choice(w.Q, 32, replace=False)
+    for mode, r, d_rq in ((1, radii, None), (2, radii, None), (0, rq, _cuda(rq)), (2, rq, _cuda(rq))):
+        ids, dist = gi.search(_cuda(q), w.nprobe, w.k, radii if d_rq is None else None, mode=mode, query_radii=d_rq)
+        rs = r if d_rq is None else r[sample]
+        o_ids, o_dist = oracle.search(q[sample], idx, w.nprobe, w.k, rs, threads=8, mode=mode)
+        assert np.array_equal(ids.cpu().numpy()[sample], o_ids), (mode, d_rq is not None)
+        assert_same_float(dist.cpu().numpy()[sample], o_dist, f"C2 mode {mode}")
+    gi.close()
+
+
 def test_coarse_degenerate_centroids(lib):
     """Thousands of identical or nearly identical centroids: the proposal's slack window
     cannot separate them, so the exact fallback and the (distance, list id) tie order

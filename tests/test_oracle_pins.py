@@ -273,6 +273,81 @@ def test_keep_rule_matches_ray_sphere_hits(golden_dir):
 
 
 # ----------------------------------------------------------------------------
+# 5b. hit-count scoring (paper Sec. 5.4) and per-query radii (Sec. 4.1)
+# ----------------------------------------------------------------------------
+
+def test_hit_count_scores_match_their_definition(tiny):
+    """Mode 1: M minus the number of subspaces whose coded entry lies inside the radius.
+    Mode 2: M minus the reward/penalty score (+1 inside the half-radius inner sphere,
+    0 inside the outer sphere only, -1 outside both).  Both from float64 distances."""
+    for name, (w, idx, centres, q) in tiny.items():
+        probes, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+        radii = wl.calibrate_radii(w, idx, centres, 0.25)
+        r = radii.astype(np.float64)[None, :]
+        offs, d1, ids1 = oracle.scan_all(q, idx, probes, radii, mode=1)
+        _, d2m, ids2 = oracle.scan_all(q, idx, probes, radii, mode=2)
+        _, d0, ids0 = oracle.scan_all(q, idx, probes, radii, mode=0)
+        assert np.array_equal(ids1, ids0) and np.array_equal(ids2, ids0)
+        assert np.all(d1 == np.floor(d1)) and np.all(d2m == np.floor(d2m))
+        assert np.all(d1 <= d2m) and np.all(d2m <= d1 + idx.M) and d1.max() <= idx.M and d2m.max() <= 2 * idx.M
+        checked = 0
+        for i in range(q.shape[0]):
+            pos = offs[i]
+            for c in probes[i]:
+                dd = np.sqrt(per_subspace_d2(idx, q[i], c))                 # [n][M] distances
+                n = dd.shape[0]
+                clear = np.all((np.abs(dd - r) > 1e-5 * r) & (np.abs(dd - 0.5 * r) > 1e-5 * r), axis=1)
+                hits = (dd <= r).sum(1)
+                score = (dd <= 0.5 * r).sum(1) - (dd > r).sum(1)
+                assert np.array_equal(d1[pos:pos + n][clear], (idx.M - hits)[clear])
+                assert np.array_equal(d2m[pos:pos + n][clear], (idx.M - score)[clear])
+                checked += int(clear.sum())
+                pos += n
+        assert checked > 1000
+        # the table itself: 0/1 (and 0/1/2) values, consistent with the keep mask of the outer radius
+        lut1, mask1 = oracle.build_lut(q, idx.centroids, idx.codebooks, probes, radii, mode=1)
+        lut2, mask2 = oracle.build_lut(q, idx.centroids, idx.codebooks, probes, radii, mode=2)
+        _, mask0 = oracle.build_lut(q, idx.centroids, idx.codebooks, probes, radii, mode=0)
+        assert np.array_equal(mask1, mask0) and np.array_equal(mask2, mask0)
+        bits = ((mask0[..., None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(bool).reshape(lut1.shape)
+        assert np.array_equal(lut1 == 0.0, bits) and set(np.unique(lut1)) <= {0.0, 1.0}
+        assert np.array_equal(lut2 == 2.0, ~bits) and set(np.unique(lut2)) <= {0.0, 1.0, 2.0}
+        # ranking by the penalty is ranking by the score; ties go to the smaller id
+        ids, dist = oracle.search(q, idx, w.nprobe, w.k, radii, mode=1)
+        for i in range(q.shape[0]):
+            sl = slice(offs[i], offs[i + 1])
+            o = np.lexsort((ids1[sl], d1[sl]))[:w.k]
+            assert np.array_equal(ids[i], ids1[sl][o]) and np.array_equal(dist[i], d1[sl][o])
+
+
+def test_per_query_radii(tiny):
+    """radii[Q][M]: each query is searched as if its own row were the shared radii."""
+    for name, (w, idx, centres, q) in tiny.items():
+        rq = wl.dynamic_radii(w, idx, centres, torch.from_numpy(q), 0.25)
+        assert rq.shape == (q.shape[0], idx.M) and np.all(rq > 0)
+        for mode in (0, 1, 2):
+            ids, dist = oracle.search(q, idx, w.nprobe, w.k, rq, mode=mode)
+            for i in (0, 1, q.shape[0] - 1):
+                ids_i, dist_i = oracle.search(q[i:i + 1], idx, w.nprobe, w.k, rq[i], mode=mode)
+                assert np.array_equal(ids[i], ids_i[0]) and np.array_equal(dist[i], dist_i[0])
+        # a constant per-query array equals the shared form
+        shared = wl.calibrate_radii(w, idx, centres, 0.25)
+        a = oracle.search(q, idx, w.nprobe, w.k, np.tile(shared[None], (q.shape[0], 1)))
+        b = oracle.search(q, idx, w.nprobe, w.k, shared)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        # closed form with per-query radii: truncated sum in float64
+        probes, _ = oracle.coarse(q, idx.centroids, w.nprobe)
+        offs, d, _ = oracle.scan_all(q, idx, probes, rq)
+        for i in range(0, q.shape[0], 7):
+            pos = offs[i]
+            for c in probes[i]:
+                d2 = per_subspace_d2(idx, q[i], c)
+                ref = np.minimum(d2, (rq[i].astype(np.float64) ** 2)[None]).sum(-1)
+                np.testing.assert_allclose(d[pos:pos + d2.shape[0]], ref, rtol=2e-5, atol=1e-30)
+                pos += d2.shape[0]
+
+
+# ----------------------------------------------------------------------------
 # 6. top-k
 # ----------------------------------------------------------------------------
 
