@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", help="C1..C5, C5_10M (default C2: 1M x 128, nprobe 32)")
     ap.add_argument("--keep", type=float, default=0.25, help="fraction of codebook entries inside the radius")
+    ap.add_argument("--score-mode", type=int, default=0,
+                    help="0 distances (default), 1 hit count, 2 reward/penalty hit count")
+    ap.add_argument("--dynamic-radii", action="store_true", help="per-query radii from the density-map recipe")
     ap.add_argument("--scan-waves", type=int, default=0)
     ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 adaptive, 1 whole blocks, 2 first half + rest on demand")
     ap.add_argument("--lds-pad", type=int, default=0, help="measurement only: extra LDS bytes per scan workgroup")
@@ -94,16 +97,20 @@ def main():
     out_dist = torch.empty((Q, k), dtype=torch.float32, device="cuda")
     lib = binding.load_library()
     stream = torch.cuda.current_stream().cuda_stream
-    rptr = radii.ctypes.data
+    d_rq = None
+    if args.dynamic_radii:
+        radii_q = wl.dynamic_radii(w, idx, centres, q, args.keep)
+        d_rq = torch.from_numpy(radii_q).cuda()
+    rptr, scoring, _keep = binding._scoring(args.score_mode, d_rq, None if args.dynamic_radii else radii, Q, w.M)
 
     def step(ev=None):
         binding._check(lib.ivfpq_coarse(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), None, ws.data_ptr(),
                                         ws.numel(), stream))
         if ev:
             ev[0].record()
-        binding._check(lib.ivfpq_scan_topk(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, rptr,
-                                           out_ids.data_ptr(), out_dist.data_ptr(), ws.data_ptr(), ws.numel(),
-                                           stream))
+        binding._check(lib.ivfpq_scan_topk_ex(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, rptr, scoring,
+                                              out_ids.data_ptr(), out_dist.data_ptr(), ws.data_ptr(), ws.numel(),
+                                              stream))
         if ev:
             ev[1].record()
 
@@ -137,7 +144,8 @@ def main():
     achieved = algo_bytes / (scan_avg_ms * 1e-3) / 1e9
 
     # the one-call entry point gives the same answer
-    ids2, dist2 = gi.search(q, nprobe, k, radii, workspace=ws)
+    ids2, dist2 = gi.search(q, nprobe, k, None if args.dynamic_radii else radii, workspace=ws,
+                            mode=args.score_mode, query_radii=d_rq)
     torch.cuda.synchronize()
     assert (args.ablate & 7) or (torch.equal(ids2, out_ids) and torch.equal(dist2, out_dist))
 
@@ -152,12 +160,14 @@ def main():
         "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} D={w.D} nlist={w.nlist} M={w.M} Q={Q} nprobe={nprobe} k={k}",
-                   "family": w.family, "keep_fraction": args.keep, "recall_at_k": recall, "r1_at_k": r1,
+                   "family": w.family, "keep_fraction": args.keep, "score_mode": args.score_mode,
+                   "radii": "per-query (density map)" if args.dynamic_radii else "per-subspace", "recall_at_k": recall, "r1_at_k": r1,
                    "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms,
                    "coarse_exact_fallbacks_per_step": binding.coarse_fallbacks() / max(1, args.steps + 1)},
         "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.keep)),
+                     "traffic": (MEASURED_TRAFFIC_BYTES.get((w.name, args.keep))
+                                 if args.score_mode == 0 and not args.dynamic_radii else None),
                      "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": scan_avg_ms},
     }
 
@@ -167,17 +177,21 @@ def main():
         threads = min(os.cpu_count() or 1, 16)
         t = time.perf_counter()
         probe_n = min(Q, 2 * threads)
-        o_ids, o_dist = oracle.search(qh[:probe_n], idx, nprobe, k, radii, threads=threads)
+        o_radii = radii_q if args.dynamic_radii else radii
+        osearch = lambda lo, hi, th: oracle.search(qh[lo:hi], idx, nprobe, k,
+                                                   o_radii[lo:hi] if args.dynamic_radii else o_radii,
+                                                   threads=th, mode=args.score_mode)
+        o_ids, o_dist = osearch(0, probe_n, threads)
         per_q = (time.perf_counter() - t) / probe_n          # wall seconds per query with all threads
         n = int(max(probe_n, min(Q, args.cpu_seconds / max(per_q, 1e-9))))
         t = time.perf_counter()
-        o_ids, o_dist = oracle.search(qh[:n], idx, nprobe, k, radii, threads=threads)
+        o_ids, o_dist = osearch(0, n, threads)
         dt = time.perf_counter() - t
         same = bool(np.array_equal(o_ids, out_ids.cpu().numpy()[:n]) and
                     np.array_equal(o_dist.view(np.uint32), out_dist.cpu().numpy()[:n].view(np.uint32)))
         n1 = int(max(1, min(n, 3.0 / max(per_q * threads, 1e-9))))
         t = time.perf_counter()
-        oracle.search(qh[:n1], idx, nprobe, k, radii, threads=1)
+        osearch(0, n1, 1)
         dt1 = time.perf_counter() - t
         result["cpu_baseline"] = {"value": n / dt, "unit": "queries/s", "cores": threads, "kind": "oracle",
                                   "sample": f"first {n} of {Q} queries, {threads} threads over disjoint query ranges",
