@@ -153,6 +153,23 @@ def test_shapes_ragged_and_empty_lists(lib, M, D):
     full_check(w, idx, q[:3], r, nprobe=2, k=1)
 
 
+@pytest.mark.parametrize("M,D", [(64, 128), (16, 64), (6, 12)])
+def test_many_probes(lib, M, D):
+    """More probed lists than the kernel stages metadata for at once (64), with and
+    without the probes of a query being split over several workgroups."""
+    rng = np.random.default_rng(5 + M)
+    nlist = 300
+    sizes = rng.integers(0, 90, size=nlist)
+    sizes[::37] = 0
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    w = wl.Workload(f"probes_M{M}", idx.N, D, nlist, M, 0, 150, 100, "gauss", 1, 1.0)
+    r = np.full(M, 0.8 * np.sqrt(D / M), dtype=np.float32)
+    q = rng.normal(size=(3000, D)).astype(np.float32)
+    full_check(w, idx, q[:9], r, nprobe=150, k=100)              # few queries: probes split over workgroups
+    full_check(w, idx, q[:5], r, nprobe=300, k=128)
+    full_check(w, idx, q, r, nprobe=130, k=20, stages=False)     # many queries: one workgroup per query
+
+
 def test_fewer_candidates_than_k_and_empty_probes(lib):
     rng = np.random.default_rng(11)
     sizes = [0, 3, 0, 0, 40, 0, 0, 2]
