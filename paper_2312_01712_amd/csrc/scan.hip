@@ -34,7 +34,8 @@ namespace {
 #define LDS __attribute__((address_space(3)))
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int RES_REGS = 48;  // vector registers a wavefront may devote to resident codebook rows
+constexpr int RES_REGS = 48;  // vector registers a wavefront may devote to resident codebook rows ...
+constexpr int RES_MAX_TOTAL = 82;  // ... as long as they and the two code register sets stay under this
 constexpr int KP = 128;                    // capacity of a wavefront's sorted list
 constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
 constexpr int64_t SENT_ID = LLONG_MAX;
@@ -520,7 +521,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   constexpr bool VEC = MT > 0 && (DSUB == 2 || DSUB == 4);
   constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
   constexpr int DS4 = VEC ? DSUB : 1;
-  constexpr int RES_CAP = RES_REGS / (4 * DS4);
+  constexpr int RES_BUDGET = RES_REGS < RES_MAX_TOTAL - 2 * (MPT / 4) ? RES_REGS : RES_MAX_TOTAL - 2 * (MPT / 4);
+  constexpr int RES_CAP = (RES_BUDGET > 0 ? RES_BUDGET : 0) / (4 * DS4);
   constexpr int RES = !VEC ? 0 : (ITER < RES_CAP ? ITER : RES_CAP);
   constexpr int STR = VEC ? ITER - RES : 0;
   float4 cbr[RES > 0 ? RES : 1][DS4];
