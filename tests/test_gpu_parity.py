@@ -181,6 +181,18 @@ def test_fewer_candidates_than_k_and_empty_probes(lib):
     full_check(w, idx, q, np.full(8, 0.5, np.float32), nprobe=1, k=10)
 
 
+def test_empty_index_and_single_point(lib):
+    """N = 0 (every list empty) and N = 1."""
+    rng = np.random.default_rng(13)
+    for sizes in ([0, 0, 0, 0], [0, 0, 1, 0]):
+        for M, D in ((64, 128), (5, 10)):
+            idx = _random_index(rng, 0, D, len(sizes), M, sizes)
+            q = rng.normal(size=(6, D)).astype(np.float32)
+            w = wl.Workload("empty", idx.N, D, idx.nlist, M, 6, 3, 10, "gauss", 1, 1.0)
+            o_ids = full_check(w, idx, q, np.full(M, 1.0, np.float32))
+            assert (o_ids[:, 1:] == -1).all()
+
+
 def test_saturated_ties_resolved_by_id(lib):
     """Radius 0 clamps every entry to 0, so every candidate ties at distance 0 and
     the k smallest ids must win; small radii saturate most candidates at sum r_m^2."""
