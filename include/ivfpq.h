@@ -29,8 +29,12 @@
  *   - Return value: IVFPQ_OK or a negative ivfpq_status.  On an argument error
  *     nothing is enqueued and no output is written.  ivfpq_last_error() gives a
  *     text for the last failure on the calling thread.
- *   - Limits: ksub == 256; D % M == 0; M <= 128; 1 <= k <= 128;
+ *   - Limits: ksub == 256; D % M == 0; M <= 128; 1 <= k <= 1024;
  *     1 <= nprobe <= min(nlist, 1024); N < 2^32; radii finite >= 0 or +inf.
+ *   - k > 128 (the paper's second quality metric retrieves 1000 neighbours,
+ *     Sec. 6.1) is served 128 results at a time: ceil(k / 128) passes over the
+ *     probed lists, each keeping the keys after the last (distance, id) of the
+ *     pass before.  For that the ids of the index must be distinct and >= 0.
  *   - NaN in queries or in the index gives unspecified (but in-bounds) results.
  */
 #ifndef IVFPQ_H
@@ -54,7 +58,7 @@ typedef enum {
 
 #define IVFPQ_KSUB 256
 #define IVFPQ_MAX_M 128
-#define IVFPQ_MAX_K 128
+#define IVFPQ_MAX_K 1024
 #define IVFPQ_MAX_NPROBE 1024
 
 typedef struct ivfpq_index ivfpq_index; /* opaque; owns its device copies */

@@ -198,6 +198,7 @@ struct ScanArgs {
   int64_t *all_ids;             // (DUMP)
   int32_t *errors;              // (DUMP)
   int32_t D, M, dsub, Mp, nlist, nprobe, k, nsplit;
+  int32_t k_out, k_off;  // rows of the outputs hold k_out keys; this launch fills [k_off, k_off + k)
   const float *query_radii;     // [Q][M] per-query radii, or NULL: the shared r_m^2 of the call
   int32_t mode;       // scoring: 0 distances, 1 hit count, 2 reward/penalty hit count
   int32_t load_mode;  // 0 adaptive, 1 whole blocks, 2 first half of the chunks, rest on demand
@@ -308,6 +309,7 @@ __device__ inline float adc_sum_rt(const LDS float *lut, const uint8_t *__restri
 struct WaveTop {
   Key L0, L1;       // sorted list, 2 keys per lane
   Key tau;          // k-th best so far (sentinel while fewer than k are known)
+  Key floor;        // only keys above this one are wanted (the last key of the previous pass)
   int qcount;       // keys waiting in the LDS queue
 };
 
@@ -365,7 +367,7 @@ __device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, 
   Key c;
   c.d = bits;
   c.id = pass ? ids[row] : SENT_ID;
-  pass = pass && kless(c, st.tau);
+  pass = pass && kless(c, st.tau) && kless(st.floor, c);
   unsigned long long bal = __ballot(pass);
   int n = __popcll(bal);
   if (n == 0) return;
@@ -423,8 +425,9 @@ __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS i
         const int i = h * 64 + lane;
         if (i < a.k) {
           const bool real = e.d != SENT_D;
-          a.out_ids[q * a.k + i] = real ? e.id : -1;
-          a.out_dist[q * a.k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+          const int64_t o = q * a.k_out + a.k_off + i;
+          a.out_ids[o] = real ? e.id : -1;
+          a.out_dist[o] = real ? __uint_as_float(e.d) : __builtin_inff();
         }
       }
     }
@@ -510,6 +513,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   st.tau.d = SENT_D;
   st.tau.id = SENT_ID;
   st.qcount = 0;
+  // More than KP keys per query are produced KP at a time: a later pass keeps only the
+  // keys above the last one of the pass before it (which that pass has already written).
+  st.floor.d = 0u;
+  st.floor.id = INT64_MIN;
+  if (!DUMP && a.k_off > 0) {
+    const int64_t o = q * a.k_out + a.k_off - 1;
+    const int64_t fid = a.out_ids[o];
+    const uint32_t fd = fid == -1 ? SENT_D : __float_as_uint(a.out_dist[o]);  // -1: nothing is left
+    st.floor.d = __builtin_amdgcn_readfirstlane(fd);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)fid);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)fid >> 32));
+    st.floor.id = (int64_t)(((uint64_t)hi << 32) | lo);
+  }
   LDS uint32_t *qd = queue_d + wave * 64;
   LDS int64_t *qid = queue_id + wave * 64;
 
@@ -702,7 +718,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // Merge the probe groups' partial lists of a query (one wavefront per query).
 __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ part_d,
                                                    const int64_t *__restrict__ part_id, int nsplit,
-                                                   int k, int64_t *__restrict__ out_ids,
+                                                   int k, int k_out, int k_off,
+                                                   int64_t *__restrict__ out_ids,
                                                    float *__restrict__ out_dist) {
   const int lane = threadIdx.x;
   const int64_t q = blockIdx.x;
@@ -725,8 +742,8 @@ __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ 
     const int i = h * 64 + lane;
     if (i < k) {
       const bool real = e.d != SENT_D;
-      out_ids[q * k + i] = real ? e.id : -1;
-      out_dist[q * k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+      out_ids[q * k_out + k_off + i] = real ? e.id : -1;
+      out_dist[q * k_out + k_off + i] = real ? __uint_as_float(e.d) : __builtin_inff();
     }
   }
 }
@@ -879,7 +896,6 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.Mp = ix->Mp;
   a.nlist = ix->nlist;
   a.nprobe = nprobe;
-  a.k = k;
   a.nsplit = nsplit;
   a.ablate = g_scan_ablate;
   a.mode = mode;
@@ -891,17 +907,25 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
     set_error("scan: %lld workgroups exceed the grid limit", (long long)grid);
     return IVFPQ_ERR_UNSUPPORTED;
   }
-  int rc;
   const int M = ix->M, ds = ix->dsub;
-  if (M == 64 && ds == 2) rc = launch_scan_nw<64, 2>(a, r2, grid, dump, s);
-  else if (M == 48 && ds == 2) rc = launch_scan_nw<48, 2>(a, r2, grid, dump, s);
-  else if (M == 100 && ds == 2) rc = launch_scan_nw<100, 2>(a, r2, grid, dump, s);
-  else if (M == 16 && ds == 4) rc = launch_scan_nw<16, 4>(a, r2, grid, dump, s);
-  else rc = launch_scan_nw<0, 0>(a, r2, grid, dump, s);
-  if (rc != IVFPQ_OK) return rc;
-  if (nsplit > 1 && !dump)
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)Q), dim3(64), 0, s, d_part_d, d_part_id, nsplit, k,
-                       d_out_ids, d_out_dist);
+  // A wavefront's sorted list holds KP keys, so k > KP takes ceil(k / KP) passes over the
+  // lists; pass j keeps the keys above the last key pass j - 1 wrote.
+  a.k_out = k;
+  for (int32_t off = 0; off == 0 || off < k; off += KP) {
+    a.k_off = off;
+    a.k = k - off < KP ? k - off : KP;
+    int rc;
+    if (M == 64 && ds == 2) rc = launch_scan_nw<64, 2>(a, r2, grid, dump, s);
+    else if (M == 48 && ds == 2) rc = launch_scan_nw<48, 2>(a, r2, grid, dump, s);
+    else if (M == 100 && ds == 2) rc = launch_scan_nw<100, 2>(a, r2, grid, dump, s);
+    else if (M == 16 && ds == 4) rc = launch_scan_nw<16, 4>(a, r2, grid, dump, s);
+    else rc = launch_scan_nw<0, 0>(a, r2, grid, dump, s);
+    if (rc != IVFPQ_OK) return rc;
+    if (dump) break;
+    if (nsplit > 1)
+      hipLaunchKernelGGL(merge_kernel, dim3((unsigned)Q), dim3(64), 0, s, d_part_d, d_part_id, nsplit, a.k,
+                         a.k_out, a.k_off, d_out_ids, d_out_dist);
+  }
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;
 }

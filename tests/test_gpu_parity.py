@@ -170,6 +170,44 @@ def test_many_probes(lib, M, D):
     full_check(w, idx, q, r, nprobe=130, k=20, stages=False)     # many queries: one workgroup per query
 
 
+@pytest.mark.parametrize("M,D", [(64, 128), (16, 64), (6, 12)])
+def test_more_than_128_neighbours(lib, M, D):
+    """k above what one pass of the kernel keeps per query (128): results come from
+    several passes and must still be the oracle's, including ties that straddle a
+    pass boundary, fewer candidates than k, and hit-count scores."""
+    b = _binding()
+    rng = np.random.default_rng(77 + M)
+    nlist = 24
+    sizes = rng.integers(40, 400, size=nlist)
+    sizes[3] = 0
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    w = wl.Workload(f"bigk_M{M}", idx.N, D, nlist, M, 0, 8, 1000, "gauss", 1, 1.0)
+    r = np.full(M, 0.8 * np.sqrt(D / M), dtype=np.float32)
+    q = rng.normal(size=(2100, D)).astype(np.float32)
+    for k in (129, 256, 1000, 1024):
+        full_check(w, idx, q[:7], r, nprobe=8, k=k, stages=(k == 1000))   # probes split over workgroups
+    full_check(w, idx, q, r, nprobe=6, k=300, stages=False)               # one workgroup per query
+    full_check(w, idx, q[:5], np.zeros(M, np.float32), nprobe=8, k=700, stages=False)  # every candidate ties at 0
+    o_ids = full_check(w, idx, q[:9], r, nprobe=1, k=1000, stages=False)               # one list: < k candidates
+    assert (o_ids == -1).any()
+    # candidates end inside the first pass, and exactly at its end
+    for n_first in (100, 128):
+        idx2 = _random_index(rng, 0, D, 4, M, [n_first, 0, 0, 0])
+        idx2.centroids[0] = 0.0
+        idx2.centroids[1:] = 50.0
+        w2 = wl.Workload("bigk_short", idx2.N, D, 4, M, 0, 1, 400, "gauss", 1, 1.0)
+        o_ids = full_check(w2, idx2, (0.01 * q[:4]).astype(np.float32), r, nprobe=1, k=400, stages=False)
+        assert (o_ids[:, :n_first] >= 0).all() and (o_ids[:, n_first:] == -1).all()
+    # hit-count scores: a few distinct values, ties everywhere
+    gi = b.IvfPqIndex.from_index(idx)
+    for Q in (6, 2100):
+        o_ids, o_dist = oracle.search(q[:Q], idx, 8, 500, r, threads=8, mode=1)
+        ids, dist = gi.search(_cuda(q[:Q]), 8, 500, r, mode=1)
+        assert np.array_equal(ids.cpu().numpy(), o_ids), Q
+        assert_same_float(dist.cpu().numpy(), o_dist, f"hit counts, k=500, Q={Q}")
+    gi.close()
+
+
 def test_fewer_candidates_than_k_and_empty_probes(lib):
     rng = np.random.default_rng(11)
     sizes = [0, 3, 0, 0, 40, 0, 0, 2]
@@ -345,7 +383,7 @@ def test_argument_errors(lib):
         (dict(nprobe=0, k=5, radii=ok), b.ERR_INVALID_ARGUMENT),
         (dict(nprobe=idx.nlist + 1, k=5, radii=ok), b.ERR_INVALID_ARGUMENT),
         (dict(nprobe=2, k=0, radii=ok), b.ERR_INVALID_ARGUMENT),
-        (dict(nprobe=2, k=129, radii=ok), b.ERR_UNSUPPORTED),
+        (dict(nprobe=2, k=1025, radii=ok), b.ERR_UNSUPPORTED),
         (dict(nprobe=2, k=5, radii=np.full(idx.M, -1.0, np.float32)), b.ERR_INVALID_ARGUMENT),
         (dict(nprobe=2, k=5, radii=np.full(idx.M, np.nan, np.float32)), b.ERR_INVALID_ARGUMENT),
         (dict(nprobe=2, k=5, radii=ok, workspace=torch.empty(256, dtype=torch.uint8, device="cuda")), b.ERR_WORKSPACE),
