@@ -34,8 +34,15 @@ namespace {
 #define LDS __attribute__((address_space(3)))
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int RES_REGS = 48;  // vector registers a wavefront may devote to resident codebook rows ...
-constexpr int RES_MAX_TOTAL = 82;  // ... as long as they and the two code register sets stay under this
+// Wavefronts per SIMD the scan kernel is compiled for: 4 (two 8-wave workgroups per CU, 128
+// vector registers each).  Tables of more than 72 KiB allow one workgroup per CU anyway;
+// with at most 8 wavefronts in it each SIMD holds 2 and a wavefront may use 256 registers,
+// enough to keep every codebook row it needs resident.
+constexpr int scan_wpe(int mt, int nw) { return mt > 72 && nw <= 8 ? 2 : 4; }
+// Vector registers a wavefront may devote to resident codebook rows ...
+constexpr int res_regs(int wpe) { return wpe == 2 ? 112 : 48; }
+// ... as long as they and the two code register sets stay under this.
+constexpr int res_max_total(int wpe) { return wpe == 2 ? 200 : 82; }
 constexpr int KP = 128;                    // capacity of a wavefront's sorted list
 constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
 constexpr int64_t SENT_ID = LLONG_MAX;
@@ -434,10 +441,8 @@ __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS i
   }
 }
 
-// At least 4 wavefronts per SIMD (two 8-wave workgroups or one 16-wave workgroup
-// per CU), i.e. at most 128 vector registers.
 template <int MT, int DSUB, int NW, bool DUMP>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) void scan_kernel(ScanArgs a, RadiiSq r2) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wpe(MT, NW)))) void scan_kernel(ScanArgs a, RadiiSq r2) {
   constexpr int NT = NW * 64;
   constexpr int MPT = (MT + 3) / 4 * 4;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -537,6 +542,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   constexpr bool VEC = MT > 0 && (DSUB == 2 || DSUB == 4);
   constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
   constexpr int DS4 = VEC ? DSUB : 1;
+  constexpr int WPE = scan_wpe(MT, NW);
+  constexpr int RES_REGS = res_regs(WPE), RES_MAX_TOTAL = res_max_total(WPE);
   constexpr int RES_BUDGET = RES_REGS < RES_MAX_TOTAL - 2 * (MPT / 4) ? RES_REGS : RES_MAX_TOTAL - 2 * (MPT / 4);
   constexpr int RES_CAP = (RES_BUDGET > 0 ? RES_BUDGET : 0) / (4 * DS4);
   constexpr int RES = !VEC ? 0 : (ITER < RES_CAP ? ITER : RES_CAP);
@@ -853,7 +860,9 @@ int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump,
 template <int MT, int DSUB>
 int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   int nw = g_scan_waves;
-  if (nw == 0) nw = a.M > 72 ? 16 : 8;
+  // One workgroup per CU once the table passes 72 KiB: the specialised kernels then run 8
+  // wavefronts with twice the registers, the run-time-M kernel (few registers) runs 16.
+  if (nw == 0) nw = (MT == 0 && a.M > 72) ? 16 : 8;
   if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
   if (nw >= 8) return launch_scan_t<MT, DSUB, 8>(a, r2, grid, dump, s);
   return launch_scan_t<MT, DSUB, 4>(a, r2, grid, dump, s);
