@@ -344,6 +344,35 @@ def test_coarse_degenerate_centroids(lib):
         say(f"  coarse, {name}: ok")
 
 
+def test_query_chunks_large_nlist(lib):
+    """So many lists that the coarse scores of all queries exceed the 1 GiB the planner allows
+    at once: the queries go through coarse quantisation in several chunks."""
+    rng = np.random.default_rng(31)
+    D, M, nlist, Q = 8, 4, 70001, 4200     # 3712 queries fit the first chunk
+    sizes = np.zeros(nlist, dtype=np.int64)
+    sizes[rng.permutation(nlist)[:40000]] = 1
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    q = rng.normal(size=(Q, D)).astype(np.float32)
+    b = _binding()
+    gi = b.IvfPqIndex.from_index(idx)
+    assert gi.workspace_bytes(Q, 7, 5) < (1 << 30) + 16 * Q * 7 + 4096
+    from concurrent.futures import ThreadPoolExecutor
+    cuts = np.linspace(0, Q, 9).astype(int)
+    with ThreadPoolExecutor(8) as ex:   # the oracle routine is single-threaded; ctypes releases the GIL
+        parts = list(ex.map(lambda i: oracle.coarse(q[cuts[i]:cuts[i + 1]], idx.centroids, 7), range(8)))
+    o_pid, o_pd = np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+    pid, pd = gi.coarse(_cuda(q), 7)
+    torch.cuda.synchronize()
+    assert np.array_equal(pid.cpu().numpy(), o_pid)
+    assert_same_float(pd.cpu().numpy(), o_pd, "probe distances, chunked queries")
+    r = np.full(M, 1.0, np.float32)
+    o_ids, o_dist = oracle.search(q, idx, 7, 5, r, threads=8)
+    ids, dist = gi.search(_cuda(q), 7, 5, r)
+    assert np.array_equal(ids.cpu().numpy(), o_ids)
+    assert_same_float(dist.cpu().numpy(), o_dist, "top-k, chunked queries")
+    gi.close()
+
+
 def test_batch_sizes_and_probe_groups(lib):
     """Q = 1, 2, 100, 3000: small batches split the probes of a query over several
     workgroups and merge; results must not depend on that."""
