@@ -54,13 +54,13 @@ def _f32(a):
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
-def coarse(queries, centroids, nprobe: int) -> Tuple[np.ndarray, np.ndarray]:
+def coarse(queries, centroids, nprobe: int, metric: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     q, c = _f32(queries), _f32(centroids)
     Q, D = q.shape
     ids = np.empty((Q, nprobe), dtype=np.int32)
     dist = np.empty((Q, nprobe), dtype=np.float32)
     rc = _load().oracle_coarse(ctypes.c_int64(Q), D, c.shape[0], _p(q, _f32p), _p(c, _f32p), nprobe,
-                               _p(ids, _i32p), _p(dist, _f32p))
+                               metric, _p(ids, _i32p), _p(dist, _f32p))
     if rc:
         raise ValueError("oracle_coarse: invalid argument")
     return ids, dist
@@ -75,7 +75,8 @@ def _stride(r: np.ndarray, Q: int, M: int) -> int:
     raise ValueError(f"radii must have shape ({M},) or ({Q}, {M})")
 
 
-def build_lut(queries, centroids, codebooks, probe_ids, radii, mode: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+def build_lut(queries, centroids, codebooks, probe_ids, radii, mode: int = 0,
+              metric: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     q, c, cb, r = _f32(queries), _f32(centroids), _f32(codebooks), _f32(radii)
     pid = np.ascontiguousarray(probe_ids, dtype=np.int32)
     Q, D = q.shape
@@ -84,14 +85,15 @@ def build_lut(queries, centroids, codebooks, probe_ids, radii, mode: int = 0) ->
     lut = np.empty((Q, nprobe, M, 256), dtype=np.float32)
     mask = np.empty((Q, nprobe, M, 4), dtype=np.uint64)
     rc = _load().oracle_build_lut(ctypes.c_int64(Q), D, M, _p(q, _f32p), _p(c, _f32p), _p(cb, _f32p),
-                                  _p(pid, _i32p), nprobe, _p(r, _f32p), _stride(r, Q, M), mode, _p(lut, _f32p),
-                                  _p(mask, _u64p))
+                                  _p(pid, _i32p), nprobe, _p(r, _f32p), _stride(r, Q, M), mode, metric,
+                                  _p(lut, _f32p), _p(mask, _u64p))
     if rc:
         raise ValueError("oracle_build_lut: invalid argument")
     return lut, mask
 
 
-def scan_all(queries, index, probe_ids, radii, mode: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def scan_all(queries, index, probe_ids, radii, mode: int = 0,
+             metric: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """(cand_offsets [Q+1], dist [total], ids [total]) for every candidate."""
     q, r = _f32(queries), _f32(radii)
     pid = np.ascontiguousarray(probe_ids, dtype=np.int32)
@@ -102,7 +104,8 @@ def scan_all(queries, index, probe_ids, radii, mode: int = 0) -> Tuple[np.ndarra
     args = lambda d, i: (ctypes.c_int64(Q), D, index.M, _p(q, _f32p), _p(index.centroids, _f32p),
                          _p(index.codebooks, _f32p), _p(index.list_offsets, _i64p),
                          _p(index.codes, _u8p), _p(index.ids, _i64p), _p(pid, _i32p), nprobe,
-                         _p(r, _f32p), _stride(r, Q, index.M), mode, _p(offs, _i64p), _p(d, _f32p), _p(i, _i64p))
+                         _p(r, _f32p), _stride(r, Q, index.M), mode, metric, _p(offs, _i64p), _p(d, _f32p),
+                         _p(i, _i64p))
     if lib.oracle_scan_all(*args(None, None)):
         raise ValueError("oracle_scan_all: invalid argument")
     total = int(offs[Q])
@@ -123,7 +126,8 @@ def topk(dist, ids, k: int) -> Tuple[np.ndarray, np.ndarray]:
 
 
 def search(queries, index, nprobe: int, k: int, radii, threads: int = 1,
-           q_range: Optional[Tuple[int, int]] = None, mode: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+           q_range: Optional[Tuple[int, int]] = None, mode: int = 0,
+           metric: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Whole search path.  threads > 1 runs the same single-threaded routine on
     disjoint query ranges from Python threads (ctypes releases the GIL)."""
     q, r = _f32(queries), _f32(radii)
@@ -137,7 +141,7 @@ def search(queries, index, nprobe: int, k: int, radii, threads: int = 1,
         rc = lib.oracle_search(ctypes.c_int64(a), ctypes.c_int64(b), D, index.nlist, index.M,
                                _p(q, _f32p), _p(index.centroids, _f32p), _p(index.codebooks, _f32p),
                                _p(index.list_offsets, _i64p), _p(index.codes, _u8p),
-                               _p(index.ids, _i64p), nprobe, k, _p(r, _f32p), _stride(r, Q, index.M), mode,
+                               _p(index.ids, _i64p), nprobe, k, _p(r, _f32p), _stride(r, Q, index.M), mode, metric,
                                _p(out_ids, _i64p), _p(out_dist, _f32p))
         if rc:
             raise ValueError("oracle_search: invalid argument")
@@ -152,12 +156,12 @@ def search(queries, index, nprobe: int, k: int, radii, threads: int = 1,
     return out_ids, out_dist
 
 
-def exact_knn(base, queries, k: int) -> Tuple[np.ndarray, np.ndarray]:
+def exact_knn(base, queries, k: int, metric: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     b, q = _f32(base), _f32(queries)
     N, D = b.shape
     Q = q.shape[0]
     oi = np.empty((Q, k), dtype=np.int64)
     od = np.empty((Q, k), dtype=np.float64)
     _load().oracle_exact_knn(ctypes.c_int64(N), D, _p(b, _f32p), ctypes.c_int64(Q), _p(q, _f32p), k,
-                             _p(oi, _i64p), _p(od, _f64p))
+                             metric, _p(oi, _i64p), _p(od, _f64p))
     return oi, od

@@ -34,8 +34,21 @@
 //       Rankings are those of the paper's scores; ties go to the smaller id;
 //   R15 a per-query radius (Sec. 4.1 "Determining Proper Threshold": query-specific
 //       thresholds times a user scale) is an input array radii[Q][M]; how it is
-//       derived from densities is outside the search path.
+//       derived from densities is outside the search path;
+//   R16 inner-product metric (Sec. 4.2 "Inner Product Similarity Support").  The
+//       paper enlarges the sphere of entry e to R'^2 = R^2 + |e|^2 and shoots the ray
+//       from the projection of the QUERY (its x_q, y_q are constant per query, so not
+//       a residual).  The ray hits iff |q_m - e|^2 <= r_m^2 + |e|^2, which is the same
+//       as IP(e, q_m) >= (|q_m|^2 - r_m^2) / 2 =: thr_m, the form used here (no
+//       subtraction of nearly equal squares).  A kept entry stores -IP (smaller is
+//       better in every mode), a missed one the bound -thr_m it cannot beat, which is
+//       what the clamp r_m^2 is under L2 (R1).  The table depends on the query only;
+//       a point of list c scores -IP(q, centroid_c) plus the sum of its table values,
+//       i.e. minus the inner product of q with the point's reconstruction, and lists
+//       are filtered by the same -IP(q, centroid).  For the hit-count modes the inner
+//       sphere is the same construction with r_m / 2;
 //
+// Metric: 0 = squared L2, 1 = inner product (R16).
 // Scoring modes: 0 = distances (the paper's JUNO-H), 1 = hit count (JUNO-L),
 // 2 = reward/penalty hit count (JUNO-M).  radii_stride = 0 means one radii[M] for all
 // queries, radii_stride = M means radii[Q][M].
@@ -45,7 +58,11 @@
 // closed form and monotonicity of the thresholded one, the paper's ray/sphere
 // formulation of the keep rule (t_hit <= t_max) with its printed 0.6/0.8/0.64
 // example, argmin / full-permutation cases of the coarse stage, and
-// sort-based selection for top-k.  No function here is "parity unpinned".
+// sort-based selection for top-k; for the inner-product metric the enlarged-sphere
+// form of the keep rule, the identity IP = (|e|^2 + |q|^2 - L2^2) / 2 against the L2
+// table, reconstruction of -IP by the unthresholded sum, and brute-force maximum
+// inner product search on identity-codebook indexes.  No function here is "parity
+// unpinned".
 
 #include <algorithm>
 #include <cmath>
@@ -72,18 +89,28 @@ inline bool cand_less(const Cand& a, const Cand& b) {
 // distance from the query to every IVF centroid, then the nprobe closest.
 // Distance: t = q_i - c_i, acc = fmaf(t, t, acc), i ascending, acc0 = 0.
 // Order of the result: (distance, list id) ascending.
-void coarse_one(const float* q, int D, const float* centroids, int nlist, int nprobe,
-                int32_t* out_ids, float* out_dist) {
-  std::vector<std::pair<float, int32_t>> d(nlist);
-  for (int c = 0; c < nlist; ++c) {
-    const float* cen = centroids + (size_t)c * D;
-    float acc = 0.0f;
-    for (int i = 0; i < D; ++i) {
+//
+// Inner-product metric (R16): the score of a list is minus the inner product of the
+// query with its centroid, acc = fmaf(q_i, c_i, acc), i ascending, acc0 = 0; "minus"
+// is written 0 - acc here and in the table, so that no score is a negative zero (which
+// would compare equal to +0 but differ in bits).
+inline float list_score(const float* q, const float* cen, int D, int metric) {
+  float acc = 0.0f;
+  for (int i = 0; i < D; ++i) {
+    if (metric == 0) {
       float t = q[i] - cen[i];
       acc = std::fmaf(t, t, acc);
+    } else {
+      acc = std::fmaf(q[i], cen[i], acc);
     }
-    d[c] = {acc, c};
   }
+  return metric == 0 ? acc : 0.0f - acc;
+}
+
+void coarse_one(const float* q, int D, const float* centroids, int nlist, int nprobe, int metric,
+                int32_t* out_ids, float* out_dist) {
+  std::vector<std::pair<float, int32_t>> d(nlist);
+  for (int c = 0; c < nlist; ++c) d[c] = {list_score(q, centroids + (size_t)c * D, D, metric), c};
   std::sort(d.begin(), d.end());
   for (int p = 0; p < nprobe; ++p) {
     out_ids[p] = d[p].second;
@@ -127,13 +154,59 @@ void lut_one(const float* q, const float* cen, int D, int M, const float* codebo
   }
 }
 
+// The same table under the inner-product metric (paper Sec. 4.2, R16), for one query
+// (it does not depend on the list): for every subspace m and entry e, with q_m the
+// query's projection,
+//   qq   = q_m0*q_m0, then qq = fmaf(q_mj, q_mj, qq)
+//   thr  = 0.5 * (qq - r_m^2)
+//   ip   = q_m0*e_0, then ip = fmaf(q_mj, e_j, ip)
+//   keep = ip >= thr          (the ray from q_m hits the sphere of radius sqrt(r_m^2 + |e|^2))
+//   lut[m][e] = keep ? 0 - ip : 0 - thr
+// Hit-count modes: mode 1 stores 0 / 1 for kept / missed; mode 2 uses the inner
+// threshold thr_in = 0.5 * (qq - r_m^2 / 4): 0 if ip >= thr_in, else 1 if kept, else 2.
+void lut_one_ip(const float* q, int D, int M, const float* codebooks, const float* radii, int mode,
+                float* lut, uint64_t* mask) {
+  const int dsub = D / M;
+  for (int m = 0; m < M; ++m) {
+    const float* qm = q + m * dsub;
+    const float r2 = radii[m] * radii[m];
+    float qq = 0.0f;
+    for (int j = 0; j < dsub; ++j) qq = (j == 0) ? qm[j] * qm[j] : std::fmaf(qm[j], qm[j], qq);
+    const float thr = 0.5f * (qq - r2);
+    const float thr_in = 0.5f * (qq - 0.25f * r2);
+    if (mask) for (int w = 0; w < 4; ++w) mask[m * 4 + w] = 0;
+    for (int e = 0; e < E; ++e) {
+      const float* cb = codebooks + ((size_t)m * E + e) * dsub;
+      float ip = 0.0f;
+      for (int j = 0; j < dsub; ++j) ip = (j == 0) ? qm[j] * cb[j] : std::fmaf(qm[j], cb[j], ip);
+      const bool keep = ip >= thr;
+      if (mode == 0) lut[m * E + e] = keep ? 0.0f - ip : 0.0f - thr;
+      else if (mode == 1) lut[m * E + e] = keep ? 0.0f : 1.0f;
+      else lut[m * E + e] = ip >= thr_in ? 0.0f : (keep ? 1.0f : 2.0f);
+      if (mask && keep) mask[m * 4 + (e >> 6)] |= (uint64_t)1 << (e & 63);
+    }
+  }
+}
+
+// Table of (query, list) under either metric.
+void lut_any(const float* q, const float* cen, int D, int M, const float* codebooks,
+             const float* radii, int mode, int metric, float* lut, uint64_t* mask) {
+  if (metric == 0) lut_one(q, cen, D, M, codebooks, radii, mode, lut, mask);
+  else lut_one_ip(q, D, M, codebooks, radii, mode, lut, mask);
+}
+
 // Distance calculation (paper Sec. 2.1 step D; Sec. 5.3): the distance of an
 // encoded point is the sum over subspaces of the table value of its code,
-// fp32, m ascending, starting from 0.
-inline float adc_one(const float* lut, const uint8_t* code, int M) {
-  float dist = 0.0f;
+// fp32, m ascending, starting from `start`: 0 under L2 and for the hit counts; under
+// the inner-product metric with mode 0 the list's score -IP(q, centroid) (R16).
+inline float adc_one(const float* lut, const uint8_t* code, int M, float start) {
+  float dist = start;
   for (int m = 0; m < M; ++m) dist += lut[m * E + code[m]];
   return dist;
+}
+
+inline float adc_start(const float* q, const float* cen, int D, int mode, int metric) {
+  return (metric == 1 && mode == 0) ? list_score(q, cen, D, 1) : 0.0f;
 }
 
 // Top-k (paper Sec. 2.1, last paragraph of "Online Search"): the k smallest by
@@ -158,10 +231,11 @@ extern "C" {
 
 // Batched filtering stage.  out_ids [Q][nprobe], out_dist [Q][nprobe] (may be null).
 int oracle_coarse(int64_t Q, int32_t D, int32_t nlist, const float* queries,
-                  const float* centroids, int32_t nprobe, int32_t* out_ids, float* out_dist) {
-  if (nprobe > nlist || nprobe < 1) return -1;
+                  const float* centroids, int32_t nprobe, int32_t metric, int32_t* out_ids,
+                  float* out_dist) {
+  if (nprobe > nlist || nprobe < 1 || metric < 0 || metric > 1) return -1;
   for (int64_t q = 0; q < Q; ++q)
-    coarse_one(queries + q * D, D, centroids, nlist, nprobe, out_ids + q * nprobe,
+    coarse_one(queries + q * D, D, centroids, nlist, nprobe, metric, out_ids + q * nprobe,
                out_dist ? out_dist + q * nprobe : nullptr);
   return 0;
 }
@@ -170,14 +244,16 @@ int oracle_coarse(int64_t Q, int32_t D, int32_t nlist, const float* queries,
 // out_mask [Q][nprobe][M][4] uint64 (may be null).
 int oracle_build_lut(int64_t Q, int32_t D, int32_t M, const float* queries, const float* centroids,
                      const float* codebooks, const int32_t* probe_ids, int32_t nprobe,
-                     const float* radii, int32_t radii_stride, int32_t mode, float* out_lut,
-                     uint64_t* out_mask) {
-  if (D % M || mode < 0 || mode > 2 || (radii_stride != 0 && radii_stride != M)) return -1;
+                     const float* radii, int32_t radii_stride, int32_t mode, int32_t metric,
+                     float* out_lut, uint64_t* out_mask) {
+  if (D % M || mode < 0 || mode > 2 || metric < 0 || metric > 1 ||
+      (radii_stride != 0 && radii_stride != M))
+    return -1;
   for (int64_t q = 0; q < Q; ++q)
     for (int p = 0; p < nprobe; ++p) {
       const size_t row = (size_t)q * nprobe + p;
-      lut_one(queries + q * D, centroids + (size_t)probe_ids[row] * D, D, M, codebooks,
-              radii + q * radii_stride, mode, out_lut + row * M * E,
+      lut_any(queries + q * D, centroids + (size_t)probe_ids[row] * D, D, M, codebooks,
+              radii + q * radii_stride, mode, metric, out_lut + row * M * E,
               out_mask ? out_mask + row * M * 4 : nullptr);
     }
   return 0;
@@ -190,9 +266,11 @@ int oracle_build_lut(int64_t Q, int32_t D, int32_t M, const float* queries, cons
 int oracle_scan_all(int64_t Q, int32_t D, int32_t M, const float* queries, const float* centroids,
                     const float* codebooks, const int64_t* list_offsets, const uint8_t* codes,
                     const int64_t* ids, const int32_t* probe_ids, int32_t nprobe,
-                    const float* radii, int32_t radii_stride, int32_t mode, int64_t* cand_offsets,
-                    float* out_dist, int64_t* out_ids) {
-  if (D % M || mode < 0 || mode > 2 || (radii_stride != 0 && radii_stride != M)) return -1;
+                    const float* radii, int32_t radii_stride, int32_t mode, int32_t metric,
+                    int64_t* cand_offsets, float* out_dist, int64_t* out_ids) {
+  if (D % M || mode < 0 || mode > 2 || metric < 0 || metric > 1 ||
+      (radii_stride != 0 && radii_stride != M))
+    return -1;
   std::vector<float> lut((size_t)M * E);
   int64_t pos = 0;
   for (int64_t q = 0; q < Q; ++q) {
@@ -201,10 +279,11 @@ int oracle_scan_all(int64_t Q, int32_t D, int32_t M, const float* queries, const
       const int32_t c = probe_ids[q * nprobe + p];
       const int64_t b = list_offsets[c], e = list_offsets[c + 1];
       if (out_dist) {
-        lut_one(queries + q * D, centroids + (size_t)c * D, D, M, codebooks,
-                radii + q * radii_stride, mode, lut.data(), nullptr);
+        lut_any(queries + q * D, centroids + (size_t)c * D, D, M, codebooks,
+                radii + q * radii_stride, mode, metric, lut.data(), nullptr);
+        const float start = adc_start(queries + q * D, centroids + (size_t)c * D, D, mode, metric);
         for (int64_t i = b; i < e; ++i) {
-          out_dist[pos + (i - b)] = adc_one(lut.data(), codes + i * M, M);
+          out_dist[pos + (i - b)] = adc_one(lut.data(), codes + i * M, M, start);
           out_ids[pos + (i - b)] = ids ? ids[i] : i;
         }
       }
@@ -232,23 +311,24 @@ int oracle_search(int64_t q_begin, int64_t q_end, int32_t D, int32_t nlist, int3
                   const float* queries, const float* centroids, const float* codebooks,
                   const int64_t* list_offsets, const uint8_t* codes, const int64_t* ids,
                   int32_t nprobe, int32_t k, const float* radii, int32_t radii_stride, int32_t mode,
-                  int64_t* out_ids, float* out_dist) {
-  if (D % M || nprobe > nlist || nprobe < 1 || k < 1 || mode < 0 || mode > 2 ||
-      (radii_stride != 0 && radii_stride != M))
+                  int32_t metric, int64_t* out_ids, float* out_dist) {
+  if (D % M || nprobe > nlist || nprobe < 1 || k < 1 || mode < 0 || mode > 2 || metric < 0 ||
+      metric > 1 || (radii_stride != 0 && radii_stride != M))
     return -1;
   std::vector<float> lut((size_t)M * E);
   std::vector<int32_t> probes(nprobe);
   std::vector<Cand> cand;
   for (int64_t q = q_begin; q < q_end; ++q) {
     const float* qv = queries + q * D;
-    coarse_one(qv, D, centroids, nlist, nprobe, probes.data(), nullptr);
+    coarse_one(qv, D, centroids, nlist, nprobe, metric, probes.data(), nullptr);
     cand.clear();
     for (int p = 0; p < nprobe; ++p) {
       const int32_t c = probes[p];
-      lut_one(qv, centroids + (size_t)c * D, D, M, codebooks, radii + q * radii_stride, mode,
-              lut.data(), nullptr);
+      lut_any(qv, centroids + (size_t)c * D, D, M, codebooks, radii + q * radii_stride, mode,
+              metric, lut.data(), nullptr);
+      const float start = adc_start(qv, centroids + (size_t)c * D, D, mode, metric);
       for (int64_t i = list_offsets[c]; i < list_offsets[c + 1]; ++i)
-        cand.push_back({adc_one(lut.data(), codes + i * M, M), ids ? ids[i] : i});
+        cand.push_back({adc_one(lut.data(), codes + i * M, M, start), ids ? ids[i] : i});
     }
     topk_select(cand, k, out_ids + q * k, out_dist + q * k);
   }
@@ -256,16 +336,21 @@ int oracle_search(int64_t q_begin, int64_t q_end, int32_t D, int32_t nlist, int3
 }
 
 // Exact k nearest neighbours by the metric definition L2(q,x) = sum (x_i-q_i)^2
-// (paper Sec. 2.1), accumulated in double, order (distance, id).  Brute force.
+// (paper Sec. 2.1), or k largest inner products sum x_i q_i (reported negated, so
+// that smaller is better), accumulated in double, order (value, id).  Brute force.
 int oracle_exact_knn(int64_t N, int32_t D, const float* base, int64_t Q, const float* queries,
-                     int32_t k, int64_t* out_ids, double* out_dist) {
+                     int32_t k, int32_t metric, int64_t* out_ids, double* out_dist) {
   std::vector<std::pair<double, int64_t>> d((size_t)N);
   for (int64_t q = 0; q < Q; ++q) {
     for (int64_t i = 0; i < N; ++i) {
       double acc = 0.0;
       for (int j = 0; j < D; ++j) {
-        double t = (double)base[i * D + j] - (double)queries[q * D + j];
-        acc += t * t;
+        if (metric == 0) {
+          double t = (double)base[i * D + j] - (double)queries[q * D + j];
+          acc += t * t;
+        } else {
+          acc -= (double)base[i * D + j] * (double)queries[q * D + j];
+        }
       }
       d[i] = {acc, i};
     }

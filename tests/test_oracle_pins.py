@@ -396,3 +396,156 @@ def test_recall_sane_and_monotone(tiny):
     r_few = wl.recall_at_k(oracle.search(q, idx, 1, w.k, inf)[0], truth)[0]
     r_thr = wl.recall_at_k(oracle.search(q, idx, idx.nlist, w.k, wl.calibrate_radii(w, idx, centres, 0.10))[0], truth)[0]
     assert r_all >= r_few and r_all >= r_thr and r_all > 0.3
+
+
+# ----------------------------------------------------------------------------
+# 9. inner-product metric (paper Sec. 4.2 "Inner Product Similarity Support")
+# ----------------------------------------------------------------------------
+
+def _ip_radii(idx, q, frac):
+    """Per-subspace radii that keep about `frac` of the entries under the inner-product
+    rule (an entry is kept iff |q_m - e|^2 - |e|^2 <= r_m^2), from float64."""
+    qm = q.astype(np.float64).reshape(q.shape[0], idx.M, 1, idx.dsub)
+    ent = idx.codebooks.astype(np.float64)[None]
+    g = ((qm - ent) ** 2).sum(-1) - (ent ** 2).sum(-1)                       # [Q][M][256]
+    r2 = np.quantile(g.transpose(1, 0, 2).reshape(idx.M, -1), frac, axis=1)
+    return np.sqrt(np.maximum(r2, 0.0)).astype(np.float32)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_ip_identity_codebook_equals_bruteforce_mips(seed):
+    """Lossless integer codes, every list probed, nothing thresholded: the search is exact
+    maximum inner product search (all arithmetic exact in fp32)."""
+    rng = np.random.default_rng(100 + seed)
+    base, idx = identity_index(rng)
+    Q, k = 20, 15
+    queries = rng.integers(-64, 64, size=(Q, idx.D)).astype(np.int64)
+    radii = np.full(idx.M, np.inf, dtype=np.float32)
+    ids, dist = oracle.search(queries.astype(np.float32), idx, idx.nlist, k, radii, metric=1)
+    ip = queries @ base.T                                                    # int64, exact
+    for i in range(Q):
+        o = np.lexsort((np.arange(base.shape[0]), -ip[i]))[:k]
+        assert np.array_equal(ids[i], o)
+        assert np.array_equal(dist[i].astype(np.int64), -ip[i][o])
+    eid, edist = oracle.exact_knn(base.astype(np.float32), queries.astype(np.float32), k, metric=1)
+    assert np.array_equal(eid, ids) and np.array_equal(edist, dist.astype(np.float64))
+    # fewer probes: lists by largest q.centroid (ties to the smaller list id), exact within them
+    nprobe = 2
+    ids2, dist2 = oracle.search(queries.astype(np.float32), idx, nprobe, k, radii, metric=1)
+    pid, pdist = oracle.coarse(queries.astype(np.float32), idx.centroids, nprobe, metric=1)
+    cent = idx.centroids.astype(np.int64)
+    labels = np.empty(idx.N, dtype=np.int64)
+    labels[idx.ids] = np.repeat(np.arange(idx.nlist), np.diff(idx.list_offsets))
+    for i in range(Q):
+        sc = -(cent @ queries[i])
+        probes = np.lexsort((np.arange(idx.nlist), sc))[:nprobe]
+        assert np.array_equal(pid[i], probes) and np.array_equal(pdist[i].astype(np.int64), sc[probes])
+        members = np.nonzero(np.isin(labels, probes))[0]
+        o = np.lexsort((members, -ip[i][members]))[:k]
+        assert np.array_equal(ids2[i], members[o])
+        assert np.array_equal(dist2[i].astype(np.int64), -ip[i][members][o])
+
+
+def test_ip_coarse_orders_lists_by_inner_product(tiny):
+    for name, (w, idx, _, q) in tiny.items():
+        ids, dist = oracle.coarse(q, idx.centroids, idx.nlist, metric=1)
+        s64 = -(q.astype(np.float64) @ idx.centroids.astype(np.float64).T)
+        scale = np.linalg.norm(q, axis=1)[:, None] * np.linalg.norm(idx.centroids, axis=1)[None, :]
+        for i in range(q.shape[0]):
+            assert sorted(ids[i].tolist()) == list(range(idx.nlist))
+            assert np.all(np.diff(dist[i]) >= 0)
+            assert np.all(np.abs(dist[i] - s64[i][ids[i]]) <= 1e-5 * scale[i][ids[i]] + 1e-30)
+            ref = np.argsort(s64[i], kind="stable")
+            gaps = np.diff(s64[i][ref]) > 1e-5 * scale[i].max()
+            same = ids[i] == ref
+            assert np.all(same[:-1][gaps & np.r_[True, gaps[:-1]]])
+
+
+def test_ip_table_keep_rule_identity_and_clamp(tiny):
+    """The keep rule is the paper's enlarged sphere (radius^2 = r^2 + |e|^2 around the entry,
+    ray from the query's projection); kept values satisfy the paper's identity
+    IP = (|e|^2 + |q|^2 - L2^2) / 2 with L2^2 taken from the (separately pinned) L2 table of
+    a list whose centroid is the origin; missed entries hold the bound (r^2 - |q_m|^2) / 2."""
+    for name, (w, idx, _, q) in tiny.items():
+        radii = _ip_radii(idx, q, 0.3)
+        probes = np.zeros((q.shape[0], 1), dtype=np.int32)
+        lut, mask = oracle.build_lut(q, idx.centroids, idx.codebooks, probes, radii, metric=1)
+        lut, mask = lut[:, 0], mask[:, 0]
+        bits = ((mask[..., None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(bool).reshape(lut.shape)
+        qm = q.astype(np.float64).reshape(q.shape[0], idx.M, 1, idx.dsub)
+        ent = idx.codebooks.astype(np.float64)[None]
+        e2 = (ent ** 2).sum(-1)
+        l2 = ((qm - ent) ** 2).sum(-1)
+        r2 = radii.astype(np.float64)[None, :, None] ** 2
+        inside = l2 <= r2 + e2                                              # enlarged sphere
+        scale = (qm ** 2).sum(-1) + e2 + r2
+        clear = np.abs(l2 - r2 - e2) > 1e-5 * scale
+        assert np.array_equal(bits[clear], inside[clear]) and clear.mean() > 0.99
+        assert 0.2 < bits.mean() < 0.4
+        # identity against the L2 table of a zero centroid (residual == query)
+        zero_c = np.zeros((1, idx.D), dtype=np.float32)
+        l2_lut, _ = oracle.build_lut(q, zero_c, idx.codebooks, probes, np.full(idx.M, np.inf, np.float32))
+        ip_from_l2 = (e2 + (qm ** 2).sum(-1) - l2_lut[:, 0].astype(np.float64)) / 2
+        kept = bits
+        assert np.all(np.abs(-lut.astype(np.float64) - ip_from_l2)[kept] <= 2e-6 * scale[kept])
+        # the clamp
+        clampv = np.broadcast_to((r2 - (qm ** 2).sum(-1)) / 2, lut.shape)
+        assert np.all(np.abs(lut.astype(np.float64) - clampv)[~kept] <= 2e-6 * scale[~kept])
+        # the table does not depend on the list
+        lut_b, _ = oracle.build_lut(q, idx.centroids, idx.codebooks, probes + (idx.nlist - 1), radii, metric=1)
+        assert np.array_equal(lut_b[:, 0], lut)
+        # no radius: everything kept, value = -IP
+        lut_inf, mask_inf = oracle.build_lut(q, idx.centroids, idx.codebooks, probes,
+                                             np.full(idx.M, np.inf, np.float32), metric=1)
+        assert np.all(mask_inf == np.uint64(0xFFFFFFFFFFFFFFFF))
+        ip64 = (qm * ent).sum(-1)
+        assert np.all(np.abs(lut_inf[:, 0].astype(np.float64) + ip64) <= 2e-6 * scale)
+
+
+def test_ip_scores_closed_forms(tiny):
+    """Unthresholded: score = -<q, reconstruction>.  Thresholded: list term plus
+    sum_m -max(ip_m, thr_m); hit counts = number of subspaces with ip_m < thr_m."""
+    for name, (w, idx, _, q) in tiny.items():
+        probes, pdist = oracle.coarse(q, idx.centroids, w.nprobe, metric=1)
+        rec, labels = reconstruct(idx)
+        inf = np.full(idx.M, np.inf, dtype=np.float32)
+        offs, d, ids = oracle.scan_all(q, idx, probes, inf, metric=1)
+        pos_of = {int(v): i for i, v in enumerate(idx.ids)}
+        radii = _ip_radii(idx, q, 0.3)
+        _, dt, idst = oracle.scan_all(q, idx, probes, radii, metric=1)
+        _, d1, _ = oracle.scan_all(q, idx, probes, radii, mode=1, metric=1)
+        _, d2m, _ = oracle.scan_all(q, idx, probes, radii, mode=2, metric=1)
+        assert np.array_equal(idst, ids)
+        r2 = radii.astype(np.float64) ** 2
+        checked = 0
+        for i in range(q.shape[0]):
+            rows = np.array([pos_of[int(v)] for v in ids[offs[i]:offs[i + 1]]])
+            q64 = q[i].astype(np.float64)
+            want = -(rec[rows] @ q64)
+            scale = np.linalg.norm(rec[rows], axis=1) * np.linalg.norm(q64) + 1e-30
+            assert np.all(np.abs(d[offs[i]:offs[i + 1]] - want) <= 1e-5 * scale)
+            # thresholded closed form
+            qm = q64.reshape(idx.M, idx.dsub)
+            ent = idx.codebooks.astype(np.float64)[np.arange(idx.M)[None, :], idx.codes[rows].astype(np.int64)]
+            ipm = (ent * qm[None]).sum(-1)                                   # [n][M]
+            thr = ((qm ** 2).sum(-1) - r2) / 2
+            thr_in = ((qm ** 2).sum(-1) - r2 / 4) / 2
+            start = -(idx.centroids[labels[rows]].astype(np.float64) @ q64)
+            want_t = start - np.maximum(ipm, thr[None]).sum(1)
+            assert np.all(np.abs(dt[offs[i]:offs[i + 1]] - want_t) <= 2e-5 * (scale + np.abs(thr).sum()))
+            band = 1e-5 * ((qm ** 2).sum(-1)[None] + (ent ** 2).sum(-1) + r2[None])
+            clear = np.all((np.abs(ipm - thr[None]) > band) & (np.abs(ipm - thr_in[None]) > band), axis=1)
+            miss = (ipm < thr[None]).sum(1)
+            pen = miss + (ipm < thr_in[None]).sum(1)
+            assert np.array_equal(d1[offs[i]:offs[i + 1]][clear], miss[clear])
+            assert np.array_equal(d2m[offs[i]:offs[i + 1]][clear], pen[clear])
+            checked += int(clear.sum())
+        assert checked > 1000
+        # thresholding can only lower a score (the clamp is a bound no missed entry reaches)
+        assert np.all(dt <= d + 1e-5 * (np.abs(d) + 1))
+        # search = top-k of those scores by (score, id)
+        ids_s, dist_s = oracle.search(q, idx, w.nprobe, w.k, radii, metric=1)
+        for i in range(q.shape[0]):
+            sl = slice(offs[i], offs[i + 1])
+            o = np.lexsort((ids[sl], dt[sl]))[:w.k]
+            assert np.array_equal(ids_s[i], ids[sl][o]) and np.array_equal(dist_s[i], dt[sl][o])
