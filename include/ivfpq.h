@@ -63,6 +63,25 @@ typedef enum {
 
 typedef struct ivfpq_index ivfpq_index; /* opaque; owns its device copies */
 
+/* Similarity an index is searched by.
+ *   IVFPQ_METRIC_L2  squared L2 distance (paper Sec. 2.1), everything above.
+ *   IVFPQ_METRIC_IP  maximum inner product (paper Sec. 4.2, "Inner Product Similarity
+ *     Support").  All results are NEGATED inner products, so that smaller is better and
+ *     the (value, id) order of every output stays as for L2:
+ *       lists      are ranked by -IP(q, centroid), acc = fmaf(q_i, c_i, acc), i ascending;
+ *       the table  is one per QUERY (the paper's ray starts at the query's projection q_m,
+ *                  not at a residual); entry e of subspace m is kept iff the ray hits its
+ *                  enlarged sphere, |q_m - e|^2 <= r_m^2 + |e|^2, evaluated in the equivalent
+ *                  form IP(e, q_m) >= thr_m = (|q_m|^2 - r_m^2) / 2; a kept entry stores
+ *                  0 - IP(e, q_m), a missed one the bound 0 - thr_m that it cannot beat;
+ *       a point    of list c scores -IP(q, centroid_c) plus the sum of its table values
+ *                  (fp32, subspaces ascending), i.e. minus the inner product of the query
+ *                  with the point's reconstruction when nothing is missed.
+ *     With the hit-count scorings the table holds the same penalties as under L2 (inner
+ *     sphere: the same construction with r_m / 2) and the list term is left out.
+ *     ivfpq_build_lut returns the per-query table once per probe, [Q][nprobe][M][256]. */
+typedef enum { IVFPQ_METRIC_L2 = 0, IVFPQ_METRIC_IP = 1 } ivfpq_metric;
+
 /* A trained index as the offline phase leaves it (paper Sec. 2.1, Algorithm 1:
  * IVF centroids and labels, residual codebooks, encoded points).  All pointers
  * are caller-owned and read-only; they may be host or device pointers. */
@@ -77,6 +96,7 @@ typedef struct {
   const int64_t *list_offsets; /* [nlist+1], non-decreasing, [0] = 0, [nlist] = N           */
   const uint8_t *codes;        /* [N][M]; rows list_offsets[c] .. list_offsets[c+1] are list c */
   const int64_t *ids;          /* [N] result ids in the same row order; NULL = row number   */
+  int32_t metric;              /* an ivfpq_metric                                           */
 } ivfpq_index_desc;
 
 /* Copies the index to the current device, re-laid out for the scan (codes in
@@ -186,6 +206,7 @@ typedef struct {
   int32_t D, nlist, M, dsub;
   int64_t code_bytes;   /* bytes of the interleaved code array on the device   */
   int64_t max_list_len; /* longest inverted list                                */
+  int32_t metric;       /* the ivfpq_metric it was created with                 */
 } ivfpq_index_info;
 int ivfpq_index_get_info(const ivfpq_index *index, ivfpq_index_info *info);
 

@@ -27,6 +27,7 @@ SYMBOLS = [
 ]
 
 SCORE_DISTANCE, SCORE_HIT_COUNT, SCORE_HIT_REWARD = 0, 1, 2
+METRIC_L2, METRIC_IP = 0, 1
 
 OK, ERR_INVALID_ARGUMENT, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5
 
@@ -41,7 +42,7 @@ class _Desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("D", ctypes.c_int32), ("nlist", ctypes.c_int32),
                 ("M", ctypes.c_int32), ("ksub", ctypes.c_int32), ("centroids", ctypes.c_void_p),
                 ("codebooks", ctypes.c_void_p), ("list_offsets", ctypes.c_void_p),
-                ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p)]
+                ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p), ("metric", ctypes.c_int32)]
 
 
 class _Scoring(ctypes.Structure):
@@ -51,7 +52,7 @@ class _Scoring(ctypes.Structure):
 class _Info(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("D", ctypes.c_int32), ("nlist", ctypes.c_int32),
                 ("M", ctypes.c_int32), ("dsub", ctypes.c_int32), ("code_bytes", ctypes.c_int64),
-                ("max_list_len", ctypes.c_int64)]
+                ("max_list_len", ctypes.c_int64), ("metric", ctypes.c_int32)]
 
 
 def load_library():
@@ -151,7 +152,7 @@ class IvfPqIndex:
     """Device-resident index.  `ivfpq_index_create` copies and re-lays out the
     arrays; the numpy inputs are not kept."""
 
-    def __init__(self, centroids, codebooks, list_offsets, codes, ids=None):
+    def __init__(self, centroids, codebooks, list_offsets, codes, ids=None, metric: int = METRIC_L2):
         lib = load_library()
         cent = np.ascontiguousarray(centroids, dtype=np.float32)
         cb = np.ascontiguousarray(codebooks, dtype=np.float32)
@@ -174,17 +175,17 @@ class IvfPqIndex:
         M = cb.shape[0]
         desc = _Desc(N=N, D=D, nlist=nlist, M=M, ksub=cb.shape[1], centroids=cent.ctypes.data,
                      codebooks=cb.ctypes.data, list_offsets=offs.ctypes.data,
-                     codes=codes_ptr if N > 0 else (codes_ptr or None), ids=ids_ptr)
+                     codes=codes_ptr if N > 0 else (codes_ptr or None), ids=ids_ptr, metric=int(metric))
         handle = ctypes.c_void_p()
         self._h = None
         _check(lib.ivfpq_index_create(ctypes.byref(desc), ctypes.byref(handle)))
         self._h = handle
-        self.N, self.D, self.nlist, self.M = N, D, nlist, M
+        self.N, self.D, self.nlist, self.M, self.metric = N, D, nlist, M, int(metric)
         del codes_ref, ids_ref
 
     @classmethod
-    def from_index(cls, idx) -> "IvfPqIndex":
-        return cls(idx.centroids, idx.codebooks, idx.list_offsets, idx.codes, idx.ids)
+    def from_index(cls, idx, metric: int = METRIC_L2) -> "IvfPqIndex":
+        return cls(idx.centroids, idx.codebooks, idx.list_offsets, idx.codes, idx.ids, metric=metric)
 
     def info(self) -> dict:
         i = _Info()

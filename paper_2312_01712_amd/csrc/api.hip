@@ -164,6 +164,10 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
     return IVFPQ_ERR_INVALID_ARGUMENT;
   }
   if (d->D % d->M) { set_error("%s: D = %d is not a multiple of M = %d", fn, d->D, d->M); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (d->metric != IVFPQ_METRIC_L2 && d->metric != IVFPQ_METRIC_IP) {
+    set_error("%s: metric = %d unknown", fn, d->metric);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
   if (d->M > IVFPQ_MAX_M) { set_error("%s: M = %d above the limit %d", fn, d->M, IVFPQ_MAX_M); return IVFPQ_ERR_UNSUPPORTED; }
   if (d->N >= ((int64_t)1 << 32)) { set_error("%s: N = %lld must be below 2^32", fn, (long long)d->N); return IVFPQ_ERR_UNSUPPORTED; }
   if (!d->centroids || !d->codebooks || !d->list_offsets || (d->N > 0 && !d->codes)) {
@@ -203,6 +207,7 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
   if (!ix) { set_error("%s: out of host memory", fn); return IVFPQ_ERR_NO_MEMORY; }
   memset(ix, 0, sizeof *ix);
   ix->N = d->N; ix->D = d->D; ix->nlist = d->nlist; ix->M = d->M; ix->dsub = d->D / d->M;
+  ix->metric = d->metric;
   ix->Mp = (d->M + 3) & ~3;
   ix->total_blocks = blocks[d->nlist];
   ix->code_bytes = ix->total_blocks * ivfpq_block_bytes(ix->Mp);
@@ -286,6 +291,7 @@ int ivfpq_index_get_info(const ivfpq_index *ix, ivfpq_index_info *info) {
   if (!ix || !info) { set_error("index_get_info: NULL argument"); return IVFPQ_ERR_INVALID_ARGUMENT; }
   info->N = ix->N; info->D = ix->D; info->nlist = ix->nlist; info->M = ix->M; info->dsub = ix->dsub;
   info->code_bytes = ix->code_bytes; info->max_list_len = ix->max_list_len;
+  info->metric = ix->metric;
   return IVFPQ_OK;
 }
 

@@ -12,6 +12,10 @@
 // enough under a rounding-error bound; otherwise that query falls back to
 // reference-order distances for all lists.  The result is therefore identical
 // to a plain scan in the reference order, whatever the matrix unit rounds.
+//
+// Under the inner-product metric (paper Sec. 4.2, last sentence) lists are ranked
+// by 0 - IP(q, centroid), reference order acc = fmaf(q_i, c_i, acc); the same
+// scheme applies with the product itself as the proposal.
 
 #include "ivfpq_internal.h"
 
@@ -41,13 +45,13 @@ __device__ inline void load4(const float *base, bool row_ok, int64_t off, int k,
 }
 
 // out[q][c] = ||c||^2 - 2 q.c  (the ||q||^2 term is constant per query and does
-// not change the ranking).  One workgroup of 4 wavefronts computes a 128 x 128
+// not change the ranking); -q.c under the inner-product metric.  One workgroup of 4 wavefronts computes a 128 x 128
 // tile; each wavefront owns a 64 x 64 quadrant as 2 x 2 MFMA 32x32x2 blocks.
 __global__ __launch_bounds__(256) void coarse_gemm_kernel(const float *__restrict__ Qm,
                                                           const float *__restrict__ Cm,
                                                           const float *__restrict__ cnorm,
                                                           float *__restrict__ out, int Qn, int nlist,
-                                                          int D, int ldo, int vec) {
+                                                          int D, int ldo, int vec, int ip) {
   __shared__ float sA[BK][LDT];
   __shared__ float sB[BK][LDT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -99,7 +103,7 @@ __global__ __launch_bounds__(256) void coarse_gemm_kernel(const float *__restric
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int q = q0 + wm * 64 + bi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (q < Qn && c < nlist) out[(int64_t)q * ldo + c] = cn - 2.0f * acc[bi][bj][v];
+        if (q < Qn && c < nlist) out[(int64_t)q * ldo + c] = ip ? -acc[bi][bj][v] : cn - 2.0f * acc[bi][bj][v];
       }
     }
 }
@@ -141,6 +145,27 @@ __device__ inline float exact_dist(const float *sq, const float *__restrict__ ce
   return acc;
 }
 
+// Reference-order list score under the inner-product metric: 0 - q.c
+__device__ inline float exact_neg_ip(const float *sq, const float *__restrict__ cen, int D) {
+  float acc = 0.0f;
+  int i = 0;
+  if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(cen) & 15) == 0) {
+    for (; i < D; i += 4) {
+      const float4 c4 = *reinterpret_cast<const float4 *>(cen + i);
+      acc = fmaf(sq[i], c4.x, acc);
+      acc = fmaf(sq[i + 1], c4.y, acc);
+      acc = fmaf(sq[i + 2], c4.z, acc);
+      acc = fmaf(sq[i + 3], c4.w, acc);
+    }
+  }
+  for (; i < D; ++i) acc = fmaf(sq[i], cen[i], acc);
+  return 0.0f - acc;
+}
+
+__device__ inline float exact_score(const float *sq, const float *__restrict__ cen, int D, int ip) {
+  return ip ? exact_neg_ip(sq, cen, D) : exact_dist(sq, cen, D);
+}
+
 // inclusive prefix sum over the 256 threads of the workgroup (tmp: 2 x 256)
 __device__ inline uint32_t scan256(uint32_t v, uint32_t *tmp, int tid) {
   int cur = 0;
@@ -176,7 +201,7 @@ __device__ inline unsigned long long row_key(const float *row, int c) {
 // are sorted by (distance, list id), and the first nprobe are emitted.
 __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
     float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int nlist,
-    int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm,
+    int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm, int ip,
     int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
   extern __shared__ float sq[];  // [D]
   __shared__ uint32_t hist[NBINS];
@@ -207,7 +232,7 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
     if (attempt == 1) {
       // fallback: reference-order distances for every list
       if (tid == 0) atomicAdd(&g_coarse_fallbacks, 1u);
-      for (int c = tid; c < nlist; c += SEL_THREADS) row[c] = exact_dist(sq, cent + (int64_t)c * D, D);
+      for (int c = tid; c < nlist; c += SEL_THREADS) row[c] = exact_score(sq, cent + (int64_t)c * D, D, ip);
       __syncthreads();
     }
     // ---- smallest and largest key of the row ----
@@ -301,8 +326,8 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
       unsigned long long key = ~0ull;
       if (i < nsel) {
         const int c = (int)(uint32_t)keys[i];
-        const float d = attempt == 1 ? row[c] : exact_dist(sq, cent + (int64_t)c * D, D);
-        key = ((unsigned long long)__float_as_uint(d) << 32) | (uint32_t)c;
+        const float d = attempt == 1 ? row[c] : exact_score(sq, cent + (int64_t)c * D, D, ip);
+        key = ((unsigned long long)orderable(d) << 32) | (uint32_t)c;
       }
       keys[i] = key;
     }
@@ -326,8 +351,9 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
     // every list that was not selected has a proposal value >= the cut's; accept if
     // that lower bound clears the nprobe-th reference distance by more than the
     // rounding-error bound of the matrix product
-    const float t_prop = unorderable((uint32_t)(cut >> 32)) + qq;
-    const float tau = __uint_as_float((uint32_t)(keys[nprobe - 1] >> 32));
+    // (|q.c| <= (|q|^2 + |c|^2) / 2, so the same bound covers the product alone)
+    const float t_prop = unorderable((uint32_t)(cut >> 32)) + (ip ? 0.0f : qq);
+    const float tau = unorderable((uint32_t)(keys[nprobe - 1] >> 32));
     const float bound = err_scale * (qq + max_cnorm);
     const bool ok = (t_prop - tau) > bound;  // false for NaN
     __syncthreads();
@@ -336,7 +362,7 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
   for (int p = tid; p < nprobe; p += SEL_THREADS) {
     const unsigned long long key = keys[p];
     out_ids[q * nprobe + p] = (int32_t)(uint32_t)key;
-    if (out_dist) out_dist[q * nprobe + p] = __uint_as_float((uint32_t)(key >> 32));
+    if (out_dist) out_dist[q * nprobe + p] = unorderable((uint32_t)(key >> 32));
   }
 }
 
@@ -378,10 +404,10 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
     const float *qm = d_queries + q0 * D;
     dim3 grid((nlist + BN - 1) / BN, (qn + BM - 1) / BM);
     hipLaunchKernelGGL(coarse_gemm_kernel, grid, dim3(256), 0, s, qm, ix->d_centroids, ix->d_cnorm,
-                       d_scratch, qn, nlist, D, nlist_pad, vec);
+                       d_scratch, qn, nlist, D, nlist_pad, vec, ix->metric == IVFPQ_METRIC_IP);
     hipLaunchKernelGGL(coarse_select_kernel, dim3(qn), dim3(SEL_THREADS), (size_t)D * sizeof(float), s,
                        d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe, kprop,
-                       err_scale, ix->max_cnorm, d_probe_ids + q0 * nprobe,
+                       err_scale, ix->max_cnorm, ix->metric == IVFPQ_METRIC_IP, d_probe_ids + q0 * nprobe,
                        d_probe_dist ? d_probe_dist + q0 * nprobe : nullptr);
   }
   IVFPQ_HIP_TRY(hipGetLastError());

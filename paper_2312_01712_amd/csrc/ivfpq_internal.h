@@ -11,6 +11,7 @@
 struct ivfpq_index {
   int64_t N;
   int32_t D, nlist, M, dsub;
+  int32_t metric;           // IVFPQ_METRIC_L2 or IVFPQ_METRIC_IP
   int32_t Mp;               // code bytes per point in the device layout, M rounded up to 4
   int device;
   float *d_centroids;       // [nlist][D]

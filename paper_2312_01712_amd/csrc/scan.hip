@@ -48,9 +48,25 @@ constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any dist
 constexpr int64_t SENT_ID = LLONG_MAX;
 
 struct Key {
-  uint32_t d;  // distance bits (distances are >= 0, so bits order like values)
+  uint32_t d;  // distance as an unsigned integer that orders like the value (see dist_key)
   int64_t id;
 };
+
+// Distances are >= 0 under L2 and for the hit counts, so their bits already order like
+// the values.  Scores under the inner-product metric have either sign (SGN): the usual
+// order-preserving map is applied (flip all bits of a negative, set the top bit of a
+// non-negative), and undone on output.
+template <bool SGN>
+__device__ inline uint32_t dist_key(float v) {
+  const uint32_t u = __float_as_uint(v);
+  if (!SGN) return u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+template <bool SGN>
+__device__ inline float key_dist(uint32_t k) {
+  if (!SGN) return __uint_as_float(k);
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
 
 __device__ inline bool kless(const Key &a, const Key &b) {
   return a.d < b.d || (a.d == b.d && a.id < b.id);
@@ -260,8 +276,9 @@ __device__ inline void load_codes(const uint8_t *__restrict__ list_base, int nb,
 }
 
 template <int MT>
-__device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r) {
-  float dist = 0.0f;
+__device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
+                                float start = 0.0f) {
+  float dist = start;
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
@@ -296,9 +313,9 @@ __device__ inline bool adc_part_exit(const LDS float *lut, const CodeRegs<((MT +
 
 // runtime-M variant: dwords are fetched as they are needed
 __device__ inline float adc_sum_rt(const LDS float *lut, const uint8_t *__restrict__ list_base, int nb, int b,
-                                   int lane, int M, int Mp) {
+                                   int lane, int M, int Mp, float start = 0.0f) {
   const int n16 = Mp >> 4;
-  float dist = 0.0f;
+  float dist = start;
   for (int d = 0; d < (Mp >> 2); ++d) {
     const uint8_t *p = d < 4 * n16
                            ? list_base + ((int64_t)(d >> 2) * nb + b) * 1024 + lane * 16 + (d & 3) * 4
@@ -363,10 +380,11 @@ __device__ __forceinline__ void wave_flush(WaveTop &st, LDS uint32_t *qd, LDS in
 }
 
 // Offer this block's distances to the wavefront's top-k.
+template <bool SGN = false>
 __device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, int64_t row,
                                   const int64_t *__restrict__ ids, LDS uint32_t *qd, LDS int64_t *qid,
                                   int lane, int k, const SharedTau &sh) {
-  const uint32_t bits = __float_as_uint(dist);
+  const uint32_t bits = dist_key<SGN>(dist);
   const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
   const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
   bool pass = valid && bits <= pref;
@@ -393,10 +411,33 @@ __device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, 
   st.qcount += n;
 }
 
+// Empty top-k state.  More than KP keys per query are produced KP at a time: a later pass
+// keeps only the keys above the last one of the pass before it (which that pass has
+// already written to the output row).
+template <bool SGN, bool DUMP>
+__device__ inline void init_wave_top(WaveTop &st, const ScanArgs &a, int64_t q) {
+  st.L0.d = st.L1.d = SENT_D;
+  st.L0.id = st.L1.id = SENT_ID;
+  st.tau.d = SENT_D;
+  st.tau.id = SENT_ID;
+  st.qcount = 0;
+  st.floor.d = 0u;
+  st.floor.id = INT64_MIN;
+  if (!DUMP && a.k_off > 0) {
+    const int64_t o = q * a.k_out + a.k_off - 1;
+    const int64_t fid = a.out_ids[o];
+    const uint32_t fd = fid == -1 ? SENT_D : dist_key<SGN>(a.out_dist[o]);  // -1: nothing is left
+    st.floor.d = __builtin_amdgcn_readfirstlane(fd);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)fid);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)fid >> 32));
+    st.floor.id = (int64_t)(((uint64_t)hi << 32) | lo);
+  }
+}
+
 // End of a workgroup's work: fold the queues, merge the wavefronts' sorted lists
 // through LDS (the table region is free by then) and write the first k keys, or
 // the whole list when the probes of the query were split over several workgroups.
-template <int NW>
+template <int NW, bool SGN = false>
 __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS int64_t *qid, int lane,
                                             int wave, const SharedTau &sh, LDS unsigned char *smem3,
                                             const ScanArgs &a, int64_t q, int split) {
@@ -434,7 +475,7 @@ __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS i
           const bool real = e.d != SENT_D;
           const int64_t o = q * a.k_out + a.k_off + i;
           a.out_ids[o] = real ? e.id : -1;
-          a.out_dist[o] = real ? __uint_as_float(e.d) : __builtin_inff();
+          a.out_dist[o] = real ? key_dist<SGN>(e.d) : __builtin_inff();
         }
       }
     }
@@ -513,24 +554,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   sh.jrank = (a.k + NW - 1) / NW;
 
   WaveTop st;
-  st.L0.d = st.L1.d = SENT_D;
-  st.L0.id = st.L1.id = SENT_ID;
-  st.tau.d = SENT_D;
-  st.tau.id = SENT_ID;
-  st.qcount = 0;
-  // More than KP keys per query are produced KP at a time: a later pass keeps only the
-  // keys above the last one of the pass before it (which that pass has already written).
-  st.floor.d = 0u;
-  st.floor.id = INT64_MIN;
-  if (!DUMP && a.k_off > 0) {
-    const int64_t o = q * a.k_out + a.k_off - 1;
-    const int64_t fid = a.out_ids[o];
-    const uint32_t fd = fid == -1 ? SENT_D : __float_as_uint(a.out_dist[o]);  // -1: nothing is left
-    st.floor.d = __builtin_amdgcn_readfirstlane(fd);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)fid);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)fid >> 32));
-    st.floor.id = (int64_t)(((uint64_t)hi << 32) | lo);
-  }
+  init_wave_top<false, DUMP>(st, a, q);
   LDS uint32_t *qd = queue_d + wave * 64;
   LDS int64_t *qid = queue_id + wave * 64;
 
@@ -722,10 +746,218 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
+
+// ---------------------------------------------------------------------------
+// Inner-product metric (paper Sec. 4.2 "Inner Product Similarity Support").
+//
+// The paper enlarges the sphere of entry e to radius^2 = r_m^2 + |e|^2 and starts the
+// ray at the projection q_m of the QUERY; it hits iff |q_m - e|^2 <= r_m^2 + |e|^2, i.e.
+// iff IP(e, q_m) >= thr_m = (|q_m|^2 - r_m^2) / 2, which is the form evaluated here.
+// A kept entry stores 0 - IP, a missed one the bound 0 - thr_m.  The table depends on
+// the query only, so a workgroup builds it once and then streams the probed lists with
+// no barrier between them; a point of list c scores (0 - IP(q, centroid_c)) plus the
+// sum of its table values, subspaces ascending.  Scores have either sign: no early
+// exit of the sums, and keys go through the order-preserving map of dist_key.
+
+template <int MODE>
+__device__ inline float table_value_ip(float ip, float thr, float thr_in) {
+  if (MODE == 0) return ip >= thr ? 0.0f - ip : 0.0f - thr;
+  if (MODE == 1) return ip >= thr ? 0.0f : 1.0f;
+  return ip >= thr_in ? 0.0f : (ip >= thr ? 1.0f : 2.0f);
+}
+__device__ inline float table_value_ip(float ip, float thr, float thr_in, int mode) {
+  return mode == 0 ? table_value_ip<0>(ip, thr, thr_in)
+                   : (mode == 1 ? table_value_ip<1>(ip, thr, thr_in) : table_value_ip<2>(ip, thr, thr_in));
+}
+
+// ip = q_0 e_0, then ip = fmaf(q_j, e_j, ip)
+template <typename SP>
+__device__ inline float entry_ip(SP qm, const float *__restrict__ cb, int dsub) {
+  float ip = qm[0] * cb[0];
+  for (int j = 1; j < dsub; ++j) ip = fmaf(qm[j], cb[j], ip);
+  return ip;
+}
+
+// thr = (|q_m|^2 - r2) / 2 and the same with the half radius; |q_m|^2 as q_0 q_0, then fmaf
+template <typename SP>
+__device__ inline void ip_thresholds(SP qm, int dsub, float r2, float &thr, float &thr_in) {
+  float qq = qm[0] * qm[0];
+  for (int j = 1; j < dsub; ++j) qq = fmaf(qm[j], qm[j], qq);
+  thr = 0.5f * (qq - r2);
+  thr_in = 0.5f * (qq - 0.25f * r2);
+}
+
+// 0 - q.c with acc = fmaf(q_i, c_i, acc), i ascending (the list term of a score)
+template <typename SP>
+__device__ inline float neg_ip_chain(SP sq, const float *__restrict__ cen, int D) {
+  float acc = 0.0f;
+  int i = 0;
+  if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(cen) & 15) == 0) {
+    for (; i < D; i += 4) {
+      const float4 c4 = *reinterpret_cast<const float4 *>(cen + i);
+      acc = fmaf(sq[i], c4.x, acc);
+      acc = fmaf(sq[i + 1], c4.y, acc);
+      acc = fmaf(sq[i + 2], c4.z, acc);
+      acc = fmaf(sq[i + 3], c4.w, acc);
+    }
+  }
+  for (; i < D; ++i) acc = fmaf(sq[i], cen[i], acc);
+  return 0.0f - acc;
+}
+
+template <int MT, int NW, bool DUMP>
+__global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2) {
+  constexpr int NT = NW * 64;
+  constexpr int MPT = (MT + 3) / 4 * 4;
+  constexpr int META = 64;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int M = MT > 0 ? MT : a.M;
+  const int Mp = MT > 0 ? MPT : a.Mp;
+  const int D = a.D, dsub = a.dsub;
+  // LDS carve: table | merge staging (aliases the table) | query | queues | bounds | list metadata | thresholds
+  const int lut_bytes = M * 1024;
+  const int stage_bytes = NW * KP * 12;
+  const int region0 = lut_bytes > stage_bytes ? lut_bytes : stage_bytes;
+  LDS unsigned char *smem3 = (LDS unsigned char *)smem;
+  LDS float *lut = (LDS float *)smem3;
+  LDS float *sq = (LDS float *)(smem3 + region0);
+  const int sq_bytes = (D * 4 + 15) & ~15;
+  LDS int64_t *queue_id = (LDS int64_t *)(smem3 + region0 + sq_bytes);
+  LDS uint32_t *queue_d = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 8);
+  LDS uint32_t *tau_words = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12);
+  const int tau_bytes = (4 * (NW + 1) + 15) & ~15;
+  LDS int64_t *meta_row0 = (LDS int64_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12 + tau_bytes);
+  LDS int64_t *meta_blk = meta_row0 + META;
+  LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
+  LDS float *meta_start = (LDS float *)(meta_len + META);
+  LDS float *sthr = meta_start + META;  // [M]
+  LDS float *sthr_in = sthr + IVFPQ_MAX_M;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t q = blockIdx.x / a.nsplit;
+  const int split = blockIdx.x % a.nsplit;
+  const int p_begin = (int)((int64_t)a.nprobe * split / a.nsplit);
+  const int p_end = (int)((int64_t)a.nprobe * (split + 1) / a.nsplit);
+  const int32_t *probes = a.probe_ids + q * a.nprobe;
+  const int mode = a.mode;
+
+  int64_t dump_pos = 0;
+  if (DUMP) {
+    int64_t total = 0;
+    for (int p = 0; p < a.nprobe; ++p) {
+      const int32_t c = probes[p];
+      if ((uint32_t)c < (uint32_t)a.nlist) total += a.list_offsets[c + 1] - a.list_offsets[c];
+    }
+    if (total != a.cand_offsets[q + 1] - a.cand_offsets[q]) {
+      if (tid == 0) atomicAdd(a.errors, 1);
+      return;
+    }
+    dump_pos = a.cand_offsets[q];
+  }
+
+  for (int i = tid; i < D; i += NT) sq[i] = a.queries[q * D + i];
+  if (tid <= NW) tau_words[tid] = SENT_D;
+  __syncthreads();
+  for (int m = tid; m < M; m += NT) {
+    float v = r2.v[m];
+    if (a.query_radii) {
+      const float r = a.query_radii[q * M + m];
+      v = r * r;
+    }
+    float thr, thr_in;
+    ip_thresholds(sq + m * dsub, dsub, v, thr, thr_in);
+    sthr[m] = thr;
+    sthr_in[m] = thr_in;
+  }
+  SharedTau sh;
+  sh.bound = tau_words;
+  sh.rank = tau_words + 1;
+  sh.nw = NW;
+  sh.wave = wave;
+  sh.jrank = (a.k + NW - 1) / NW;
+  WaveTop st;
+  init_wave_top<true, DUMP>(st, a, q);
+  LDS uint32_t *qd = queue_d + wave * 64;
+  LDS int64_t *qid = queue_id + wave * 64;
+  __syncthreads();
+  // ---- the query's table, built once ----
+  {
+    const int e = tid & 255;
+    for (int m = tid >> 8; m < M; m += NT >> 8) {
+      const int mu = __builtin_amdgcn_readfirstlane(m);
+      const float ip = entry_ip(sq + mu * dsub, a.codebooks + ((int64_t)mu * 256 + e) * dsub, dsub);
+      lut[mu * 256 + e] = table_value_ip(ip, sthr[mu], sthr_in[mu], mode);
+    }
+  }
+  // ---- the probed lists, META at a time ----
+  for (int p0 = p_begin; p0 < p_end; p0 += META) {
+    __syncthreads();  // table written; nobody still reads the previous metadata
+    if (tid < META && p0 + tid < p_end) {
+      const int32_t cc = probes[p0 + tid];
+      const bool ok = (uint32_t)cc < (uint32_t)a.nlist;
+      const int64_t r0 = ok ? a.list_offsets[cc] : 0;
+      meta_row0[tid] = r0;
+      meta_len[tid] = ok ? (int)(a.list_offsets[cc + 1] - r0) : 0;  // outside [0, nlist): an empty list
+      meta_blk[tid] = ok ? a.list_blocks[cc] : 0;
+      meta_start[tid] = (ok && mode == 0) ? neg_ip_chain(sq, a.centroids + (int64_t)cc * D, D) : 0.0f;
+    }
+    __syncthreads();
+    const int pn = p_end - p0 < META ? p_end - p0 : META;
+    for (int pm = 0; pm < pn; ++pm) {
+      const int64_t row0 = meta_row0[pm];
+      const int len = __builtin_amdgcn_readfirstlane(meta_len[pm]);
+      const int nb = (len + 63) >> 6;
+      const uint8_t *base = a.codes + meta_blk[pm] * ivfpq_block_bytes(Mp);
+      const float start = meta_start[pm];
+      if constexpr (MT > 0) {
+        if (wave < nb) {
+          const int last = nb - 1;
+          CodeRegs<MPT / 4> nxt;
+          load_codes<MPT>(base, nb, wave, lane, nxt);
+          for (int b = wave; b < nb; b += NW) {
+            CodeRegs<MPT / 4> cur = nxt;
+            const int bn = b + NW < last ? b + NW : last;
+            load_codes<MPT>(base, nb, bn, lane, nxt);
+            const float dist = adc_sum<MT>(lut, cur, start);
+            const int i = b * 64 + lane;
+            const bool valid = i < len;
+            if (DUMP) {
+              if (valid) {
+                a.all_dist[dump_pos + i] = dist;
+                a.all_ids[dump_pos + i] = a.ids[row0 + i];
+              }
+            } else {
+              wave_offer<true>(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
+            }
+          }
+        }
+      } else {
+        for (int b = wave; b < nb; b += NW) {
+          const float dist = adc_sum_rt(lut, base, nb, b, lane, M, Mp, start);
+          const int i = b * 64 + lane;
+          const bool valid = i < len;
+          if (DUMP) {
+            if (valid) {
+              a.all_dist[dump_pos + i] = dist;
+              a.all_ids[dump_pos + i] = a.ids[row0 + i];
+            }
+          } else {
+            wave_offer<true>(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
+          }
+        }
+      }
+      if (DUMP) dump_pos += len;
+    }
+  }
+  if (DUMP) return;
+  finish_topk<NW, true>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
+}
+
 // Merge the probe groups' partial lists of a query (one wavefront per query).
 __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ part_d,
                                                    const int64_t *__restrict__ part_id, int nsplit,
-                                                   int k, int k_out, int k_off,
+                                                   int k, int k_out, int k_off, int sgn,
                                                    int64_t *__restrict__ out_ids,
                                                    float *__restrict__ out_dist) {
   const int lane = threadIdx.x;
@@ -750,7 +982,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ 
     if (i < k) {
       const bool real = e.d != SENT_D;
       out_ids[q * k_out + k_off + i] = real ? e.id : -1;
-      out_dist[q * k_out + k_off + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+      out_dist[q * k_out + k_off + i] = real ? (sgn ? key_dist<true>(e.d) : key_dist<false>(e.d)) : __builtin_inff();
     }
   }
 }
@@ -763,7 +995,7 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
                                                   const float *__restrict__ centroids,
                                                   const float *__restrict__ codebooks, int D, int M,
                                                   int dsub_rt, int nlist, int nprobe, RadiiSq r2,
-                                                  const float *__restrict__ query_radii, int mode,
+                                                  const float *__restrict__ query_radii, int mode, int ip,
                                                   float *__restrict__ out_lut,
                                                   uint64_t *__restrict__ out_mask) {
   extern __shared__ float sqv[];
@@ -783,8 +1015,17 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
       const float r = query_radii[q * M + m];
       rm2 = r * r;
     }
-    const float v = lut_entry<DSUB>(sqv + m * dsub, cen + m * dsub,
-                                    codebooks + ((int64_t)m * 256 + e) * dsub, dsub, rm2, mode, keep);
+    float v;
+    if (ip) {  // inner-product metric: the table of the query (the list does not enter)
+      float thr, thr_in;
+      ip_thresholds(sqv + m * dsub, dsub, rm2, thr, thr_in);
+      const float x = entry_ip(sqv + m * dsub, codebooks + ((int64_t)m * 256 + e) * dsub, dsub);
+      keep = x >= thr;
+      v = table_value_ip(x, thr, thr_in, mode);
+    } else {
+      v = lut_entry<DSUB>(sqv + m * dsub, cen + m * dsub, codebooks + ((int64_t)m * 256 + e) * dsub, dsub,
+                          rm2, mode, keep);
+    }
     out_lut[(qp * M + m) * 256 + e] = v;
     const unsigned long long bal = __ballot(keep);
     if (out_mask && lane == 0) out_mask[(qp * M + m) * 4 + wave] = bal;
@@ -868,6 +1109,34 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
   return launch_scan_t<MT, DSUB, 4>(a, r2, grid, dump, s);
 }
 
+size_t scan_ip_lds(const ScanArgs &a, int nw) {
+  const int lut_bytes = a.M * 1024, stage = nw * KP * 12;
+  return (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) + (size_t)nw * 64 * 12 +
+         ((4 * (nw + 1) + 15) & ~15) + 64 * 24 + 2 * IVFPQ_MAX_M * 4;
+}
+
+template <int MT, int NW>
+int launch_scan_ip_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
+  const size_t lds = scan_ip_lds(a, NW);
+  if (lds > 160 * 1024) {
+    ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  auto kern = dump ? scan_ip_kernel<MT, NW, true> : scan_ip_kernel<MT, NW, false>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) (void)hipGetLastError();
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
+  return IVFPQ_OK;
+}
+
+// Inner-product metric: 8 wavefronts while two workgroups fit a CU, else 16.
+template <int MT>
+int launch_scan_ip(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
+  if (2 * scan_ip_lds(a, 8) <= 160 * 1024) return launch_scan_ip_t<MT, 8>(a, r2, grid, dump, s);
+  return launch_scan_ip_t<MT, 16>(a, r2, grid, dump, s);
+}
+
 }  // namespace
 
 namespace ivfpq {
@@ -917,6 +1186,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
     return IVFPQ_ERR_UNSUPPORTED;
   }
   const int M = ix->M, ds = ix->dsub;
+  const bool ip = ix->metric == IVFPQ_METRIC_IP;
   // A wavefront's sorted list holds KP keys, so k > KP takes ceil(k / KP) passes over the
   // lists; pass j keeps the keys above the last key pass j - 1 wrote.
   a.k_out = k;
@@ -924,6 +1194,13 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
     a.k_off = off;
     a.k = k - off < KP ? k - off : KP;
     int rc;
+    if (ip) {
+      if (M == 64) rc = launch_scan_ip<64>(a, r2, grid, dump, s);
+      else if (M == 48) rc = launch_scan_ip<48>(a, r2, grid, dump, s);
+      else if (M == 100) rc = launch_scan_ip<100>(a, r2, grid, dump, s);
+      else if (M == 16) rc = launch_scan_ip<16>(a, r2, grid, dump, s);
+      else rc = launch_scan_ip<0>(a, r2, grid, dump, s);
+    } else
     if (M == 64 && ds == 2) rc = launch_scan_nw<64, 2>(a, r2, grid, dump, s);
     else if (M == 48 && ds == 2) rc = launch_scan_nw<48, 2>(a, r2, grid, dump, s);
     else if (M == 100 && ds == 2) rc = launch_scan_nw<100, 2>(a, r2, grid, dump, s);
@@ -933,7 +1210,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
     if (dump) break;
     if (nsplit > 1)
       hipLaunchKernelGGL(merge_kernel, dim3((unsigned)Q), dim3(64), 0, s, d_part_d, d_part_id, nsplit, a.k,
-                         a.k_out, a.k_off, d_out_ids, d_out_dist);
+                         a.k_out, a.k_off, (int)ip, d_out_ids, d_out_dist);
   }
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;
@@ -951,7 +1228,8 @@ int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, i
 #define LUT_LAUNCH(DS)                                                                           \
   hipLaunchKernelGGL(lut_kernel<DS>, dim3((unsigned)grid), dim3(256), lds, s, d_queries,         \
                      d_probe_ids, ix->d_centroids, ix->d_codebooks, ix->D, ix->M, ix->dsub,      \
-                     ix->nlist, nprobe, r2, d_query_radii, mode, d_lut, d_mask)
+                     ix->nlist, nprobe, r2, d_query_radii, mode, (int)(ix->metric == IVFPQ_METRIC_IP), d_lut, \
+                     d_mask)
   if (ix->dsub == 2) LUT_LAUNCH(2);
   else if (ix->dsub == 4) LUT_LAUNCH(4);
   else LUT_LAUNCH(0);

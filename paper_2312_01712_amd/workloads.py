@@ -330,9 +330,13 @@ def train_index(w: Workload, device="cpu", progress=None) -> Tuple[Index, torch.
 
 
 def calibrate_radii(w: Workload, index: Index, centres: torch.Tensor, keep_frac: Optional[float] = None,
-                    n_cal: int = 1000) -> np.ndarray:
+                    n_cal: int = 1000, metric: int = 0) -> np.ndarray:
     """Per-subspace radius such that about `keep_frac` of the codebook entries
     lie within it of a query residual's projection.
+
+    metric = 1 (inner product, paper Sec. 4.2): the ray starts at the query's own
+    projection q_m and entry e has the enlarged sphere of radius^2 r_m^2 + |e|^2, so the
+    pooled quantity is |q_m - e|^2 - |e|^2 (clipped at 0) instead of a squared distance.
 
     Calibration queries (sub-seed 3) are assigned their nprobe nearest lists;
     for each subspace the squared distances from every residual projection to
@@ -346,6 +350,15 @@ def calibrate_radii(w: Workload, index: Index, centres: torch.Tensor, keep_frac:
     qc = queries(w, centres, n_cal, sub=3)
     cent = torch.from_numpy(index.centroids).to(device)
     cb = torch.from_numpy(index.codebooks).to(device)
+    if metric == 1:
+        qm = qc.reshape(-1, index.M, index.dsub)
+        radii = np.empty(index.M, dtype=np.float32)
+        for m in range(index.M):
+            diff = qm[:, m, None, :] - cb[m][None, :, :]
+            g = ((diff * diff).sum(2) - (cb[m] * cb[m]).sum(1)[None, :]).reshape(-1)
+            kth = max(1, int(math.ceil(kf * g.numel())))
+            radii[m] = np.sqrt(np.float32(max(torch.kthvalue(g.cpu(), kth).values.item(), 0.0)))
+        return radii
     d = (cent * cent).sum(1)[None, :] - 2.0 * (qc @ cent.T)
     probes = d.topk(min(w.nprobe, index.nlist), dim=1, largest=False).indices  # [n][nprobe]
     res = (qc[:, None, :] - cent[probes]).reshape(-1, index.M, index.dsub)     # [n*nprobe][M][dsub]
@@ -414,10 +427,11 @@ def dynamic_radii(w: Workload, index: Index, centres: torch.Tensor, q: torch.Ten
     return np.ascontiguousarray((pred * scale).to(torch.float32).numpy())
 
 
-def exact_knn(w: Workload, centres: torch.Tensor, q: torch.Tensor, k: int) -> np.ndarray:
+def exact_knn(w: Workload, centres: torch.Tensor, q: torch.Tensor, k: int, metric: int = 0) -> np.ndarray:
     """Ground-truth neighbours for recall reporting: ids [Q][k] of the k nearest
-    base vectors by squared L2 (paper Sec. 2.1, metric definition), streamed over
-    regenerated base chunks with a running top-k (fp32 on `centres.device`)."""
+    base vectors by squared L2 (paper Sec. 2.1, metric definition), or of the k largest
+    inner products (metric = 1), streamed over regenerated base chunks with a running
+    top-k (fp32 on `centres.device`)."""
     device = centres.device
     best_d = torch.full((q.shape[0], k), float("inf"), device=device)
     best_i = torch.full((q.shape[0], k), -1, dtype=torch.int64, device=device)
@@ -425,7 +439,7 @@ def exact_knn(w: Workload, centres: torch.Tensor, q: torch.Tensor, k: int) -> np
     for s in range(0, w.N, BASE_CHUNK):
         c = min(BASE_CHUNK, w.N - s)
         x = base_chunk(w, centres, s, c)
-        d = qq - 2.0 * (q @ x.T) + (x * x).sum(1)[None, :]
+        d = -(q @ x.T) if metric == 1 else qq - 2.0 * (q @ x.T) + (x * x).sum(1)[None, :]
         dk, ik = d.topk(min(k, c), dim=1, largest=False)
         cat_d = torch.cat([best_d, dk], 1)
         cat_i = torch.cat([best_i, ik + s], 1)

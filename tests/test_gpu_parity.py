@@ -53,36 +53,38 @@ def cand_offsets(idx, probes):
     return offs
 
 
-def full_check(w, idx, q, radii, nprobe=None, k=None, stages=True):
+def full_check(w, idx, q, radii, nprobe=None, k=None, stages=True, metric=0, mode=0):
     """All entry points against the oracle for one (index, queries, radii)."""
     b = _binding()
     nprobe = w.nprobe if nprobe is None else nprobe
     k = w.k if k is None else k
-    say(f"  case {w.name}: N={idx.N} D={idx.D} nlist={idx.nlist} M={idx.M} Q={q.shape[0]} nprobe={nprobe} k={k}")
-    gi = b.IvfPqIndex.from_index(idx)
+    say(f"  case {w.name}: N={idx.N} D={idx.D} nlist={idx.nlist} M={idx.M} Q={q.shape[0]} nprobe={nprobe} k={k}"
+        + (f" metric={metric} mode={mode}" if metric or mode else ""))
+    gi = b.IvfPqIndex.from_index(idx, metric=metric)
     dq = _cuda(q)
-    o_pid, o_pd = oracle.coarse(q, idx.centroids, nprobe)
+    okw = dict(mode=mode, metric=metric)
+    o_pid, o_pd = oracle.coarse(q, idx.centroids, nprobe, metric=metric)
     if stages:
         pid, pd = gi.coarse(dq, nprobe)
         torch.cuda.synchronize()
         assert np.array_equal(pid.cpu().numpy(), o_pid), "probe lists differ"
         assert_same_float(pd.cpu().numpy(), o_pd, "probe distances")
-        lut, mask = gi.build_lut(dq, _cuda(o_pid), radii)
-        o_lut, o_mask = oracle.build_lut(q, idx.centroids, idx.codebooks, o_pid, radii)
+        lut, mask = gi.build_lut(dq, _cuda(o_pid), radii, mode=mode)
+        o_lut, o_mask = oracle.build_lut(q, idx.centroids, idx.codebooks, o_pid, radii, **okw)
         torch.cuda.synchronize()
         assert np.array_equal(mask.cpu().numpy().view(np.uint64), o_mask), "keep masks differ"
         assert_same_float(lut.cpu().numpy(), o_lut, "table values")
-        o_offs, o_cd, o_ci = oracle.scan_all(q, idx, o_pid, radii)
+        o_offs, o_cd, o_ci = oracle.scan_all(q, idx, o_pid, radii, **okw)
         assert np.array_equal(o_offs, cand_offsets(idx, o_pid))
-        cd, ci, err = gi.scan_all(dq, _cuda(o_pid), radii, _cuda(o_offs))
+        cd, ci, err = gi.scan_all(dq, _cuda(o_pid), radii, _cuda(o_offs), mode=mode)
         torch.cuda.synchronize()
         assert int(err.item()) == 0
         assert np.array_equal(ci.cpu().numpy(), o_ci), "candidate sets differ"
         assert_same_float(cd.cpu().numpy(), o_cd, "candidate distances")
-        ids2, dist2 = gi.scan_topk(dq, _cuda(o_pid), k, radii)
-    ids, dist = gi.search(dq, nprobe, k, radii)
+        ids2, dist2 = gi.scan_topk(dq, _cuda(o_pid), k, radii, mode=mode)
+    ids, dist = gi.search(dq, nprobe, k, radii, mode=mode)
     torch.cuda.synchronize()
-    o_ids, o_dist = oracle.search(q, idx, nprobe, k, radii, threads=8)
+    o_ids, o_dist = oracle.search(q, idx, nprobe, k, radii, threads=8, **okw)
     assert np.array_equal(ids.cpu().numpy(), o_ids), "top-k ids differ"
     assert_same_float(dist.cpu().numpy(), o_dist, "top-k distances")
     # both ways of loading code blocks (whole, or first half with the rest on demand) must
@@ -90,7 +92,7 @@ def full_check(w, idx, q, radii, nprobe=None, k=None, stages=True):
     for variant in (1, 2):
         b.set_option("scan_loads", variant)
         try:
-            ids_v, dist_v = gi.search(dq, nprobe, k, radii)
+            ids_v, dist_v = gi.search(dq, nprobe, k, radii, mode=mode)
             torch.cuda.synchronize()
         finally:
             b.set_option("scan_loads", 0)
@@ -312,6 +314,110 @@ def test_hit_count_scoring_1m(lib):
         assert np.array_equal(ids.cpu().numpy()[sample], o_ids), (mode, d_rq is not None)
         assert_same_float(dist.cpu().numpy()[sample], o_dist, f"C2 mode {mode}")
     gi.close()
+
+
+def _ip_radii(idx, q, frac):
+    """Per-subspace radii that keep about `frac` of the entries under the inner-product keep
+    rule (|q_m - e|^2 - |e|^2 <= r_m^2); input recipe only."""
+    qm = q.astype(np.float64).reshape(q.shape[0], idx.M, 1, idx.dsub)
+    ent = idx.codebooks.astype(np.float64)[None]
+    g = ((qm - ent) ** 2).sum(-1) - (ent ** 2).sum(-1)
+    r2 = np.quantile(g.transpose(1, 0, 2).reshape(idx.M, -1), frac, axis=1)
+    return np.sqrt(np.maximum(r2, 0.0)).astype(np.float32)
+
+
+@pytest.mark.parametrize("name", ["T_gauss", "T_sift", "T_deep", "T_tti"])
+def test_inner_product_tiny_workloads(lib, name):
+    """Inner-product metric, every stage and every scoring mode against the oracle."""
+    w = wl.WORKLOADS[name]
+    idx, centres = wl.train_index(w)
+    q = wl.queries(w, centres).numpy()
+    for frac in (0.3, 1.0):
+        radii = _ip_radii(idx, q, frac) if frac < 1.0 else np.full(idx.M, np.inf, np.float32)
+        for mode in (0, 1, 2):
+            full_check(w, idx, q, radii, metric=1, mode=mode)
+    radii = _ip_radii(idx, q, 0.3)
+    full_check(w, idx, q[:7], radii, nprobe=idx.nlist, metric=1)
+    full_check(w, idx, q[:7], radii, nprobe=1, metric=1)
+    # radii per query, on the device
+    b = _binding()
+    rq = np.stack([_ip_radii(idx, q[i:i + 1], 0.3) for i in range(q.shape[0])])
+    gi = b.IvfPqIndex.from_index(idx, metric=b.METRIC_IP)
+    assert gi.info()["metric"] == 1
+    for mode in (0, 2):
+        o_ids, o_dist = oracle.search(q, idx, w.nprobe, w.k, rq, mode=mode, metric=1)
+        ids, dist = gi.search(_cuda(q), w.nprobe, w.k, None, mode=mode, query_radii=_cuda(rq))
+        assert np.array_equal(ids.cpu().numpy(), o_ids), mode
+        assert_same_float(dist.cpu().numpy(), o_dist, f"per-query radii, inner product, mode {mode}")
+    gi.close()
+
+
+@pytest.mark.parametrize("M,D", [(64, 128), (48, 96), (100, 200), (16, 64), (12, 12), (5, 15), (128, 128)])
+def test_inner_product_shapes(lib, M, D):
+    """Specialised and run-time-M kernels under the inner-product metric; ragged and empty
+    lists; more probes than one metadata chunk; k above one pass; negative and positive scores."""
+    rng = np.random.default_rng(M * 77 + D)
+    sizes = [0, 1, 63, 64, 65, 0, 130, 700, 5, 1500, 64 * 9, 0, 333, 2, 127, 129]
+    idx = _random_index(rng, 0, D, len(sizes), M, sizes)
+    q = rng.normal(size=(33, D)).astype(np.float32)
+    q[0] = 0.0                                                     # every score is zero: ties by id
+    w = wl.Workload(f"ip_M{M}", idx.N, D, idx.nlist, M, 33, 6, 100, "gauss", 1, 1.0)
+    r = _ip_radii(idx, q, 0.4)
+    full_check(w, idx, q, r, metric=1)
+    full_check(w, idx, q[:5], np.full(M, np.inf, np.float32), nprobe=idx.nlist, k=128, metric=1)
+    full_check(w, idx, q[:5], r, nprobe=idx.nlist, k=700, metric=1, stages=False)
+    full_check(w, idx, q[:3], np.zeros(M, np.float32), nprobe=2, k=1, metric=1)
+    qs = rng.normal(size=(2100, D)).astype(np.float32)
+    full_check(w, idx, qs, r, nprobe=5, k=150, metric=1, stages=False)   # one workgroup per query, two passes
+    nlist = 200
+    idx2 = _random_index(rng, 0, D, nlist, M, rng.integers(0, 90, size=nlist))
+    w2 = wl.Workload(f"ip_probes_M{M}", idx2.N, D, nlist, M, 0, 150, 100, "gauss", 1, 1.0)
+    full_check(w2, idx2, qs[:9], _ip_radii(idx2, qs[:9], 0.4), nprobe=150, k=100, metric=1)
+
+
+def test_inner_product_identity_codebook_exact_mips(lib):
+    """Lossless codes, all lists probed, nothing thresholded: exact maximum inner product search."""
+    from helpers import identity_index
+    rng = np.random.default_rng(3)
+    base, idx = identity_index(rng)
+    queries = rng.integers(-64, 64, size=(20, idx.D)).astype(np.int64)
+    b = _binding()
+    gi = b.IvfPqIndex.from_index(idx, metric=b.METRIC_IP)
+    ids, dist = gi.search(_cuda(queries.astype(np.float32)), idx.nlist, 15, np.full(idx.M, np.inf, np.float32))
+    ip = queries @ base.T
+    for i in range(queries.shape[0]):
+        o = np.lexsort((np.arange(base.shape[0]), -ip[i]))[:15]
+        assert np.array_equal(ids[i].cpu().numpy(), o)
+        assert np.array_equal(dist[i].cpu().numpy().astype(np.int64), -ip[i][o])
+    gi.close()
+
+
+def test_inner_product_coarse_degenerate(lib):
+    """Coarse stage under the inner-product metric with identical and nearly identical
+    centroids (exact fallback, ties by list id) and with many lists."""
+    rng = np.random.default_rng(22)
+    b = _binding()
+    D, M = 16, 4
+    for name, cent in [
+        ("all equal", np.tile(rng.normal(size=(1, D)).astype(np.float32), (5000, 1))),
+        ("tiny jitter", (rng.normal(size=(1, D)) + 1e-7 * rng.normal(size=(3000, D))).astype(np.float32)),
+        ("ordinary", rng.normal(size=(20000, D)).astype(np.float32)),
+        ("zero", np.zeros((700, D), dtype=np.float32)),
+    ]:
+        nlist = cent.shape[0]
+        idx = _random_index(rng, 0, D, nlist, M, np.full(nlist, 1, dtype=np.int64))
+        idx.centroids = np.ascontiguousarray(cent)
+        q = rng.normal(size=(20, D)).astype(np.float32)
+        gi = b.IvfPqIndex.from_index(idx, metric=b.METRIC_IP)
+        for nprobe in (1, 10, 200, 1000):
+            nprobe = min(nprobe, nlist)
+            o_pid, o_pd = oracle.coarse(q, idx.centroids, nprobe, metric=1)
+            pid, pd = gi.coarse(_cuda(q), nprobe)
+            torch.cuda.synchronize()
+            assert np.array_equal(pid.cpu().numpy(), o_pid), (name, nprobe)
+            assert_same_float(pd.cpu().numpy(), o_pd, f"{name} nprobe={nprobe}")
+        gi.close()
+        say(f"  coarse (inner product), {name}: ok")
 
 
 def test_coarse_degenerate_centroids(lib):
