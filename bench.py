@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # elementwise pass over 1 GiB: x2.000 and x1.000).  Commands and raw figures: profiles/.
 MEASURED_TRAFFIC_BYTES = {
     ("C2", 0.25): 4.73323e6 * 1024 * 2.000 + 171875 * 1024 * 1.000,
-    ("C5", 0.25): 1.18555e8 * 1024 * 2.000 + 231875 * 1024 * 1.000,
+    ("C5", 0.25): 1.1869e8 * 1024 * 2.000 + 171875 * 1024 * 1.000,
 }
 
 
