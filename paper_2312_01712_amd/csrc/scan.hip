@@ -756,8 +756,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
 // A kept entry stores 0 - IP, a missed one the bound 0 - thr_m.  The table depends on
 // the query only, so a workgroup builds it once and then streams the probed lists with
 // no barrier between them; a point of list c scores (0 - IP(q, centroid_c)) plus the
-// sum of its table values, subspaces ascending.  Scores have either sign: no early
-// exit of the sums, and keys go through the order-preserving map of dist_key.
+// sum of its table values, subspaces ascending.  Scores have either sign: keys go
+// through the order-preserving map of dist_key, and the early exit of the sums works
+// from a lower bound on what the remaining subspaces can still add (adc_ip_exit).
 
 template <int MODE>
 __device__ inline float table_value_ip(float ip, float thr, float thr_in) {
@@ -805,6 +806,36 @@ __device__ inline float neg_ip_chain(SP sq, const float *__restrict__ cen, int D
   return 0.0f - acc;
 }
 
+// Sum with early exit for terms of either sign.  suf[j] is the fp32 sum of the row minima
+// of subspaces >= 8 j, and slack >= (4 M + 8) 2^-24 (|start| + sum_m max_e |table[m][e]|).
+// Every fp32 addition is monotone in both operands, so the final sum is at least what the
+// chain gives when each remaining term is replaced by its row minimum; that in turn is at
+// least partial + (exact sum of the minima) - M 2^-24 (|start| + sum of max |term|) by the
+// usual bound on sequential summation.  suf, slack and the test expression are themselves
+// rounded; all of these errors together stay below half of slack.  So if
+// fl(partial + fl(suf - slack)) is above the bound on the k-th best score for every point of
+// the block, no point of it can enter the result and the rest of the block is skipped.
+// Points that survive get exactly the sum adc_sum computes.
+template <int MT>
+__device__ inline bool adc_ip_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r, float start,
+                                   uint32_t pref, bool valid, const LDS float *suf, float slack, float &out) {
+  float dist = start;
+#pragma unroll
+  for (int g = 0; g < MT; g += 8) {
+#pragma unroll
+    for (int m = g; m < (g + 8 < MT ? g + 8 : MT); ++m) {
+      const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
+      dist += lut[m * 256 + code];
+    }
+    if (g + 8 < MT) {
+      const float lb = dist + (suf[(g + 8) >> 3] - slack);
+      if (__ballot(valid && dist_key<true>(lb) <= pref) == 0) return false;
+    }
+  }
+  out = dist;
+  return true;
+}
+
 template <int MT, int NW, bool DUMP>
 __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2) {
   constexpr int NT = NW * 64;
@@ -832,6 +863,9 @@ __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2
   LDS float *meta_start = (LDS float *)(meta_len + META);
   LDS float *sthr = meta_start + META;  // [M]
   LDS float *sthr_in = sthr + IVFPQ_MAX_M;
+  LDS float *srmin = sthr_in + IVFPQ_MAX_M;    // [M] smallest value of each table row
+  LDS float *srabs = srmin + IVFPQ_MAX_M;      // [M] largest magnitude of each table row
+  LDS float *ssuf = srabs + IVFPQ_MAX_M;       // [M/8 + 2] suffix sums of srmin at the check points, then sum srabs
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -890,6 +924,34 @@ __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2
       lut[mu * 256 + e] = table_value_ip(ip, sthr[mu], sthr_in[mu], mode);
     }
   }
+  // ---- row minima and magnitudes for the early exit (one row per wavefront and pass) ----
+  if constexpr (MT > 0 && !DUMP) {
+    __syncthreads();
+    for (int m = wave; m < M; m += NW) {
+      const floatx4 v = *(const LDS floatx4 *)(lut + m * 256 + 4 * lane);
+      float lo = fminf(fminf(v[0], v[1]), fminf(v[2], v[3]));
+      float hi = fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3])));
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off));
+        hi = fmaxf(hi, __shfl_xor(hi, off));
+      }
+      if (lane == 0) {
+        srmin[m] = lo;
+        srabs[m] = hi;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      float acc = 0.0f, mag = 0.0f;
+      for (int m = M - 1; m >= 0; --m) {
+        acc += srmin[m];
+        mag += srabs[m];
+        if ((m & 7) == 0) ssuf[m >> 3] = acc;
+      }
+      ssuf[(M + 7) / 8] = mag;
+    }
+  }
   // ---- the probed lists, META at a time ----
   for (int p0 = p_begin; p0 < p_end; p0 += META) {
     __syncthreads();  // table written; nobody still reads the previous metadata
@@ -913,21 +975,26 @@ __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2
       if constexpr (MT > 0) {
         if (wave < nb) {
           const int last = nb - 1;
+          const float slack = (float)(4 * MT + 8) * 5.9604645e-08f * (fabsf(start) + ssuf[(MT + 7) / 8]);
           CodeRegs<MPT / 4> nxt;
           load_codes<MPT>(base, nb, wave, lane, nxt);
           for (int b = wave; b < nb; b += NW) {
             CodeRegs<MPT / 4> cur = nxt;
             const int bn = b + NW < last ? b + NW : last;
             load_codes<MPT>(base, nb, bn, lane, nxt);
-            const float dist = adc_sum<MT>(lut, cur, start);
             const int i = b * 64 + lane;
             const bool valid = i < len;
             if (DUMP) {
+              const float dist = adc_sum<MT>(lut, cur, start);
               if (valid) {
                 a.all_dist[dump_pos + i] = dist;
                 a.all_ids[dump_pos + i] = a.ids[row0 + i];
               }
             } else {
+              const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
+              const uint32_t pref = (a.ablate & 8) ? SENT_D : (shared < st.tau.d ? shared : st.tau.d);
+              float dist;
+              if (!adc_ip_exit<MT>(lut, cur, start, pref, valid, ssuf, slack, dist)) continue;
               wave_offer<true>(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
             }
           }
@@ -1112,7 +1179,7 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
 size_t scan_ip_lds(const ScanArgs &a, int nw) {
   const int lut_bytes = a.M * 1024, stage = nw * KP * 12;
   return (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) + (size_t)nw * 64 * 12 +
-         ((4 * (nw + 1) + 15) & ~15) + 64 * 24 + 2 * IVFPQ_MAX_M * 4;
+         ((4 * (nw + 1) + 15) & ~15) + 64 * 24 + 4 * IVFPQ_MAX_M * 4 + (IVFPQ_MAX_M / 8 + 2) * 4;
 }
 
 template <int MT, int NW>
