@@ -50,6 +50,8 @@ def _desc(**over):
     (dict(nlist=0), binding.ERR_INVALID_ARGUMENT),
     (dict(N=-1), binding.ERR_INVALID_ARGUMENT),
     (dict(N=1 << 33), binding.ERR_UNSUPPORTED),
+    (dict(metric=2), binding.ERR_INVALID_ARGUMENT),
+    (dict(metric=-1), binding.ERR_INVALID_ARGUMENT),
     (dict(centroids=None), binding.ERR_INVALID_ARGUMENT),
     (dict(codes=None), binding.ERR_INVALID_ARGUMENT),
     (dict(list_offsets=np.array([0, 3, 2, 7, 10], np.int64)), binding.ERR_INVALID_ARGUMENT),
