@@ -44,6 +44,8 @@ constexpr int res_regs(int wpe) { return wpe == 2 ? 112 : 48; }
 // ... as long as they and the two code register sets stay under this.
 constexpr int res_max_total(int wpe) { return wpe == 2 ? 200 : 82; }
 constexpr int KP = 128;                    // capacity of a wavefront's sorted list
+constexpr int cmin(int a, int b) { return a < b ? a : b; }
+constexpr int LOOKUP_GROUP = 8;            // table look-ups a wavefront keeps in flight
 constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
 constexpr int64_t SENT_ID = LLONG_MAX;
 
@@ -275,15 +277,54 @@ __device__ inline void load_codes(const uint8_t *__restrict__ list_base, int nb,
   load_chunks<MP, 0, MP / 16 + (MP % 16) / 4>(list_base, nb, b, lane, r);
 }
 
+// Byte offset of a point's code in a 1 KiB table row: 4 * byte j of w.  The byte select of
+// the sub-dword addressing form does the extraction and the shift in one instruction
+// (the compiler emits a bit-field extract plus a shift-add for the plain expression, which
+// makes the vector ALU the limit of the look-up loop).
+__device__ __forceinline__ uint32_t code_offset(uint32_t w, int j) {
+  uint32_t a;
+  const uint32_t two = 2u;
+  switch (j) {
+    case 0: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(a) : "s"(two), "v"(w)); break;
+    case 1: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(a) : "s"(two), "v"(w)); break;
+    case 2: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(a) : "s"(two), "v"(w)); break;
+    default: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(a) : "s"(two), "v"(w)); break;
+  }
+  return a;
+}
+
+// dist += table value of the point's code, for subspaces [h, h1), in subspace order.  The
+// look-ups are issued together and only then added: the sums form a dependent chain, and
+// without the fences the scheduler pairs every read with its add, so that a wavefront has
+// one LDS read in flight at a time.
+template <int MT>
+__device__ __forceinline__ void lookup_group(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
+                                             int h, int h1, float &dist) {
+  float t[LOOKUP_GROUP];
+#pragma unroll
+  for (int j = 0; j < LOOKUP_GROUP; ++j) {
+    const int m = h + j;
+    if (m < h1) {
+      // The table starts at LDS address 0 (the kernels declare no static LDS; the launcher
+      // checks it), so the row offset fits the instruction's immediate and the look-up
+      // needs no address arithmetic beyond code_offset.
+      const uint32_t off = code_offset(r.w[m >> 2], m & 3);
+      t[j] = *(const LDS float *)(uintptr_t)(uint32_t)(m * 1024 + off);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < LOOKUP_GROUP; ++j)
+    if (h + j < h1) dist += t[j];
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int MT>
 __device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
                                 float start = 0.0f) {
   float dist = start;
 #pragma unroll
-  for (int m = 0; m < MT; ++m) {
-    const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
-    dist += lut[m * 256 + code];
-  }
+  for (int h = 0; h < MT; h += LOOKUP_GROUP) lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, MT), dist);
   return dist;
 }
 
@@ -300,11 +341,9 @@ __device__ inline bool adc_part_exit(const LDS float *lut, const CodeRegs<((MT +
 #pragma unroll
   for (int g = M0; g < M1; g += 8) {
 #pragma unroll
-    for (int m = g; m < (g + 8 < M1 ? g + 8 : M1); ++m) {
-      const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
-      dist += lut[m * 256 + code];
-    }
-    if ((g + 8 < M1 ? g + 8 : M1) < MT) {
+    for (int h = g; h < cmin(g + 8, M1); h += LOOKUP_GROUP)
+      lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, cmin(g + 8, M1)), dist);
+    if (cmin(g + 8, M1) < MT) {
       if (__ballot(valid && __float_as_uint(dist) <= pref) == 0) return false;
     }
   }
@@ -823,10 +862,8 @@ __device__ inline bool adc_ip_exit(const LDS float *lut, const CodeRegs<((MT + 3
 #pragma unroll
   for (int g = 0; g < MT; g += 8) {
 #pragma unroll
-    for (int m = g; m < (g + 8 < MT ? g + 8 : MT); ++m) {
-      const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
-      dist += lut[m * 256 + code];
-    }
+    for (int h = g; h < cmin(g + 8, MT); h += LOOKUP_GROUP)
+      lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, cmin(g + 8, MT)), dist);
     if (g + 8 < MT) {
       const float lb = dist + (suf[(g + 8) >> 3] - slack);
       if (__ballot(valid && dist_key<true>(lb) <= pref) == 0) return false;
@@ -1148,6 +1185,21 @@ int g_scan_ablate = 0;
 int g_scan_variant = 0;  // code loads: 0 = adaptive, 1 = always whole blocks, 2 = always first half + rest on demand
 int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
 
+// The look-up code addresses the table at LDS address 0, which holds as long as a kernel
+// has no static LDS in front of its dynamic allocation.  Checked once per kernel.
+template <typename K>
+int check_no_static_lds(K kern, bool &checked) {
+  if (checked) return IVFPQ_OK;
+  hipFuncAttributes attr;
+  IVFPQ_HIP_TRY(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kern)));
+  if (attr.sharedSizeBytes != 0) {
+    ivfpq::set_error("scan: kernel has %zu bytes of static LDS, 0 expected", (size_t)attr.sharedSizeBytes);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  checked = true;
+  return IVFPQ_OK;
+}
+
 template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
@@ -1158,6 +1210,8 @@ int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump,
     return IVFPQ_ERR_UNSUPPORTED;
   }
   auto kern = dump ? scan_kernel<MT, DSUB, NW, true> : scan_kernel<MT, DSUB, NW, false>;
+  static bool lds_checked[2] = {false, false};
+  if (int rc = check_no_static_lds(kern, lds_checked[dump ? 1 : 0])) return rc;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) (void)hipGetLastError();  // not fatal: the launch itself reports a real limit
@@ -1190,6 +1244,8 @@ int launch_scan_ip_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool du
     return IVFPQ_ERR_UNSUPPORTED;
   }
   auto kern = dump ? scan_ip_kernel<MT, NW, true> : scan_ip_kernel<MT, NW, false>;
+  static bool lds_checked[2] = {false, false};
+  if (int rc = check_no_static_lds(kern, lds_checked[dump ? 1 : 0])) return rc;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) (void)hipGetLastError();
