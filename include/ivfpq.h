@@ -225,7 +225,8 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  * rest only when needed.  Results do not depend on it.
  * "scan_ablate": bit mask that switches off parts of the scan kernel to attribute
  * its time (1 table arithmetic, 2 list scan, 4 top-k offers: results are
- * meaningless with any of these; 8 turns off the early exit of the distance sums:
+ * meaningless with any of these; 8 turns off the early exit of the distance sums,
+ * 32 the switch to plain scanning for queries whose blocks rarely end early:
  * results unchanged). */
 int ivfpq_set_option(const char *name, int value);
 

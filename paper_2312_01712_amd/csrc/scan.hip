@@ -45,6 +45,7 @@ constexpr int res_regs(int wpe) { return wpe == 2 ? 112 : 48; }
 constexpr int res_max_total(int wpe) { return wpe == 2 ? 200 : 82; }
 constexpr int KP = 128;                    // capacity of a wavefront's sorted list
 constexpr int cmin(int a, int b) { return a < b ? a : b; }
+constexpr int SUF_SLOTS = IVFPQ_MAX_M / 8 + 4;  // floats per wavefront for the suffix sums of the row minima
 constexpr int LOOKUP_GROUP = 8;            // table look-ups a wavefront keeps in flight
 constexpr uint32_t SENT_D = 0xFFFFFFFFu;   // sentinel key: larger than any distance
 constexpr int64_t SENT_ID = LLONG_MAX;
@@ -132,15 +133,69 @@ __device__ inline Key bcast_key(const Key &a, int src) {
   return o;
 }
 
+// Cross-lane helpers on the data-parallel-primitive path (no LDS traffic).  XOR1 / XOR2 swap
+// lanes within a quad, HALF_MIRROR reverses each group of 8 lanes, ROR4 / ROR8 rotate each
+// row of 16 lanes by 4 / 8.
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(v)));
+}
+
+__device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// Minima of eight table rows at once.  lo[j] is this lane's minimum over its entries of row
+// j (bit patterns of non-negative floats, which order like the values).  Three exchange
+// steps halve the number of rows a lane carries while doubling the lanes a value covers
+// (lane bit 0, 1, 2 select which row is kept), two more combine the groups of a row of 16
+// lanes.  Afterwards lane l with (l & 15) < 8 holds the minimum of row (l & 7) over its 16
+// lanes: 5 + 2 + 1 + 1 exchanges instead of 8 x 4.
+__device__ __forceinline__ uint32_t rows8_min16(const uint32_t (&lo)[8], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+  uint32_t a[4], c[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t keep = b0 ? lo[2 * i + 1] : lo[2 * i], send = b0 ? lo[2 * i] : lo[2 * i + 1];
+    a[i] = umin32(keep, dpp_u32<DPP_XOR1>(send));        // row 2 i + b0 over a lane pair
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const uint32_t keep = b1 ? a[2 * i + 1] : a[2 * i], send = b1 ? a[2 * i] : a[2 * i + 1];
+    c[i] = umin32(keep, dpp_u32<DPP_XOR2>(send));        // row 4 i + 2 b1 + b0 over a quad
+  }
+  // a rotation by 4 within the 16 lanes pairs every lane with one whose bit 2 differs and
+  // whose bits 0 and 1 agree; over the two lanes that end up with a row (l and l + 8) the
+  // four quads of the 16 lanes are all covered
+  const uint32_t keep = b2 ? c[1] : c[0], send = b2 ? c[0] : c[1];
+  uint32_t d = umin32(keep, dpp_u32<DPP_ROR4>(send));    // row 4 b2 + 2 b1 + b0 over two quads
+  d = umin32(d, dpp_u32<DPP_ROR8>(d));                   // ... over the 16 lanes
+  return d;
+}
+
+// Sum over each group of 8 consecutive lanes, left in every lane of the group.
+__device__ __forceinline__ float group8_sum(float v) {
+  v += dpp_f32<DPP_XOR1>(v);
+  v += dpp_f32<DPP_XOR2>(v);
+  v += dpp_f32<DPP_HALF_MIRROR>(v);
+  return v;
+}
+
 // What an entry at squared distance d2 stores (r2 = r_m^2).  Mode 0: the distance,
 // clamped at r2 (written as a minimum: equal bit for bit to keep ? d2 : r2, and a NaN
-// d2 yields r2 in both forms).  Modes 1 and 2 are the hit-count scorings of paper
+// d2, whose pattern is above every number's, yields r2 in both forms).  Modes 1 and 2 are the hit-count scorings of paper
 // Sec. 5.4, expressed as penalties so that smaller is better: mode 1 stores 0 for a hit
 // and 1 for a miss (hit count = M - sum); mode 2 adds the inner sphere of radius
 // r_m / 2: 0 inside it, 1 inside the outer sphere only, 2 outside both (score = M - sum).
 template <int MODE>
 __device__ inline float table_value(float d2, float r2) {
-  if (MODE == 0) return fminf(d2, r2);
+  if (MODE == 0) {  // min(d2, r2) on the bit patterns: both are >= +0, so bits order like values
+    const uint32_t a = __float_as_uint(d2), b = __float_as_uint(r2);
+    return __uint_as_float(a < b ? a : b);
+  }
   if (MODE == 1) return d2 <= r2 ? 0.0f : 1.0f;
   return d2 <= 0.25f * r2 ? 0.0f : (d2 <= r2 ? 1.0f : 2.0f);
 }
@@ -179,12 +234,9 @@ __device__ inline float lut_entry(SP sq, const float *__restrict__ cen,
 
 // Four consecutive entries of one subspace (same arithmetic per entry as above);
 // ev holds their 4 * DSUB coordinates as loaded from the codebook.
-template <int DSUB, int MODE, typename SP>
-__device__ inline float4 lut_entry4(SP res_p, const float4 *ev, float r2) {
-  constexpr int DS = DSUB > 0 ? DSUB : 1;
-  float res[DS];  // residual projection q_m - centroid_m, computed once per list
-#pragma unroll
-  for (int j = 0; j < DSUB; ++j) res[j] = res_p[j];
+template <int DSUB, int MODE>
+__device__ inline float4 lut_entry4(const float (&res)[DSUB > 0 ? DSUB : 1], const float4 *ev, float r2) {
+  constexpr int DS = DSUB > 0 ? DSUB : 1;  // res: residual projection q_m - centroid_m, computed once per list
   float e[4 * DS];
 #pragma unroll
   for (int x = 0; x < DSUB; ++x) {
@@ -328,23 +380,29 @@ __device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) /
   return dist;
 }
 
-// Same sum, over subspaces [M0, M1), with early exit.  Table values are >= 0 and fp32 addition of a
-// non-negative term never decreases a sum, so a partial sum above the bound
-// means the final distance is above it too.  Every 8 subspaces the wavefront
-// checks whether any of its points can still reach the bound `pref` (an upper
-// bound on the k-th smallest distance); if none can, the rest of the block is
-// skipped.  Returns false in that case.  Points that survive get exactly the
-// sum adc_sum computes.
+// Same sum, over subspaces [M0, M1), with early exit.  Table values are >= 0 and fp32
+// addition is monotone in both operands, so the final sum is at least what the chain gives
+// when every remaining term is replaced by the minimum of its table row; for non-negative
+// terms that is at least (partial + exact sum of those minima) (1 - M 2^-24).  suf[j] is an
+// fp32 sum (in some order) of the row minima of subspaces >= 8 j, itself within M 2^-24 of
+// the exact one, and tauf is the bound on the k-th smallest distance enlarged by 2^-13,
+// which covers these errors and the rounding of the test itself many times over (M <= 128).
+// Every 8 subspaces the wavefront checks whether any of its points can still reach the
+// bound; if none can, the rest of the block is skipped and false returned.  Points that
+// survive get exactly the sum adc_sum computes.  With `checks` off it is the plain sum.
 template <int MT, int M0, int M1>
 __device__ inline bool adc_part_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
-                                     uint32_t pref, bool valid, float &dist) {
+                                     const LDS float *suf, float tauf, bool checks, bool valid, float &dist) {
 #pragma unroll
   for (int g = M0; g < M1; g += 8) {
+    // requested ahead of the look-ups, so that it has arrived when they have
+    float rest = 0.0f;
+    if (checks && cmin(g + 8, M1) < MT) rest = suf[cmin(g + 8, M1) >> 3];
 #pragma unroll
     for (int h = g; h < cmin(g + 8, M1); h += LOOKUP_GROUP)
       lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, cmin(g + 8, M1)), dist);
-    if (cmin(g + 8, M1) < MT) {
-      if (__ballot(valid && __float_as_uint(dist) <= pref) == 0) return false;
+    if (checks && cmin(g + 8, M1) < MT) {  // `checks` is uniform: off, a check costs a scalar branch
+      if (__ballot(valid && dist + rest <= tauf) == 0) return false;
     }
   }
   return true;
@@ -551,9 +609,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
   LDS int32_t *meta_c = meta_len + META;
   LDS float *sr2 = (LDS float *)(meta_c + META);  // [M] r_m^2 of this query
+  LDS uint32_t *srmin = (LDS uint32_t *)(sr2 + IVFPQ_MAX_M);  // [M][4] partial minima (bit patterns) of each row of the current table
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
+  LDS float *ssuf = (LDS float *)(srmin + 4 * IVFPQ_MAX_M) + wave * SUF_SLOTS;  // this wavefront's suffix sums of srmin, per 8 subspaces
+  LDS uint32_t *stat = (LDS uint32_t *)((LDS float *)(srmin + 4 * IVFPQ_MAX_M) + NW * SUF_SLOTS);  // blocks scanned / scanned to the end
   const int64_t q = blockIdx.x / a.nsplit;
   const int split = blockIdx.x % a.nsplit;
   const int p_begin = (int)((int64_t)a.nprobe * split / a.nsplit);
@@ -582,9 +643,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       v = r * r;
     }
     sr2[m] = v;
+    srmin[4 * m] = srmin[4 * m + 1] = srmin[4 * m + 2] = srmin[4 * m + 3] = 0u;
   }
   const int mode = a.mode;
   if (tid <= NW) tau_words[tid] = SENT_D;
+  if (tid < 2) stat[tid] = 0u;
   SharedTau sh;
   sh.bound = tau_words;
   sh.rank = tau_words + 1;
@@ -632,6 +695,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   constexpr bool HALF_OK = MT > 0 && HCH >= 1 && HCH < NCH && MH < MT;
   bool use_half = HALF_OK && !DUMP && a.load_mode == 2;  // the nearest list is loaded whole
   bool sres_ready = false;
+  // Pruning (row minima, checks of the partial sums, partial loads) pays only where blocks
+  // do end early.  The workgroup counts, over the first PROBE_LISTS lists of its query, how
+  // many blocks were scanned and how many of them to the end; if nearly all were, the rest
+  // of the lists are scanned plainly.  Results do not depend on it.
+  constexpr int PROBE_LISTS = 4;
+  bool prune = VEC && !DUMP;
+  uint32_t tot_blocks = 0, tot_full = 0;
   for (int p = p_begin; p < p_end; ++p) {
     const int pm = (p - p_begin) & (META - 1);
     if (pm == 0) {
@@ -689,19 +759,48 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       else load_codes<MPT>(base, nb, b0, lane, nxt);
     }
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
+    if (VEC && !DUMP && p - p_begin == PROBE_LISTS && !(a.ablate & 32)) {
+      const uint32_t nblk = stat[0], nfull = stat[1];
+      prune = 8 * (uint64_t)nfull < 7 * (uint64_t)nblk;
+    }
     // ---- selective table for (query, list c) ----
     if constexpr (VEC) {
       // one subspace per wavefront and pass, four consecutive entries per lane; the
       // scoring mode is resolved once per list, outside the unrolled passes
       auto build_rows = [&](auto mode_tag) __attribute__((always_inline)) {
         constexpr int MODE = decltype(mode_tag)::value;
+        constexpr int NBATCH = (ITER + 7) / 8;
+        uint32_t lo[NBATCH][8];  // this lane's minimum over its entries of each row (for the early exit)
+#pragma unroll
+        for (int it = 0; it < NBATCH * 8; ++it) lo[it >> 3][it & 7] = 0xFFFFFFFFu;
+        // With 256 registers (WPE == 2) the passes form straight-line code (the validity of
+        // a row is known at compile time for every pass but the last) and the compiler
+        // overlaps their LDS reads.  With 128 registers that form spills, so each row stays
+        // a block of its own.
+        constexpr bool STRAIGHT = WPE == 2;
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {
           const int m = wave + it * NW;
-          if (m < MT) {
-            const float4 v = lut_entry4<DSUB, MODE>(
-                sres + m * DSUB, it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0], sr2[m]);
+          if ((STRAIGHT && (it + 1) * NW <= MT) || m < MT) {
+            float res[DS4];
+#pragma unroll
+            for (int j = 0; j < DS4; ++j) res[j] = sres[m * DSUB + j];
+            const float4 v = lut_entry4<DSUB, MODE>(res, it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0], sr2[m]);
             *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
+            if (!DUMP)
+              lo[it >> 3][it & 7] = umin32(umin32(__float_as_uint(v.x), __float_as_uint(v.y)),
+                                           umin32(__float_as_uint(v.z), __float_as_uint(v.w)));
+          }
+        }
+        if (!DUMP && prune) {
+          // one partial minimum per row and 16 lanes goes to LDS; the reader takes the
+          // smallest of the four
+#pragma unroll
+          for (int bt = 0; bt < NBATCH; ++bt) {
+            const uint32_t d = rows8_min16(lo[bt], lane);
+            const int it = bt * 8 + (lane & 7);
+            const int m = wave + it * NW;
+            if ((lane & 15) < 8 && it < ITER && m < MT) srmin[4 * m + (lane >> 4)] = d;
           }
         }
       };
@@ -731,9 +830,34 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       // looked up.  Loads are issued for every iteration (past the end they re-read the
       // list's last block, which is in bounds), so the block in flight never has to
       // complete before the current one can be used.
+      // Suffix sums of the row minima at the check points (every 8 subspaces), per wavefront:
+      // lane l holds rows l and 64 + l, groups of 8 lanes are summed in place, then the
+      // groups are accumulated from the last one down.
+      float suf0 = 0.0f;
+      if (VEC && !DUMP && prune) {
+        constexpr int NG = (MT + 7) / 8;
+        typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+        auto row_min = [&](int m) {
+          const uintx4 p = *(const LDS uintx4 *)(srmin + 4 * m);
+          return __uint_as_float(umin32(umin32(p[0], p[1]), umin32(p[2], p[3])));
+        };
+        float v0 = lane < MT ? row_min(lane) : 0.0f;
+        float v1 = (MT > 64 && lane + 64 < MT) ? row_min((MT > 64 ? 64 : 0) + lane) : 0.0f;
+        v0 = group8_sum(v0);
+        v1 = group8_sum(v1);
+        float acc = 0.0f;
+#pragma unroll
+        for (int j = NG - 1; j >= 0; --j) {
+          const int gl = __builtin_amdgcn_readlane((int)__float_as_uint(j < 8 ? v0 : v1), (j & 7) * 8);
+          acc += __uint_as_float((uint32_t)gl);
+          if (lane == 0) ssuf[j] = acc;
+        }
+        if (lane == 0) ssuf[NG] = 0.0f;
+        suf0 = acc;
+      }
       if (wave < nb && !(a.ablate & 2)) {
         const int last = nb - 1;
-        int late = 0, blocks = 0;
+        int late = 0, blocks = 0, full = 0;
         for (int b = wave; b < nb; b += NW) {
           CodeRegs<MPT / 4> cur = nxt;
           const int bn = b + NW < last ? b + NW : last;
@@ -750,21 +874,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
           } else {
             const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
             const uint32_t pref = (a.ablate & 8) ? SENT_D : (shared < st.tau.d ? shared : st.tau.d);
+            // bound on the k-th smallest distance, enlarged as adc_part_exit needs it
+            const float tauf = pref == SENT_D ? __builtin_inff() : __uint_as_float(pref) * 1.0001220703125f;
             float dist = 0.0f;
             ++blocks;
+            if (prune && !(suf0 <= tauf)) continue;  // no point of this list can reach the bound any more
             // first half of the chunks; most blocks end here
-            if (HALF_OK && !adc_part_exit<MT, 0, MH>(lut, cur, pref, valid, dist)) continue;
+            if (HALF_OK && !adc_part_exit<MT, 0, MH>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
             ++late;
             // the rest of the block: already in registers, or fetched now (rare)
             if (HALF_OK && use_half) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
-            if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, pref, valid, dist)) continue;
+            if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
+            ++full;
             if (!(a.ablate & 4)) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
             if (a.ablate & 4) st.L0.d = st.L0.d < __float_as_uint(dist) ? st.L0.d : __float_as_uint(dist);
           }
         }
         // how the next list is loaded: whole blocks if more than a quarter of this
         // list's blocks needed all their chunks, else the first half only
-        if (HALF_OK && !DUMP && a.load_mode == 0) use_half = 4 * late <= blocks;
+        if (HALF_OK && !DUMP && a.load_mode == 0) use_half = prune && 4 * late <= blocks;
+        tot_blocks += blocks;
+        tot_full += full;
+      }
+      if (VEC && !DUMP && p - p_begin == PROBE_LISTS - 1 && lane == 0) {
+        __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     } else {
       for (int b = wave; b < nb; b += NW) {
@@ -1204,7 +1338,8 @@ template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 24 + IVFPQ_MAX_M * 4 + (size_t)g_scan_lds_pad;
+                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 24 + 5 * IVFPQ_MAX_M * 4 +
+                     (size_t)NW * SUF_SLOTS * 4 + 16 + (size_t)g_scan_lds_pad;
   if (lds > 160 * 1024) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
