@@ -119,7 +119,7 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_ablate")) {
-    set_scan_ablate(value & 31);
+    set_scan_ablate(value & 63);
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_loads")) {

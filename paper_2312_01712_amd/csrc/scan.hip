@@ -278,7 +278,7 @@ struct ScanArgs {
   int32_t k_out, k_off;  // rows of the outputs hold k_out keys; this launch fills [k_off, k_off + k)
   const float *query_radii;     // [Q][M] per-query radii, or NULL: the shared r_m^2 of the call
   int32_t mode;       // scoring: 0 distances, 1 hit count, 2 reward/penalty hit count
-  int32_t load_mode;  // 0 adaptive, 1 whole blocks, 2 first half of the chunks, rest on demand
+  int32_t load_mode;  // 0 first half of the chunks ahead while pruning, 1 whole blocks, 2 always the first half
   int32_t ablate;  // measurement only: 1 skips the table arithmetic, 2 the list scan, 4 the top-k offers,
                    // 8 disables the early exit of the distance sums (results stay valid)
 };
@@ -693,7 +693,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   constexpr int HCH = (MPT / 16 + 1) / 2;
   constexpr int MH = 16 * HCH;  // subspaces covered by the first HCH chunks
   constexpr bool HALF_OK = MT > 0 && HCH >= 1 && HCH < NCH && MH < MT;
-  bool use_half = HALF_OK && !DUMP && a.load_mode == 2;  // the nearest list is loaded whole
+  // while pruning, only the first half of a block's chunks is fetched ahead
+  bool use_half = HALF_OK && !DUMP && a.load_mode != 1;
   bool sres_ready = false;
   // Pruning (row minima, checks of the partial sums, partial loads) pays only where blocks
   // do end early.  The workgroup counts, over the first PROBE_LISTS lists of its query, how
@@ -857,7 +858,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       }
       if (wave < nb && !(a.ablate & 2)) {
         const int last = nb - 1;
-        int late = 0, blocks = 0, full = 0;
+        int blocks = 0, full = 0;
         for (int b = wave; b < nb; b += NW) {
           CodeRegs<MPT / 4> cur = nxt;
           const int bn = b + NW < last ? b + NW : last;
@@ -881,7 +882,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             if (prune && !(suf0 <= tauf)) continue;  // no point of this list can reach the bound any more
             // first half of the chunks; most blocks end here
             if (HALF_OK && !adc_part_exit<MT, 0, MH>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
-            ++late;
             // the rest of the block: already in registers, or fetched now (rare)
             if (HALF_OK && use_half) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
             if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
@@ -890,12 +890,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             if (a.ablate & 4) st.L0.d = st.L0.d < __float_as_uint(dist) ? st.L0.d : __float_as_uint(dist);
           }
         }
-        // how the next list is loaded: whole blocks if more than a quarter of this
-        // list's blocks needed all their chunks, else the first half only
-        if (HALF_OK && !DUMP && a.load_mode == 0) use_half = prune && 4 * late <= blocks;
         tot_blocks += blocks;
         tot_full += full;
       }
+      // without pruning every block is needed whole; the list during which pruning was
+      // switched off still had its blocks fetched by halves
+      if (!prune && a.load_mode != 2) use_half = false;
       if (VEC && !DUMP && p - p_begin == PROBE_LISTS - 1 && lane == 0) {
         __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1316,7 +1316,7 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
 
 int g_scan_waves = 0;  // 0 = choose from the shape
 int g_scan_ablate = 0;
-int g_scan_variant = 0;  // code loads: 0 = adaptive, 1 = always whole blocks, 2 = always first half + rest on demand
+int g_scan_variant = 0;  // code loads: 0 = first half ahead while pruning, 1 = always whole blocks, 2 = always first half + rest on demand
 int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
 
 // The look-up code addresses the table at LDS address 0, which holds as long as a kernel
