@@ -879,7 +879,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             const float tauf = pref == SENT_D ? __builtin_inff() : __uint_as_float(pref) * 1.0001220703125f;
             float dist = 0.0f;
             ++blocks;
-            if (prune && !(suf0 <= tauf)) continue;  // no point of this list can reach the bound any more
+            // no point of this list can reach the bound any more (it only tightens): the
+            // wavefront is done with the list, and requests no further blocks of it
+            if (prune && !(suf0 <= tauf)) {
+              blocks += (nb - 1 - b) / NW;
+              break;
+            }
             // first half of the chunks; most blocks end here
             if (HALF_OK && !adc_part_exit<MT, 0, MH>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
             // the rest of the block: already in registers, or fetched now (rare)
