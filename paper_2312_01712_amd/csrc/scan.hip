@@ -1169,6 +1169,9 @@ __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2
             } else {
               const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
               const uint32_t pref = (a.ablate & 8) ? SENT_D : (shared < st.tau.d ? shared : st.tau.d);
+              // no point of this list can reach the bound any more (it only tightens): the
+              // wavefront is done with the list and requests no further blocks of it
+              if (dist_key<true>(start + (ssuf[0] - slack)) > pref) break;
               float dist;
               if (!adc_ip_exit<MT>(lut, cur, start, pref, valid, ssuf, slack, dist)) continue;
               wave_offer<true>(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
