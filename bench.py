@@ -55,7 +55,7 @@ def main():
                     help="0 distances (default), 1 hit count, 2 reward/penalty hit count")
     ap.add_argument("--dynamic-radii", action="store_true", help="per-query radii from the density-map recipe")
     ap.add_argument("--scan-waves", type=int, default=0)
-    ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 first half ahead while pruning, 1 whole blocks, 2 always first half")
+    ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 default (first chunk ahead while pruning), 1 whole blocks, 2 / 3 always first half / first chunk")
     ap.add_argument("--lds-pad", type=int, default=0, help="measurement only: extra LDS bytes per scan workgroup")
     ap.add_argument("--ablate", type=int, default=0, help="measurement only: scan_ablate bit mask (results invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

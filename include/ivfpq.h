@@ -220,10 +220,10 @@ int64_t ivfpq_coarse_fallbacks(int reset);
 /* Tuning knob for measurements, process-wide, not thread-safe against running
  * searches.  "scan_waves": wavefronts per workgroup of the fused scan kernel,
  * 0 (default: chosen from the shape), 4, 8 or 16.  Results do not depend on it.
- * "scan_loads": how the scan kernel fetches code blocks, 0 (default) the first half
- * of a block's chunks ahead and the rest only when needed, whole blocks once pruning
- * has been switched off for a query; 1 always whole blocks; 2 always the first half.
- * Results do not depend on it.
+ * "scan_loads": how the scan kernel fetches code blocks: 0 (default) the first chunk
+ * (16 subspaces) of a block ahead and the rest only when the block needs it, whole
+ * blocks once pruning has been switched off for a query; 1 always whole blocks; 2 / 3
+ * always the first half / the first chunk ahead.  Results do not depend on it.
  * "scan_ablate": bit mask that switches off parts of the scan kernel to attribute
  * its time (1 table arithmetic, 2 list scan, 4 top-k offers: results are
  * meaningless with any of these; 8 turns off the early exit of the distance sums,

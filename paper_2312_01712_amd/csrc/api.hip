@@ -123,7 +123,7 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_loads")) {
-    if (value < 0 || value > 2) { set_error("set_option: scan_loads must be 0, 1 or 2"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    if (value < 0 || value > 3) { set_error("set_option: scan_loads must be 0, 1, 2 or 3"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_scan_variant(value);
     return IVFPQ_OK;
   }

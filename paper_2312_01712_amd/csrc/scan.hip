@@ -278,7 +278,7 @@ struct ScanArgs {
   int32_t k_out, k_off;  // rows of the outputs hold k_out keys; this launch fills [k_off, k_off + k)
   const float *query_radii;     // [Q][M] per-query radii, or NULL: the shared r_m^2 of the call
   int32_t mode;       // scoring: 0 distances, 1 hit count, 2 reward/penalty hit count
-  int32_t load_mode;  // 0 first half of the chunks ahead while pruning, 1 whole blocks, 2 always the first half
+  int32_t load_mode;  // 0 default policy, 1 whole blocks, 2 always the first half of the chunks ahead, 3 always the first chunk
   int32_t ablate;  // measurement only: 1 skips the table arithmetic, 2 the list scan, 4 the top-k offers,
                    // 8 disables the early exit of the distance sums (results stay valid)
 };
@@ -693,8 +693,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   constexpr int HCH = (MPT / 16 + 1) / 2;
   constexpr int MH = 16 * HCH;  // subspaces covered by the first HCH chunks
   constexpr bool HALF_OK = MT > 0 && HCH >= 1 && HCH < NCH && MH < MT;
-  // while pruning, only the first half of a block's chunks is fetched ahead
-  bool use_half = HALF_OK && !DUMP && a.load_mode != 1;
+  constexpr bool QUARTER_OK = HALF_OK && HCH >= 2;  // the first chunk alone (16 subspaces) is a proper part
+  // How much of a block is fetched ahead: 0 all chunks, 1 the first half, 2 the first chunk;
+  // the rest is fetched when a block turns out to need it.  While pruning, most blocks end
+  // within their first chunk.
+  int depth = 0;
+  if (HALF_OK && !DUMP && a.load_mode != 1) depth = (QUARTER_OK && a.load_mode != 2) ? 2 : 1;
+  auto load_ahead = [&](const uint8_t *lb, int nblk, int blk, CodeRegs<MPT / 4> &r) __attribute__((always_inline)) {
+    if constexpr (MT > 0) {
+      load_chunks<MPT, 0, HALF_OK ? 1 : NCH>(lb, nblk, blk, lane, r);
+      if constexpr (HALF_OK) {
+        if (depth < 2) load_chunks<MPT, 1, HCH>(lb, nblk, blk, lane, r);
+        if (depth < 1) load_chunks<MPT, HCH, NCH>(lb, nblk, blk, lane, r);
+      }
+    }
+  };
   bool sres_ready = false;
   // Pruning (row minima, checks of the partial sums, partial loads) pays only where blocks
   // do end early.  The workgroup counts, over the first PROBE_LISTS lists of its query, how
@@ -756,8 +769,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
     if constexpr (MT > 0) {
       // an empty list still has readable padding behind its base
       const int b0 = wave < nb ? wave : (nb > 0 ? nb - 1 : 0);
-      if (use_half) load_chunks<MPT, 0, HCH>(base, nb, b0, lane, nxt);
-      else load_codes<MPT>(base, nb, b0, lane, nxt);
+      load_ahead(base, nb, b0, nxt);
     }
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
     if (VEC && !DUMP && p - p_begin == PROBE_LISTS && !(a.ablate & 32)) {
@@ -862,8 +874,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
         for (int b = wave; b < nb; b += NW) {
           CodeRegs<MPT / 4> cur = nxt;
           const int bn = b + NW < last ? b + NW : last;
-          if (use_half) load_chunks<MPT, 0, HCH>(base, nb, bn, lane, nxt);
-          else load_codes<MPT>(base, nb, bn, lane, nxt);
+          load_ahead(base, nb, bn, nxt);
           const int i = b * 64 + lane;
           const bool valid = i < len;
           if (DUMP) {
@@ -885,10 +896,17 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
               blocks += (nb - 1 - b) / NW;
               break;
             }
-            // first half of the chunks; most blocks end here
-            if (HALF_OK && !adc_part_exit<MT, 0, MH>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
-            // the rest of the block: already in registers, or fetched now (rare)
-            if (HALF_OK && use_half) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
+            // The block in up to three parts (first chunk, rest of the first half, second
+            // half); most blocks end in an early part, and a part that was not fetched ahead
+            // is fetched when a block turns out to need it.
+            if constexpr (QUARTER_OK) {
+              if (!adc_part_exit<MT, 0, 16>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
+              if (depth == 2) load_chunks<MPT, 1, HCH>(base, nb, b, lane, cur);
+              if (!adc_part_exit<MT, 16, MH>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
+            } else if constexpr (HALF_OK) {
+              if (!adc_part_exit<MT, 0, MH>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
+            }
+            if (HALF_OK && depth >= 1) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
             if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
             ++full;
             if (!(a.ablate & 4)) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
@@ -900,7 +918,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       }
       // without pruning every block is needed whole; the list during which pruning was
       // switched off still had its blocks fetched by halves
-      if (!prune && a.load_mode != 2) use_half = false;
+      if (!prune && a.load_mode < 2) depth = 0;
       if (VEC && !DUMP && p - p_begin == PROBE_LISTS - 1 && lane == 0) {
         __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1324,7 +1342,7 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
 
 int g_scan_waves = 0;  // 0 = choose from the shape
 int g_scan_ablate = 0;
-int g_scan_variant = 0;  // code loads: 0 = first half ahead while pruning, 1 = always whole blocks, 2 = always first half + rest on demand
+int g_scan_variant = 0;  // code loads: 0 = default (first chunk ahead while pruning), 1 = always whole blocks, 2 = always the first half ahead, 3 = always the first chunk ahead
 int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
 
 // The look-up code addresses the table at LDS address 0, which holds as long as a kernel

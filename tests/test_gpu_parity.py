@@ -89,7 +89,7 @@ def full_check(w, idx, q, radii, nprobe=None, k=None, stages=True, metric=0, mod
     assert_same_float(dist.cpu().numpy(), o_dist, "top-k distances")
     # both ways of loading code blocks (whole, or first half with the rest on demand) must
     # give the same bits as the adaptive default
-    for variant in (1, 2):
+    for variant in (1, 2, 3):
         b.set_option("scan_loads", variant)
         try:
             ids_v, dist_v = gi.search(dq, nprobe, k, radii, mode=mode)
