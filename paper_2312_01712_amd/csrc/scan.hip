@@ -1012,26 +1012,27 @@ __device__ inline float neg_ip_chain(SP sq, const float *__restrict__ cen, int D
 // fl(partial + fl(suf - slack)) is above the bound on the k-th best score for every point of
 // the block, no point of it can enter the result and the rest of the block is skipped.
 // Points that survive get exactly the sum adc_sum computes.
-template <int MT>
-__device__ inline bool adc_ip_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r, float start,
-                                   uint32_t pref, bool valid, const LDS float *suf, float slack, float &out) {
-  float dist = start;
+template <int MT, int M0, int M1>
+__device__ inline bool adc_ip_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
+                                   uint32_t pref, bool valid, const LDS float *suf, float slack, float &dist) {
 #pragma unroll
-  for (int g = 0; g < MT; g += 8) {
+  for (int g = M0; g < M1; g += 8) {
+    // requested ahead of the look-ups, so that it has arrived when they have
+    float rest = 0.0f;
+    if (cmin(g + 8, M1) < MT) rest = suf[cmin(g + 8, M1) >> 3];
 #pragma unroll
-    for (int h = g; h < cmin(g + 8, MT); h += LOOKUP_GROUP)
-      lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, cmin(g + 8, MT)), dist);
-    if (g + 8 < MT) {
-      const float lb = dist + (suf[(g + 8) >> 3] - slack);
+    for (int h = g; h < cmin(g + 8, M1); h += LOOKUP_GROUP)
+      lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, cmin(g + 8, M1)), dist);
+    if (cmin(g + 8, M1) < MT) {
+      const float lb = dist + (rest - slack);
       if (__ballot(valid && dist_key<true>(lb) <= pref) == 0) return false;
     }
   }
-  out = dist;
   return true;
 }
 
 template <int MT, int NW, bool DUMP>
-__global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) void scan_ip_kernel(ScanArgs a, RadiiSq r2) {
   constexpr int NT = NW * 64;
   constexpr int MPT = (MT + 3) / 4 * 4;
   constexpr int META = 64;
@@ -1170,12 +1171,24 @@ __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2
         if (wave < nb) {
           const int last = nb - 1;
           const float slack = (float)(4 * MT + 8) * 5.9604645e-08f * (fabsf(start) + ssuf[(MT + 7) / 8]);
+          // as in the L2 kernel: only the first chunk (16 subspaces) of a block is fetched
+          // ahead, the rest of the first half and the second half when a block needs them
+          constexpr int NCH = MPT / 16 + (MPT % 16) / 4;
+          constexpr int HCH = (MPT / 16 + 1) / 2;
+          constexpr int MH = 16 * HCH;
+          constexpr bool PARTS = !DUMP && HCH >= 2 && HCH < NCH && MH < MT;
+          const bool ahead1 = PARTS && a.load_mode != 1;  // wave-uniform
+          auto load_ahead = [&](int blk, CodeRegs<MPT / 4> &r) __attribute__((always_inline)) {
+            load_chunks<MPT, 0, PARTS ? 1 : NCH>(base, nb, blk, lane, r);
+            if constexpr (PARTS)
+              if (!ahead1) load_chunks<MPT, 1, NCH>(base, nb, blk, lane, r);
+          };
           CodeRegs<MPT / 4> nxt;
-          load_codes<MPT>(base, nb, wave, lane, nxt);
+          load_ahead(wave, nxt);
           for (int b = wave; b < nb; b += NW) {
             CodeRegs<MPT / 4> cur = nxt;
             const int bn = b + NW < last ? b + NW : last;
-            load_codes<MPT>(base, nb, bn, lane, nxt);
+            load_ahead(bn, nxt);
             const int i = b * 64 + lane;
             const bool valid = i < len;
             if (DUMP) {
@@ -1190,8 +1203,16 @@ __global__ __launch_bounds__(NW * 64) void scan_ip_kernel(ScanArgs a, RadiiSq r2
               // no point of this list can reach the bound any more (it only tightens): the
               // wavefront is done with the list and requests no further blocks of it
               if (dist_key<true>(start + (ssuf[0] - slack)) > pref) break;
-              float dist;
-              if (!adc_ip_exit<MT>(lut, cur, start, pref, valid, ssuf, slack, dist)) continue;
+              float dist = start;
+              if constexpr (PARTS) {
+                if (!adc_ip_exit<MT, 0, 16>(lut, cur, pref, valid, ssuf, slack, dist)) continue;
+                if (ahead1) load_chunks<MPT, 1, HCH>(base, nb, b, lane, cur);
+                if (!adc_ip_exit<MT, 16, MH>(lut, cur, pref, valid, ssuf, slack, dist)) continue;
+                if (ahead1) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
+                if (!adc_ip_exit<MT, MH, MT>(lut, cur, pref, valid, ssuf, slack, dist)) continue;
+              } else {
+                if (!adc_ip_exit<MT, 0, MT>(lut, cur, pref, valid, ssuf, slack, dist)) continue;
+              }
               wave_offer<true>(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
             }
           }
