@@ -768,8 +768,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
     }
     if constexpr (MT > 0) {
       // an empty list still has readable padding behind its base
+      // (with 128 registers only the first chunk goes out here, whatever the depth: the
+      // registers of the other chunks stay free while the table is built)
       const int b0 = wave < nb ? wave : (nb > 0 ? nb - 1 : 0);
-      load_ahead(base, nb, b0, nxt);
+      if constexpr (WPE == 2) load_ahead(base, nb, b0, nxt);
+      else load_chunks<MPT, 0, HALF_OK ? 1 : NCH>(base, nb, b0, lane, nxt);
     }
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
     if (VEC && !DUMP && p - p_begin == PROBE_LISTS && !(a.ablate & 32)) {
@@ -871,6 +874,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       if (wave < nb && !(a.ablate & 2)) {
         const int last = nb - 1;
         int blocks = 0, full = 0;
+        if constexpr (HALF_OK && WPE != 2) {  // the rest of what is fetched ahead of the first block
+          if (depth < 2) load_chunks<MPT, 1, HCH>(base, nb, wave, lane, nxt);
+          if (depth < 1) load_chunks<MPT, HCH, NCH>(base, nb, wave, lane, nxt);
+        }
         for (int b = wave; b < nb; b += NW) {
           CodeRegs<MPT / 4> cur = nxt;
           const int bn = b + NW < last ? b + NW : last;
