@@ -199,7 +199,7 @@ __device__ inline unsigned long long row_key(const float *row, int c) {
 // of the kprop-th key when a level is too coarse; at width 1 a bin holds one key, so
 // the loop ends).  The selected lists get their distances in the reference order,
 // are sorted by (distance, list id), and the first nprobe are emitted.
-__global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
+__global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(6))) void coarse_select_kernel(
     float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int nlist,
     int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm, int ip,
     int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
@@ -209,6 +209,7 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
   __shared__ unsigned long long keys[MAX_PROPOSE];
   __shared__ unsigned long long red_lo[SEL_THREADS / 64], red_hi[SEL_THREADS / 64];
   __shared__ uint32_t sel[3];
+  __shared__ uint32_t sel_cut[2];
   __shared__ uint32_t count;
   __shared__ float red[SEL_THREADS / 64];
 
@@ -235,12 +236,36 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
       for (int c = tid; c < nlist; c += SEL_THREADS) row[c] = exact_score(sq, cent + (int64_t)c * D, D, ip);
       __syncthreads();
     }
+    int nsel = 0;
+    unsigned long long cut = 0ull;  // exclusive upper bound of the selected keys
+    for (bool allow_fast = true;; allow_fast = false) {
     // ---- smallest and largest key of the row ----
     unsigned long long kmin = ~0ull, kmax = 0ull;
     for (int c = tid; c < nlist; c += SEL_THREADS) {
       const unsigned long long k = row_key(row, c);
       kmin = k < kmin ? k : kmin;
       kmax = k > kmax ? k : kmax;
+    }
+    // Shortcut for kprop <= 256 and long rows (its fixed cost, ranking 256 minima, is more
+    // than a histogram over a short row): the threads' own minima are distinct keys of the
+    // row, so the kprop-th smallest of them is an upper bound on the kprop-th smallest key
+    // of the row.  Everything up to that bound is selected (typically 1.2-1.5 kprop keys)
+    // and the histogram is not needed; it remains the way out if too many keys tie under
+    // the bound.
+    const bool fast = allow_fast && kprop <= SEL_THREADS && nlist >= 16 * SEL_THREADS;
+    unsigned long long fast_cut = 0ull;
+    if (fast) {
+      keys[tid] = kmin;  // this thread's minimum (every thread has elements)
+      __syncthreads();
+      uint32_t rank = 0;
+#pragma unroll 4
+      for (int j = 0; j < SEL_THREADS; ++j) rank += keys[j] < kmin ? 1u : 0u;
+      if (rank == (uint32_t)kprop - 1u) {
+        sel_cut[0] = (uint32_t)(kmin + 1ull);
+        sel_cut[1] = (uint32_t)((kmin + 1ull) >> 32);
+      }
+      __syncthreads();
+      fast_cut = ((unsigned long long)sel_cut[1] << 32) | sel_cut[0];
     }
     for (int off = 32; off > 0; off >>= 1) {
       const unsigned long long a = __shfl_xor(kmin, off), b = __shfl_xor(kmax, off);
@@ -262,8 +287,11 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
     if (shift < 0) shift = 0;
     uint32_t need = kprop;   // keys still wanted from the window
     uint32_t below = 0;      // keys under the window (all selected)
-    unsigned long long cut;  // exclusive upper bound of the selected keys
     for (;;) {
+      if (fast) {
+        cut = fast_cut;
+        break;
+      }
       for (int i = tid; i < NBINS; i += SEL_THREADS) hist[i] = 0;
       __syncthreads();
       for (int c = tid; c < nlist; c += SEL_THREADS) {
@@ -317,7 +345,11 @@ __global__ __launch_bounds__(SEL_THREADS) void coarse_select_kernel(
       }
     }
     __syncthreads();
-    const int nsel = count < (uint32_t)MAX_PROPOSE ? (int)count : MAX_PROPOSE;
+    nsel = count < (uint32_t)MAX_PROPOSE ? (int)count : MAX_PROPOSE;
+    const bool overflow = fast && count > (uint32_t)MAX_PROPOSE;
+    __syncthreads();
+    if (!overflow) break;  // else masses of ties under the bound: once more, with the histogram
+    }
     int psort = 2;
     while (psort < nsel) psort <<= 1;
     // reference-order distances, one selected list per thread (dense: the sequential
