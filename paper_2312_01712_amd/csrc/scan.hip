@@ -8,7 +8,11 @@
 //      the clamp r_m^2 otherwise (res = query - list centroid);
 //   2. streams the list's codes from HBM, one point per lane, 16 bytes per load,
 //      and sums the table values of the point's codes in subspace order (fp32,
-//      the same order as a plain loop, so sums are reproducible bit for bit);
+//      the same order as a plain loop, so sums are reproducible bit for bit).
+//      A block of 64 points is dropped as soon as partial sum + (sum of the row
+//      minima of the remaining subspaces) exceeds the current k-th distance for
+//      all of its points, and code bytes that were not needed are never requested:
+//      exact, i.e. the result is that of the plain loop;
 //   3. keeps, per wavefront, the 128 best (distance, id) pairs seen so far as a
 //      sorted list spread over the lanes' registers; candidates that beat the
 //      current k-th best are queued in LDS and folded in 64 at a time with a
