@@ -479,6 +479,32 @@ def test_query_chunks_large_nlist(lib):
     gi.close()
 
 
+@pytest.mark.parametrize("name", ["T_sift", "T_deep", "T_tti"])
+def test_pruning_switches_do_not_change_results(lib, name):
+    """The early exit, the per-query switch to plain scanning and the block loading modes are
+    optimisations only: with each of them forced off (or on) the answers stay the oracle's."""
+    b = _binding()
+    w = wl.WORKLOADS[name]
+    idx, centres = wl.train_index(w)
+    q = wl.queries(w, centres).numpy()
+    nprobe = min(idx.nlist, max(w.nprobe, 12))       # more lists than the switch looks at
+    for radii in (wl.calibrate_radii(w, idx, centres, 0.25), np.full(idx.M, np.inf, np.float32)):
+        o_ids, o_dist = oracle.search(q, idx, nprobe, w.k, radii, threads=8)
+        gi = b.IvfPqIndex.from_index(idx)
+        try:
+            for ablate in (0, 8, 32, 40):
+                for loads in (0, 1, 2, 3):
+                    b.set_option("scan_ablate", ablate)
+                    b.set_option("scan_loads", loads)
+                    ids, dist = gi.search(_cuda(q), nprobe, w.k, radii)
+                    assert np.array_equal(ids.cpu().numpy(), o_ids), (ablate, loads)
+                    assert_same_float(dist.cpu().numpy(), o_dist, f"ablate {ablate} loads {loads}")
+        finally:
+            b.set_option("scan_ablate", 0)
+            b.set_option("scan_loads", 0)
+            gi.close()
+
+
 def test_batch_sizes_and_probe_groups(lib):
     """Q = 1, 2, 100, 3000: small batches split the probes of a query over several
     workgroups and merge; results must not depend on that."""
