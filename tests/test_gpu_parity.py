@@ -479,15 +479,19 @@ def test_query_chunks_large_nlist(lib):
     gi.close()
 
 
-@pytest.mark.parametrize("name", ["T_sift", "T_deep", "T_tti"])
-def test_pruning_switches_do_not_change_results(lib, name):
+@pytest.mark.parametrize("shape", [("sift", 128, 64, 20.0), ("deep", 96, 48, 0.1), ("tti", 200, 100, 0.25),
+                                   ("gauss", 64, 16, 0.15)])
+def test_pruning_switches_do_not_change_results(lib, shape):
     """The early exit, the per-query switch to plain scanning and the block loading modes are
-    optimisations only: with each of them forced off (or on) the answers stay the oracle's."""
+    optimisations only: with each of them forced off (or on) the answers stay the oracle's.
+    Shapes of the specialised kernels; data on which pruning works (sift, tti) and on which the
+    switch to plain scanning triggers (deep)."""
     b = _binding()
-    w = wl.WORKLOADS[name]
+    family, D, M, sigma = shape
+    w = wl.Workload(f"sw_{family}", 30_000, D, 32, M, 24, 12, 50, family, 64, sigma)
     idx, centres = wl.train_index(w)
     q = wl.queries(w, centres).numpy()
-    nprobe = min(idx.nlist, max(w.nprobe, 12))       # more lists than the switch looks at
+    nprobe = w.nprobe                                 # more lists than the switch looks at
     for radii in (wl.calibrate_radii(w, idx, centres, 0.25), np.full(idx.M, np.inf, np.float32)):
         o_ids, o_dist = oracle.search(q, idx, nprobe, w.k, radii, threads=8)
         gi = b.IvfPqIndex.from_index(idx)
