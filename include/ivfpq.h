@@ -227,8 +227,8 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  * "scan_ablate": bit mask that switches off parts of the scan kernel to attribute
  * its time (1 table arithmetic, 2 list scan, 4 top-k offers: results are
  * meaningless with any of these; 8 turns off the early exit of the distance sums,
- * 32 the switch to plain scanning for queries whose blocks rarely end early:
- * results unchanged). */
+ * 32 the switch to plain scanning for queries whose blocks rarely end early, 64 the
+ * list-level bound that skips a list before its table is built: results unchanged). */
 int ivfpq_set_option(const char *name, int value);
 
 /* Text for the most recent failure on this thread ("" if none). */

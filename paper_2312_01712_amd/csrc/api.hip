@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "ivfpq_internal.h"
@@ -119,7 +120,7 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_ablate")) {
-    set_scan_ablate(value & 63);
+    set_scan_ablate(value & 127);
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_loads")) {
@@ -146,6 +147,7 @@ void ivfpq_index_destroy(ivfpq_index *ix) {
   if (!ix) return;
   (void)hipFree(ix->d_centroids);
   (void)hipFree(ix->d_cnorm);
+  (void)hipFree(ix->d_box);
   (void)hipFree(ix->d_codebooks);
   (void)hipFree(ix->d_list_offsets);
   (void)hipFree(ix->d_list_blocks);
@@ -256,6 +258,41 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
     }
     ix->max_cnorm = mx;
     TRY_OR_FAIL(hipMemcpy(ix->d_cnorm, cnorm.data(), (size_t)d->nlist * 4, hipMemcpyHostToDevice));
+    {
+      // Bounding boxes of groups of entries, IVFPQ_BOXES per subspace: a lower bound on the
+      // distance from a residual projection to any entry, used to skip whole lists before
+      // their table is built.  The entries of a subspace are cut into slabs of equal count
+      // along the first coordinate and each slab likewise along the second (the last, if
+      // dsub == 1, along the first again), so that the boxes follow the shape of the cloud.
+      const int ds = ix->dsub, nb = IVFPQ_BOXES, side = nb >= 16 ? 4 : (nb >= 4 ? 2 : 1), per = 256 / nb;
+      std::vector<float> cbh((size_t)d->M * 256 * ds), box((size_t)d->M * nb * 2 * ds);
+      TRY_OR_FAIL(hipMemcpy(cbh.data(), ix->d_codebooks, kb, hipMemcpyDeviceToHost));
+      std::vector<int> order(256);
+      for (int m = 0; m < d->M; ++m) {
+        const float *e = cbh.data() + (size_t)m * 256 * ds;
+        for (int i = 0; i < 256; ++i) order[i] = i;
+        std::sort(order.begin(), order.end(), [&](int a, int b) { return e[a * ds] < e[b * ds]; });
+        const int c2 = ds > 1 ? 1 : 0;
+        for (int sl = 0; sl < side; ++sl)
+          std::sort(order.begin() + sl * (256 / side), order.begin() + (sl + 1) * (256 / side),
+                    [&](int a, int b) { return e[a * ds + c2] < e[b * ds + c2]; });
+        for (int b = 0; b < nb; ++b) {
+          float *bx = box.data() + ((size_t)m * nb + b) * 2 * ds;
+          for (int j = 0; j < ds; ++j) {
+            float lo = e[order[b * per] * ds + j], hi = lo;
+            for (int t = 1; t < per; ++t) {
+              const float v = e[order[b * per + t] * ds + j];
+              lo = v < lo ? v : lo;  // a NaN entry leaves the box as it is: such input gives unspecified results
+              hi = v > hi ? v : hi;
+            }
+            bx[j] = lo;
+            bx[ds + j] = hi;
+          }
+        }
+      }
+      TRY_OR_FAIL(hipMalloc(&ix->d_box, box.size() * 4));
+      TRY_OR_FAIL(hipMemcpy(ix->d_box, box.data(), box.size() * 4, hipMemcpyHostToDevice));
+    }
     if (d->N > 0) {
       bool codes_dev = false;
       if (hipPointerGetAttributes(&attr, d->codes) == hipSuccess) codes_dev = attr.type == hipMemoryTypeDevice;
@@ -378,7 +415,8 @@ int ivfpq_scan_topk_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q,
   return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, w.nsplit,
                      reinterpret_cast<uint32_t *>(base + w.part_d),
                      reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, mode, qr, static_cast<hipStream_t>(stream));
+                     nullptr, nullptr, nullptr, mode, qr, reinterpret_cast<float *>(base + w.probe_dist),
+                     static_cast<hipStream_t>(stream));
 }
 
 int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
@@ -412,7 +450,7 @@ int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
   return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
                      reinterpret_cast<uint32_t *>(base + w.part_d),
                      reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, mode, qr, s);
+                     nullptr, nullptr, nullptr, mode, qr, reinterpret_cast<float *>(base + w.probe_dist), s);
 }
 
 int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
@@ -443,7 +481,7 @@ int ivfpq_scan_all_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, 
   if (rc || Q == 0) return rc;
   // the dump variant of the scan kernel keeps no top-k, so k and the result pointers are unused
   return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, 0, r2, 1, nullptr, nullptr, nullptr, nullptr,
-                     d_cand_offsets, d_all_dist, d_all_ids, d_errors, mode, qr, s);
+                     d_cand_offsets, d_all_dist, d_all_ids, d_errors, mode, qr, nullptr, s);
 }
 
 int ivfpq_scan_all(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,

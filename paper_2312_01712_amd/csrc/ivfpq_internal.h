@@ -8,6 +8,11 @@
 #include "ivfpq.h"
 
 // Device-side image of an index.
+// Groups of entries per subspace that get a bounding box (1, 4 or 16).  More boxes give a
+// tighter list-level bound, but the bound kernel re-reads them for every (query, probe):
+// measured, one box is the best trade on every configuration but the largest.
+constexpr int IVFPQ_BOXES = 1;
+
 struct ivfpq_index {
   int64_t N;
   int32_t D, nlist, M, dsub;
@@ -16,6 +21,7 @@ struct ivfpq_index {
   int device;
   float *d_centroids;       // [nlist][D]
   float *d_cnorm;           // [nlist] squared norms (only used to propose probe lists)
+  float *d_box;             // [M][IVFPQ_BOXES][2][dsub] bounding boxes (low corner, high corner) of groups of entries
   float *d_codebooks;       // [M][256][dsub]
   int64_t *d_list_offsets;  // [nlist+1] in points
   int64_t *d_list_blocks;   // [nlist+1] in 64-point blocks of the interleaved layout
@@ -59,7 +65,7 @@ int hip_fail(hipError_t e, const char *what);
 struct Workspace {
   size_t coarse_dist;   // [Qc][nlist_pad] fp32 approximate distances of one query chunk
   size_t probe_ids;     // [Q][nprobe] int32
-  size_t probe_dist;    // [Q][nprobe] fp32
+  size_t probe_dist;    // [Q][nprobe] fp32: list-level lower bounds for the scan
   size_t part_d;        // [Q][nsplit][128] uint32 (only when nsplit > 1)
   size_t part_id;       // [Q][nsplit][128] int64
   size_t total;
@@ -80,7 +86,8 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
                 uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
                 const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
-                int32_t *d_errors, int32_t mode, const float *d_query_radii, hipStream_t s);
+                int32_t *d_errors, int32_t mode, const float *d_query_radii, float *d_probe_lb,
+                hipStream_t s);
 int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);
 int coarse_fallbacks(int reset, unsigned int *out);

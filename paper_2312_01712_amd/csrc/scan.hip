@@ -266,6 +266,7 @@ struct ScanArgs {
   const int32_t *probe_ids;     // [Q][nprobe]
   const float *centroids;       // [nlist][D]
   const float *codebooks;       // [M][256][dsub]
+  const float *probe_lb;        // [Q][nprobe] lower bound on the distance of any point of the probed list, or NULL
   const int64_t *list_offsets;  // [nlist+1]
   const int64_t *list_blocks;   // [nlist+1]
   const uint8_t *codes;         // interleaved blocks
@@ -612,7 +613,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   LDS int64_t *meta_blk = meta_row0 + META;
   LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
   LDS int32_t *meta_c = meta_len + META;
-  LDS float *sr2 = (LDS float *)(meta_c + META);  // [M] r_m^2 of this query
+  LDS float *meta_lb = (LDS float *)(meta_c + META);
+  LDS float *sr2 = meta_lb + META;  // [M] r_m^2 of this query
   LDS uint32_t *srmin = (LDS uint32_t *)(sr2 + IVFPQ_MAX_M);  // [M][4] partial minima (bit patterns) of each row of the current table
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -733,6 +735,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
         meta_row0[tid] = r0;
         meta_len[tid] = ok ? (int)(a.list_offsets[cc + 1] - r0) : 0;
         meta_blk[tid] = ok ? a.list_blocks[cc] : 0;
+        meta_lb[tid] = (ok && a.probe_lb) ? a.probe_lb[q * a.nprobe + p + tid] : 0.0f;
       }
       __syncthreads();
     }
@@ -782,6 +785,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
     if (VEC && !DUMP && p - p_begin == PROBE_LISTS && !(a.ablate & 32)) {
       const uint32_t nblk = stat[0], nfull = stat[1];
       prune = 8 * (uint64_t)nfull < 7 * (uint64_t)nblk;
+    }
+    // List-level bound (probe_bound_kernel): if not even the lower bound on any point of
+    // this list is within the workgroup's bound on the k-th distance, neither table nor scan
+    // is needed.  Between the two barriers nobody scans, so every wavefront reads the same
+    // shared bound and the decision is uniform over the workgroup.
+    bool skip_list = false;
+    if (VEC && !DUMP) {
+      const uint32_t bnd = *(volatile LDS uint32_t *)sh.bound;
+      skip_list = bnd != SENT_D && meta_lb[pm] > __uint_as_float(bnd);
+    }
+    if (skip_list) {
+      __syncthreads();  // still separates this list's readers of the residual from the write of the next one
+      if constexpr (VEC) {
+        if (next_known && tid < D) sres[tid] = sq[tid] - cen_next;
+        sres_ready = next_known;
+      }
+      if (wave < nb) tot_blocks += (nb - 1 - wave) / NW + 1;  // all pruned: counts for the switch below
+      if (VEC && !DUMP && p - p_begin == PROBE_LISTS - 1 && lane == 0) {
+        __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+      continue;
     }
     // ---- selective table for (query, list c) ----
     if constexpr (VEC) {
@@ -1250,6 +1275,68 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   finish_topk<NW, true>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
+// List-level lower bound for the L2 metric with distance scoring.  The entries of every
+// subspace are covered by IVFPQ_BOXES bounding boxes (index build), so the squared distance
+// from the residual projection to any entry is at least the smallest squared distance to a
+// box, and a table value is at least min(that, r_m^2).  out[q][p] is the sum over the
+// subspaces, reduced by 2^-12 relative against the handful of roundings that separate this
+// evaluation from the table's (the residual is the same fp32 value q - c the table uses).
+// One wavefront per (query, probe).
+__global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
+                                                          const int32_t *__restrict__ probe_ids,
+                                                          const float *__restrict__ centroids,
+                                                          const float *__restrict__ box, int D, int M, int dsub,
+                                                          int nlist, int64_t total, int nprobe, RadiiSq r2,
+                                                          const float *__restrict__ query_radii,
+                                                          float *__restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t qp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (qp >= total) return;
+  const int64_t q = qp / nprobe;
+  const int32_t c = probe_ids[qp];
+  float lb = 0.0f;
+  if ((uint32_t)c < (uint32_t)nlist) {
+    for (int m = lane; m < M; m += 64) {
+      float best = __builtin_inff();
+      if (dsub == 2) {  // a box is one 16-byte load: (low x, low y, high x, high y)
+        const float2 qv = *reinterpret_cast<const float2 *>(queries + q * D + 2 * m);
+        const float2 cv = *reinterpret_cast<const float2 *>(centroids + (int64_t)c * D + 2 * m);
+        const float x0 = qv.x - cv.x, x1 = qv.y - cv.y;
+        const float4 *bx = reinterpret_cast<const float4 *>(box) + (int64_t)m * IVFPQ_BOXES;
+        float4 v[IVFPQ_BOXES];
+#pragma unroll
+        for (int b = 0; b < IVFPQ_BOXES; ++b) v[b] = bx[b];
+#pragma unroll
+        for (int b = 0; b < IVFPQ_BOXES; ++b) {
+          const float t0 = fmaxf(fmaxf(v[b].x - x0, x0 - v[b].z), 0.0f);
+          const float t1 = fmaxf(fmaxf(v[b].y - x1, x1 - v[b].w), 0.0f);
+          best = fminf(best, fmaf(t1, t1, t0 * t0));
+        }
+      } else {
+        for (int b = 0; b < IVFPQ_BOXES; ++b) {
+          const float *bx = box + ((int64_t)m * IVFPQ_BOXES + b) * 2 * dsub;
+          float d2 = 0.0f;
+          for (int j = 0; j < dsub; ++j) {
+            const int i = m * dsub + j;
+            const float x = queries[q * D + i] - centroids[(int64_t)c * D + i];
+            const float t = fmaxf(fmaxf(bx[j] - x, x - bx[dsub + j]), 0.0f);
+            d2 = fmaf(t, t, d2);
+          }
+          best = fminf(best, d2);
+        }
+      }
+      float rm2 = r2.v[m];
+      if (query_radii) {
+        const float r = query_radii[q * M + m];
+        rm2 = r * r;
+      }
+      lb += fminf(best, rm2);
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) lb += __shfl_xor(lb, off);
+  if (lane == 0) out[qp] = lb * 0.999755859375f;
+}
+
 // Merge the probe groups' partial lists of a query (one wavefront per query).
 __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ part_d,
                                                    const int64_t *__restrict__ part_id, int nsplit,
@@ -1396,7 +1483,7 @@ template <int MT, int DSUB, int NW>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 24 + 5 * IVFPQ_MAX_M * 4 +
+                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 28 + 5 * IVFPQ_MAX_M * 4 +
                      (size_t)NW * SUF_SLOTS * 4 + 16 + (size_t)g_scan_lds_pad;
   if (lds > 160 * 1024) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
@@ -1466,12 +1553,14 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
                 uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
                 const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
-                int32_t *d_errors, int32_t mode, const float *d_query_radii, hipStream_t s) {
+                int32_t *d_errors, int32_t mode, const float *d_query_radii, float *d_probe_lb,
+                hipStream_t s) {
   ScanArgs a;
   a.queries = d_queries;
   a.probe_ids = d_probe_ids;
   a.centroids = ix->d_centroids;
   a.codebooks = ix->d_codebooks;
+  a.probe_lb = nullptr;
   a.list_offsets = ix->d_list_offsets;
   a.list_blocks = ix->d_list_blocks;
   a.codes = ix->d_codes;
@@ -1503,6 +1592,13 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   }
   const int M = ix->M, ds = ix->dsub;
   const bool ip = ix->metric == IVFPQ_METRIC_IP;
+  if (d_probe_lb && !dump && !ip && mode == IVFPQ_SCORE_DISTANCE && !(g_scan_ablate & 64)) {
+    const int64_t total = Q * nprobe;
+    hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, d_queries,
+                       d_probe_ids, ix->d_centroids, ix->d_box, ix->D, M, ds, ix->nlist, total, nprobe, r2,
+                       d_query_radii, d_probe_lb);
+    a.probe_lb = d_probe_lb;
+  }
   // A wavefront's sorted list holds KP keys, so k > KP takes ceil(k / KP) passes over the
   // lists; pass j keeps the keys above the last key pass j - 1 wrote.
   a.k_out = k;

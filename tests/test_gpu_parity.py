@@ -496,7 +496,7 @@ def test_pruning_switches_do_not_change_results(lib, shape):
         o_ids, o_dist = oracle.search(q, idx, nprobe, w.k, radii, threads=8)
         gi = b.IvfPqIndex.from_index(idx)
         try:
-            for ablate in (0, 8, 32, 40):
+            for ablate in (0, 8, 32, 64, 104):
                 for loads in (0, 1, 2, 3):
                     b.set_option("scan_ablate", ablate)
                     b.set_option("scan_loads", loads)
