@@ -722,6 +722,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   constexpr int PROBE_LISTS = 4;
   bool prune = VEC && !DUMP;
   uint32_t tot_blocks = 0, tot_full = 0;
+  bool pushed = false, decided = false;
+  auto push_counts = [&](int last_list) __attribute__((always_inline)) {
+    if (VEC && !DUMP && !pushed && last_list - p_begin >= PROBE_LISTS - 1) {
+      pushed = true;
+      if (lane == 0) {
+        __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    }
+  };
   for (int p = p_begin; p < p_end; ++p) {
     const int pm = (p - p_begin) & (META - 1);
     if (pm == 0) {
@@ -782,9 +792,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       else load_chunks<MPT, 0, HALF_OK ? 1 : NCH>(base, nb, b0, lane, nxt);
     }
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
-    if (VEC && !DUMP && p - p_begin == PROBE_LISTS && !(a.ablate & 32)) {
-      const uint32_t nblk = stat[0], nfull = stat[1];
-      prune = 8 * (uint64_t)nfull < 7 * (uint64_t)nblk;
+    if (VEC && !DUMP && !decided && p - p_begin >= PROBE_LISTS) {  // every wavefront has pushed its counts
+      decided = true;
+      if (!(a.ablate & 32)) {
+        const uint32_t nblk = stat[0], nfull = stat[1];
+        prune = 8 * (uint64_t)nfull < 7 * (uint64_t)nblk;
+      }
     }
     // List-level bound (probe_bound_kernel): if not even the lower bound on any point of
     // this list is within the workgroup's bound on the k-th distance, neither table nor scan
@@ -796,16 +809,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       skip_list = bnd != SENT_D && meta_lb[pm] > __uint_as_float(bnd);
     }
     if (skip_list) {
-      __syncthreads();  // still separates this list's readers of the residual from the write of the next one
-      if constexpr (VEC) {
-        if (next_known && tid < D) sres[tid] = sq[tid] - cen_next;
-        sres_ready = next_known;
-      }
-      if (wave < nb) tot_blocks += (nb - 1 - wave) / NW + 1;  // all pruned: counts for the switch below
-      if (VEC && !DUMP && p - p_begin == PROBE_LISTS - 1 && lane == 0) {
-        __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
+      // Ruled out.  The bound cannot change while nobody scans, so the following probes of
+      // this metadata chunk are checked right here and the workgroup goes on with the first
+      // one that is not ruled out: a run of skipped lists costs one barrier.
+      const float bound_f = __uint_as_float(*(volatile LDS uint32_t *)sh.bound);
+      int pn = p;
+      do {
+        const int pmn = (pn - p_begin) & (META - 1);
+        const int nbn = (meta_len[pmn] + 63) >> 6;
+        if (wave < nbn) tot_blocks += (nbn - 1 - wave) / NW + 1;  // all pruned: counts for the switch
+        ++pn;
+      } while (pn < p_end && ((pn - p_begin) & (META - 1)) != 0 && meta_lb[(pn - p_begin) & (META - 1)] > bound_f);
+      push_counts(pn - 1);
+      __syncthreads();  // nobody still reads the metadata when the next chunk is staged
+      sres_ready = false;
+      p = pn - 1;
       continue;
     }
     // ---- selective table for (query, list c) ----
@@ -955,10 +973,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       // without pruning every block is needed whole; the list during which pruning was
       // switched off still had its blocks fetched by halves
       if (!prune && a.load_mode < 2) depth = 0;
-      if (VEC && !DUMP && p - p_begin == PROBE_LISTS - 1 && lane == 0) {
-        __hip_atomic_fetch_add(stat, tot_blocks, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(stat + 1, tot_full, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
+      push_counts(p);
     } else {
       for (int b = wave; b < nb; b += NW) {
         const float dist = adc_sum_rt(lut, base, nb, b, lane, M, Mp);
