@@ -171,7 +171,7 @@ def main():
                    "radii": "per-query (density map)" if args.dynamic_radii else "per-subspace", "recall_at_k": recall, "recall_truth_k": min(k, 100), "r1_at_k": r1,
                    "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms,
                    "coarse_exact_fallbacks_per_step": binding.coarse_fallbacks() / max(1, args.steps + 1)},
-        "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k), timed with probe_bound_kernel (list-level bounds, 7 % of it on C2)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (MEASURED_TRAFFIC_BYTES.get((w.name, args.keep))
                                  if args.score_mode == 0 and not args.dynamic_radii and k == w.k and not metric else None),
