@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for an
 # elementwise pass over 1 GiB: x2.000 and x1.000).  Commands and raw figures: profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", 0.25): 2.37769e6 * 1024 * 2.000 + 490975 * 1024 * 1.000,
-    ("C5", 0.25): 1.20743e7 * 1024 * 2.000 + 653097 * 1024 * 1.000,
+    ("C2", 0.25): (568274 + 27094) * 1024 * 2.000 + (434145 + 2500) * 1024 * 1.000,
+    ("C5", 0.25): (1.16202e7 + 93878) * 1024 * 2.000 + (527529 + 5000) * 1024 * 1.000,
 }
 
 
