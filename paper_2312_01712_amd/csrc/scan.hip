@@ -1290,19 +1290,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   finish_topk<NW, true>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
-// List-level lower bound for the L2 metric with distance scoring.  The entries of every
+// List-level lower bound for the L2 metric.  The entries of every
 // subspace are covered by IVFPQ_BOXES bounding boxes (index build), so the squared distance
 // from the residual projection to any entry is at least the smallest squared distance to a
 // box, and a table value is at least min(that, r_m^2).  out[q][p] is the sum over the
 // subspaces, reduced by 2^-12 relative against the handful of roundings that separate this
 // evaluation from the table's (the residual is the same fp32 value q - c the table uses).
+// For the hit-count scorings the bound of a subspace is the penalty that every entry gets when
+// the whole box lies outside the (inner) sphere, decided with the same margin.
 // One wavefront per (query, probe).
 __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
                                                           const int32_t *__restrict__ probe_ids,
                                                           const float *__restrict__ centroids,
                                                           const float *__restrict__ box, int D, int M, int dsub,
                                                           int nlist, int64_t total, int nprobe, RadiiSq r2,
-                                                          const float *__restrict__ query_radii,
+                                                          const float *__restrict__ query_radii, int mode,
                                                           float *__restrict__ out) {
   const int lane = threadIdx.x & 63;
   const int64_t qp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -1345,11 +1347,16 @@ __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restric
         const float r = query_radii[q * M + m];
         rm2 = r * r;
       }
-      lb += fminf(best, rm2);
+      if (mode == 0) {
+        lb += fminf(best, rm2);
+      } else {  // 1 per subspace whose box is outside the sphere; mode 2: 2, and 1 if only outside the inner sphere
+        const float b = best * 0.999755859375f;
+        lb += b > rm2 ? (mode == 1 ? 1.0f : 2.0f) : ((mode == 2 && b > 0.25f * rm2) ? 1.0f : 0.0f);
+      }
     }
   }
   for (int off = 32; off > 0; off >>= 1) lb += __shfl_xor(lb, off);
-  if (lane == 0) out[qp] = lb * 0.999755859375f;
+  if (lane == 0) out[qp] = mode == 0 ? lb * 0.999755859375f : lb;  // the counts are exact
 }
 
 // Merge the probe groups' partial lists of a query (one wavefront per query).
@@ -1607,11 +1614,11 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   }
   const int M = ix->M, ds = ix->dsub;
   const bool ip = ix->metric == IVFPQ_METRIC_IP;
-  if (d_probe_lb && !dump && !ip && mode == IVFPQ_SCORE_DISTANCE && !(g_scan_ablate & 64)) {
+  if (d_probe_lb && !dump && !ip && !(g_scan_ablate & 64)) {
     const int64_t total = Q * nprobe;
     hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, d_queries,
                        d_probe_ids, ix->d_centroids, ix->d_box, ix->D, M, ds, ix->nlist, total, nprobe, r2,
-                       d_query_radii, d_probe_lb);
+                       d_query_radii, mode, d_probe_lb);
     a.probe_lb = d_probe_lb;
   }
   // A wavefront's sorted list holds KP keys, so k > KP takes ceil(k / KP) passes over the
