@@ -703,8 +703,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   // How much of a block is fetched ahead: 0 all chunks, 1 the first half, 2 the first chunk;
   // the rest is fetched when a block turns out to need it.  While pruning, most blocks end
   // within their first chunk.
-  int depth = 0;
-  if (HALF_OK && !DUMP && a.load_mode != 1) depth = (QUARTER_OK && a.load_mode != 2) ? 2 : 1;
+  int depth = 0, depth_later = 0;
+  if (HALF_OK && !DUMP && a.load_mode != 1) depth_later = (QUARTER_OK && a.load_mode != 2) ? 2 : 1;
+  // the first list of a query is scanned without any bound, so every block of it is needed
+  // whole: it is fetched whole (in the default mode), the lists after it by parts
+  if (a.load_mode != 0) depth = depth_later;
   auto load_ahead = [&](const uint8_t *lb, int nblk, int blk, CodeRegs<MPT / 4> &r) __attribute__((always_inline)) {
     if constexpr (MT > 0) {
       load_chunks<MPT, 0, HALF_OK ? 1 : NCH>(lb, nblk, blk, lane, r);
@@ -972,7 +975,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       }
       // without pruning every block is needed whole; the list during which pruning was
       // switched off still had its blocks fetched by halves
-      if (!prune && a.load_mode < 2) depth = 0;
+      depth = (!prune && a.load_mode < 2) ? 0 : depth_later;
       push_counts(p);
     } else {
       for (int b = wave; b < nb; b += NW) {
