@@ -547,21 +547,29 @@ __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS i
   __syncthreads();  // tables no longer needed: their LDS becomes the staging area
   LDS uint32_t *stage_d = (LDS uint32_t *)smem3;
   LDS int64_t *stage_id = (LDS int64_t *)(smem3 + NW * KP * 4);
-  if (wave > 0) {
+  auto put = [&]() __attribute__((always_inline)) {
     stage_d[wave * KP + lane] = st.L0.d;
     stage_d[wave * KP + 64 + lane] = st.L1.d;
     stage_id[wave * KP + lane] = st.L0.id;
     stage_id[wave * KP + 64 + lane] = st.L1.id;
-  }
+  };
+  if (wave > 0) put();
   __syncthreads();
-  if (wave == 0) {
-    for (int w = 1; w < NW; ++w)
+  // pairwise rounds: wavefront w takes the list of w + stride, for stride = 1, 2, 4, ...
+  for (int stride = 1; stride < NW; stride <<= 1) {
+    if ((wave & (2 * stride - 1)) == 0 && wave + stride < NW) {
+      const int w = wave + stride;
       for (int h = 0; h < 2; ++h) {
         Key qk;  // the half is sorted ascending: read it reversed to get descending
         qk.d = stage_d[w * KP + h * 64 + (63 - lane)];
         qk.id = stage_id[w * KP + h * 64 + (63 - lane)];
         wave_merge(st.L0, st.L1, qk, lane);
       }
+      if (wave > 0 && 2 * stride < NW) put();  // read by another wavefront in a later round
+    }
+    if (2 * stride < NW) __syncthreads();
+  }
+  if (wave == 0) {
     if (a.nsplit > 1) {
       const int64_t o = (q * a.nsplit + split) * KP;
       a.part_d[o + lane] = st.L0.d;
