@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for an
 # elementwise pass over 1 GiB: x2.000 and x1.000).  Commands and raw figures: profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", 0.25): (568274 + 27094) * 1024 * 2.000 + (434145 + 2500) * 1024 * 1.000,
-    ("C5", 0.25): (1.16202e7 + 93878) * 1024 * 2.000 + (527529 + 5000) * 1024 * 1.000,
+    ("C2", 0.25): (593323 + 27094) * 1024 * 2.000 + (448863 + 2500) * 1024 * 1.000,
+    ("C5", 0.25): (1.16689e7 + 93842) * 1024 * 2.000 + (528869 + 5000) * 1024 * 1.000,
 }
 
 
@@ -171,7 +171,7 @@ def main():
                    "radii": "per-query (density map)" if args.dynamic_radii else "per-subspace", "recall_at_k": recall, "recall_truth_k": min(k, 100), "r1_at_k": r1,
                    "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms,
                    "coarse_exact_fallbacks_per_step": binding.coarse_fallbacks() / max(1, args.steps + 1)},
-        "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k), timed with probe_bound_kernel (list-level bounds, 7 % of it on C2)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k), timed with probe_bound_kernel (list-level bounds, 8 % of it on C2)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (MEASURED_TRAFFIC_BYTES.get((w.name, args.keep))
                                  if args.score_mode == 0 and not args.dynamic_radii and k == w.k and not metric else None),
