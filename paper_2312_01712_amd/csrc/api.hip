@@ -8,7 +8,6 @@
 #include <string.h>
 
 #include <new>
-#include <algorithm>
 #include <vector>
 
 #include "ivfpq_internal.h"
@@ -258,41 +257,10 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
     }
     ix->max_cnorm = mx;
     TRY_OR_FAIL(hipMemcpy(ix->d_cnorm, cnorm.data(), (size_t)d->nlist * 4, hipMemcpyHostToDevice));
-    {
-      // Bounding boxes of groups of entries, IVFPQ_BOXES per subspace: a lower bound on the
-      // distance from a residual projection to any entry, used to skip whole lists before
-      // their table is built.  The entries of a subspace are cut into slabs of equal count
-      // along the first coordinate and each slab likewise along the second (the last, if
-      // dsub == 1, along the first again), so that the boxes follow the shape of the cloud.
-      const int ds = ix->dsub, nb = IVFPQ_BOXES, side = nb >= 16 ? 4 : (nb >= 4 ? 2 : 1), per = 256 / nb;
-      std::vector<float> cbh((size_t)d->M * 256 * ds), box((size_t)d->M * nb * 2 * ds);
-      TRY_OR_FAIL(hipMemcpy(cbh.data(), ix->d_codebooks, kb, hipMemcpyDeviceToHost));
-      std::vector<int> order(256);
-      for (int m = 0; m < d->M; ++m) {
-        const float *e = cbh.data() + (size_t)m * 256 * ds;
-        for (int i = 0; i < 256; ++i) order[i] = i;
-        std::sort(order.begin(), order.end(), [&](int a, int b) { return e[a * ds] < e[b * ds]; });
-        const int c2 = ds > 1 ? 1 : 0;
-        for (int sl = 0; sl < side; ++sl)
-          std::sort(order.begin() + sl * (256 / side), order.begin() + (sl + 1) * (256 / side),
-                    [&](int a, int b) { return e[a * ds + c2] < e[b * ds + c2]; });
-        for (int b = 0; b < nb; ++b) {
-          float *bx = box.data() + ((size_t)m * nb + b) * 2 * ds;
-          for (int j = 0; j < ds; ++j) {
-            float lo = e[order[b * per] * ds + j], hi = lo;
-            for (int t = 1; t < per; ++t) {
-              const float v = e[order[b * per + t] * ds + j];
-              lo = v < lo ? v : lo;  // a NaN entry leaves the box as it is: such input gives unspecified results
-              hi = v > hi ? v : hi;
-            }
-            bx[j] = lo;
-            bx[ds + j] = hi;
-          }
-        }
-      }
-      TRY_OR_FAIL(hipMalloc(&ix->d_box, box.size() * 4));
-      TRY_OR_FAIL(hipMemcpy(ix->d_box, box.data(), box.size() * 4, hipMemcpyHostToDevice));
-    }
+    // per list and subspace, the bounding box of the entries the list's points use (filled
+    // below from the codes; an empty list keeps the all-zero box)
+    TRY_OR_FAIL(hipMalloc(&ix->d_box, (size_t)d->nlist * d->D * 2 * 4));
+    TRY_OR_FAIL(hipMemset(ix->d_box, 0, (size_t)d->nlist * d->D * 2 * 4));
     if (d->N > 0) {
       bool codes_dev = false;
       if (hipPointerGetAttributes(&attr, d->codes) == hipSuccess) codes_dev = attr.type == hipMemoryTypeDevice;
@@ -305,6 +273,8 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
         TRY_OR_FAIL(hipMemcpy(d_rows, d->codes, (size_t)d->N * d->M, hipMemcpyHostToDevice));
       }
       rc = launch_relayout(ix, d_rows, nullptr);
+      if (rc != IVFPQ_OK) goto fail;
+      rc = launch_list_boxes(ix, d_rows, nullptr);
       if (rc != IVFPQ_OK) goto fail;
       if (d->ids) TRY_OR_FAIL(hipMemcpy(ix->d_ids, d->ids, (size_t)d->N * 8, hipMemcpyDefault));
       else {

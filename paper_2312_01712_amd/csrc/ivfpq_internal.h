@@ -8,11 +8,6 @@
 #include "ivfpq.h"
 
 // Device-side image of an index.
-// Groups of entries per subspace that get a bounding box (1, 4 or 16).  More boxes give a
-// tighter list-level bound, but the bound kernel re-reads them for every (query, probe):
-// measured, one box is the best trade on every configuration but the largest.
-constexpr int IVFPQ_BOXES = 1;
-
 struct ivfpq_index {
   int64_t N;
   int32_t D, nlist, M, dsub;
@@ -21,7 +16,7 @@ struct ivfpq_index {
   int device;
   float *d_centroids;       // [nlist][D]
   float *d_cnorm;           // [nlist] squared norms (only used to propose probe lists)
-  float *d_box;             // [M][IVFPQ_BOXES][2][dsub] bounding boxes (low corner, high corner) of groups of entries
+  float *d_box;             // [nlist][M][2][dsub] per list and subspace: bounding box (low corner, high corner) of the entries its points use
   float *d_codebooks;       // [M][256][dsub]
   int64_t *d_list_offsets;  // [nlist+1] in points
   int64_t *d_list_blocks;   // [nlist+1] in 64-point blocks of the interleaved layout
@@ -89,6 +84,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 int32_t *d_errors, int32_t mode, const float *d_query_radii, float *d_probe_lb,
                 hipStream_t s);
 int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
+int launch_list_boxes(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);
 int coarse_fallbacks(int reset, unsigned int *out);
 int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);

@@ -1301,15 +1301,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   finish_topk<NW, true>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
-// List-level lower bound for the L2 metric.  The entries of every
-// subspace are covered by IVFPQ_BOXES bounding boxes (index build), so the squared distance
-// from the residual projection to any entry is at least the smallest squared distance to a
-// box, and a table value is at least min(that, r_m^2).  out[q][p] is the sum over the
-// subspaces, reduced by 2^-12 relative against the handful of roundings that separate this
-// evaluation from the table's (the residual is the same fp32 value q - c the table uses).
-// For the hit-count scorings the bound of a subspace is the penalty that every entry gets when
-// the whole box lies outside the (inner) sphere, decided with the same margin.
-// One wavefront per (query, probe).
+// List-level lower bound for the L2 metric.  For every list and subspace the index holds
+// the bounding box of the entries that the list's points use (list_box_kernel), so the
+// squared distance from the residual projection to the entry of any point of the list is at
+// least the squared distance to that box, and the point's table value is at least
+// min(that, r_m^2).  out[q][p] is the sum over the subspaces, reduced by 2^-12 relative
+// against the handful of roundings that separate this evaluation from the table's (the
+// residual is the same fp32 value q - c the table uses).  For the hit-count scorings the bound
+// of a subspace is the penalty that every such entry gets when the whole box lies outside the
+// (inner) sphere, decided with the same margin.  One wavefront per (query, probe).
 __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
                                                           const int32_t *__restrict__ probe_ids,
                                                           const float *__restrict__ centroids,
@@ -1324,33 +1324,24 @@ __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restric
   const int32_t c = probe_ids[qp];
   float lb = 0.0f;
   if ((uint32_t)c < (uint32_t)nlist) {
+    const float *lbox = box + (int64_t)c * D * 2;  // this list's boxes: [M][2][dsub]
     for (int m = lane; m < M; m += 64) {
-      float best = __builtin_inff();
+      float best = 0.0f;
       if (dsub == 2) {  // a box is one 16-byte load: (low x, low y, high x, high y)
         const float2 qv = *reinterpret_cast<const float2 *>(queries + q * D + 2 * m);
         const float2 cv = *reinterpret_cast<const float2 *>(centroids + (int64_t)c * D + 2 * m);
         const float x0 = qv.x - cv.x, x1 = qv.y - cv.y;
-        const float4 *bx = reinterpret_cast<const float4 *>(box) + (int64_t)m * IVFPQ_BOXES;
-        float4 v[IVFPQ_BOXES];
-#pragma unroll
-        for (int b = 0; b < IVFPQ_BOXES; ++b) v[b] = bx[b];
-#pragma unroll
-        for (int b = 0; b < IVFPQ_BOXES; ++b) {
-          const float t0 = fmaxf(fmaxf(v[b].x - x0, x0 - v[b].z), 0.0f);
-          const float t1 = fmaxf(fmaxf(v[b].y - x1, x1 - v[b].w), 0.0f);
-          best = fminf(best, fmaf(t1, t1, t0 * t0));
-        }
+        const float4 v = reinterpret_cast<const float4 *>(lbox)[m];
+        const float t0 = fmaxf(fmaxf(v.x - x0, x0 - v.z), 0.0f);
+        const float t1 = fmaxf(fmaxf(v.y - x1, x1 - v.w), 0.0f);
+        best = fmaf(t1, t1, t0 * t0);
       } else {
-        for (int b = 0; b < IVFPQ_BOXES; ++b) {
-          const float *bx = box + ((int64_t)m * IVFPQ_BOXES + b) * 2 * dsub;
-          float d2 = 0.0f;
-          for (int j = 0; j < dsub; ++j) {
-            const int i = m * dsub + j;
-            const float x = queries[q * D + i] - centroids[(int64_t)c * D + i];
-            const float t = fmaxf(fmaxf(bx[j] - x, x - bx[dsub + j]), 0.0f);
-            d2 = fmaf(t, t, d2);
-          }
-          best = fminf(best, d2);
+        const float *bx = lbox + (int64_t)m * 2 * dsub;
+        for (int j = 0; j < dsub; ++j) {
+          const int i = m * dsub + j;
+          const float x = queries[q * D + i] - centroids[(int64_t)c * D + i];
+          const float t = fmaxf(fmaxf(bx[j] - x, x - bx[dsub + j]), 0.0f);
+          best = fmaf(t, t, best);
         }
       }
       float rm2 = r2.v[m];
@@ -1445,6 +1436,52 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
     out_lut[(qp * M + m) * 256 + e] = v;
     const unsigned long long bal = __ballot(keep);
     if (out_mask && lane == 0) out_mask[(qp * M + m) * 4 + wave] = bal;
+  }
+}
+
+// Index build: for every list and subspace the bounding box of the entries that the list's
+// points use, box[c][m] = (low corner [dsub], high corner [dsub]).  One workgroup per list,
+// thread = (slice of the list's points, subspace); the slices are combined through LDS.
+__global__ __launch_bounds__(256) void list_box_kernel(const uint8_t *__restrict__ rows,
+                                                       const int64_t *__restrict__ list_offsets,
+                                                       const float *__restrict__ codebooks, int M, int dsub,
+                                                       float *__restrict__ box) {
+  extern __shared__ float sred[];  // [slices][M][2 * dsub]
+  const int c = blockIdx.x;
+  const int64_t r0 = list_offsets[c], n = list_offsets[c + 1] - r0;
+  if (n <= 0) return;  // keeps the zero box
+  const int slices = 256 / M >= 4 ? 4 : (256 / M > 0 ? 256 / M : 1);
+  const int sl = threadIdx.x / M, m = threadIdx.x % M;
+  const int w = 2 * dsub;
+  if (sl < slices) {
+    float *mine = sred + ((size_t)sl * M + m) * w;
+    for (int j = 0; j < dsub; ++j) {
+      mine[j] = __builtin_inff();
+      mine[dsub + j] = -__builtin_inff();
+    }
+    for (int64_t i = sl; i < n; i += slices) {
+      const int code = rows[(r0 + i) * M + m];
+      const float *e = codebooks + ((int64_t)m * 256 + code) * dsub;
+      for (int j = 0; j < dsub; ++j) {
+        mine[j] = fminf(mine[j], e[j]);
+        mine[dsub + j] = fmaxf(mine[dsub + j], e[j]);
+      }
+    }
+  }
+  __syncthreads();
+  if (sl == 0) {
+    float *out = box + ((int64_t)c * M + m) * w;
+    for (int j = 0; j < dsub; ++j) {
+      float lo = __builtin_inff(), hi = -__builtin_inff();
+      for (int s2 = 0; s2 < slices; ++s2) {
+        if (s2 < n) {  // a slice beyond the list's length saw no point
+          lo = fminf(lo, sred[((size_t)s2 * M + m) * w + j]);
+          hi = fmaxf(hi, sred[((size_t)s2 * M + m) * w + dsub + j]);
+        }
+      }
+      out[j] = lo;
+      out[dsub + j] = hi;
+    }
   }
 }
 
@@ -1688,6 +1725,16 @@ int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s)
   const int64_t grid = (ix->total_blocks + 3) / 4;
   hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(256), 0, s, d_rows, ix->d_list_offsets,
                      ix->d_list_blocks, ix->nlist, ix->M, ix->Mp, ix->total_blocks, ix->d_codes);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+int launch_list_boxes(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s) {
+  if (ix->N == 0) return IVFPQ_OK;
+  const int slices = 256 / ix->M >= 4 ? 4 : (256 / ix->M > 0 ? 256 / ix->M : 1);
+  const size_t lds = (size_t)slices * ix->D * 2 * sizeof(float);
+  hipLaunchKernelGGL(list_box_kernel, dim3((unsigned)ix->nlist), dim3(256), lds, s, d_rows, ix->d_list_offsets,
+                     ix->d_codebooks, ix->M, ix->dsub, ix->d_box);
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;
 }
