@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # elementwise pass over 1 GiB: x2.000 and x1.000).  Commands and raw figures: profiles/.
 MEASURED_TRAFFIC_BYTES = {
     ("C2", 0.25): (593323 + 27094) * 1024 * 2.000 + (448863 + 2500) * 1024 * 1.000,
-    ("C5", 0.25): (1.16689e7 + 93842) * 1024 * 2.000 + (528869 + 5000) * 1024 * 1.000,
+    ("C5", 0.25): (6.63817e6 + 329406) * 1024 * 2.000 + (531216 + 5000) * 1024 * 1.000,
 }
 
 
