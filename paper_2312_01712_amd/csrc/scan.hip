@@ -267,6 +267,7 @@ struct ScanArgs {
   const float *centroids;       // [nlist][D]
   const float *codebooks;       // [M][256][dsub]
   const float *probe_lb;        // [Q][nprobe] lower bound on the distance of any point of the probed list, or NULL
+  const float *list_box;        // [nlist][M][2][dsub] per list and subspace the bounding box of the entries in use
   const int64_t *list_offsets;  // [nlist+1]
   const int64_t *list_blocks;   // [nlist+1]
   const uint8_t *codes;         // interleaved blocks
@@ -1118,7 +1119,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   LDS int64_t *meta_blk = meta_row0 + META;
   LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
   LDS float *meta_start = (LDS float *)(meta_len + META);
-  LDS float *sthr = meta_start + META;  // [M]
+  LDS float *meta_lb = meta_start + META;  // lower bound on the score of any point of the list
+  LDS float *sthr = meta_lb + META;  // [M]
   LDS float *sthr_in = sthr + IVFPQ_MAX_M;
   LDS float *srmin = sthr_in + IVFPQ_MAX_M;    // [M] smallest value of each table row
   LDS float *srabs = srmin + IVFPQ_MAX_M;      // [M] largest magnitude of each table row
@@ -1223,12 +1225,57 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
     }
     __syncthreads();
     const int pn = p_end - p0 < META ? p_end - p0 : META;
+    // List-level bound (distance scoring; a wavefront per list, a lane per subspace).  Every
+    // point of the list uses, in subspace m, an entry inside the list's box, so its inner
+    // product with q_m is at most u_m = sum_j max(q_j lo_j, q_j hi_j) and its table value
+    // 0 - max(IP, thr_m) at least 0 - max(u_m, thr_m).  The margins cover the roundings of u_m
+    // and of the table's inner product (dsub products each), of the sum below, and of the
+    // scan's own sum (the slack of adc_ip_exit).
+    if constexpr (MT > 0 && !DUMP) {
+      const bool bound_on = mode == 0 && !(a.ablate & (64 | 8));
+      for (int pm = wave; pm < pn; pm += NW) {
+        const int32_t cc = probes[p0 + pm];
+        float lbv = -__builtin_inff();
+        if (bound_on && (uint32_t)cc < (uint32_t)a.nlist) {
+          const float *bx = a.list_box + (int64_t)cc * D * 2;
+          const float eps_m = (float)(2 * dsub + 4) * 5.9604645e-08f;
+          float acc = 0.0f, amag = 0.0f;
+          for (int m = lane; m < M; m += 64) {
+            float u = 0.0f, mag = 0.0f;
+            for (int j = 0; j < dsub; ++j) {
+              const float qj = sq[m * dsub + j], lo = bx[m * 2 * dsub + j], hi = bx[m * 2 * dsub + dsub + j];
+              u += fmaxf(qj * lo, qj * hi);
+              mag += fabsf(qj) * fmaxf(fabsf(lo), fabsf(hi));
+            }
+            const float thr = sthr[m];
+            const float t = fmaxf(u, thr) + eps_m * (mag + fabsf(thr));
+            acc += t;
+            amag += fabsf(t);
+          }
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) {
+            acc += __shfl_xor(acc, off);
+            amag += __shfl_xor(amag, off);
+          }
+          const float start_l = meta_start[pm];
+          const float eps_s = 5.9604645e-08f * (fabsf(start_l) + amag + ssuf[(M + 7) / 8]);
+          lbv = (start_l - acc) - (float)(5 * M + 80) * eps_s;
+        }
+        if (lane == 0) meta_lb[pm] = lbv;
+      }
+      __syncthreads();
+    }
     for (int pm = 0; pm < pn; ++pm) {
       const int64_t row0 = meta_row0[pm];
       const int len = __builtin_amdgcn_readfirstlane(meta_len[pm]);
       const int nb = (len + 63) >> 6;
       const uint8_t *base = a.codes + meta_blk[pm] * ivfpq_block_bytes(Mp);
       const float start = meta_start[pm];
+      if constexpr (MT > 0 && !DUMP) {  // ruled out by the list-level bound: nothing of the list is requested
+        const uint32_t shared0 = *(volatile LDS uint32_t *)sh.bound;
+        const uint32_t pref0 = shared0 < st.tau.d ? shared0 : st.tau.d;
+        if (dist_key<true>(meta_lb[pm]) > pref0) continue;
+      }
       if constexpr (MT > 0) {
         if (wave < nb) {
           const int last = nb - 1;
@@ -1583,7 +1630,7 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
 size_t scan_ip_lds(const ScanArgs &a, int nw) {
   const int lut_bytes = a.M * 1024, stage = nw * KP * 12;
   return (size_t)(lut_bytes > stage ? lut_bytes : stage) + ((a.D * 4 + 15) & ~15) + (size_t)nw * 64 * 12 +
-         ((4 * (nw + 1) + 15) & ~15) + 64 * 24 + 4 * IVFPQ_MAX_M * 4 + (IVFPQ_MAX_M / 8 + 2) * 4;
+         ((4 * (nw + 1) + 15) & ~15) + 64 * 28 + 4 * IVFPQ_MAX_M * 4 + (IVFPQ_MAX_M / 8 + 2) * 4;
 }
 
 template <int MT, int NW>
@@ -1631,6 +1678,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.centroids = ix->d_centroids;
   a.codebooks = ix->d_codebooks;
   a.probe_lb = nullptr;
+  a.list_box = ix->d_box;
   a.list_offsets = ix->d_list_offsets;
   a.list_blocks = ix->d_list_blocks;
   a.codes = ix->d_codes;
