@@ -165,3 +165,36 @@ def exact_knn(base, queries, k: int, metric: int = 0) -> Tuple[np.ndarray, np.nd
     _load().oracle_exact_knn(ctypes.c_int64(N), D, _p(b, _f32p), ctypes.c_int64(Q), _p(q, _f32p), k,
                              metric, _p(oi, _i64p), _p(od, _f64p))
     return oi, od
+
+
+def density_map(proj, lo, cells_per_unit, G: int) -> np.ndarray:
+    """[M][G][G] fp64 densities (count / cell area) of projections [n][M][2]."""
+    pr, l, c = _f32(proj), _f32(lo), _f32(cells_per_unit)
+    n, M, two = pr.shape
+    assert two == 2 and l.shape == (M, 2) and c.shape == (M, 2)
+    out = np.empty((M, G, G), dtype=np.float64)
+    if _load().oracle_density_map(ctypes.c_int64(n), M, _p(pr, _f32p), _p(l, _f32p), _p(c, _f32p), G,
+                                  _p(out, _f64p)):
+        raise ValueError("oracle_density_map: invalid argument")
+    return out
+
+
+def query_radii(queries, centroids, nearest, lo, cells_per_unit, fmap, coef, fallback,
+                scale: float) -> np.ndarray:
+    """radii [Q][M] from a per-subspace grid map [M][G][G] and polynomial [M][degree+1]
+    (lowest power first), looked up at the residual w.r.t. list nearest[q]."""
+    q, c = _f32(queries), _f32(centroids)
+    l, cpu, mp, cf, fb = _f32(lo), _f32(cells_per_unit), _f32(fmap), _f32(coef), _f32(fallback)
+    near = np.ascontiguousarray(nearest, dtype=np.int32)
+    Q, D = q.shape
+    M, G = mp.shape[0], mp.shape[1]
+    assert mp.shape == (M, G, G) and l.shape == (M, 2) and cpu.shape == (M, 2)
+    assert cf.shape[0] == M and fb.shape == (M,) and near.shape == (Q,)
+    out = np.empty((Q, M), dtype=np.float32)
+    rc = _load().oracle_query_radii(ctypes.c_int64(Q), D, M, _p(q, _f32p), _p(c, _f32p), c.shape[0],
+                                    _p(near, _i32p), G, _p(l, _f32p), _p(cpu, _f32p), _p(mp, _f32p),
+                                    cf.shape[1] - 1, _p(cf, _f32p), _p(fb, _f32p),
+                                    ctypes.c_float(scale), _p(out, _f32p))
+    if rc:
+        raise ValueError("oracle_query_radii: invalid argument")
+    return out

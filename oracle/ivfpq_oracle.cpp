@@ -47,6 +47,20 @@
 //       i.e. minus the inner product of q with the point's reconstruction, and lists
 //       are filtered by the same -IP(q, centroid).  For the hit-count modes the inner
 //       sphere is the same construction with r_m / 2;
+//   R17 dynamic threshold (Sec. 4.1 "Determining Proper Threshold"; the threshold step of
+//       Algorithm 2).  Offline the paper cuts every (two-dimensional) subspace into a
+//       G x G grid, G = 100, a cell's density being the number of search point
+//       projections in it divided by its area, and fits a polynomial from that density
+//       to the threshold a projection needs; online the density at the query's
+//       projection is looked up, the polynomial evaluated and the result multiplied by
+//       the user's scale.  The listing evaluates this inside the loop over the selected
+//       lists, before the centroid is subtracted, and keeps overwriting (x, y); read
+//       here as: ONE threshold per (query, subspace), looked up at the projection of
+//       the residual w.r.t. the query's NEAREST list (entries and search point
+//       projections live in residual space, R5), which fills radii[Q][M] of R15.  The
+//       map stores the polynomial's input (the density, or whatever fixed transform of
+//       it the fit used); a value that is not positive and finite is replaced by a
+//       per-subspace fallback radius before scaling;
 //
 // Metric: 0 = squared L2, 1 = inner product (R16).
 // Scoring modes: 0 = distances (the paper's JUNO-H), 1 = hit count (JUNO-L),
@@ -61,8 +75,9 @@
 // sort-based selection for top-k; for the inner-product metric the enlarged-sphere
 // form of the keep rule, the identity IP = (|e|^2 + |q|^2 - L2^2) / 2 against the L2
 // table, reconstruction of -IP by the unthresholded sum, and brute-force maximum
-// inner product search on identity-codebook indexes.  No function here is "parity
-// unpinned".
+// inner product search on identity-codebook indexes; for the dynamic threshold a
+// hand-computed grid example, counting by cell inequalities, and the constant /
+// identity polynomial cases.  No function here is "parity unpinned".
 
 #include <algorithm>
 #include <cmath>
@@ -359,6 +374,65 @@ int oracle_exact_knn(int64_t N, int32_t D, const float* base, int64_t Q, const f
     for (int i = 0; i < k; ++i) {
       out_ids[q * k + i] = (size_t)i < kk ? d[i].second : -1;
       out_dist[q * k + i] = (size_t)i < kk ? d[i].first : std::numeric_limits<double>::infinity();
+    }
+  }
+  return 0;
+}
+
+// Grid cell of a coordinate (R17): t = (x - lo) * cells_per_unit in fp32, cell =
+// floor(t) clamped to [0, G-1] (projections outside the map use the border cell).
+static inline int grid_cell(float x, float lo, float cells_per_unit, int G) {
+  const float t = (x - lo) * cells_per_unit;
+  if (!(t >= 1.0f)) return 0;
+  if (t >= (float)G) return G - 1;
+  return (int)t;
+}
+
+// Density map (paper Sec. 4.1): for every subspace a G x G grid; density of a cell =
+// (number of projections that fall into it) / (area of the cell).  proj is
+// [n][M][2], lo and cells_per_unit are [M][2] (cell width along axis j is
+// 1 / cells_per_unit[m][j]); out is [M][G][G] with cell (i0, i1) at i0 * G + i1.
+int oracle_density_map(int64_t n, int32_t M, const float* proj, const float* lo,
+                       const float* cells_per_unit, int32_t G, double* out) {
+  if (n < 0 || M < 1 || G < 1) return 1;
+  for (int64_t i = 0; i < (int64_t)M * G * G; ++i) out[i] = 0.0;
+  for (int64_t p = 0; p < n; ++p)
+    for (int m = 0; m < M; ++m) {
+      const int i0 = grid_cell(proj[(p * M + m) * 2 + 0], lo[m * 2 + 0], cells_per_unit[m * 2 + 0], G);
+      const int i1 = grid_cell(proj[(p * M + m) * 2 + 1], lo[m * 2 + 1], cells_per_unit[m * 2 + 1], G);
+      out[((int64_t)m * G + i0) * G + i1] += 1.0;
+    }
+  for (int m = 0; m < M; ++m) {
+    const double area = 1.0 / ((double)cells_per_unit[m * 2 + 0] * (double)cells_per_unit[m * 2 + 1]);
+    for (int c = 0; c < G * G; ++c) out[(int64_t)m * G * G + c] /= area;
+  }
+  return 0;
+}
+
+// Query-specific thresholds (paper Sec. 4.1; Algorithm 2 threshold step; R17).
+// For query q and subspace m (dsub = 2), with c = nearest[q]:
+//   (x, y) = q[2m .. 2m+1] - centroid_c[2m .. 2m+1]
+//   f      = map[m][cell(x)][cell(y)]
+//   p      = coef[m][degree]; p = fmaf(p, f, coef[m][d]) for d = degree-1 .. 0
+//   thres  = (0 < p < inf ? p : fallback[m]) * scale
+int oracle_query_radii(int64_t Q, int32_t D, int32_t M, const float* queries, const float* centroids,
+                       int32_t nlist, const int32_t* nearest, int32_t G, const float* lo,
+                       const float* cells_per_unit, const float* map, int32_t degree,
+                       const float* coef, const float* fallback, float scale, float* out) {
+  if (Q < 0 || M < 1 || D != 2 * M || G < 1 || degree < 0) return 1;
+  for (int64_t q = 0; q < Q; ++q) {
+    const int32_t c = nearest[q];
+    if (c < 0 || c >= nlist) return 1;
+    for (int m = 0; m < M; ++m) {
+      const float x = queries[q * D + 2 * m] - centroids[(int64_t)c * D + 2 * m];
+      const float y = queries[q * D + 2 * m + 1] - centroids[(int64_t)c * D + 2 * m + 1];
+      const int i0 = grid_cell(x, lo[m * 2 + 0], cells_per_unit[m * 2 + 0], G);
+      const int i1 = grid_cell(y, lo[m * 2 + 1], cells_per_unit[m * 2 + 1], G);
+      const float f = map[((int64_t)m * G + i0) * G + i1];
+      float p = coef[m * (degree + 1) + degree];
+      for (int d = degree - 1; d >= 0; --d) p = std::fmaf(p, f, coef[m * (degree + 1) + d]);
+      const bool usable = p > 0.0f && p < std::numeric_limits<float>::infinity();
+      out[q * M + m] = (usable ? p : fallback[m]) * scale;
     }
   }
   return 0;

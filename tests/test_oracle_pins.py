@@ -549,3 +549,100 @@ def test_ip_scores_closed_forms(tiny):
             sl = slice(offs[i], offs[i + 1])
             o = np.lexsort((ids[sl], dt[sl]))[:w.k]
             assert np.array_equal(ids_s[i], ids[sl][o]) and np.array_equal(dist_s[i], dt[sl][o])
+
+
+# ----------------------------------------------------------------------------
+# dynamic threshold (paper Sec. 4.1 "Determining Proper Threshold"; Algorithm 2)
+# ----------------------------------------------------------------------------
+
+def test_density_map_counts_points_per_cell_area():
+    """Density = (projections in the cell) / (cell area), by testing the cell's
+    inequalities point by point -- no floor, no index arithmetic.  Coordinates are
+    multiples of 1/64 and cells are 1/4 wide, so every comparison is exact."""
+    rng = np.random.default_rng(5)
+    n, M, G = 3000, 3, 8
+    lo = np.array([[-1.0, -1.0], [0.0, -0.5], [-2.0, 1.0]], dtype=np.float32)
+    width = np.array([[0.25, 0.25], [0.25, 0.125], [0.5, 0.25]], dtype=np.float32)
+    cpu = (1.0 / width).astype(np.float32)
+    proj = (rng.integers(-16, G * 16 + 16, size=(n, M, 2)) / 64.0).astype(np.float32) * (width * 4)[None] + lo[None]
+    dens = oracle.density_map(proj, lo, cpu, G)
+    assert dens.shape == (M, G, G)
+    for m in range(M):
+        area = float(width[m, 0]) * float(width[m, 1])
+        for i0 in range(G):
+            for i1 in range(G):
+                inside = np.ones(n, dtype=bool)
+                for axis, i in ((0, i0), (1, i1)):
+                    a = float(lo[m, axis]) + i * float(width[m, axis])
+                    b = a + float(width[m, axis])
+                    x = proj[:, m, axis].astype(np.float64)
+                    # border cells also take what lies outside the map on their side
+                    inside &= ((x >= a) | (i == 0)) & ((x < b) | (i == G - 1))
+                assert dens[m, i0, i1] == inside.sum() / area, (m, i0, i1)
+    assert np.isclose(dens.sum(axis=(1, 2)) @ np.ones(M), sum(n / (float(w0) * float(w1)) for w0, w1 in width))
+
+
+def test_query_radii_hand_example():
+    """Two subspaces, a 3 x 3 grid with nine different values per subspace (a transposed
+    or shifted cell shows), two lists, polynomial 0.5 + 0.25 f + 2 f^2; every number
+    below is a dyadic fraction worked out by hand."""
+    cent = np.array([[1.0, -1.0, 0.5, 2.0], [0.0, 0.0, 0.0, 0.0]], dtype=np.float32)
+    lo = np.array([[-1.5, 0.0], [0.0, -3.0]], dtype=np.float32)
+    cpu = np.array([[1.0, 2.0], [0.5, 1.0]], dtype=np.float32)   # cell widths (1, 1/2) and (2, 1)
+    fmap = np.array([[[0.0, 0.25, 0.5], [0.75, 1.0, 1.25], [1.5, 1.75, 2.0]],
+                     [[2.0, 1.75, 1.5], [1.25, 1.0, 0.75], [0.5, 0.25, 0.0]]], dtype=np.float32)
+    coef = np.array([[0.5, 0.25, 2.0], [1.0, 0.0, -1.0]], dtype=np.float32)
+    fallback = np.array([7.0, 9.0], dtype=np.float32)
+    q = np.array([[1.25, -0.25, 3.0, 0.25],     # list 0: residual (0.25, 0.75 | 2.5, -1.75)
+                  [1.25, -0.25, 3.0, 0.25]],    # list 1: residual = the query itself
+                 dtype=np.float32)
+    near = np.array([0, 1], dtype=np.int32)
+    r = oracle.query_radii(q, cent, near, lo, cpu, fmap, coef, fallback, 0.5)
+    # query 0, subspace 0: t = (0.25+1.5)*1 = 1.75 -> 1 ; (0.75-0)*2 = 1.5 -> 1 ; f = 1.0
+    #   p = 0.5 + 0.25 + 2 = 2.75 ; times 0.5 = 1.375
+    # query 0, subspace 1: t = 2.5*0.5 = 1.25 -> 1 ; (-1.75+3)*1 = 1.25 -> 1 ; f = 1.0
+    #   p = 1 - 1 = 0 -> not positive -> fallback 9 ; times 0.5 = 4.5
+    # query 1, subspace 0: t = 2.75 -> 2 ; (-0.25)*2 < 0 -> 0 ; f = map[2][0] = 1.5
+    #   p = 0.5 + 0.375 + 4.5 = 5.375 ; times 0.5 = 2.6875
+    # query 1, subspace 1: t = 3*0.5 = 1.5 -> 1 ; (0.25+3) = 3.25 -> clamped to 2 ; f = 0.75
+    #   p = 1 - 0.5625 = 0.4375 ; times 0.5 = 0.21875
+    assert r.tolist() == [[1.375, 4.5], [2.6875, 0.21875]]
+
+
+def test_query_radii_special_polynomials(tiny):
+    """Degree 0: every radius is the constant times the scale.  Identity polynomial on a
+    map that stores the cell number: the radius names the cell, which is checked against
+    the cell's inequalities in float64.  Scale is a plain factor."""
+    w, idx, centres, q = tiny["T_sift"]
+    assert idx.dsub == 2
+    M, G = idx.M, 10
+    probe, _ = oracle.coarse(q, idx.centroids, 1)
+    near = probe[:, 0]
+    res = (q - idx.centroids[near]).reshape(-1, M, 2)
+    lo = res.min(0).astype(np.float32)
+    span = (res.max(0) - lo).astype(np.float32)
+    cpu = (np.float32(G) / span).astype(np.float32)
+    fb = np.full(M, 3.0, dtype=np.float32)
+    const = np.linspace(0.5, 2.0, M).astype(np.float32)[:, None]
+    r = oracle.query_radii(q, idx.centroids, near, lo, cpu, np.zeros((M, G, G), np.float32), const, fb, 1.5)
+    assert np.array_equal(r, np.tile((const[:, 0] * np.float32(1.5))[None], (q.shape[0], 1)))
+    cellno = np.tile(np.arange(1, G * G + 1, dtype=np.float32).reshape(1, G, G), (M, 1, 1))
+    ident = np.tile(np.array([[0.0, 1.0]], dtype=np.float32), (M, 1))
+    r1 = oracle.query_radii(q, idx.centroids, near, lo, cpu, cellno, ident, fb, 1.0)
+    r2 = oracle.query_radii(q, idx.centroids, near, lo, cpu, cellno, ident, fb, 0.25)
+    assert np.array_equal(r2, r1 * np.float32(0.25))
+    cell = r1.astype(np.int64) - 1
+    i0, i1 = cell // G, cell % G
+    t = (res.astype(np.float64) - lo[None]) * cpu[None].astype(np.float64)   # position in cell units
+    checked = 0
+    for axis, i in ((0, i0), (1, i1)):
+        ta = t[:, :, axis]
+        clear = np.abs(ta - np.round(ta)) > 1e-4       # away from a cell border, fp32 and fp64 agree
+        ok = ((ta >= i) | (i == 0)) & ((ta < i + 1) | (i == G - 1))
+        assert np.all(ok[clear])
+        checked += int(clear.sum())
+    assert checked > 0.9 * 2 * cell.size
+    # a different nearest list moves the residual: the look-up must follow it
+    other = (near + 1) % idx.nlist
+    r3 = oracle.query_radii(q, idx.centroids, other, lo, cpu, cellno, ident, fb, 1.0)
+    assert not np.array_equal(r3, r1)
