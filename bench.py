@@ -16,6 +16,7 @@ The step issues ivfpq_coarse then ivfpq_scan_topk (the two launches
 ivfpq_search makes) so that an event can sit between them.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -53,7 +54,9 @@ def main():
     ap.add_argument("--keep", type=float, default=0.25, help="fraction of codebook entries inside the radius")
     ap.add_argument("--score-mode", type=int, default=0,
                     help="0 distances (default), 1 hit count, 2 reward/penalty hit count")
-    ap.add_argument("--dynamic-radii", action="store_true", help="per-query radii from the density-map recipe")
+    ap.add_argument("--dynamic-radii", action="store_true",
+                    help="per-query radii: density map + polynomial fitted offline, looked up by ivfpq_query_radii in every step")
+    ap.add_argument("--radius-scale", type=float, default=1.0, help="user scale on the dynamic radii")
     ap.add_argument("--scan-waves", type=int, default=0)
     ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 default (first chunk ahead while pruning), 1 whole blocks, 2 / 3 always first half / first chunk")
     ap.add_argument("--lds-pad", type=int, default=0, help="measurement only: extra LDS bytes per scan workgroup")
@@ -104,15 +107,20 @@ def main():
     out_dist = torch.empty((Q, k), dtype=torch.float32, device="cuda")
     lib = binding.load_library()
     stream = torch.cuda.current_stream().cuda_stream
-    d_rq = None
-    if args.dynamic_radii:
-        radii_q = wl.dynamic_radii(w, idx, centres, q, args.keep)
-        d_rq = torch.from_numpy(radii_q).cuda()
+    d_rq = rmodel = None
+    if args.dynamic_radii:   # offline: density maps + polynomial (an input); online: ivfpq_query_radii in every step
+        model = wl.fit_radius_model(w, idx, centres, args.keep)
+        model_arrays = (model["lo"], model["cells_per_unit"], model["map"], model["coef"], model["fallback"])
+        rmodel = binding.RadiusModel(gi, *model_arrays)
+        d_rq = torch.empty((Q, w.M), dtype=torch.float32, device="cuda")
     rptr, scoring, _keep = binding._scoring(args.score_mode, d_rq, None if args.dynamic_radii else radii, Q, w.M)
 
     def step(ev=None):
         binding._check(lib.ivfpq_coarse(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), None, ws.data_ptr(),
                                         ws.numel(), stream))
+        if rmodel is not None:
+            binding._check(lib.ivfpq_query_radii(gi._h, rmodel._h, q.data_ptr(), Q, pid.data_ptr(), nprobe,
+                                                 ctypes.c_float(args.radius_scale), d_rq.data_ptr(), stream))
         if ev:
             ev[0].record()
         binding._check(lib.ivfpq_scan_topk_ex(gi._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, rptr, scoring,
@@ -184,7 +192,11 @@ def main():
         threads = min(os.cpu_count() or 1, 16)
         t = time.perf_counter()
         probe_n = min(Q, 2 * threads)
-        o_radii = radii_q if args.dynamic_radii else radii
+        if args.dynamic_radii:   # the oracle's own chain: nearest list, map look-up, polynomial, scale
+            o_near, _ = oracle.coarse(qh, idx.centroids, 1)
+            o_radii = oracle.query_radii(qh, idx.centroids, o_near[:, 0], *model_arrays, args.radius_scale)
+        else:
+            o_radii = radii
         osearch = lambda lo, hi, th: oracle.search(qh[lo:hi], idx, nprobe, k,
                                                    o_radii[lo:hi] if args.dynamic_radii else o_radii,
                                                    threads=th, mode=args.score_mode, metric=metric)

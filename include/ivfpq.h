@@ -200,6 +200,54 @@ int ivfpq_scan_all_ex(const ivfpq_index *index, const float *d_queries, int64_t 
                       const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
                       int32_t *d_errors, void *hip_stream);
 
+/* ---- dynamic thresholds ------------------------------------------------------
+ * Paper Sec. 4.1 "Determining Proper Threshold" and the threshold step of
+ * Algorithm 2: offline, every two-dimensional subspace is cut into a grid x grid
+ * map (the paper uses 100 x 100) that records the density of search point
+ * projections per cell, and a polynomial is fitted from that density to the
+ * threshold a projection needs; online, the value at the query's projection is
+ * looked up, the polynomial evaluated and the result multiplied by the user's
+ * scale.  Here: one threshold per (query, subspace), looked up at the projection
+ * of the residual of the query w.r.t. its NEAREST list (the space the entries and
+ * the encoded points live in); the result is the d_query_radii array of
+ * ivfpq_scoring.  The map and the polynomial are inputs (the offline fit is not
+ * part of the search path). */
+typedef struct {
+  int32_t M;                   /* number of subspaces; must equal the index's, with dsub == 2   */
+  int32_t grid;                /* cells per axis, 1 .. 1024                                      */
+  int32_t degree;              /* degree of the polynomial, 0 .. 8                               */
+  const float *lo;             /* host [M][2]  low corner of the map                             */
+  const float *cells_per_unit; /* host [M][2]  1 / cell width along each axis, finite and > 0    */
+  const float *map;            /* host [M][grid][grid]  the polynomial's input per cell (the
+                                  density or a fixed transform of it); cell (i0, i1), i0 from the
+                                  subspace's first coordinate, at i0 * grid + i1                 */
+  const float *coef;           /* host [M][degree + 1]  lowest power first                       */
+  const float *fallback;       /* host [M]  radius used where the polynomial gives no positive
+                                  finite value                                                   */
+} ivfpq_radius_model_desc;
+
+typedef struct ivfpq_radius_model ivfpq_radius_model; /* opaque; owns its device copy */
+
+/* Copies the model to the current device.  Synchronous; allocates. */
+int ivfpq_radius_model_create(const ivfpq_index *index, const ivfpq_radius_model_desc *desc,
+                              ivfpq_radius_model **out);
+void ivfpq_radius_model_destroy(ivfpq_radius_model *model);
+
+/* d_radii[q][m] for a batch, all in fp32, with c = d_probe_ids[q * nprobe] (the first
+ * entry of a row of ivfpq_coarse's output: the nearest list):
+ *   x_j  = q[2m + j] - centroid_c[2m + j],                       j = 0, 1
+ *   i_j  = floor((x_j - lo[m][j]) * cells_per_unit[m][j]) clamped to [0, grid - 1]
+ *          (NaN goes to cell 0)
+ *   f    = map[m][i_0][i_1]
+ *   p    = coef[m][degree];  p = fmaf(p, f, coef[m][d]) for d = degree - 1 .. 0
+ *   d_radii[q][m] = (0 < p < inf ? p : fallback[m]) * scale
+ * d_queries device [Q][D]; d_probe_ids device [Q][nprobe] int32 with ids in [0, nlist)
+ * (a row whose first id is outside gets the fallback); d_radii device [Q][M] fp32.
+ * scale must be finite and >= 0.  Enqueues one kernel; allocates nothing. */
+int ivfpq_query_radii(const ivfpq_index *index, const ivfpq_radius_model *model,
+                      const float *d_queries, int64_t Q, const int32_t *d_probe_ids, int32_t nprobe,
+                      float scale, float *d_radii, void *hip_stream);
+
 /* Shape of an index and of its device layout. */
 typedef struct {
   int64_t N;

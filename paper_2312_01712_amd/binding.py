@@ -24,6 +24,7 @@ SYMBOLS = [
     "ivfpq_coarse", "ivfpq_build_lut", "ivfpq_scan_topk", "ivfpq_scan_all", "ivfpq_index_get_info",
     "ivfpq_set_option", "ivfpq_coarse_fallbacks", "ivfpq_last_error",
     "ivfpq_search_ex", "ivfpq_build_lut_ex", "ivfpq_scan_topk_ex", "ivfpq_scan_all_ex",
+    "ivfpq_radius_model_create", "ivfpq_radius_model_destroy", "ivfpq_query_radii",
 ]
 
 SCORE_DISTANCE, SCORE_HIT_COUNT, SCORE_HIT_REWARD = 0, 1, 2
@@ -80,6 +81,10 @@ def load_library():
     lib.ivfpq_build_lut_ex.argtypes = [vp, vp, i64, i32, vp, vp, sp, vp, vp, vp]
     lib.ivfpq_scan_topk_ex.argtypes = [vp, vp, i64, i32, vp, i32, vp, sp, vp, vp, vp, sz, vp]
     lib.ivfpq_scan_all_ex.argtypes = [vp, vp, i64, i32, vp, vp, sp, vp, vp, vp, vp, vp]
+    lib.ivfpq_radius_model_create.argtypes = [vp, ctypes.POINTER(_RadiusModelDesc), ctypes.POINTER(vp)]
+    lib.ivfpq_radius_model_destroy.argtypes = [vp]
+    lib.ivfpq_radius_model_destroy.restype = None
+    lib.ivfpq_query_radii.argtypes = [vp, vp, vp, i64, vp, i32, ctypes.c_float, vp, vp]
     lib.ivfpq_index_get_info.argtypes = [vp, ctypes.POINTER(_Info)]
     lib.ivfpq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.ivfpq_coarse_fallbacks.argtypes = [ctypes.c_int]
@@ -146,6 +151,46 @@ def _scoring(mode: int, query_radii: Optional[torch.Tensor], radii, Q: int, M: i
         sc = _Scoring(mode=int(mode), d_query_radii=qr_ptr)
         keep.append(sc)
     return r_ptr, (ctypes.byref(sc) if sc is not None else None), keep
+
+
+class _RadiusModelDesc(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int32), ("grid", ctypes.c_int32), ("degree", ctypes.c_int32),
+                ("lo", ctypes.c_void_p), ("cells_per_unit", ctypes.c_void_p), ("map", ctypes.c_void_p),
+                ("coef", ctypes.c_void_p), ("fallback", ctypes.c_void_p)]
+
+
+class RadiusModel:
+    """Device copy of a threshold model (`ivfpq_radius_model_create`): per subspace a
+    grid map [M][G][G] with its low corner and cells per unit [M][2], polynomial
+    coefficients [M][degree+1] (lowest power first) and a fallback radius [M]."""
+
+    def __init__(self, index: "IvfPqIndex", lo, cells_per_unit, fmap, coef, fallback):
+        arr = [np.ascontiguousarray(a, dtype=np.float32) for a in (lo, cells_per_unit, fmap, coef, fallback)]
+        l, c, mp, cf, fb = arr
+        M = mp.shape[0]
+        if mp.ndim != 3 or mp.shape[1] != mp.shape[2] or l.shape != (M, 2) or c.shape != (M, 2) \
+                or cf.ndim != 2 or cf.shape[0] != M or fb.shape != (M,):
+            raise ValueError("radius model arrays have inconsistent shapes")
+        desc = _RadiusModelDesc(M=M, grid=mp.shape[1], degree=cf.shape[1] - 1, lo=l.ctypes.data,
+                                cells_per_unit=c.ctypes.data, map=mp.ctypes.data, coef=cf.ctypes.data,
+                                fallback=fb.ctypes.data)
+        handle = ctypes.c_void_p()
+        self._h = None
+        _check(load_library().ivfpq_radius_model_create(index._h, ctypes.byref(desc), ctypes.byref(handle)))
+        self._h = handle
+        self.M = M
+        del arr
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().ivfpq_radius_model_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class IvfPqIndex:
@@ -239,6 +284,21 @@ class IvfPqIndex:
         _check(load_library().ivfpq_coarse(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), pd.data_ptr(),
                                            ws.data_ptr(), ws.numel(), _stream()))
         return pid, pd
+
+    def query_radii(self, model: RadiusModel, queries: torch.Tensor, probe_ids: torch.Tensor, scale: float = 1.0,
+                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Per-(query, subspace) radii [Q][M] from the threshold model, looked up at the
+        residual w.r.t. the first list of each row of probe_ids."""
+        q = _dev(queries, torch.float32)
+        pid = _dev(probe_ids, torch.int32)
+        Q, nprobe = pid.shape
+        r = out if out is not None else torch.empty((Q, self.M), dtype=torch.float32, device=q.device)
+        _dev(r, torch.float32)
+        if tuple(r.shape) != (Q, self.M) or q.shape[0] != Q:
+            raise ValueError("query_radii: shapes of queries, probe_ids and out do not agree")
+        _check(load_library().ivfpq_query_radii(self._h, model._h, q.data_ptr(), Q, pid.data_ptr(), nprobe,
+                                                ctypes.c_float(scale), r.data_ptr(), _stream()))
+        return r
 
     def build_lut(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, mode: int = SCORE_DISTANCE,
                   query_radii: Optional[torch.Tensor] = None):

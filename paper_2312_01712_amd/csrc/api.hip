@@ -302,6 +302,97 @@ int ivfpq_index_get_info(const ivfpq_index *ix, ivfpq_index_info *info) {
   return IVFPQ_OK;
 }
 
+void ivfpq_radius_model_destroy(ivfpq_radius_model *md) {
+  if (!md) return;
+  (void)hipFree(md->d_block);
+  delete md;
+}
+
+int ivfpq_radius_model_create(const ivfpq_index *ix, const ivfpq_radius_model_desc *d,
+                              ivfpq_radius_model **out) {
+  const char *fn = "radius_model_create";
+  if (!ix || !d || !out) { set_error("%s: NULL argument", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  *out = nullptr;
+  if (!d->lo || !d->cells_per_unit || !d->map || !d->coef || !d->fallback) {
+    set_error("%s: NULL array in the description", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (d->M != ix->M) {
+    set_error("%s: M = %d differs from the index's %d", fn, d->M, ix->M);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (ix->dsub != 2) {
+    set_error("%s: the density map is two-dimensional; the index has dsub = %d", fn, ix->dsub);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  if (d->grid < 1 || d->grid > 1024 || d->degree < 0 || d->degree > 8) {
+    set_error("%s: grid = %d outside [1, 1024] or degree = %d outside [0, 8]", fn, d->grid, d->degree);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  const int M = d->M, G = d->grid, nc = d->degree + 1;
+  for (int i = 0; i < 2 * M; ++i) {
+    if (!isfinite(d->lo[i]) || !isfinite(d->cells_per_unit[i]) || !(d->cells_per_unit[i] > 0.0f)) {
+      set_error("%s: lo / cells_per_unit of subspace %d not finite or not positive", fn, i / 2);
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+  }
+  for (int m = 0; m < M; ++m) {
+    if (!isfinite(d->fallback[m]) || d->fallback[m] < 0.0f) {
+      set_error("%s: fallback[%d] must be finite and >= 0", fn, m);
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+  }
+  ivfpq_radius_model *md = new (std::nothrow) ivfpq_radius_model;
+  if (!md) { set_error("%s: out of host memory", fn); return IVFPQ_ERR_NO_MEMORY; }
+  memset(md, 0, sizeof *md);
+  md->M = M; md->grid = G; md->degree = d->degree;
+  // lo | cells_per_unit | coef | fallback | map; every part starts on a multiple of 8 bytes
+  const size_t n_lo = 2 * (size_t)M, n_coef = ((size_t)M * nc + 1) & ~(size_t)1, n_fb = ((size_t)M + 1) & ~(size_t)1;
+  const size_t n_map = (size_t)M * G * G;
+  std::vector<float> host(2 * n_lo + n_coef + n_fb + n_map, 0.0f);
+  memcpy(host.data(), d->lo, n_lo * 4);
+  memcpy(host.data() + n_lo, d->cells_per_unit, n_lo * 4);
+  memcpy(host.data() + 2 * n_lo, d->coef, (size_t)M * nc * 4);
+  memcpy(host.data() + 2 * n_lo + n_coef, d->fallback, (size_t)M * 4);
+  memcpy(host.data() + 2 * n_lo + n_coef + n_fb, d->map, n_map * 4);
+  hipError_t e = hipGetDevice(&md->device);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&md->d_block), host.size() * 4);
+  if (e == hipSuccess) e = hipMemcpy(md->d_block, host.data(), host.size() * 4, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    ivfpq_radius_model_destroy(md);
+    if (e == hipErrorOutOfMemory) { set_error("%s: out of device memory", fn); return IVFPQ_ERR_NO_MEMORY; }
+    return hip_fail(e, fn);
+  }
+  md->d_lo = md->d_block;
+  md->d_cpu = md->d_lo + n_lo;
+  md->d_coef = md->d_cpu + n_lo;
+  md->d_fallback = md->d_coef + n_coef;
+  md->d_map = md->d_fallback + n_fb;
+  *out = md;
+  return IVFPQ_OK;
+}
+
+int ivfpq_query_radii(const ivfpq_index *ix, const ivfpq_radius_model *md, const float *d_queries,
+                      int64_t Q, const int32_t *d_probe_ids, int32_t nprobe, float scale,
+                      float *d_radii, void *stream) {
+  const char *fn = "query_radii";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  if (!md) { set_error("%s: model is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (md->M != ix->M || ix->dsub != 2) {
+    set_error("%s: the model was made for another index shape", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (!isfinite(scale) || scale < 0.0f) {
+    set_error("%s: scale must be finite and >= 0", fn);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (Q == 0) return IVFPQ_OK;
+  if (!d_probe_ids || !d_radii) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  return launch_query_radii(ix, md, d_queries, Q, d_probe_ids, nprobe, scale, d_radii,
+                            static_cast<hipStream_t>(stream));
+}
+
 size_t ivfpq_search_workspace_bytes(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k) {
   if (!ix || Q < 0 || nprobe < 1 || nprobe > ix->nlist || k < 1) return 0;
   const Workspace w = plan_workspace(ix, Q, nprobe, k);

@@ -28,6 +28,18 @@ struct ivfpq_index {
   float max_cnorm;
 };
 
+// Device-side image of a threshold model (ivfpq_radius_model_desc); one allocation.
+struct ivfpq_radius_model {
+  int32_t M, grid, degree;
+  int device;
+  float *d_block;     // the allocation: lo | cells_per_unit | coef | fallback | map
+  float *d_lo;        // [M][2]
+  float *d_cpu;       // [M][2]
+  float *d_coef;      // [M][degree+1]
+  float *d_fallback;  // [M]
+  float *d_map;       // [M][grid][grid]
+};
+
 // Device layout of the codes.  Every inverted list is padded to a multiple of 64
 // points (nb blocks) and occupies nb*64*Mp bytes, stored chunk-major: a point's Mp
 // code bytes are cut into Mp/16 chunks of 16 bytes followed by (Mp%16)/4 chunks of
@@ -83,6 +95,9 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
                 int32_t *d_errors, int32_t mode, const float *d_query_radii, float *d_probe_lb,
                 hipStream_t s);
+int launch_query_radii(const ivfpq_index *ix, const ivfpq_radius_model *md, const float *d_queries,
+                       int64_t Q, const int32_t *d_probe_ids, int32_t nprobe, float scale,
+                       float *d_radii, hipStream_t s);
 int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_list_boxes(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);

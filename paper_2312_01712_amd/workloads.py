@@ -372,59 +372,63 @@ def calibrate_radii(w: Workload, index: Index, centres: torch.Tensor, keep_frac:
     return radii
 
 
-def dynamic_radii(w: Workload, index: Index, centres: torch.Tensor, q: torch.Tensor,
-                  keep_frac: Optional[float] = None, scale: float = 1.0, n_cal: int = 512) -> np.ndarray:
-    """Per-(query, subspace) radii [Q][M] in the manner of the paper's Sec. 4.1
-    ("Determining Proper Threshold"): offline, a 100 x 100 density map of the residual
-    projections per subspace and a polynomial regression from the density at a
-    projection to the radius it needs; online, the density at the query's residual
-    projection (w.r.t. its nearest list) is looked up, the polynomial evaluated and the
-    result multiplied by the user's scale.  The radius a calibration projection "needs"
-    is here the one that keeps `keep_frac` of the 256 entries (the paper regresses the
-    radius that contains the top-100 neighbours, which needs its datasets).  Only
-    defined for 2-dimensional subspaces, like the paper's; other shapes get the static
-    calibrated radii for every query.  This produces an *input* of the search path."""
+def fit_radius_model(w: Workload, index: Index, centres: torch.Tensor, keep_frac: Optional[float] = None,
+                     n_cal: int = 512, G: int = 100, n_base: int = 200_000, with_projections: bool = False) -> dict:
+    """Offline half of the paper's dynamic threshold (Sec. 4.1, "Determining Proper
+    Threshold"): per subspace a G x G density map of the residual projections of
+    search points (count / cell area; the paper's G is 100) and a polynomial from the
+    density at a projection to the radius it needs.  Here the map stores log(1 +
+    density), the polynomial is a quadratic in it fitted by least squares on `n_cal`
+    calibration queries, and the radius a projection "needs" is the one that keeps
+    `keep_frac` of the 256 entries (the paper regresses the radius that contains the
+    top-100 neighbours, which needs its datasets).  Two-dimensional subspaces only,
+    like the paper's.  Returns host arrays in the layout of the library's radius
+    model: lo [M][2], cells_per_unit [M][2], map [M][G][G], coef [M][3] (lowest power
+    first), fallback [M].  Like the k-means training this is an *input* of the search
+    path; the online look-up runs in the library."""
+    if index.dsub != 2:
+        raise ValueError("the density map needs two-dimensional subspaces")
     kf = w.keep_frac if keep_frac is None else keep_frac
     device = centres.device
-    Q = q.shape[0]
-    if index.dsub != 2 or kf >= 1.0:
-        return np.tile(calibrate_radii(w, index, centres, kf)[None, :] * np.float32(scale), (Q, 1)).astype(np.float32)
     cent = torch.from_numpy(index.centroids).to(device)
     cb = torch.from_numpy(index.codebooks).to(device)
-    G = 100
+    M = index.M
 
     def projections(x):
         lab = _nearest(x, cent)
-        return (x - cent[lab]).reshape(-1, index.M, 2)
+        return (x - cent[lab]).reshape(-1, M, 2)
 
-    base = base_chunk(w, centres, 0, min(BASE_CHUNK, w.N, 200_000))
+    base = base_chunk(w, centres, 0, min(BASE_CHUNK, w.N, n_base))
     pb = projections(base)                                     # [n][M][2]
     lo = pb.amin(0)                                            # [M][2]
     span = (pb.amax(0) - lo).clamp(min=1e-12)
+    cpu = (float(G) / span).to(torch.float32)                  # cells per unit length
 
-    def cells(p):
-        ij = ((p - lo) / span * G).floor().clamp(0, G - 1).to(torch.int64)
+    def cells(p):   # the library's rule: floor((x - lo) * cells_per_unit), clamped to the map
+        ij = ((p - lo) * cpu).floor().clamp(0, G - 1).to(torch.int64)
         return ij[..., 0] * G + ij[..., 1]                     # [n][M]
 
-    m_idx = torch.arange(index.M, device=device)[None, :]
-    dens = torch.zeros(index.M * G * G, device=device)
-    dens.index_add_(0, (m_idx * G * G + cells(pb)).reshape(-1), torch.ones(pb.shape[0] * index.M, device=device))
-    dens = dens.reshape(index.M, G * G) / (span[:, 0] * span[:, 1] / (G * G))[:, None]
-
-    def feature(p):
-        x = torch.log1p(torch.gather(dens, 1, cells(p).T).T)   # [n][M]
-        return torch.stack([torch.ones_like(x), x, x * x], -1)  # [n][M][3]
+    m_idx = torch.arange(M, device=device)[None, :]
+    count = torch.zeros(M * G * G, device=device, dtype=torch.float64)
+    count.index_add_(0, (m_idx * G * G + cells(pb)).reshape(-1),
+                     torch.ones(pb.shape[0] * M, device=device, dtype=torch.float64))
+    area = 1.0 / (cpu[:, 0].double() * cpu[:, 1].double())
+    fmap = torch.log1p(count.reshape(M, G * G) / area[:, None]).to(torch.float32)
 
     pc = projections(queries(w, centres, n_cal, sub=3))
+    x = torch.gather(fmap, 1, cells(pc).T).T                   # [n][M]
+    X = torch.stack([torch.ones_like(x), x, x * x], -1).transpose(0, 1)   # [M][n][3]
     d2 = ((pc[:, :, None, :] - cb[None]) ** 2).sum(-1)         # [n][M][256]
-    kth = max(1, int(math.ceil(kf * KSUB)))
+    kth = max(1, min(KSUB, int(math.ceil(kf * KSUB))))
     target = d2.kthvalue(kth, dim=2).values.sqrt()             # [n][M]
-    X = feature(pc).transpose(0, 1)                            # [M][n][3]
-    coef = torch.linalg.lstsq(X.cpu().double(), target.T.cpu().double()[:, :, None]).solution[:, :, 0]  # [M][3]
-    pred = (feature(projections(q)).cpu().double() * coef[None]).sum(-1)
-    fallback = target.mean(0).cpu().double()[None, :]
-    pred = torch.where(torch.isfinite(pred) & (pred > 0), pred, fallback)
-    return np.ascontiguousarray((pred * scale).to(torch.float32).numpy())
+    coef = torch.linalg.lstsq(X.cpu().double(), target.T.cpu().double()[:, :, None]).solution[:, :, 0]
+    out = {"lo": lo.cpu().numpy().astype(np.float32), "cells_per_unit": cpu.cpu().numpy(),
+           "map": np.ascontiguousarray(fmap.reshape(M, G, G).cpu().numpy()),
+           "coef": np.ascontiguousarray(coef.to(torch.float32).numpy()),
+           "fallback": target.mean(0).cpu().numpy().astype(np.float32)}
+    if with_projections:
+        out["projections"] = pb.cpu().numpy()
+    return out
 
 
 def exact_knn(w: Workload, centres: torch.Tensor, q: torch.Tensor, k: int, metric: int = 0) -> np.ndarray:

@@ -32,3 +32,12 @@ def brute_knn_int(base, queries, k):
         o = np.lexsort((np.arange(base.shape[0]), d[q]))[:k]
         ids[q], dist[q] = o, d[q][o]
     return ids, dist
+
+
+def per_query_radii(w, idx, centres, q, keep=0.25, seed=11):
+    """A radii[Q][M] input for the per-query-radius tests: the calibrated shared radii,
+    each query's row stretched by seeded factors in [0.7, 1.3] (different per query and
+    subspace, so that a row or column mix-up shows)."""
+    shared = wl.calibrate_radii(w, idx, centres, keep)
+    f = np.random.default_rng(seed).uniform(0.7, 1.3, size=(q.shape[0], idx.M)).astype(np.float32)
+    return np.ascontiguousarray(shared[None, :] * f)

@@ -74,3 +74,6 @@ def test_null_handles_are_rejected():
     assert lib.ivfpq_index_get_info(None, None) == binding.ERR_INVALID_ARGUMENT
     assert lib.ivfpq_set_option(b"no_such_option", 1) == binding.ERR_INVALID_ARGUMENT
     lib.ivfpq_index_destroy(None)
+    assert lib.ivfpq_radius_model_create(None, None, None) == binding.ERR_INVALID_ARGUMENT
+    assert lib.ivfpq_query_radii(None, None, None, 1, None, 1, ctypes.c_float(1.0), None, None) == binding.ERR_INVALID_ARGUMENT
+    lib.ivfpq_radius_model_destroy(None)

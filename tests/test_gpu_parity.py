@@ -15,6 +15,8 @@ import torch
 import oracle
 from paper_2312_01712_amd import workloads as wl
 
+from helpers import per_query_radii  # noqa: E402
+
 pytestmark = pytest.mark.gpu
 
 REL_TOL = 1e-4
@@ -269,7 +271,7 @@ def test_hit_count_scoring_and_per_query_radii(lib, name):
     idx, centres = wl.train_index(w)
     q = wl.queries(w, centres).numpy()
     shared = wl.calibrate_radii(w, idx, centres, 0.25)
-    rq = wl.dynamic_radii(w, idx, centres, torch.from_numpy(q), 0.25)
+    rq = per_query_radii(w, idx, centres, q, 0.25)
     gi = b.IvfPqIndex.from_index(idx)
     dq = _cuda(q)
     o_pid, _ = oracle.coarse(q, idx.centroids, w.nprobe)
@@ -297,6 +299,92 @@ def test_hit_count_scoring_and_per_query_radii(lib, name):
     gi.close()
 
 
+def _model_arrays(md):
+    return md["lo"], md["cells_per_unit"], md["map"], md["coef"], md["fallback"]
+
+
+@pytest.mark.parametrize("name", ["T_sift", "T_deep", "T_tti", "C2"])
+def test_dynamic_thresholds(lib, name):
+    """ivfpq_query_radii against the oracle, bit for bit: fitted model (100 x 100 maps),
+    several scales, queries far outside the map, and the search that consumes the radii."""
+    b = _binding()
+    w = wl.WORKLOADS[name]
+    big = name == "C2"
+    idx, centres = wl.train_index(w, device="cuda" if big else "cpu")
+    q = wl.queries(w, centres).cpu().numpy()
+    md = wl.fit_radius_model(w, idx, centres, 0.25)
+    gi = b.IvfPqIndex.from_index(idx)
+    rm = b.RadiusModel(gi, *_model_arrays(md))
+    # a third of the queries pushed away from the data: projections leave the map on every side
+    rng = np.random.default_rng(9)
+    q = q.copy()
+    far = rng.choice(q.shape[0], q.shape[0] // 3, replace=False)
+    q[far] += rng.normal(0, 4 * np.abs(q).mean(), size=(far.size, q.shape[1])).astype(np.float32)
+    dq = _cuda(q)
+    pid, _ = gi.coarse(dq, w.nprobe)
+    o_pid, _ = oracle.coarse(q, idx.centroids, 1)
+    assert np.array_equal(pid.cpu().numpy()[:, 0], o_pid[:, 0])
+    for scale in (1.0, 0.5, 1.7):
+        say(f"[{name}] query radii, scale {scale}")
+        r = gi.query_radii(rm, dq, pid, scale)
+        o_r = oracle.query_radii(q, idx.centroids, o_pid[:, 0], *_model_arrays(md), scale)
+        assert_same_float(r.cpu().numpy(), o_r, f"{name} radii scale {scale}")
+    assert np.all(o_r > 0) and len(np.unique(o_r)) > 10
+    # the radii feed the search: same result as the oracle's search with the oracle's radii
+    r = gi.query_radii(rm, dq, pid, 1.0)
+    o_r = oracle.query_radii(q, idx.centroids, o_pid[:, 0], *_model_arrays(md), 1.0)
+    sample = np.arange(q.shape[0]) if not big else rng.choice(q.shape[0], 32, replace=False)
+    ids, dist = gi.search(dq, w.nprobe, w.k, None, query_radii=r)
+    o_ids, o_dist = oracle.search(q[sample], idx, w.nprobe, w.k, o_r[sample], threads=8)
+    assert np.array_equal(ids.cpu().numpy()[sample], o_ids)
+    assert_same_float(dist.cpu().numpy()[sample], o_dist, f"{name} search with dynamic radii")
+    rm.close()
+    gi.close()
+
+
+def test_dynamic_threshold_model_edge_cases(lib):
+    """Hand-made models: 1 x 1 grid, degree 0 and degree 8, polynomial values that are
+    negative, zero, infinite (fallback), a first probe id outside the index (fallback),
+    Q = 0, and the argument errors."""
+    b = _binding()
+    rng = np.random.default_rng(3)
+    M, nlist, N, Q = 5, 7, 300, 257
+    cent = rng.normal(size=(nlist, 2 * M)).astype(np.float32)
+    cb = rng.normal(size=(M, 256, 2)).astype(np.float32)
+    offs = np.linspace(0, N, nlist + 1).astype(np.int64)
+    codes = rng.integers(0, 256, size=(N, M)).astype(np.uint8)
+    gi = b.IvfPqIndex(cent, cb, offs, codes)
+    q = rng.normal(size=(Q, 2 * M)).astype(np.float32) * 2
+    near = rng.integers(0, nlist, size=(Q, 3)).astype(np.int32)
+    for G, degree in ((1, 0), (4, 8), (37, 3), (1024, 1)):
+        lo = rng.uniform(-3, -1, size=(M, 2)).astype(np.float32)
+        cpu = (G / rng.uniform(2, 6, size=(M, 2))).astype(np.float32)
+        fmap = rng.uniform(0, 2, size=(M, G, G)).astype(np.float32)
+        coef = rng.normal(size=(M, degree + 1)).astype(np.float32)   # about half the values come out negative
+        if degree == 3:
+            coef[0, 3] = 3e38                                         # overflows to inf: fallback
+            coef[1, :] = 0.0                                          # exactly zero: fallback
+        fb = rng.uniform(0.5, 1.5, size=M).astype(np.float32)
+        rm = b.RadiusModel(gi, lo, cpu, fmap, coef, fb)
+        r = gi.query_radii(rm, _cuda(q), _cuda(near), 0.75)
+        o_r = oracle.query_radii(q, cent, near[:, 0], lo, cpu, fmap, coef, fb, 0.75)
+        assert_same_float(r.cpu().numpy(), o_r, f"grid {G} degree {degree}")
+        if degree == 3:
+            assert np.array_equal(o_r[:, 1], np.full(Q, fb[1] * np.float32(0.75)))
+        # a first probe id outside [0, nlist): that query gets the fallback
+        bad = near.copy()
+        bad[5, 0], bad[6, 0] = -1, nlist
+        r = gi.query_radii(rm, _cuda(q), _cuda(bad), 2.0).cpu().numpy()
+        assert np.array_equal(r[5], fb * np.float32(2.0)) and np.array_equal(r[6], fb * np.float32(2.0))
+        assert gi.query_radii(rm, _cuda(q[:0]), _cuda(near[:0]), 1.0).shape == (0, M)
+        for scale in (-1.0, float("nan"), float("inf")):
+            with pytest.raises(b.IvfpqError) as e:
+                gi.query_radii(rm, _cuda(q), _cuda(near), scale)
+            assert e.value.status == b.ERR_INVALID_ARGUMENT
+        rm.close()
+    gi.close()
+
+
 def test_hit_count_scoring_1m(lib):
     """Hit-count scoring on the 1M x 128 configuration (specialised kernel, ties en masse)."""
     b = _binding()
@@ -304,7 +392,7 @@ def test_hit_count_scoring_1m(lib):
     idx, centres = wl.train_index(w, device="cuda")
     q = wl.queries(w, centres).cpu().numpy()
     radii = wl.calibrate_radii(w, idx, centres, 0.25)
-    rq = wl.dynamic_radii(w, idx, centres, torch.from_numpy(q).cuda(), 0.25)
+    rq = per_query_radii(w, idx, centres, q, 0.25)
     gi = b.IvfPqIndex.from_index(idx)
     sample = np.random.default_rng(2).choice(w.Q, 32, replace=False)
     for mode, r, d_rq in ((1, radii, None), (2, radii, None), (0, rq, _cuda(rq)), (2, rq, _cuda(rq))):

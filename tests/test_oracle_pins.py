@@ -24,7 +24,7 @@ from paper_2312_01712_amd import workloads as wl
 # helpers (independent of the oracle)
 # ----------------------------------------------------------------------------
 
-from helpers import identity_index, brute_knn_int  # noqa: E402
+from helpers import identity_index, brute_knn_int, per_query_radii  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -323,7 +323,7 @@ def test_hit_count_scores_match_their_definition(tiny):
 def test_per_query_radii(tiny):
     """radii[Q][M]: each query is searched as if its own row were the shared radii."""
     for name, (w, idx, centres, q) in tiny.items():
-        rq = wl.dynamic_radii(w, idx, centres, torch.from_numpy(q), 0.25)
+        rq = per_query_radii(w, idx, centres, q, 0.25)
         assert rq.shape == (q.shape[0], idx.M) and np.all(rq > 0)
         for mode in (0, 1, 2):
             ids, dist = oracle.search(q, idx, w.nprobe, w.k, rq, mode=mode)
@@ -646,3 +646,22 @@ def test_query_radii_special_polynomials(tiny):
     other = (near + 1) % idx.nlist
     r3 = oracle.query_radii(q, idx.centroids, other, lo, cpu, cellno, ident, fb, 1.0)
     assert not np.array_equal(r3, r1)
+
+
+def test_fitted_radius_model_map_is_the_density_map(tiny):
+    """The offline fit (input recipe) stores log(1 + density): its map must be the
+    oracle's density map of the same projections, and its radii must be usable."""
+    w, idx, centres, q = tiny["T_sift"]
+    md = wl.fit_radius_model(w, idx, centres, 0.25, G=20, with_projections=True)
+    dens = oracle.density_map(md["projections"], md["lo"], md["cells_per_unit"], 20)
+    assert dens.sum() > 0
+    np.testing.assert_allclose(md["map"], np.log1p(dens), rtol=1e-6, atol=1e-7)
+    near, _ = oracle.coarse(q, idx.centroids, 1)
+    r = oracle.query_radii(q, idx.centroids, near[:, 0], md["lo"], md["cells_per_unit"], md["map"],
+                           md["coef"], md["fallback"], 1.0)
+    assert np.all(r > 0) and np.all(np.isfinite(r))
+    # the radii keep roughly the fraction of entries they were fitted for
+    probes, _ = oracle.coarse(q, idx.centroids, 1)
+    _, mask = oracle.build_lut(q, idx.centroids, idx.codebooks, probes, r)
+    bits = np.unpackbits(mask.view(np.uint8)).sum() / (q.shape[0] * idx.M * 256.0)
+    assert 0.1 < bits < 0.5, bits
