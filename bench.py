@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--dynamic-radii", action="store_true",
                     help="per-query radii: density map + polynomial fitted offline, looked up by ivfpq_query_radii in every step")
     ap.add_argument("--radius-scale", type=float, default=1.0, help="user scale on the dynamic radii")
+    ap.add_argument("--radius-target", choices=["top", "keep"], default="top",
+                    help="what the offline polynomial is fitted to: the radius that contains the entries of the true "
+                         "top-100 neighbours (the paper's), or the radius that keeps --keep of the entries")
     ap.add_argument("--scan-waves", type=int, default=0)
     ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 default (first chunk ahead while pruning), 1 whole blocks, 2 / 3 always first half / first chunk")
     ap.add_argument("--lds-pad", type=int, default=0, help="measurement only: extra LDS bytes per scan workgroup")
@@ -109,7 +112,7 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     d_rq = rmodel = None
     if args.dynamic_radii:   # offline: density maps + polynomial (an input); online: ivfpq_query_radii in every step
-        model = wl.fit_radius_model(w, idx, centres, args.keep)
+        model = wl.fit_radius_model(w, idx, centres, args.keep, target=args.radius_target)
         model_arrays = (model["lo"], model["cells_per_unit"], model["map"], model["coef"], model["fallback"])
         rmodel = binding.RadiusModel(gi, *model_arrays)
         d_rq = torch.empty((Q, w.M), dtype=torch.float32, device="cuda")
@@ -176,7 +179,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} D={w.D} nlist={w.nlist} M={w.M} Q={Q} nprobe={nprobe} k={k}",
                    "family": w.family, "similarity": args.metric, "keep_fraction": args.keep, "score_mode": args.score_mode,
-                   "radii": "per-query (density map)" if args.dynamic_radii else "per-subspace", "recall_at_k": recall, "recall_truth_k": min(k, 100), "r1_at_k": r1,
+                   "radii": f"per-query (density map, fitted to {args.radius_target}, scale {args.radius_scale})" if args.dynamic_radii else "per-subspace", "recall_at_k": recall, "recall_truth_k": min(k, 100), "r1_at_k": r1,
                    "coarse_ms": float(np.mean(coarse_ms)), "scan_ms": scan_avg_ms,
                    "coarse_exact_fallbacks_per_step": binding.coarse_fallbacks() / max(1, args.steps + 1)},
         "roofline": {"bound": "hbm", "kernel": "scan_kernel (table + ADC scan + top-k), timed with probe_bound_kernel (list-level bounds, 8 % of it on C2)", "achieved": achieved,

@@ -373,15 +373,20 @@ def calibrate_radii(w: Workload, index: Index, centres: torch.Tensor, keep_frac:
 
 
 def fit_radius_model(w: Workload, index: Index, centres: torch.Tensor, keep_frac: Optional[float] = None,
-                     n_cal: int = 512, G: int = 100, n_base: int = 200_000, with_projections: bool = False) -> dict:
+                     n_cal: int = 512, G: int = 100, n_base: int = 200_000, with_projections: bool = False,
+                     target: str = "keep", top: int = 100) -> dict:
     """Offline half of the paper's dynamic threshold (Sec. 4.1, "Determining Proper
     Threshold"): per subspace a G x G density map of the residual projections of
     search points (count / cell area; the paper's G is 100) and a polynomial from the
     density at a projection to the radius it needs.  Here the map stores log(1 +
     density), the polynomial is a quadratic in it fitted by least squares on `n_cal`
-    calibration queries, and the radius a projection "needs" is the one that keeps
-    `keep_frac` of the 256 entries (the paper regresses the radius that contains the
-    top-100 neighbours, which needs its datasets).  Two-dimensional subspaces only,
+    calibration queries.  The radius a projection "needs" (the regression target) is
+    either target="top": the paper's -- the radius that contains the entries of the
+    query's true `top` nearest neighbours (exact search over the regenerated base
+    vectors; each neighbour's entry is measured from the query's residual w.r.t. that
+    neighbour's own list) -- or target="keep": the radius that keeps `keep_frac` of
+    the 256 entries around the residual w.r.t. the nearest list (no exact search
+    needed; for the sizes where one is too slow).  Two-dimensional subspaces only,
     like the paper's.  Returns host arrays in the layout of the library's radius
     model: lo [M][2], cells_per_unit [M][2], map [M][G][G], coef [M][3] (lowest power
     first), fallback [M].  Like the k-means training this is an *input* of the search
@@ -415,17 +420,31 @@ def fit_radius_model(w: Workload, index: Index, centres: torch.Tensor, keep_frac
     area = 1.0 / (cpu[:, 0].double() * cpu[:, 1].double())
     fmap = torch.log1p(count.reshape(M, G * G) / area[:, None]).to(torch.float32)
 
-    pc = projections(queries(w, centres, n_cal, sub=3))
+    qc = queries(w, centres, n_cal, sub=3)
+    pc = projections(qc)
     x = torch.gather(fmap, 1, cells(pc).T).T                   # [n][M]
     X = torch.stack([torch.ones_like(x), x, x * x], -1).transpose(0, 1)   # [M][n][3]
-    d2 = ((pc[:, :, None, :] - cb[None]) ** 2).sum(-1)         # [n][M][256]
-    kth = max(1, min(KSUB, int(math.ceil(kf * KSUB))))
-    target = d2.kthvalue(kth, dim=2).values.sqrt()             # [n][M]
-    coef = torch.linalg.lstsq(X.cpu().double(), target.T.cpu().double()[:, :, None]).solution[:, :, 0]
+    if target == "top":
+        truth = exact_knn(w, centres, qc, min(top, w.N))       # ids [n][top]
+        row_of_id = np.empty(index.N, dtype=np.int64)
+        row_of_id[index.ids] = np.arange(index.N)
+        rows = row_of_id[truth]
+        lists = np.searchsorted(index.list_offsets, rows, side="right") - 1
+        codes = torch.from_numpy(index.codes[rows].astype(np.int64)).to(device)        # [n][top][M]
+        ent = cb[torch.arange(M, device=device)[None, None, :], codes]                  # [n][top][M][2]
+        res = (qc[:, None, :] - cent[torch.from_numpy(lists).to(device)]).reshape(qc.shape[0], -1, M, 2)
+        need = ((res - ent) ** 2).sum(-1).amax(1).sqrt()       # [n][M]: contains every neighbour's entry
+    elif target == "keep":
+        d2 = ((pc[:, :, None, :] - cb[None]) ** 2).sum(-1)     # [n][M][256]
+        kth = max(1, min(KSUB, int(math.ceil(kf * KSUB))))
+        need = d2.kthvalue(kth, dim=2).values.sqrt()           # [n][M]
+    else:
+        raise ValueError("target must be 'top' or 'keep'")
+    coef = torch.linalg.lstsq(X.cpu().double(), need.T.cpu().double()[:, :, None]).solution[:, :, 0]
     out = {"lo": lo.cpu().numpy().astype(np.float32), "cells_per_unit": cpu.cpu().numpy(),
            "map": np.ascontiguousarray(fmap.reshape(M, G, G).cpu().numpy()),
            "coef": np.ascontiguousarray(coef.to(torch.float32).numpy()),
-           "fallback": target.mean(0).cpu().numpy().astype(np.float32)}
+           "fallback": need.mean(0).cpu().numpy().astype(np.float32)}
     if with_projections:
         out["projections"] = pb.cpu().numpy()
     return out
