@@ -595,6 +595,22 @@ def test_pruning_switches_do_not_change_results(lib, shape):
             b.set_option("scan_ablate", 0)
             b.set_option("scan_loads", 0)
             gi.close()
+    # the inner-product kernel has its own early exit, list skip and list-level bound
+    radii = _ip_radii(idx, q, 0.25)
+    o_ids, o_dist = oracle.search(q, idx, nprobe, w.k, radii, threads=8, metric=1)
+    gi = b.IvfPqIndex.from_index(idx, metric=b.METRIC_IP)
+    try:
+        for ablate in (0, 8, 64):
+            for loads in (0, 1):
+                b.set_option("scan_ablate", ablate)
+                b.set_option("scan_loads", loads)
+                ids, dist = gi.search(_cuda(q), nprobe, w.k, radii)
+                assert np.array_equal(ids.cpu().numpy(), o_ids), ("ip", ablate, loads)
+                assert_same_float(dist.cpu().numpy(), o_dist, f"ip ablate {ablate} loads {loads}")
+    finally:
+        b.set_option("scan_ablate", 0)
+        b.set_option("scan_loads", 0)
+        gi.close()
 
 
 def test_batch_sizes_and_probe_groups(lib):
