@@ -1621,7 +1621,9 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
   int nw = g_scan_waves;
   // One workgroup per CU once the table passes 72 KiB: the specialised kernels then run 8
   // wavefronts with twice the registers, the run-time-M kernel (few registers) runs 16.
-  if (nw == 0) nw = (MT == 0 && a.M > 72) ? 16 : 8;
+  // Tables of at most 32 KiB leave room for four workgroups per CU: 4 wavefronts each, so that
+  // a workgroup's serial phases (table, barriers, final merge) overlap with three others'.
+  if (nw == 0) nw = (MT == 0 && a.M > 72) ? 16 : (a.M <= 32 ? 4 : 8);
   if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
   if (nw >= 8) return launch_scan_t<MT, DSUB, 8>(a, r2, grid, dump, s);
   return launch_scan_t<MT, DSUB, 4>(a, r2, grid, dump, s);
