@@ -121,12 +121,33 @@ __device__ inline float unorderable(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
-// Reference-order distance (see header).
+// Reference-order distance (see header).  The chain over D is sequential by definition; what
+// can overlap is the fetch of the centroid row: eight 16-byte loads are issued before the
+// chain consumes them (one load per step left the chain waiting a memory round trip per 4
+// dimensions).  Same operations in the same order either way.
+constexpr int ROW_BATCH = 8;
+
 __device__ inline float exact_dist(const float *sq, const float *__restrict__ cen, int D) {
   float acc = 0.0f;
   int i = 0;
   if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(cen) & 15) == 0) {
-    for (; i < D; i += 4) {  // same order of operations, 16-byte loads
+    for (; i + 4 * ROW_BATCH <= D; i += 4 * ROW_BATCH) {
+      float4 c[ROW_BATCH];
+#pragma unroll
+      for (int b = 0; b < ROW_BATCH; ++b) c[b] = *reinterpret_cast<const float4 *>(cen + i + 4 * b);
+#pragma unroll
+      for (int b = 0; b < ROW_BATCH; ++b) {
+        float t = sq[i + 4 * b] - c[b].x;
+        acc = fmaf(t, t, acc);
+        t = sq[i + 4 * b + 1] - c[b].y;
+        acc = fmaf(t, t, acc);
+        t = sq[i + 4 * b + 2] - c[b].z;
+        acc = fmaf(t, t, acc);
+        t = sq[i + 4 * b + 3] - c[b].w;
+        acc = fmaf(t, t, acc);
+      }
+    }
+    for (; i < D; i += 4) {
       const float4 c4 = *reinterpret_cast<const float4 *>(cen + i);
       float t = sq[i] - c4.x;
       acc = fmaf(t, t, acc);
@@ -150,6 +171,18 @@ __device__ inline float exact_neg_ip(const float *sq, const float *__restrict__ 
   float acc = 0.0f;
   int i = 0;
   if ((D & 3) == 0 && (reinterpret_cast<uintptr_t>(cen) & 15) == 0) {
+    for (; i + 4 * ROW_BATCH <= D; i += 4 * ROW_BATCH) {
+      float4 c[ROW_BATCH];
+#pragma unroll
+      for (int b = 0; b < ROW_BATCH; ++b) c[b] = *reinterpret_cast<const float4 *>(cen + i + 4 * b);
+#pragma unroll
+      for (int b = 0; b < ROW_BATCH; ++b) {
+        acc = fmaf(sq[i + 4 * b], c[b].x, acc);
+        acc = fmaf(sq[i + 4 * b + 1], c[b].y, acc);
+        acc = fmaf(sq[i + 4 * b + 2], c[b].z, acc);
+        acc = fmaf(sq[i + 4 * b + 3], c[b].w, acc);
+      }
+    }
     for (; i < D; i += 4) {
       const float4 c4 = *reinterpret_cast<const float4 *>(cen + i);
       acc = fmaf(sq[i], c4.x, acc);
@@ -199,7 +232,7 @@ __device__ inline unsigned long long row_key(const float *row, int c) {
 // of the kprop-th key when a level is too coarse; at width 1 a bin holds one key, so
 // the loop ends).  The selected lists get their distances in the reference order,
 // are sorted by (distance, list id), and the first nprobe are emitted.
-__global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(6))) void coarse_select_kernel(
+__global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4))) void coarse_select_kernel(
     float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int nlist,
     int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm, int ip,
     int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
