@@ -1714,6 +1714,10 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   const bool ip = ix->metric == IVFPQ_METRIC_IP;
   if (d_probe_lb && !dump && !ip && !(g_scan_ablate & 64)) {
     const int64_t total = Q * nprobe;
+    if ((total + 3) / 4 > 0x7FFFFFFFll) {
+      set_error("scan: %lld (query, probe) pairs exceed the grid limit of the bound kernel", (long long)total);
+      return IVFPQ_ERR_UNSUPPORTED;
+    }
     hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, d_queries,
                        d_probe_ids, ix->d_centroids, ix->d_box, ix->D, M, ds, ix->nlist, total, nprobe, r2,
                        d_query_radii, mode, d_probe_lb);
