@@ -684,7 +684,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
   constexpr int DS4 = VEC ? DSUB : 1;
   constexpr int WPE = scan_wpe(MT, NW);
-  constexpr int RES_REGS = res_regs(WPE), RES_MAX_TOTAL = res_max_total(WPE);
+  // (a dsub = 4 row takes 16 registers and its table arithmetic more temporaries: with resident
+  // rows the kernel spilled up to 198 registers, so those rows are all streamed)
+  constexpr int RES_REGS = DS4 == 4 ? 0 : res_regs(WPE), RES_MAX_TOTAL = res_max_total(WPE);
   constexpr int RES_BUDGET = RES_REGS < RES_MAX_TOTAL - 2 * (MPT / 4) ? RES_REGS : RES_MAX_TOTAL - 2 * (MPT / 4);
   constexpr int RES_CAP = (RES_BUDGET > 0 ? RES_BUDGET : 0) / (4 * DS4);
   constexpr int RES = !VEC ? 0 : (ITER < RES_CAP ? ITER : RES_CAP);
