@@ -79,34 +79,67 @@ __device__ inline bool kless(const Key &a, const Key &b) {
   return a.d < b.d || (a.d == b.d && a.id < b.id);
 }
 
-__device__ inline Key shfl_xor_key(const Key &a, int m) {
+// Cross-lane helpers on the data-parallel-primitive path (no LDS traffic).  XOR1 / XOR2 swap
+// lanes within a quad, QUAD_MIRROR reverses a quad, HALF_MIRROR reverses each group of 8
+// lanes, ROR4 / ROR8 rotate each row of 16 lanes by 4 / 8.
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_QUAD_MIRROR = 0x1B, DPP_HALF_MIRROR = 0x141, DPP_ROR4 = 0x124,
+              DPP_ROR8 = 0x128;
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(v)));
+}
+
+// The value of lane ^ J.  J = 1, 2, 8 are one register-to-register move (8: a rotation by half
+// a row of 16), J = 4 is two (reverse the group of 8, then reverse the quad: 7 ^ 3 = 4); only
+// J = 16 and 32 go through the LDS crossbar.  A 64-key bitonic sort has 18 of its 21 stages
+// at J <= 8.
+template <int J>
+__device__ __forceinline__ uint32_t xor_u32(uint32_t v) {
+  if constexpr (J == 1) return dpp_u32<DPP_XOR1>(v);
+  else if constexpr (J == 2) return dpp_u32<DPP_XOR2>(v);
+  else if constexpr (J == 4) return dpp_u32<DPP_QUAD_MIRROR>(dpp_u32<DPP_HALF_MIRROR>(v));
+  else if constexpr (J == 8) return dpp_u32<DPP_ROR8>(v);
+  else return (uint32_t)__shfl_xor((int)v, J);
+}
+
+template <int J>
+__device__ __forceinline__ Key xor_key(const Key &a) {
   Key o;
-  o.d = (uint32_t)__shfl_xor((int)a.d, m);
-  const int lo = __shfl_xor((int)(uint32_t)a.id, m);
-  const int hi = __shfl_xor((int)(uint32_t)((uint64_t)a.id >> 32), m);
-  o.id = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+  o.d = xor_u32<J>(a.d);
+  const uint32_t lo = xor_u32<J>((uint32_t)a.id);
+  const uint32_t hi = xor_u32<J>((uint32_t)((uint64_t)a.id >> 32));
+  o.id = (int64_t)(((uint64_t)hi << 32) | lo);
   return o;
 }
 
-// compare-exchange with lane ^ j; this lane keeps the smaller key iff keep_small
-__device__ inline void cx_lane(Key &a, int j, bool keep_small) {
-  const Key o = shfl_xor_key(a, j);
+// compare-exchange with lane ^ J; this lane keeps the smaller key iff keep_small
+template <int J>
+__device__ __forceinline__ void cx_lane(Key &a, bool keep_small) {
+  const Key o = xor_key<J>(a);
   const bool take = keep_small ? kless(o, a) : kless(a, o);
   if (take) a = o;
 }
 
-// Sort 64 keys (one per lane) in DESCENDING lane order.
-__device__ inline void wave_sort_desc(Key &a, int lane) {
-#pragma unroll
-  for (int k2 = 2; k2 <= 64; k2 <<= 1) {
-    const bool desc_block = (lane & k2) == 0 || k2 == 64;  // block sorted descending
-#pragma unroll
-    for (int j = k2 >> 1; j > 0; j >>= 1) {
-      const bool lower = (lane & j) == 0;
-      cx_lane(a, j, desc_block ? !lower : lower);
-    }
-  }
+// the stages J, J/2, ..., 1 of one bitonic level; desc: this lane's block sorts descending
+template <int J>
+__device__ __forceinline__ void cx_cascade(Key &a, int lane, bool desc) {
+  const bool lower = (lane & J) == 0;
+  cx_lane<J>(a, desc ? !lower : lower);
+  if constexpr (J > 1) cx_cascade<J / 2>(a, lane, desc);
 }
+
+template <int K2>
+__device__ __forceinline__ void sort_levels_desc(Key &a, int lane) {
+  cx_cascade<K2 / 2>(a, lane, (lane & K2) == 0 || K2 == 64);
+  if constexpr (K2 < 64) sort_levels_desc<K2 * 2>(a, lane);
+}
+
+// Sort 64 keys (one per lane) in DESCENDING lane order.
+__device__ inline void wave_sort_desc(Key &a, int lane) { sort_levels_desc<2>(a, lane); }
 
 // L0/L1 hold a sorted list of 128 keys (element i lives in lane i%64, register
 // i/64).  qd holds 64 keys sorted descending by lane.  Afterwards L0/L1 hold the
@@ -120,12 +153,8 @@ __device__ inline void wave_merge(Key &L0, Key &L1, const Key &qd, int lane) {
     L0 = L1;
     L1 = t;
   }
-#pragma unroll
-  for (int j = 32; j > 0; j >>= 1) {
-    const bool lower = (lane & j) == 0;
-    cx_lane(L0, j, lower);
-    cx_lane(L1, j, lower);
-  }
+  cx_cascade<32>(L0, lane, false);
+  cx_cascade<32>(L1, lane, false);
 }
 
 __device__ inline Key bcast_key(const Key &a, int src) {
@@ -135,19 +164,6 @@ __device__ inline Key bcast_key(const Key &a, int src) {
   const int hi = __shfl((int)(uint32_t)((uint64_t)a.id >> 32), src);
   o.id = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
   return o;
-}
-
-// Cross-lane helpers on the data-parallel-primitive path (no LDS traffic).  XOR1 / XOR2 swap
-// lanes within a quad, HALF_MIRROR reverses each group of 8 lanes, ROR4 / ROR8 rotate each
-// row of 16 lanes by 4 / 8.
-constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v) {
-  return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(v)));
 }
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
