@@ -1374,7 +1374,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // against the handful of roundings that separate this evaluation from the table's (the
 // residual is the same fp32 value q - c the table uses).  For the hit-count scorings the bound
 // of a subspace is the penalty that every such entry gets when the whole box lies outside the
-// (inner) sphere, decided with the same margin.  One wavefront per (query, probe).
+// (inner) sphere, decided with the same margin.  One wavefront per BOUND_PAIRS (query, probe)
+// pairs, lane = subspace.
+constexpr int BOUND_PAIRS = 4;  // (query, probe) pairs per wavefront: their loads are issued together
+
 __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
                                                           const int32_t *__restrict__ probe_ids,
                                                           const float *__restrict__ centroids,
@@ -1383,47 +1386,75 @@ __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restric
                                                           const float *__restrict__ query_radii, int mode,
                                                           float *__restrict__ out) {
   const int lane = threadIdx.x & 63;
-  const int64_t qp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (qp >= total) return;
-  const int64_t q = qp / nprobe;
-  const int32_t c = probe_ids[qp];
-  float lb = 0.0f;
-  if ((uint32_t)c < (uint32_t)nlist) {
-    const float *lbox = box + (int64_t)c * D * 2;  // this list's boxes: [M][2][dsub]
-    for (int m = lane; m < M; m += 64) {
-      float best = 0.0f;
-      if (dsub == 2) {  // a box is one 16-byte load: (low x, low y, high x, high y)
-        const float2 qv = *reinterpret_cast<const float2 *>(queries + q * D + 2 * m);
-        const float2 cv = *reinterpret_cast<const float2 *>(centroids + (int64_t)c * D + 2 * m);
-        const float x0 = qv.x - cv.x, x1 = qv.y - cv.y;
-        const float4 v = reinterpret_cast<const float4 *>(lbox)[m];
-        const float t0 = fmaxf(fmaxf(v.x - x0, x0 - v.z), 0.0f);
-        const float t1 = fmaxf(fmaxf(v.y - x1, x1 - v.w), 0.0f);
-        best = fmaf(t1, t1, t0 * t0);
-      } else {
-        const float *bx = lbox + (int64_t)m * 2 * dsub;
-        for (int j = 0; j < dsub; ++j) {
-          const int i = m * dsub + j;
-          const float x = queries[q * D + i] - centroids[(int64_t)c * D + i];
-          const float t = fmaxf(fmaxf(bx[j] - x, x - bx[dsub + j]), 0.0f);
-          best = fmaf(t, t, best);
-        }
+  const int64_t qp0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * BOUND_PAIRS;
+  if (qp0 >= total) return;
+  int64_t qs[BOUND_PAIRS];
+  int32_t cs[BOUND_PAIRS];
+  bool ok[BOUND_PAIRS];
+  float lb[BOUND_PAIRS];
+#pragma unroll
+  for (int i = 0; i < BOUND_PAIRS; ++i) {
+    const int64_t qp = qp0 + i < total ? qp0 + i : total - 1;  // a clamped pair is computed and not stored
+    qs[i] = qp / nprobe;
+    cs[i] = probe_ids[qp];
+    ok[i] = (uint32_t)cs[i] < (uint32_t)nlist;
+    if (!ok[i]) cs[i] = 0;
+    lb[i] = 0.0f;
+  }
+  for (int m = lane; m < M; m += 64) {
+    float best[BOUND_PAIRS];
+    if (dsub == 2) {  // a box is one 16-byte load: (low x, low y, high x, high y)
+      float2 qv[BOUND_PAIRS], cv[BOUND_PAIRS];
+      float4 v[BOUND_PAIRS];
+#pragma unroll
+      for (int i = 0; i < BOUND_PAIRS; ++i) {
+        qv[i] = *reinterpret_cast<const float2 *>(queries + qs[i] * D + 2 * m);
+        cv[i] = *reinterpret_cast<const float2 *>(centroids + (int64_t)cs[i] * D + 2 * m);
+        v[i] = reinterpret_cast<const float4 *>(box + (int64_t)cs[i] * D * 2)[m];
       }
+#pragma unroll
+      for (int i = 0; i < BOUND_PAIRS; ++i) {
+        const float x0 = qv[i].x - cv[i].x, x1 = qv[i].y - cv[i].y;
+        const float t0 = fmaxf(fmaxf(v[i].x - x0, x0 - v[i].z), 0.0f);
+        const float t1 = fmaxf(fmaxf(v[i].y - x1, x1 - v[i].w), 0.0f);
+        best[i] = fmaf(t1, t1, t0 * t0);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < BOUND_PAIRS; ++i) {
+        const float *bx = box + (int64_t)cs[i] * D * 2 + (int64_t)m * 2 * dsub;  // this list's boxes: [M][2][dsub]
+        float acc = 0.0f;
+        for (int j = 0; j < dsub; ++j) {
+          const int d = m * dsub + j;
+          const float x = queries[qs[i] * D + d] - centroids[(int64_t)cs[i] * D + d];
+          const float t = fmaxf(fmaxf(bx[j] - x, x - bx[dsub + j]), 0.0f);
+          acc = fmaf(t, t, acc);
+        }
+        best[i] = acc;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < BOUND_PAIRS; ++i) {
       float rm2 = r2.v[m];
       if (query_radii) {
-        const float r = query_radii[q * M + m];
+        const float r = query_radii[qs[i] * M + m];
         rm2 = r * r;
       }
       if (mode == 0) {
-        lb += fminf(best, rm2);
+        lb[i] += fminf(best[i], rm2);
       } else {  // 1 per subspace whose box is outside the sphere; mode 2: 2, and 1 if only outside the inner sphere
-        const float b = best * 0.999755859375f;
-        lb += b > rm2 ? (mode == 1 ? 1.0f : 2.0f) : ((mode == 2 && b > 0.25f * rm2) ? 1.0f : 0.0f);
+        const float b = best[i] * 0.999755859375f;
+        lb[i] += b > rm2 ? (mode == 1 ? 1.0f : 2.0f) : ((mode == 2 && b > 0.25f * rm2) ? 1.0f : 0.0f);
       }
     }
   }
-  for (int off = 32; off > 0; off >>= 1) lb += __shfl_xor(lb, off);
-  if (lane == 0) out[qp] = mode == 0 ? lb * 0.999755859375f : lb;  // the counts are exact
+#pragma unroll
+  for (int i = 0; i < BOUND_PAIRS; ++i) {
+    float v = lb[i];
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if (lane == 0 && qp0 + i < total)
+      out[qp0 + i] = !ok[i] ? 0.0f : (mode == 0 ? v * 0.999755859375f : v);  // the counts are exact
+  }
 }
 
 // Merge the probe groups' partial lists of a query (one wavefront per query).
@@ -1736,7 +1767,8 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
       set_error("scan: %lld (query, probe) pairs exceed the grid limit of the bound kernel", (long long)total);
       return IVFPQ_ERR_UNSUPPORTED;
     }
-    hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, d_queries,
+    const int64_t per_block = 4 * BOUND_PAIRS;
+    hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + per_block - 1) / per_block)), dim3(256), 0, s, d_queries,
                        d_probe_ids, ix->d_centroids, ix->d_box, ix->D, M, ds, ix->nlist, total, nprobe, r2,
                        d_query_radii, mode, d_probe_lb);
     a.probe_lb = d_probe_lb;
