@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for an
 # elementwise pass over 1 GiB: x2.000 and x1.000).  Commands and raw figures: profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", 0.25): (593323 + 27094) * 1024 * 2.000 + (448863 + 2500) * 1024 * 1.000,
+    ("C2", 0.25): (593718 + 12451) * 1024 * 2.000 + (449093 + 1250) * 1024 * 1.000,
     ("C5", 0.25): (6.63817e6 + 329406) * 1024 * 2.000 + (531216 + 5000) * 1024 * 1.000,
 }
 
