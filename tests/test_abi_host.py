@@ -77,3 +77,23 @@ def test_null_handles_are_rejected():
     assert lib.ivfpq_radius_model_create(None, None, None) == binding.ERR_INVALID_ARGUMENT
     assert lib.ivfpq_query_radii(None, None, None, 1, None, 1, ctypes.c_float(1.0), None, None) == binding.ERR_INVALID_ARGUMENT
     lib.ivfpq_radius_model_destroy(None)
+
+
+def test_header_is_plain_c():
+    """include/ivfpq.h must compile as C (no C++ constructs, no torch or HIP types)."""
+    import subprocess
+    import tempfile
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "use.c")
+        with open(src, "w") as f:
+            f.write('#include "ivfpq.h"\n'
+                    "int probe(const ivfpq_index *ix, const float *q, void *ws, size_t n) {\n"
+                    "  ivfpq_scoring sc = {IVFPQ_SCORE_DISTANCE, 0};\n"
+                    "  ivfpq_radius_model_desc md = {0};\n"
+                    "  (void)md;\n"
+                    "  return ivfpq_search_ex(ix, q, 1, 1, 1, 0, &sc, 0, 0, ws, n, 0);\n"
+                    "}\n")
+        r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I",
+                            os.path.join(ROOT, "include"), "-c", src, "-o", os.path.join(d, "use.o")],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr

@@ -382,7 +382,38 @@ def test_dynamic_threshold_model_edge_cases(lib):
                 gi.query_radii(rm, _cuda(q), _cuda(near), scale)
             assert e.value.status == b.ERR_INVALID_ARGUMENT
         rm.close()
+    # descriptions the library must refuse
+    lo = np.zeros((M, 2), np.float32)
+    cpu = np.ones((M, 2), np.float32)
+    fb = np.ones(M, np.float32)
+    good = dict(lo=lo, cells_per_unit=cpu, fmap=np.zeros((M, 3, 3), np.float32), coef=np.ones((M, 2), np.float32),
+                fallback=fb)
+    b.RadiusModel(gi, **good).close()
+    bad_cases = [
+        dict(good, cells_per_unit=np.zeros((M, 2), np.float32)),               # cell width infinite
+        dict(good, lo=np.full((M, 2), np.nan, np.float32)),
+        dict(good, fallback=-fb),
+        dict(good, coef=np.ones((M, 10), np.float32)),                          # degree 9
+        dict(good, fmap=np.zeros((M, 1025, 1025), np.float32)),                 # grid above the limit
+    ]
+    for kw in bad_cases:
+        with pytest.raises(b.IvfpqError) as e:
+            b.RadiusModel(gi, **kw)
+        assert e.value.status == b.ERR_INVALID_ARGUMENT
+    other_m = dict(lo=np.zeros((M + 1, 2), np.float32), cells_per_unit=np.ones((M + 1, 2), np.float32),
+                   fmap=np.zeros((M + 1, 3, 3), np.float32), coef=np.ones((M + 1, 2), np.float32),
+                   fallback=np.ones(M + 1, np.float32))
+    with pytest.raises(b.IvfpqError) as e:
+        b.RadiusModel(gi, **other_m)                                            # M differs from the index's
+    assert e.value.status == b.ERR_INVALID_ARGUMENT
     gi.close()
+    # an index whose subspaces are not two-dimensional has no density map
+    gi4 = b.IvfPqIndex(rng.normal(size=(nlist, 4 * M)).astype(np.float32),
+                       rng.normal(size=(M, 256, 4)).astype(np.float32), offs, codes)
+    with pytest.raises(b.IvfpqError) as e:
+        b.RadiusModel(gi4, **good)
+    assert e.value.status == b.ERR_UNSUPPORTED
+    gi4.close()
 
 
 def test_hit_count_scoring_1m(lib):
