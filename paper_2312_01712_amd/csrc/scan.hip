@@ -93,57 +93,61 @@ __device__ __forceinline__ float dpp_f32(float v) {
   return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(v)));
 }
 
-// The value of lane ^ J.  J = 1, 2, 8 are one register-to-register move (8: a rotation by half
-// a row of 16), J = 4 is two (reverse the group of 8, then reverse the quad: 7 ^ 3 = 4); only
-// J = 16 and 32 go through the LDS crossbar.  A 64-key bitonic sort has 18 of its 21 stages
-// at J <= 8.
-template <int J>
+// The value of lane ^ J.  With DPP, J = 1, 2, 8 are one register-to-register move (8: a
+// rotation by half a row of 16), J = 4 is two (reverse the group of 8, then reverse the quad:
+// 7 ^ 3 = 4) and only J = 16 and 32 go through the LDS crossbar; a 64-key bitonic sort has 18
+// of its 21 stages at J <= 8.  Measured: 2-3 % faster in the L2 kernels (C2, C3), 10 % slower in
+// the 16-wavefront inner-product kernel (C4: 11.3 -> 12.4 ms), which therefore keeps the
+// crossbar shuffles (DPP = false).
+template <int J, bool DPP>
 __device__ __forceinline__ uint32_t xor_u32(uint32_t v) {
-  if constexpr (J == 1) return dpp_u32<DPP_XOR1>(v);
-  else if constexpr (J == 2) return dpp_u32<DPP_XOR2>(v);
-  else if constexpr (J == 4) return dpp_u32<DPP_QUAD_MIRROR>(dpp_u32<DPP_HALF_MIRROR>(v));
-  else if constexpr (J == 8) return dpp_u32<DPP_ROR8>(v);
+  if constexpr (DPP && J == 1) return dpp_u32<DPP_XOR1>(v);
+  else if constexpr (DPP && J == 2) return dpp_u32<DPP_XOR2>(v);
+  else if constexpr (DPP && J == 4) return dpp_u32<DPP_QUAD_MIRROR>(dpp_u32<DPP_HALF_MIRROR>(v));
+  else if constexpr (DPP && J == 8) return dpp_u32<DPP_ROR8>(v);
   else return (uint32_t)__shfl_xor((int)v, J);
 }
 
-template <int J>
+template <int J, bool DPP>
 __device__ __forceinline__ Key xor_key(const Key &a) {
   Key o;
-  o.d = xor_u32<J>(a.d);
-  const uint32_t lo = xor_u32<J>((uint32_t)a.id);
-  const uint32_t hi = xor_u32<J>((uint32_t)((uint64_t)a.id >> 32));
+  o.d = xor_u32<J, DPP>(a.d);
+  const uint32_t lo = xor_u32<J, DPP>((uint32_t)a.id);
+  const uint32_t hi = xor_u32<J, DPP>((uint32_t)((uint64_t)a.id >> 32));
   o.id = (int64_t)(((uint64_t)hi << 32) | lo);
   return o;
 }
 
 // compare-exchange with lane ^ J; this lane keeps the smaller key iff keep_small
-template <int J>
+template <int J, bool DPP>
 __device__ __forceinline__ void cx_lane(Key &a, bool keep_small) {
-  const Key o = xor_key<J>(a);
+  const Key o = xor_key<J, DPP>(a);
   const bool take = keep_small ? kless(o, a) : kless(a, o);
   if (take) a = o;
 }
 
 // the stages J, J/2, ..., 1 of one bitonic level; desc: this lane's block sorts descending
-template <int J>
+template <int J, bool DPP>
 __device__ __forceinline__ void cx_cascade(Key &a, int lane, bool desc) {
   const bool lower = (lane & J) == 0;
-  cx_lane<J>(a, desc ? !lower : lower);
-  if constexpr (J > 1) cx_cascade<J / 2>(a, lane, desc);
+  cx_lane<J, DPP>(a, desc ? !lower : lower);
+  if constexpr (J > 1) cx_cascade<J / 2, DPP>(a, lane, desc);
 }
 
-template <int K2>
+template <int K2, bool DPP>
 __device__ __forceinline__ void sort_levels_desc(Key &a, int lane) {
-  cx_cascade<K2 / 2>(a, lane, (lane & K2) == 0 || K2 == 64);
-  if constexpr (K2 < 64) sort_levels_desc<K2 * 2>(a, lane);
+  cx_cascade<K2 / 2, DPP>(a, lane, (lane & K2) == 0 || K2 == 64);
+  if constexpr (K2 < 64) sort_levels_desc<K2 * 2, DPP>(a, lane);
 }
 
 // Sort 64 keys (one per lane) in DESCENDING lane order.
-__device__ inline void wave_sort_desc(Key &a, int lane) { sort_levels_desc<2>(a, lane); }
+template <bool DPP>
+__device__ inline void wave_sort_desc(Key &a, int lane) { sort_levels_desc<2, DPP>(a, lane); }
 
 // L0/L1 hold a sorted list of 128 keys (element i lives in lane i%64, register
 // i/64).  qd holds 64 keys sorted descending by lane.  Afterwards L0/L1 hold the
 // 128 smallest of the 192, sorted ascending.
+template <bool DPP>
 __device__ inline void wave_merge(Key &L0, Key &L1, const Key &qd, int lane) {
   // element 64+l against the l-th largest queued key: the 128 survivors form a
   // bitonic sequence
@@ -153,8 +157,8 @@ __device__ inline void wave_merge(Key &L0, Key &L1, const Key &qd, int lane) {
     L0 = L1;
     L1 = t;
   }
-  cx_cascade<32>(L0, lane, false);
-  cx_cascade<32>(L1, lane, false);
+  cx_cascade<32, DPP>(L0, lane, false);
+  cx_cascade<32, DPP>(L1, lane, false);
 }
 
 __device__ inline Key bcast_key(const Key &a, int src) {
@@ -472,13 +476,14 @@ struct SharedTau {
 //   (ii) the wavefronts see disjoint points, so if each of the NW wavefronts
 //        knows j = ceil(k/NW) keys no larger than x_w, at least k keys are no
 //        larger than max_w x_w.
+template <bool DPP>
 __device__ __forceinline__ void wave_flush(WaveTop &st, LDS uint32_t *qd, LDS int64_t *qid, int lane, int k,
                                   const SharedTau &sh) {
   Key q;
   q.d = lane < st.qcount ? qd[lane] : SENT_D;
   q.id = lane < st.qcount ? qid[lane] : SENT_ID;
-  wave_sort_desc(q, lane);
-  wave_merge(st.L0, st.L1, q, lane);
+  wave_sort_desc<DPP>(q, lane);
+  wave_merge<DPP>(st.L0, st.L1, q, lane);
   st.qcount = 0;
   const Key t0 = bcast_key(st.L0, (k - 1) & 63), t1 = bcast_key(st.L1, (k - 1) & 63);
   st.tau = (k - 1) < 64 ? t0 : t1;
@@ -516,7 +521,7 @@ __device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, 
   int n = __popcll(bal);
   if (n == 0) return;
   if (st.qcount + n > 64) {
-    wave_flush(st, qd, qid, lane, k, sh);
+    wave_flush<!SGN>(st, qd, qid, lane, k, sh);
     pass = pass && kless(c, st.tau);
     bal = __ballot(pass);
     n = __popcll(bal);
@@ -560,7 +565,7 @@ template <int NW, bool SGN = false>
 __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS int64_t *qid, int lane,
                                             int wave, const SharedTau &sh, LDS unsigned char *smem3,
                                             const ScanArgs &a, int64_t q, int split) {
-  if (st.qcount > 0) wave_flush(st, qd, qid, lane, a.k, sh);
+  if (st.qcount > 0) wave_flush<!SGN>(st, qd, qid, lane, a.k, sh);
   __syncthreads();  // tables no longer needed: their LDS becomes the staging area
   LDS uint32_t *stage_d = (LDS uint32_t *)smem3;
   LDS int64_t *stage_id = (LDS int64_t *)(smem3 + NW * KP * 4);
@@ -580,7 +585,7 @@ __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS i
         Key qk;  // the half is sorted ascending: read it reversed to get descending
         qk.d = stage_d[w * KP + h * 64 + (63 - lane)];
         qk.id = stage_id[w * KP + h * 64 + (63 - lane)];
-        wave_merge(st.L0, st.L1, qk, lane);
+        wave_merge<!SGN>(st.L0, st.L1, qk, lane);
       }
       if (wave > 0 && 2 * stride < NW) put();  // read by another wavefront in a later round
     }
@@ -1476,7 +1481,7 @@ __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ 
       Key qk;
       qk.d = part_d[o + s * KP + h * 64 + (63 - lane)];
       qk.id = part_id[o + s * KP + h * 64 + (63 - lane)];
-      wave_merge(L0, L1, qk, lane);
+      wave_merge<true>(L0, L1, qk, lane);
     }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
