@@ -1381,7 +1381,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // of a subspace is the penalty that every such entry gets when the whole box lies outside the
 // (inner) sphere, decided with the same margin.  One wavefront per BOUND_PAIRS (query, probe)
 // pairs, lane = subspace.
-constexpr int BOUND_PAIRS = 4;  // (query, probe) pairs per wavefront: their loads are issued together
+constexpr int BOUND_PAIRS = 2;  // (query, probe) pairs per wavefront: their loads are issued together
 
 __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
                                                           const int32_t *__restrict__ probe_ids,
