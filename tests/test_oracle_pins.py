@@ -700,3 +700,78 @@ def test_radius_model_fitted_to_true_neighbours(tiny):
             inside += int((np.sqrt(((res - ent) ** 2).sum(1)) <= r[i]).sum())
             total += idx.M
     assert inside / total > 0.85, inside / total
+
+
+# ----------------------------------------------------------------------------
+# random odd shapes against a float64 transcription of the definitions
+# ----------------------------------------------------------------------------
+
+def _definition_search(q, idx, nprobe, k, radii, metric):
+    """The search path from its definitions, in float64 numpy, one query: list scores,
+    nprobe best lists by (score, list), truncated table sums (L2) or negated inner
+    products with the threshold bound (inner product), k best by (value, id)."""
+    q = q.astype(np.float64)
+    cen = idx.centroids.astype(np.float64)
+    cb = idx.codebooks.astype(np.float64)
+    M, dsub = idx.M, idx.dsub
+    score = ((q[None] - cen) ** 2).sum(1) if metric == 0 else -(cen @ q)
+    probes = np.lexsort((np.arange(idx.nlist), score))[:nprobe]
+    r2 = radii.astype(np.float64) ** 2
+    vals, ids = [], []
+    for c in probes:
+        lo, hi = idx.list_offsets[c], idx.list_offsets[c + 1]
+        codes = idx.codes[lo:hi]
+        ent = cb[np.arange(M)[None, :], codes]                      # [n][M][dsub]
+        if metric == 0:
+            res = (q - cen[c]).reshape(M, dsub)
+            d2 = ((res[None] - ent) ** 2).sum(-1)
+            v = np.minimum(d2, r2[None]).sum(1)
+        else:
+            qm = q.reshape(M, dsub)
+            ip = (ent * qm[None]).sum(-1)
+            thr = 0.5 * ((qm ** 2).sum(1) - r2)
+            v = -(cen[c] @ q) - np.maximum(ip, thr[None]).sum(1)
+        vals.append(v)
+        ids.append(idx.ids[lo:hi])
+    vals, ids = np.concatenate(vals), np.concatenate(ids)
+    order = np.lexsort((ids, vals))[:k]
+    return probes, vals[order], ids[order], np.sort(vals)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_odd_shapes_against_definitions(seed):
+    rng = np.random.default_rng(1000 + seed)
+    dsub = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    M = int(rng.choice([1, 2, 3, 7, 16]))
+    D = M * dsub
+    nlist = int(rng.choice([1, 2, 5, 9]))
+    sizes = rng.integers(0, 40, size=nlist)
+    if seed % 3 == 0:
+        sizes[rng.integers(0, nlist)] = 0                           # an empty list
+    N = int(sizes.sum())
+    offs = np.zeros(nlist + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(sizes)
+    idx = wl.Index(N=N, D=D, nlist=nlist, M=M, centroids=rng.normal(size=(nlist, D)).astype(np.float32),
+                   codebooks=(0.7 * rng.normal(size=(M, 256, dsub))).astype(np.float32), list_offsets=offs,
+                   codes=rng.integers(0, 256, size=(N, M), dtype=np.uint8),
+                   ids=(rng.permutation(N) * 2 + 5).astype(np.int64))
+    nprobe = int(rng.integers(1, nlist + 1))
+    k = int(rng.choice([1, 3, 10, 64]))
+    q = rng.normal(size=(6, D)).astype(np.float32)
+    radii = (np.sqrt(dsub) * rng.uniform(0.4, 1.6, size=M)).astype(np.float32)
+    if seed % 4 == 1:
+        radii[:] = np.inf
+    for metric in (0, 1):
+        o_ids, o_val = oracle.search(q, idx, nprobe, k, radii, metric=metric)
+        o_probes, _ = oracle.coarse(q, idx.centroids, nprobe, metric=metric)
+        for i in range(q.shape[0]):
+            probes, vals, ids, allv = _definition_search(q[i], idx, nprobe, k, radii, metric)
+            assert np.array_equal(o_probes[i], probes), (seed, metric, i)   # random scores: no near ties
+            n = len(vals)
+            assert np.all(o_ids[i, n:] == -1) and np.all(np.isinf(o_val[i, n:]))
+            np.testing.assert_allclose(o_val[i, :n], vals, rtol=2e-5, atol=2e-5)
+            # ids agree wherever the value is separated from its neighbours in the full order
+            for j in range(n):
+                gap = np.abs(allv - vals[j])
+                if (gap < 1e-4 * (1 + abs(vals[j]))).sum() == 1:
+                    assert o_ids[i, j] == ids[j], (seed, metric, i, j)
