@@ -157,6 +157,31 @@ def test_shapes_ragged_and_empty_lists(lib, M, D):
     full_check(w, idx, q[:3], r, nprobe=2, k=1)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_odd_shapes(lib, seed):
+    """Small random indexes in shapes no workload has: dsub 1-8, M from 1, a single list,
+    empty lists, k above the number of candidates, infinite radii; both metrics, every stage."""
+    rng = np.random.default_rng(2000 + seed)
+    dsub = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    M = int(rng.choice([1, 2, 3, 7, 16]))
+    D = M * dsub
+    nlist = int(rng.choice([1, 2, 5, 9]))
+    sizes = rng.integers(0, 200, size=nlist)
+    if seed % 3 == 0 and nlist > 1:
+        sizes[rng.integers(0, nlist)] = 0
+    sizes[0] = max(sizes[0], 1)
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    nprobe = int(rng.integers(1, nlist + 1))
+    k = int(rng.choice([1, 3, 10, 100]))
+    q = rng.normal(size=(9, D)).astype(np.float32)
+    radii = (0.5 * np.sqrt(dsub) * rng.uniform(0.4, 1.6, size=M)).astype(np.float32)
+    if seed % 4 == 1:
+        radii[:] = np.inf
+    w = wl.Workload(f"odd_{seed}", idx.N, D, nlist, M, 9, nprobe, k, "gauss", 1, 1.0)
+    for metric in (0, 1):
+        full_check(w, idx, q, radii, nprobe=nprobe, k=k, metric=metric)
+
+
 @pytest.mark.parametrize("M,D", [(64, 128), (16, 64), (6, 12)])
 def test_many_probes(lib, M, D):
     """More probed lists than the kernel stages metadata for at once (64), with and
