@@ -182,6 +182,19 @@ def test_random_odd_shapes(lib, seed):
         full_check(w, idx, q, radii, nprobe=nprobe, k=k, metric=metric)
 
 
+@pytest.mark.parametrize("M,D", [(64, 128), (5, 15)])
+def test_index_without_points(lib, M, D):
+    """N = 0 is a valid index: every search returns k times (-1, +inf)."""
+    rng = np.random.default_rng(77)
+    idx = _random_index(rng, 0, D, 3, M, [0, 0, 0])
+    assert idx.N == 0
+    q = rng.normal(size=(5, D)).astype(np.float32)
+    w = wl.Workload(f"empty_M{M}", 0, D, 3, M, 5, 2, 10, "gauss", 1, 1.0)
+    for metric in (0, 1):
+        o_ids = full_check(w, idx, q, np.full(M, 0.5, np.float32), nprobe=2, k=10, metric=metric)
+        assert np.all(o_ids == -1)
+
+
 @pytest.mark.parametrize("M,D", [(64, 128), (16, 64), (6, 12)])
 def test_many_probes(lib, M, D):
     """More probed lists than the kernel stages metadata for at once (64), with and
