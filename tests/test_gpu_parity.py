@@ -182,6 +182,29 @@ def test_random_odd_shapes(lib, seed):
         full_check(w, idx, q, radii, nprobe=nprobe, k=k, metric=metric)
 
 
+@pytest.mark.parametrize("M,D", [(16, 64), (8, 16)])
+def test_maximum_nprobe(lib, M, D):
+    """nprobe at its limit of 1024: sixteen metadata chunks per query in one workgroup (large
+    batch) and probes split over 64 workgroups (small batch); both metrics."""
+    rng = np.random.default_rng(4 * M + 1)
+    nlist = 1030
+    sizes = rng.integers(0, 20, size=nlist)
+    sizes[::50] = 0
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    w = wl.Workload(f"maxprobe_M{M}", idx.N, D, nlist, M, 0, 1024, 100, "gauss", 1, 1.0)
+    r = np.full(M, 0.8 * np.sqrt(D / M), dtype=np.float32)
+    q = rng.normal(size=(2100, D)).astype(np.float32)
+    full_check(w, idx, q[:3], r, nprobe=1024, k=100)
+    full_check(w, idx, q, r, nprobe=1024, k=10, stages=False)
+    full_check(w, idx, q[:3], r, nprobe=1024, k=100, metric=1)
+    b = _binding()
+    gi = b.IvfPqIndex.from_index(idx)
+    with pytest.raises(b.IvfpqError) as e:
+        gi.search(_cuda(q[:3]), 1025, 10, r)
+    assert e.value.status == b.ERR_UNSUPPORTED
+    gi.close()
+
+
 @pytest.mark.parametrize("M,D", [(64, 128), (5, 15)])
 def test_index_without_points(lib, M, D):
     """N = 0 is a valid index: every search returns k times (-1, +inf)."""
