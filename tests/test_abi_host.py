@@ -97,3 +97,13 @@ def test_header_is_plain_c():
                             os.path.join(ROOT, "include"), "-c", src, "-o", os.path.join(d, "use.o")],
                            capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N above 1 exits with a message that says so."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
