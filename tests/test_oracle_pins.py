@@ -775,3 +775,26 @@ def test_random_odd_shapes_against_definitions(seed):
                 gap = np.abs(allv - vals[j])
                 if (gap < 1e-4 * (1 + abs(vals[j]))).sum() == 1:
                     assert o_ids[i, j] == ids[j], (seed, metric, i, j)
+
+
+def test_recall_ground_truth_and_measure(tiny):
+    """The benchmark's recall figures rest on workloads.exact_knn (streamed fp32 matrix form) and
+    workloads.recall_at_k: the first must agree with the oracle's float64 brute force except
+    where distances nearly tie, the second is checked on a hand-made case."""
+    for name in ("T_sift", "T_tti"):
+        w, idx, centres, q = tiny[name]
+        base = wl.base_vectors(w, centres).numpy()
+        for metric in (0, 1):
+            fast = wl.exact_knn(w, centres, torch.from_numpy(q), w.k, metric=metric)
+            slow, sdist = oracle.exact_knn(base, q, w.k + 1, metric=metric)
+            for i in range(q.shape[0]):
+                # the k-th and (k+1)-th true distances are apart: the set is well defined
+                if sdist[i, w.k] - sdist[i, w.k - 1] > 1e-4 * (1 + abs(sdist[i, w.k])):
+                    assert set(fast[i].tolist()) == set(slow[i, :w.k].tolist()), (name, metric, i)
+            assert np.mean(fast[:, 0] == slow[:, 0]) > 0.9
+    found = np.array([[1, 2, 3, -1], [9, 8, 7, 6]])
+    truth = np.array([[3, 2, 5, 4], [6, 0, 1, 2]])
+    rec, r1 = wl.recall_at_k(found, truth)
+    assert rec == (2 + 1) / 8.0 and r1 == 1.0     # first row holds truth[0][0] = 3, second holds 6
+    rec, r1 = wl.recall_at_k(np.array([[0, 1]]), np.array([[2, 0]]))
+    assert rec == 0.5 and r1 == 0.0
