@@ -21,8 +21,11 @@
  *
  * Conventions for every call
  *   - "host" pointers are ordinary process memory, "device" pointers are HIP
- *     device memory on the current device.  Nothing passed in is retained
- *     except by ivfpq_index_create, which copies what it needs.
+ *     device memory on the current device, which must be the device the index
+ *     was created on.  Nothing passed in is retained except by
+ *     ivfpq_index_create, which copies what it needs.
+ *   - d_queries must be 16-byte aligned (rows are read with vector loads); other
+ *     device arrays need the natural alignment of their element type.
  *   - Search-side calls allocate nothing and never synchronise: they enqueue
  *     kernels on `hip_stream` (a hipStream_t, NULL = the default stream) and
  *     return.  Results are valid once the stream has reached that point.
@@ -265,18 +268,20 @@ int ivfpq_index_get_info(const ivfpq_index *index, ivfpq_index_info *info);
  * the device.  Negative: an ivfpq_status. */
 int64_t ivfpq_coarse_fallbacks(int reset);
 
-/* Tuning knob for measurements, process-wide, not thread-safe against running
- * searches.  "scan_waves": wavefronts per workgroup of the fused scan kernel,
- * 0 (default: chosen from the shape), 4, 8 or 16.  Results do not depend on it.
- * "scan_loads": how the scan kernel fetches code blocks: 0 (default) the first chunk
- * (16 subspaces) of a block ahead and the rest only when the block needs it, whole
- * blocks once pruning has been switched off for a query; 1 always whole blocks; 2 / 3
- * always the first half / the first chunk ahead.  Results do not depend on it.
- * "scan_ablate": bit mask that switches off parts of the scan kernel to attribute
- * its time (1 table arithmetic, 2 list scan, 4 top-k offers: results are
- * meaningless with any of these; 8 turns off the early exit of the distance sums,
- * 32 the switch to plain scanning for queries whose blocks rarely end early, 64 the
- * list-level bound that skips a list before its table is built: results unchanged). */
+/* Tuning switches, process-wide.  None of them changes a result; each takes effect for the
+ * calls that start after it returns and may be set from any thread.  Unknown names and values
+ * outside the stated sets give IVFPQ_ERR_INVALID_ARGUMENT.
+ *   "scan_waves"   wavefronts per workgroup of the fused scan kernel: 0 (default: chosen from
+ *                  the shape), 4, 8 or 16.
+ *   "scan_loads"   how the scan kernel fetches code blocks: 0 (default) the first chunk (16
+ *                  subspaces) of a block ahead and the rest only when the block needs it, whole
+ *                  blocks once pruning has been switched off for a query; 1 always whole blocks;
+ *                  2 / 3 always the first half / the first chunk ahead.
+ *   "scan_ablate"  bit mask that switches exact pruning off, to measure what it saves: 8 the
+ *                  early exit of the distance sums, 32 the switch to plain scanning for queries
+ *                  whose blocks rarely end early, 64 the list-level bound that skips a list
+ *                  before its table is built.  8 | 32 | 64 with "scan_loads" 1 is the plain scan:
+ *                  every code byte of every probed list is read and looked up. */
 int ivfpq_set_option(const char *name, int value);
 
 /* Text for the most recent failure on this thread ("" if none). */

@@ -118,9 +118,19 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
-    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
-        raise ValueError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+def _dev(t: torch.Tensor, dtype, shape=None, device=None, what: str = "tensor") -> torch.Tensor:
+    """A tensor the kernels may read or write as it is: on the GPU (the index's, when
+    `device` is given), contiguous, of the stated dtype and, when given, shape (None in a
+    position leaves that extent free).  The kernels index by these shapes without a bounds
+    check of their own, so a mismatch is refused here."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{what}: expected a contiguous CUDA tensor of {dtype}, got "
+                         f"{getattr(t, 'dtype', type(t))} on {getattr(t, 'device', 'the host')}")
+    if device is not None and t.device.index != device:
+        raise ValueError(f"{what}: on cuda:{t.device.index}, the index lives on cuda:{device}")
+    if shape is not None:
+        if t.dim() != len(shape) or any(e is not None and int(g) != int(e) for g, e in zip(t.shape, shape)):
+            raise ValueError(f"{what}: shape {tuple(t.shape)} does not match {tuple(shape)}")
     return t
 
 
@@ -136,9 +146,7 @@ def _scoring(mode: int, query_radii: Optional[torch.Tensor], radii, Q: int, M: i
     keep = []
     qr_ptr = None
     if query_radii is not None:
-        qr = _dev(query_radii, torch.float32)
-        if tuple(qr.shape) != (Q, M):
-            raise ValueError(f"query_radii must have shape ({Q}, {M})")
+        qr = _dev(query_radii, torch.float32, (Q, M), what="query_radii")
         qr_ptr = qr.data_ptr()
         keep.append(qr)
     r_ptr = None
@@ -226,6 +234,7 @@ class IvfPqIndex:
         _check(lib.ivfpq_index_create(ctypes.byref(desc), ctypes.byref(handle)))
         self._h = handle
         self.N, self.D, self.nlist, self.M, self.metric = N, D, nlist, M, int(metric)
+        self.device = torch.cuda.current_device()
         del codes_ref, ids_ref
 
     @classmethod
@@ -259,12 +268,11 @@ class IvfPqIndex:
     def search(self, queries: torch.Tensor, nprobe: int, k: int, radii, workspace: Optional[torch.Tensor] = None,
                out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, mode: int = SCORE_DISTANCE,
                query_radii: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
-        q = _dev(queries, torch.float32)
+        q = self._queries(queries)
         Q = q.shape[0]
         r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
-        ws = workspace if workspace is not None else self.workspace(Q, nprobe, k)
-        ids, dist = out if out is not None else (torch.empty((Q, k), dtype=torch.int64, device=q.device),
-                                                 torch.empty((Q, k), dtype=torch.float32, device=q.device))
+        ws = self._workspace(workspace, Q, nprobe, k)
+        ids, dist = self._outputs(out, Q, k, q.device)
         lib = load_library()
         if sc is None:
             _check(lib.ivfpq_search(self._h, q.data_ptr(), Q, nprobe, k, r_ptr, ids.data_ptr(),
@@ -275,13 +283,37 @@ class IvfPqIndex:
         del keep
         return ids, dist
 
-    def coarse(self, queries: torch.Tensor, nprobe: int, workspace: Optional[torch.Tensor] = None):
-        q = _dev(queries, torch.float32)
+    # ---- argument checks shared by the calls below ---------------------------
+    def _queries(self, queries) -> torch.Tensor:
+        return _dev(queries, torch.float32, (None, self.D), self.device, "queries")
+
+    def _probes(self, probe_ids, Q: int) -> torch.Tensor:
+        return _dev(probe_ids, torch.int32, (Q, None), self.device, "probe_ids")
+
+    def _workspace(self, workspace, Q: int, nprobe: int, k: int) -> torch.Tensor:
+        if workspace is None:
+            return self.workspace(Q, nprobe, k)
+        return _dev(workspace, torch.uint8, (None,), self.device, "workspace")
+
+    def _outputs(self, out, Q: int, k: int, device):
+        if out is None:
+            return (torch.empty((Q, k), dtype=torch.int64, device=device),
+                    torch.empty((Q, k), dtype=torch.float32, device=device))
+        return (_dev(out[0], torch.int64, (Q, k), self.device, "out ids"),
+                _dev(out[1], torch.float32, (Q, k), self.device, "out distances"))
+
+    def coarse(self, queries: torch.Tensor, nprobe: int, workspace: Optional[torch.Tensor] = None,
+               out: Optional[torch.Tensor] = None, with_distances: bool = True):
+        """Probe lists [Q][nprobe] int32 (written into `out` when given) and, unless
+        with_distances is False, their distances."""
+        q = self._queries(queries)
         Q = q.shape[0]
-        ws = workspace if workspace is not None else self.workspace(Q, nprobe, 1)
-        pid = torch.empty((Q, nprobe), dtype=torch.int32, device=q.device)
-        pd = torch.empty((Q, nprobe), dtype=torch.float32, device=q.device)
-        _check(load_library().ivfpq_coarse(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), pd.data_ptr(),
+        ws = self._workspace(workspace, Q, nprobe, 1)
+        pid = torch.empty((Q, nprobe), dtype=torch.int32, device=q.device) if out is None \
+            else _dev(out, torch.int32, (Q, nprobe), self.device, "out probe ids")
+        pd = torch.empty((Q, nprobe), dtype=torch.float32, device=q.device) if with_distances else None
+        _check(load_library().ivfpq_coarse(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(),
+                                           pd.data_ptr() if pd is not None else None,
                                            ws.data_ptr(), ws.numel(), _stream()))
         return pid, pd
 
@@ -289,21 +321,19 @@ class IvfPqIndex:
                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """Per-(query, subspace) radii [Q][M] from the threshold model, looked up at the
         residual w.r.t. the first list of each row of probe_ids."""
-        q = _dev(queries, torch.float32)
-        pid = _dev(probe_ids, torch.int32)
+        q = self._queries(queries)
+        pid = self._probes(probe_ids, q.shape[0])
         Q, nprobe = pid.shape
         r = out if out is not None else torch.empty((Q, self.M), dtype=torch.float32, device=q.device)
-        _dev(r, torch.float32)
-        if tuple(r.shape) != (Q, self.M) or q.shape[0] != Q:
-            raise ValueError("query_radii: shapes of queries, probe_ids and out do not agree")
+        _dev(r, torch.float32, (Q, self.M), self.device, "out radii")
         _check(load_library().ivfpq_query_radii(self._h, model._h, q.data_ptr(), Q, pid.data_ptr(), nprobe,
                                                 ctypes.c_float(scale), r.data_ptr(), _stream()))
         return r
 
     def build_lut(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, mode: int = SCORE_DISTANCE,
                   query_radii: Optional[torch.Tensor] = None):
-        q = _dev(queries, torch.float32)
-        pid = _dev(probe_ids, torch.int32)
+        q = self._queries(queries)
+        pid = self._probes(probe_ids, q.shape[0])
         Q, nprobe = pid.shape
         r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
         lut = torch.empty((Q, nprobe, self.M, 256), dtype=torch.float32, device=q.device)
@@ -315,14 +345,14 @@ class IvfPqIndex:
 
     def scan_topk(self, queries: torch.Tensor, probe_ids: torch.Tensor, k: int, radii,
                   workspace: Optional[torch.Tensor] = None, mode: int = SCORE_DISTANCE,
-                  query_radii: Optional[torch.Tensor] = None):
-        q = _dev(queries, torch.float32)
-        pid = _dev(probe_ids, torch.int32)
+                  query_radii: Optional[torch.Tensor] = None,
+                  out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+        q = self._queries(queries)
+        pid = self._probes(probe_ids, q.shape[0])
         Q, nprobe = pid.shape
         r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
-        ws = workspace if workspace is not None else self.workspace(Q, nprobe, k)
-        ids = torch.empty((Q, k), dtype=torch.int64, device=q.device)
-        dist = torch.empty((Q, k), dtype=torch.float32, device=q.device)
+        ws = self._workspace(workspace, Q, nprobe, k)
+        ids, dist = self._outputs(out, Q, k, q.device)
         _check(load_library().ivfpq_scan_topk_ex(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, r_ptr, sc,
                                                  ids.data_ptr(), dist.data_ptr(), ws.data_ptr(), ws.numel(),
                                                  _stream()))
@@ -332,10 +362,10 @@ class IvfPqIndex:
     def scan_all(self, queries: torch.Tensor, probe_ids: torch.Tensor, radii, cand_offsets: torch.Tensor,
                  mode: int = SCORE_DISTANCE, query_radii: Optional[torch.Tensor] = None):
         """Every candidate's (distance, id); cand_offsets [Q+1] int64 on the device."""
-        q = _dev(queries, torch.float32)
-        pid = _dev(probe_ids, torch.int32)
-        offs = _dev(cand_offsets, torch.int64)
+        q = self._queries(queries)
+        pid = self._probes(probe_ids, q.shape[0])
         Q, nprobe = pid.shape
+        offs = _dev(cand_offsets, torch.int64, (Q + 1,), self.device, "cand_offsets")
         r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
         total = int(offs[-1].item()) if Q > 0 else 0
         dist = torch.empty(max(total, 1), dtype=torch.float32, device=q.device)

@@ -30,24 +30,39 @@ int hip_fail(hipError_t e, const char *what) {
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k) {
+// budget == 0: the proposal matrix of the filtering stage takes up to 1 GiB (queries are
+// processed in chunks of q_chunk).  budget > 0: everything must fit in `budget` bytes; the
+// chunk shrinks (in steps of 128 queries) to make it fit, and total = SIZE_MAX says that not
+// even the smallest chunk does.
+Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k, size_t budget) {
   (void)k;
   Workspace w;
   memset(&w, 0, sizeof w);
   w.nlist_pad = (ix->nlist + 63) & ~63;
-  int64_t qc = ((int64_t)1 << 30) / ((int64_t)w.nlist_pad * 4);
-  qc &= ~(int64_t)127;
-  if (qc < 128) qc = 128;
-  if (qc > Q) qc = Q;
-  w.q_chunk = qc < 1 ? 1 : qc;
   // enough workgroups to fill 256 CUs a few times over when the batch is small
   int64_t ns = Q > 0 ? (2048 + Q - 1) / Q : 1;
   if (ns > nprobe) ns = nprobe;
   if (ns > 64) ns = 64;
   if (ns < 1) ns = 1;
   w.nsplit = (int32_t)ns;
+  size_t fixed = 2 * align256((size_t)Q * nprobe * 4);
+  if (w.nsplit > 1) fixed += align256((size_t)Q * w.nsplit * 128 * 4) + align256((size_t)Q * w.nsplit * 128 * 8);
+  const size_t row_bytes = (size_t)w.nlist_pad * 4;
+  int64_t qc = ((int64_t)1 << 30) / (int64_t)row_bytes;
+  qc &= ~(int64_t)127;
+  if (qc < 128) qc = 128;
+  if (budget > 0) {
+    const int64_t fit = fixed + 256 <= budget ? (int64_t)((budget - fixed - 256) / row_bytes) : 0;
+    if (fit < qc) qc = fit >= Q ? fit : (fit & ~(int64_t)127);
+    if (qc < 1 || (qc < 128 && qc < Q)) {
+      w.total = SIZE_MAX;
+      return w;
+    }
+  }
+  if (qc > Q) qc = Q;
+  w.q_chunk = qc < 1 ? 1 : qc;
   size_t off = 0;
-  w.coarse_dist = off; off += align256((size_t)w.q_chunk * w.nlist_pad * 4);
+  w.coarse_dist = off; off += align256((size_t)w.q_chunk * row_bytes);
   w.probe_ids = off;   off += align256((size_t)Q * nprobe * 4);
   w.probe_dist = off;  off += align256((size_t)Q * nprobe * 4);
   if (w.nsplit > 1) {
@@ -62,6 +77,15 @@ static int check_common(const ivfpq_index *ix, const void *q, int64_t Q, int32_t
   if (!ix) { set_error("%s: index is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   if (Q < 0) { set_error("%s: Q = %lld is negative", fn, (long long)Q); return IVFPQ_ERR_INVALID_ARGUMENT; }
   if (Q > 0 && !q) { set_error("%s: queries pointer is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if ((uintptr_t)q % 16) { set_error("%s: queries pointer must be 16-byte aligned", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  if (Q > 0) {  // the index lives on one device; the kernels would fault on another one's pointers
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) (void)hipGetLastError();
+    else if (dev != ix->device) {
+      set_error("%s: the index was created on device %d, the current device is %d", fn, ix->device, dev);
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+  }
   if (nprobe < 1 || nprobe > ix->nlist) {
     set_error("%s: nprobe = %d outside [1, nlist = %d]", fn, nprobe, ix->nlist);
     return IVFPQ_ERR_INVALID_ARGUMENT;
@@ -119,17 +143,16 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_ablate")) {
-    set_scan_ablate(value & 127);
+    if (value & ~(8 | 32 | 64)) {
+      set_error("set_option: scan_ablate accepts the bits 8, 32 and 64 only");
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
+    set_scan_ablate(value);
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_loads")) {
     if (value < 0 || value > 3) { set_error("set_option: scan_loads must be 0, 1, 2 or 3"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_scan_variant(value);
-    return IVFPQ_OK;
-  }
-  if (name && !strcmp(name, "scan_lds_pad")) {
-    if (value < 0 || value > 96 * 1024) { set_error("set_option: scan_lds_pad out of range"); return IVFPQ_ERR_INVALID_ARGUMENT; }
-    set_scan_lds_pad(value);
     return IVFPQ_OK;
   }
   set_error("set_option: unknown option");

@@ -80,7 +80,7 @@ struct Workspace {
   int32_t nlist_pad;    // row stride of coarse_dist
   int32_t nsplit;       // probe groups per query in the scan
 };
-Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k);
+Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k, size_t budget = 0);
 
 // ---- launchers (enqueue only) -------------------------------------------------
 int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
@@ -103,8 +103,7 @@ int launch_list_boxes(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t 
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);
 int coarse_fallbacks(int reset, unsigned int *out);
 int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);
-void set_scan_ablate(int bits);  // measurement only: skip parts of the scan kernel (results invalid)
-void set_scan_lds_pad(int bytes); // measurement only: extra LDS per scan workgroup
+void set_scan_ablate(int bits);   // pruning switches 8 | 32 | 64 (results unchanged)
 void set_scan_variant(int v);     // code loads: 0 adaptive, 1 whole blocks, 2 first half + rest on demand
 void set_scan_waves(int nw);  // wavefronts per scan workgroup: 0 (auto), 4, 8 or 16
 

@@ -27,6 +27,7 @@
 
 #include <limits.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "ivfpq_internal.h"
@@ -305,8 +306,8 @@ struct ScanArgs {
   const float *query_radii;     // [Q][M] per-query radii, or NULL: the shared r_m^2 of the call
   int32_t mode;       // scoring: 0 distances, 1 hit count, 2 reward/penalty hit count
   int32_t load_mode;  // 0 default policy, 1 whole blocks, 2 always the first half of the chunks ahead, 3 always the first chunk
-  int32_t ablate;  // measurement only: 1 skips the table arithmetic, 2 the list scan, 4 the top-k offers,
-                   // 8 disables the early exit of the distance sums (results stay valid)
+  int32_t ablate;  // pruning switches (results do not depend on them): 8 disables the early exit of the
+                   // distance sums, 32 the switch to plain scanning, 64 the list-level bound
 };
 
 // Codes of one point (the lane's) in registers.
@@ -902,11 +903,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
           }
         }
       };
-      if (!(a.ablate & 1)) {
-        if (mode == 0) build_rows(std::integral_constant<int, 0>{});
-        else if (mode == 1) build_rows(std::integral_constant<int, 1>{});
-        else build_rows(std::integral_constant<int, 2>{});
-      }
+      if (mode == 0) build_rows(std::integral_constant<int, 0>{});
+      else if (mode == 1) build_rows(std::integral_constant<int, 1>{});
+      else build_rows(std::integral_constant<int, 2>{});
     } else {
       const int e = tid & 255;
       for (int m = tid >> 8; m < M; m += NT >> 8) {
@@ -953,7 +952,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
         if (lane == 0) ssuf[NG] = 0.0f;
         suf0 = acc;
       }
-      if (wave < nb && !(a.ablate & 2)) {
+      if (wave < nb) {
         const int last = nb - 1;
         int blocks = 0, full = 0;
         if constexpr (HALF_OK && WPE != 2) {  // the rest of what is fetched ahead of the first block
@@ -998,8 +997,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             if (HALF_OK && depth >= 1) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
             if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
             ++full;
-            if (!(a.ablate & 4)) wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
-            if (a.ablate & 4) st.L0.d = st.L0.d < __float_as_uint(dist) ? st.L0.d : __float_as_uint(dist);
+            wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
           }
         }
         tot_blocks += blocks;
@@ -1630,23 +1628,33 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
   if (i < n) d[i] = v;
 }
 
-int g_scan_waves = 0;  // 0 = choose from the shape
-int g_scan_ablate = 0;
-int g_scan_variant = 0;  // code loads: 0 = default (first chunk ahead while pruning), 1 = always whole blocks, 2 = always the first half ahead, 3 = always the first chunk ahead
-int g_scan_lds_pad = 0;  // measurement only: extra dynamic LDS per workgroup (lowers residency)
+// Tuning switches (ivfpq_set_option).  None of them changes a result.  Atomics: a setter may run
+// on one host thread while another enqueues a search; a launch reads each switch once.
+std::atomic<int> g_scan_waves{0};    // 0 = choose from the shape
+std::atomic<int> g_scan_ablate{0};   // pruning switches: 8 | 32 | 64
+std::atomic<int> g_scan_variant{0};  // code loads: 0 = default (first chunk ahead while pruning), 1 = always whole blocks, 2 = always the first half ahead, 3 = always the first chunk ahead
 
-// The look-up code addresses the table at LDS address 0, which holds as long as a kernel
-// has no static LDS in front of its dynamic allocation.  Checked once per kernel.
+constexpr int LDS_PER_CU = 160 * 1024;
+
+// Once per kernel and device: the look-up code addresses the table at LDS address 0, which
+// holds as long as the kernel has no static LDS in front of its dynamic allocation (checked
+// here), and the kernel is allowed the whole LDS of a CU as dynamic allocation.  `done` has
+// one bit per device; two host threads that race through here do the same idempotent calls.
 template <typename K>
-int check_no_static_lds(K kern, bool &checked) {
-  if (checked) return IVFPQ_OK;
+int prepare_kernel(K kern, std::atomic<uint64_t> &done) {
+  int dev = 0;
+  IVFPQ_HIP_TRY(hipGetDevice(&dev));
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return IVFPQ_OK;
   hipFuncAttributes attr;
   IVFPQ_HIP_TRY(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kern)));
   if (attr.sharedSizeBytes != 0) {
     ivfpq::set_error("scan: kernel has %zu bytes of static LDS, 0 expected", (size_t)attr.sharedSizeBytes);
     return IVFPQ_ERR_UNSUPPORTED;
   }
-  checked = true;
+  IVFPQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS_PER_CU));
+  done.fetch_or(bit, std::memory_order_release);
   return IVFPQ_OK;
 }
 
@@ -1655,24 +1663,21 @@ int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump,
   const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
                      (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 28 + 5 * IVFPQ_MAX_M * 4 +
-                     (size_t)NW * SUF_SLOTS * 4 + 16 + (size_t)g_scan_lds_pad;
-  if (lds > 160 * 1024) {
+                     (size_t)NW * SUF_SLOTS * 4 + 16;
+  if (lds > (size_t)LDS_PER_CU) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
   }
   auto kern = dump ? scan_kernel<MT, DSUB, NW, true> : scan_kernel<MT, DSUB, NW, false>;
-  static bool lds_checked[2] = {false, false};
-  if (int rc = check_no_static_lds(kern, lds_checked[dump ? 1 : 0])) return rc;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) (void)hipGetLastError();  // not fatal: the launch itself reports a real limit
+  static std::atomic<uint64_t> prepared[2];
+  if (int rc = prepare_kernel(kern, prepared[dump ? 1 : 0])) return rc;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
   return IVFPQ_OK;
 }
 
 template <int MT, int DSUB>
 int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
-  int nw = g_scan_waves;
+  int nw = g_scan_waves.load(std::memory_order_relaxed);
   // One workgroup per CU once the table passes 72 KiB: the specialised kernels then run 8
   // wavefronts with twice the registers, the run-time-M kernel (few registers) runs 16.
   // Tables of at most 32 KiB leave room for four workgroups per CU: 4 wavefronts each, so that
@@ -1692,16 +1697,13 @@ size_t scan_ip_lds(const ScanArgs &a, int nw) {
 template <int MT, int NW>
 int launch_scan_ip_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const size_t lds = scan_ip_lds(a, NW);
-  if (lds > 160 * 1024) {
+  if (lds > (size_t)LDS_PER_CU) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
   }
   auto kern = dump ? scan_ip_kernel<MT, NW, true> : scan_ip_kernel<MT, NW, false>;
-  static bool lds_checked[2] = {false, false};
-  if (int rc = check_no_static_lds(kern, lds_checked[dump ? 1 : 0])) return rc;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) (void)hipGetLastError();
+  static std::atomic<uint64_t> prepared[2];
+  if (int rc = prepare_kernel(kern, prepared[dump ? 1 : 0])) return rc;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
   return IVFPQ_OK;
 }
@@ -1709,7 +1711,7 @@ int launch_scan_ip_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool du
 // Inner-product metric: 8 wavefronts while two workgroups fit a CU, else 16.
 template <int MT>
 int launch_scan_ip(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
-  if (2 * scan_ip_lds(a, 8) <= 160 * 1024) return launch_scan_ip_t<MT, 8>(a, r2, grid, dump, s);
+  if (2 * scan_ip_lds(a, 8) <= (size_t)LDS_PER_CU) return launch_scan_ip_t<MT, 8>(a, r2, grid, dump, s);
   return launch_scan_ip_t<MT, 16>(a, r2, grid, dump, s);
 }
 
@@ -1717,10 +1719,9 @@ int launch_scan_ip(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
 
 namespace ivfpq {
 
-void set_scan_waves(int nw) { g_scan_waves = nw; }
-void set_scan_ablate(int bits) { g_scan_ablate = bits; }
-void set_scan_lds_pad(int bytes) { g_scan_lds_pad = bytes; }
-void set_scan_variant(int v) { g_scan_variant = v; }
+void set_scan_waves(int nw) { g_scan_waves.store(nw, std::memory_order_relaxed); }
+void set_scan_ablate(int bits) { g_scan_ablate.store(bits, std::memory_order_relaxed); }
+void set_scan_variant(int v) { g_scan_variant.store(v, std::memory_order_relaxed); }
 
 int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
@@ -1754,10 +1755,10 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.nlist = ix->nlist;
   a.nprobe = nprobe;
   a.nsplit = nsplit;
-  a.ablate = g_scan_ablate;
+  a.ablate = g_scan_ablate.load(std::memory_order_relaxed);
   a.mode = mode;
   a.query_radii = d_query_radii;
-  a.load_mode = g_scan_variant;
+  a.load_mode = g_scan_variant.load(std::memory_order_relaxed);
   const bool dump = d_all_dist != nullptr;
   const int64_t grid = Q * nsplit;
   if (grid > 0x7FFFFFFFll) {
@@ -1766,7 +1767,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   }
   const int M = ix->M, ds = ix->dsub;
   const bool ip = ix->metric == IVFPQ_METRIC_IP;
-  if (d_probe_lb && !dump && !ip && !(g_scan_ablate & 64)) {
+  if (d_probe_lb && !dump && !ip && !(a.ablate & 64)) {
     const int64_t total = Q * nprobe;
     if ((total + 3) / 4 > 0x7FFFFFFFll) {
       set_error("scan: %lld (query, probe) pairs exceed the grid limit of the bound kernel", (long long)total);

@@ -107,3 +107,53 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in (r.stderr + r.stdout)
+
+
+def _layout_offset(list_block0, nb, Mp, b, lane, d):
+    """Byte offset of dword d of point (block b, lane) of a list that starts at block
+    list_block0 and has nb blocks, in the device layout of the codes as the interface documents
+    it: lists padded to 64-point blocks of 64 * Mp bytes; within a list chunk-major, the 16-byte
+    chunks first ([chunk][block][lane][16 B]), then the 4-byte chunks ([chunk][block][lane][4 B])."""
+    base = list_block0 * 64 * Mp
+    n16 = Mp // 16
+    if d < 4 * n16:
+        return base + ((d // 4) * nb + b) * 1024 + lane * 16 + (d % 4) * 4
+    return base + n16 * nb * 1024 + ((d - 4 * n16) * nb + b) * 256 + lane * 4
+
+
+@pytest.mark.parametrize("M,nlist,N", [(64, 16384, 100_000_000), (100, 1024, 1_000_000), (48, 1024, 1_000_000)])
+def test_code_layout_offsets_stay_in_bounds_at_full_size(M, nlist, N):
+    """The interleaved code layout at the size of the 100M-point configuration (6.4 GB: list
+    bases and chunk offsets pass 2^32) and of the M = 100 one (4-byte tail chunks): the extreme
+    addresses of every list -- first and last block, first and last lane, every dword -- are
+    distinct per list, stay below the array's size, and an empty list's single read stays
+    inside the 4 KiB of padding.  Also shows that 32-bit offset arithmetic would not do."""
+    rng = np.random.default_rng(5)
+    # list sizes with the imbalance of the trained index: some empty, some 4x the mean
+    wts = rng.gamma(2.0, 1.0, nlist)
+    wts[rng.choice(nlist, nlist // 64, replace=False)] = 0.0
+    sizes = np.floor(wts / wts.sum() * N).astype(np.int64)
+    sizes[np.argmax(sizes)] += N - sizes.sum()
+    blocks = np.zeros(nlist + 1, dtype=np.int64)
+    blocks[1:] = np.cumsum((sizes + 63) // 64)
+    Mp = (M + 3) // 4 * 4
+    code_bytes = int(blocks[-1]) * 64 * Mp
+    top = 0
+    for c in range(nlist):
+        nb = int(blocks[c + 1] - blocks[c])
+        b0 = int(blocks[c])
+        if nb == 0:   # the scan reads one 1 KiB chunk at the list's base and ignores it
+            assert b0 * 64 * Mp + 1024 <= code_bytes + 4096
+            continue
+        lo = _layout_offset(b0, nb, Mp, 0, 0, 0)
+        hi = max(_layout_offset(b0, nb, Mp, nb - 1, 63, d) + 4 for d in range(Mp // 4))
+        assert lo == b0 * 64 * Mp and hi == (b0 + nb) * 64 * Mp, (c, lo, hi)   # exactly the list's span
+        top = max(top, hi)
+    assert top == code_bytes
+    if N >= 100_000_000:
+        assert code_bytes > (1 << 32)
+        assert (code_bytes & 0xFFFFFFFF) != code_bytes     # a 32-bit offset would wrap
+    # inside one list: all (block, lane, dword) addresses distinct
+    nb = 5
+    seen = {_layout_offset(7, nb, Mp, b, l, d) for b in range(nb) for l in range(64) for d in range(Mp // 4)}
+    assert len(seen) == nb * 64 * (Mp // 4) and min(seen) == 7 * 64 * Mp and max(seen) + 4 == (7 + nb) * 64 * Mp
