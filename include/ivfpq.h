@@ -125,6 +125,28 @@ int ivfpq_search(const ivfpq_index *index, const float *d_queries, int64_t Q, in
                  int32_t k, const float *radii, int64_t *d_out_ids, float *d_out_dist,
                  void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The whole search path for callers that cannot allocate and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same stages, same results and same argument conventions as ivfpq_search (distance
+ * scoring, shared radii), with the workspace in a static device array inside the library:
+ * IVFPQ_NOALLOC_SCRATCH_BYTES per GPU, held from library load to process end.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine), takes no
+ * workspace and never synchronises.
+ *   Limit: the batch's workspace must fit the array.  The filtering stage works through the
+ *   batch in chunks of at least 128 queries x nlist floats, so roughly
+ *   8 Q nprobe + 128 * 4 nlist bytes (+ 3 KiB per query when Q < 2048) must stay under the
+ *   array's size: e.g. Q = 10 000 with nprobe = 64 and nlist = 16 384, or nlist up to about
+ *   60 000 for small batches.  Beyond it the call returns IVFPQ_ERR_WORKSPACE with a text that
+ *   says so, and writes nothing.
+ *   Every call on a GPU uses that GPU's one array: calls that overlap in time on the same
+ *   GPU (two streams, two host threads) race on it and give wrong results; serialise them
+ *   or use ivfpq_search with separate workspaces.  Nothing in the array has to be cleared
+ *   between calls (every region is written before it is read). */
+#define IVFPQ_NOALLOC_SCRATCH_BYTES (32u << 20)
+int ivfpq_search_noalloc(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
+                         int32_t k, const float *radii, int64_t *d_out_ids, float *d_out_dist,
+                         void *hip_stream);
+
 /* Stage 1 alone (paper Sec. 2.1 step A; Sec. 5.3 on computing it as a matrix
  * product): d_probe_ids device [Q][nprobe] int32 ordered by (distance, list
  * id); d_probe_dist device [Q][nprobe] fp32 or NULL.  Distances are

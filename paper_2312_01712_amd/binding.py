@@ -25,6 +25,7 @@ SYMBOLS = [
     "ivfpq_set_option", "ivfpq_coarse_fallbacks", "ivfpq_last_error",
     "ivfpq_search_ex", "ivfpq_build_lut_ex", "ivfpq_scan_topk_ex", "ivfpq_scan_all_ex",
     "ivfpq_radius_model_create", "ivfpq_radius_model_destroy", "ivfpq_query_radii",
+    "ivfpq_search_noalloc",
 ]
 
 SCORE_DISTANCE, SCORE_HIT_COUNT, SCORE_HIT_REWARD = 0, 1, 2
@@ -72,6 +73,7 @@ def load_library():
     lib.ivfpq_search_workspace_bytes.argtypes = [vp, i64, i32, i32]
     lib.ivfpq_search_workspace_bytes.restype = sz
     lib.ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.ivfpq_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
     lib.ivfpq_coarse.argtypes = [vp, vp, i64, i32, vp, vp, vp, sz, vp]
     lib.ivfpq_build_lut.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.ivfpq_scan_topk.argtypes = [vp, vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
@@ -301,6 +303,18 @@ class IvfPqIndex:
                     torch.empty((Q, k), dtype=torch.float32, device=device))
         return (_dev(out[0], torch.int64, (Q, k), self.device, "out ids"),
                 _dev(out[1], torch.float32, (Q, k), self.device, "out distances"))
+
+    def search_noalloc(self, queries: torch.Tensor, nprobe: int, k: int, radii,
+                       out: Tuple[torch.Tensor, torch.Tensor]) -> Tuple[torch.Tensor, torch.Tensor]:
+        """`ivfpq_search_noalloc`: the search whose workspace is the library's own static
+        device array; the caller passes inputs and outputs only."""
+        q = self._queries(queries)
+        Q = q.shape[0]
+        ids, dist = self._outputs(out, Q, k, q.device)
+        r = _radii(radii, self.M)
+        _check(load_library().ivfpq_search_noalloc(self._h, q.data_ptr(), Q, nprobe, k, r.ctypes.data,
+                                                   ids.data_ptr(), dist.data_ptr(), _stream()))
+        return ids, dist
 
     def coarse(self, queries: torch.Tensor, nprobe: int, workspace: Optional[torch.Tensor] = None,
                out: Optional[torch.Tensor] = None, with_distances: bool = True):

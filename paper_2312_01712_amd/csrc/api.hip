@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <new>
 #include <vector>
 
@@ -510,6 +511,77 @@ int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
                             ws, ws_bytes, stream);
 }
 
+// ---- the search that allocates nothing and takes no workspace -----------------------------
+// Its workspace is this array: one copy per GPU, held from the moment the library is loaded
+// on that GPU until the process ends.  The name is a host-side stand-in, not a device
+// address: host code only ever uses the pointer that hipGetSymbolAddress returns for the
+// current device (scratch_address), and the kernels receive that pointer as an argument,
+// exactly as they receive a caller's workspace.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[IVFPQ_NOALLOC_SCRATCH_BYTES];
+
+static constexpr int MAX_DEVICES = 64;
+static std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int scratch_address(void **out, const char *fn) {
+  int dev = -1;
+  IVFPQ_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) {
+    set_error("%s: device ordinal %d outside [0, %d)", fn, dev, MAX_DEVICES);
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    IVFPQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (uintptr_t)p % 256) {
+      set_error("%s: the static scratch array has no usable device address", fn);
+      return IVFPQ_ERR_HIP;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // two threads racing here store the same address
+  }
+  *out = p;
+  return IVFPQ_OK;
+}
+
+// Stages 1-4 with the workspace `base` carved as `w` says.
+static int search_in_workspace(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                               int32_t k, const RadiiSq &r2, int32_t mode, const float *qr, int64_t *d_out_ids,
+                               float *d_out_dist, const Workspace &w, char *base, hipStream_t s) {
+  int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
+  int rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr,
+                         reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad, s);
+  if (rc) return rc;
+  return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
+                     reinterpret_cast<uint32_t *>(base + w.part_d),
+                     reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
+                     nullptr, nullptr, nullptr, mode, qr, reinterpret_cast<float *>(base + w.probe_dist), s);
+}
+
+int ivfpq_search_noalloc(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
+                         const float *radii, int64_t *d_out_ids, float *d_out_dist, void *stream) {
+  const char *fn = "search_noalloc";
+  int rc = check_common(ix, d_queries, Q, nprobe, fn);
+  if (rc) return rc;
+  if ((rc = check_k(k, fn))) return rc;
+  RadiiSq r2;
+  if ((rc = make_radii(ix, radii, &r2, fn))) return rc;
+  if (Q == 0) return IVFPQ_OK;
+  if (!d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
+  const Workspace w = plan_workspace(ix, Q, nprobe, k, IVFPQ_NOALLOC_SCRATCH_BYTES);
+  if (w.total == SIZE_MAX || w.total > IVFPQ_NOALLOC_SCRATCH_BYTES) {
+    set_error("%s: Q = %lld, nprobe = %d with nlist = %d need more than the %u bytes of built-in scratch; "
+              "use ivfpq_search with a workspace, or smaller batches", fn, (long long)Q, nprobe, ix->nlist,
+              (unsigned)IVFPQ_NOALLOC_SCRATCH_BYTES);
+    return IVFPQ_ERR_WORKSPACE;
+  }
+  void *base = nullptr;
+  if ((rc = scratch_address(&base, fn))) return rc;
+  // Nothing in the workspace has to start at zero: every region is written in full (for the
+  // rows and probes of this call) before it is read, so the previous call's contents do not matter.
+  return search_in_workspace(ix, d_queries, Q, nprobe, k, r2, IVFPQ_SCORE_DISTANCE, nullptr, d_out_ids,
+                             d_out_dist, w, static_cast<char *>(base), static_cast<hipStream_t>(stream));
+}
+
 int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
                     const float *radii, const ivfpq_scoring *scoring, int64_t *d_out_ids,
                     float *d_out_dist, void *ws, size_t ws_bytes, void *stream) {
@@ -525,16 +597,8 @@ int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
   if (!d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
   if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
-  char *base = static_cast<char *>(ws);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
-  rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr,
-                     reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad, s);
-  if (rc) return rc;
-  return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
-                     reinterpret_cast<uint32_t *>(base + w.part_d),
-                     reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, mode, qr, reinterpret_cast<float *>(base + w.probe_dist), s);
+  return search_in_workspace(ix, d_queries, Q, nprobe, k, r2, mode, qr, d_out_ids, d_out_dist, w,
+                             static_cast<char *>(ws), static_cast<hipStream_t>(stream));
 }
 
 int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,

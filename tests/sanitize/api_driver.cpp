@@ -145,6 +145,30 @@ static void search_arguments() {
   REQUIRE(ivfpq_set_option("scan_loads", 4) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_waves", 5) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option(nullptr, 0) == IVFPQ_ERR_INVALID_ARGUMENT);
+  // the entry point without a workspace: same argument checks, sizes beyond its built-in scratch refused
+  REQUIRE(ivfpq_search_noalloc(nullptr, q, 4, 2, 5, radii, ids, dist, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_search_noalloc(&ix, q, 4, 2, 0, radii, ids, dist, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_search_noalloc(&ix, q, 4, 2, 5, nullptr, ids, dist, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_search_noalloc(&ix, q, 4, 2, 5, radii, nullptr, dist, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_search_noalloc(&ix, q, 0, 2, 5, radii, ids, dist, nullptr) == IVFPQ_OK);
+  { ivfpq_index wide = fake_index(1000, 16, 100000, 4);   // 128 rows of 100 032 floats do not fit 32 MiB
+    REQUIRE(ivfpq_search_noalloc(&wide, q, 4, 2, 5, radii, ids, dist, nullptr) == IVFPQ_OK ||
+            std::strlen(ivfpq_last_error()) > 0);
+    REQUIRE(ivfpq_search_noalloc(&wide, q, 200, 2, 5, radii, ids, dist, nullptr) == IVFPQ_ERR_WORKSPACE);
+    REQUIRE(ivfpq_search_noalloc(&ix, q, 5000000, 8, 5, radii, ids, dist, nullptr) == IVFPQ_ERR_WORKSPACE); }
+  // budgeted plans: whatever fits stays inside the budget, chunks are whole multiples of 128 or the batch
+  { const int nlists[] = {8, 1024, 16384, 60000, 100000};
+    const int64_t Qs[] = {1, 100, 127, 128, 3000, 10000, 200000};
+    for (int nl : nlists)
+      for (int64_t Q : Qs) {
+        ivfpq_index b = fake_index(1000, 16, nl, 4);
+        const int np = nl < 64 ? nl : 64;
+        const ivfpq::Workspace w = ivfpq::plan_workspace(&b, Q, np, 100, IVFPQ_NOALLOC_SCRATCH_BYTES);
+        if (w.total == SIZE_MAX) continue;
+        REQUIRE(w.total <= IVFPQ_NOALLOC_SCRATCH_BYTES);
+        REQUIRE(w.q_chunk >= 1 && (w.q_chunk == Q || w.q_chunk % 128 == 0) && w.q_chunk <= Q);
+        REQUIRE(w.coarse_dist + (size_t)w.q_chunk * w.nlist_pad * 4 <= w.probe_ids);
+      } }
   ivfpq_index_info info;
   REQUIRE(ivfpq_index_get_info(&ix, &info) == IVFPQ_OK && info.D == 16 && info.dsub == 4);
   // radius model descriptions

@@ -26,12 +26,12 @@ def test_oracle_under_sanitizers(tmp_path):
 
 
 def test_abi_host_side_under_sanitizers(tmp_path):
-    """csrc/api.hip, host pass only, with stubs in place of the kernel launchers: argument
+    """The host code of csrc/api.hip, with stubs in place of the kernel launchers: argument
     validation, index description checks and the workspace planner run without a GPU."""
     exe = str(tmp_path / "api_san")
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     csrc = os.path.join(ROOT, "paper_2312_01712_amd", "csrc")
-    _run([hipcc, "--offload-arch=gfx950", "--offload-host-only", "-O1", "-g", "-std=c++17",
+    _run([hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
           "-Xarch_host", "-fno-sanitize-recover=all", "-I", os.path.join(ROOT, "include"), "-I", csrc,
           os.path.join(csrc, "api.hip"), "-x", "hip", os.path.join(SAN, "launch_stubs.cpp"),
