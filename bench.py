@@ -32,26 +32,35 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
-PLAIN_SCAN = 8 | 32 | 64   # scan_ablate: early exit of the sums, plain-scan switch, list-level bound all off
+PLAIN_SCAN = 8 | 16 | 64   # scan_ablate: no early exit of the sums, no per-block pruning at all, no list-level bound
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
-SCAN_SOURCE = os.path.join(ROOT, "paper_2312_01712_amd", "csrc", "scan.hip")
+CSRC = os.path.join(ROOT, "paper_2312_01712_amd", "csrc")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def csrc_sha256() -> str:
+    """Hash of the kernel sources (every .hip and .h under csrc/, in name order)."""
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode() + b"\0" + open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(workload: str, keep: float, which: str):
     """HBM bytes per scan-kernel launch from the rocprofv3 counter runs recorded in
     profiles/traffic.json (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read
-    for a copy of known size).  The file names the scan kernel source it was taken with (a
-    hash of csrc/scan.hip); with any other source the figure is stale and None is returned."""
+    for a copy of known size).  The file names the kernel sources it was taken with (the hash
+    above); with any other sources the figure is stale and None is returned."""
     try:
         rec = json.load(open(TRAFFIC_FILE))
-        sha = hashlib.sha256(open(SCAN_SOURCE, "rb").read()).hexdigest()
+        sha = csrc_sha256()
     except (OSError, ValueError):
         return None
-    if rec.get("scan_hip_sha256") != sha:
+    if rec.get("csrc_sha256") != sha:
         return None
     e = rec.get("launches", {}).get(f"{workload}:keep={keep:g}:{which}")
     if not e:
@@ -87,7 +96,8 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
 
     Q, nprobe, k = w.Q, w.nprobe, (args.k or w.k)
     passes = (k + 127) // 128   # the scan kernel keeps 128 keys per query and launch
-    ws = gi.workspace(Q, nprobe, k)
+    strategy = binding.SCAN_LIST_MAJOR if args.strategy == "list-major" else binding.SCAN_AUTO
+    ws = gi.workspace(Q, nprobe, k, strategy)
     pid = torch.empty((Q, nprobe), dtype=torch.int32, device="cuda")
     out = (torch.empty((Q, k), dtype=torch.int64, device="cuda"), torch.empty((Q, k), dtype=torch.float32, device="cuda"))
     d_rq = rmodel = model_arrays = None
@@ -98,13 +108,16 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
         d_rq = torch.empty((Q, w.M), dtype=torch.float32, device="cuda")
     shared_radii = None if args.dynamic_radii else radii
 
+    plain_strategy = [strategy]   # the plain-scan leg below always runs query-major
+
     def step(ev=None, outputs=out):
         gi.coarse(q, nprobe, workspace=ws, out=pid, with_distances=False)
         if rmodel is not None:
             gi.query_radii(rmodel, q, pid, args.radius_scale, out=d_rq)
         if ev:
             ev[0].record()
-        gi.scan_topk(q, pid, k, shared_radii, workspace=ws, mode=args.score_mode, query_radii=d_rq, out=outputs)
+        gi.scan_topk(q, pid, k, shared_radii, workspace=ws, mode=args.score_mode, query_radii=d_rq, out=outputs,
+                     strategy=plain_strategy[0])
         if ev:
             ev[1].record()
 
@@ -141,7 +154,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
     algo_bytes = scanned_points * w.M           # per launch (a pass of 128 keys)
 
     # the one-call entry point gives the same answer
-    ids2, dist2 = gi.search(q, nprobe, k, shared_radii, workspace=ws, mode=args.score_mode, query_radii=d_rq)
+    ids2, dist2 = gi.search(q, nprobe, k, shared_radii, workspace=ws, mode=args.score_mode, query_radii=d_rq, strategy=strategy)
     torch.cuda.synchronize()
     assert torch.equal(ids2, out[0]) and torch.equal(dist2, out[1]), "ivfpq_search differs from coarse + scan_topk"
 
@@ -151,12 +164,14 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
         out_p = (torch.empty_like(out[0]), torch.empty_like(out[1]))
         binding.set_option("scan_ablate", PLAIN_SCAN)
         binding.set_option("scan_loads", 1)
+        plain_strategy[0] = binding.SCAN_AUTO
         try:
             step(outputs=out_p)
             _, plain_ms, _ = timed(plain_steps, out_p)
         finally:
             binding.set_option("scan_ablate", 0)
             binding.set_option("scan_loads", 0)
+            plain_strategy[0] = strategy
         assert torch.equal(out_p[0], out[0]) and torch.equal(out_p[1], out[1]), "plain scan differs from the default scan"
         plain = plain_ms / passes
 
@@ -172,6 +187,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
         "value": Q * steps / elapsed, "ms_per_step": elapsed / steps * 1e3,
         "config": {"workload": f"{w.name}: N={w.N} D={w.D} nlist={w.nlist} M={w.M} Q={Q} nprobe={nprobe} k={k}",
                    "family": w.family, "similarity": args.metric, "keep_fraction": args.keep, "score_mode": args.score_mode,
+                   "scan_strategy": args.strategy,
                    "radii": f"per-query (density map, fitted to {args.radius_target}, scale {args.radius_scale})" if args.dynamic_radii else "per-subspace",
                    "keep_fraction_note": "with exact pruning on, the radius sets recall, not throughput",
                    "recall_at_k": recall, "recall_truth_k": min(k, 100), "r1_at_k": r1,
@@ -185,7 +201,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
               "hbm_rate_from_traffic": (default_traffic / (launch_ms * 1e-3) / 1e9) if default_traffic else None}
     if plain is not None:
         achieved = algo_bytes / (plain * 1e-3) / 1e9
-        res["roofline"] = {"bound": "hbm", "kernel": "scan_kernel, plain scan (table + ADC scan + top-k; scan_ablate 8|32|64, scan_loads 1; results equal to the default scan's)",
+        res["roofline"] = {"bound": "hbm", "kernel": "scan_kernel, plain scan (table + ADC scan + top-k; scan_ablate 8|16|64, scan_loads 1; results equal to the default scan's)",
                            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                            "traffic": measured_traffic(w.name, args.keep, "plain") if (args.score_mode == 0 and not args.dynamic_radii and k == w.k and not metric) else None,
                            "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": plain,
@@ -253,18 +269,27 @@ def main():
     ap.add_argument("--radius-target", choices=["top", "keep"], default="top",
                     help="what the offline polynomial is fitted to: the radius that contains the entries of the true "
                          "top-100 neighbours (the paper's), or the radius that keeps --keep of the entries")
+    ap.add_argument("--strategy", choices=["query-major", "list-major"], default="query-major",
+                    help="how stages 2-4 walk the (query, list) pairs; list-major: queries that probe a list share "
+                         "one pass over its codes (for data without cluster structure, e.g. C3)")
+    ap.add_argument("--lm-first", type=int, default=0, help="list-major: lists per query scanned query-major first (0: the library's default)")
+    ap.add_argument("--lm-cap", type=int, default=0, help="list-major: candidate slots per query (0: the library's default)")
     ap.add_argument("--scan-waves", type=int, default=0)
     ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 default (first chunk ahead while pruning), 1 whole blocks, 2 / 3 always first half / first chunk")
-    ap.add_argument("--scan-ablate", type=int, default=0, help="exact-pruning switches to turn off: 8 | 32 | 64 (results unchanged)")
+    ap.add_argument("--scan-ablate", type=int, default=0, help="exact-pruning switches to turn off: 8 | 16 | 32 | 64 (results unchanged)")
     ap.add_argument("--plain-steps", type=int, default=5, help="timed steps of the plain scan (0: skip it)")
     ap.add_argument("--no-c5", action="store_true", help="skip the 100M-point leg of the default run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--print-source-hash", action="store_true", help="print the hash of the kernel sources that profiles/traffic.json is keyed by, and exit")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one elementwise pass over 1 GiB (read 1 GiB, write 1 GiB): the known-size "
                          "kernel that scales the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
+    if args.print_source_hash:
+        print(csrc_sha256())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
 
@@ -275,6 +300,10 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
     binding.load_library()
+    if args.lm_first:
+        binding.set_option("lm_first", args.lm_first)
+    if args.lm_cap:
+        binding.set_option("lm_cap", args.lm_cap)
     if args.scan_waves:
         binding.set_option("scan_waves", args.scan_waves)
     if args.scan_loads:
@@ -297,7 +326,7 @@ def main():
 
     # The second half of the metric -- the ADC scan's HBM rate against the peak -- is quoted on the
     # 100M-point workload (6.4 GB of codes: the only one that no cache holds).  The default run adds it.
-    default_run = (args.workload == "C2" and not args.no_c5 and k == 100 and not metric and args.score_mode == 0
+    default_run = (args.workload == "C2" and args.strategy == "query-major" and not args.no_c5 and k == 100 and not metric and args.score_mode == 0
                    and not args.dynamic_radii and not args.scan_loads and not args.scan_ablate and not args.scan_waves)
     if default_run:
         r5 = run_workload(args, "C5", 5, 2, 0.0 if args.no_cpu_baseline else 4.0, 3)

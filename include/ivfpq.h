@@ -205,10 +205,29 @@ typedef enum {
   IVFPQ_SCORE_HIT_REWARD = 2
 } ivfpq_score_mode;
 
+/* How stages 2-4 walk the (query, probed list) pairs.  Results do not depend on it.
+ *   IVFPQ_SCAN_QUERY_MAJOR  one workgroup per query scans the query's lists nearest first and
+ *     prunes against its running k-th distance (the default; best where lists differ in
+ *     how much they can contribute, i.e. on clustered data).
+ *   IVFPQ_SCAN_LIST_MAJOR   the CDNA4 counterpart of the paper's entry -> points map
+ *     (Sec. 5.2, Algorithm 1; Sec. 5.3): the queries that selected a list are served together,
+ *     two per pass over the list's codes, with their tables interleaved so that one look-up
+ *     serves both; the first lists of a query are still scanned query-major and give the
+ *     bound that filters the rest.  Best where nothing can be pruned (no cluster structure).
+ *     Needs the L2 metric, k <= 128 and an (M, dsub) of (48, 2), (64, 2) or (16, 4); any other
+ *     call is served query-major.  Takes a larger workspace: size it with
+ *     ivfpq_search_workspace_bytes_ex. */
+typedef enum { IVFPQ_SCAN_AUTO = 0, IVFPQ_SCAN_QUERY_MAJOR = 1, IVFPQ_SCAN_LIST_MAJOR = 2 } ivfpq_scan_strategy;
+
 typedef struct {
   int32_t mode;               /* an ivfpq_score_mode                              */
   const float *d_query_radii; /* device [Q][M], or NULL for the shared host radii */
+  int32_t strategy;           /* an ivfpq_scan_strategy; AUTO is QUERY_MAJOR       */
 } ivfpq_scoring;
+
+/* Workspace bytes for the *_ex calls with this scoring (the strategy decides). */
+size_t ivfpq_search_workspace_bytes_ex(const ivfpq_index *index, int64_t Q, int32_t nprobe, int32_t k,
+                                       const ivfpq_scoring *scoring);
 
 int ivfpq_search_ex(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
                     int32_t k, const float *radii, const ivfpq_scoring *scoring, int64_t *d_out_ids,
@@ -299,11 +318,18 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  *                  subspaces) of a block ahead and the rest only when the block needs it, whole
  *                  blocks once pruning has been switched off for a query; 1 always whole blocks;
  *                  2 / 3 always the first half / the first chunk ahead.
+ *   "lm_first"     list-major scan: probed lists per query that are scanned query-major first
+ *                  (1 .. 64, default 2); they give the bound that filters the other lists.
+ *   "lm_cap"       list-major scan: candidate slots per query (64 .. 65536, default 4096); a
+ *                  query that overflows them is redone query-major.  Set both before sizing
+ *                  the workspace.
  *   "scan_ablate"  bit mask that switches exact pruning off, to measure what it saves: 8 the
- *                  early exit of the distance sums, 32 the switch to plain scanning for queries
- *                  whose blocks rarely end early, 64 the list-level bound that skips a list
- *                  before its table is built.  8 | 32 | 64 with "scan_loads" 1 is the plain scan:
- *                  every code byte of every probed list is read and looked up. */
+ *                  early exit of the distance sums, 16 all of the per-block pruning from the
+ *                  first list on (no row minima, no checks: what the kernel otherwise switches
+ *                  to by itself for queries whose blocks rarely end early), 32 that switch,
+ *                  64 the list-level bound that skips a list before its table is built.
+ *                  8 | 16 | 64 with "scan_loads" 1 is the plain scan: every code byte of every
+ *                  probed list is read and looked up. */
 int ivfpq_set_option(const char *name, int value);
 
 /* Text for the most recent failure on this thread ("" if none). */

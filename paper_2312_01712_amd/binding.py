@@ -25,10 +25,11 @@ SYMBOLS = [
     "ivfpq_set_option", "ivfpq_coarse_fallbacks", "ivfpq_last_error",
     "ivfpq_search_ex", "ivfpq_build_lut_ex", "ivfpq_scan_topk_ex", "ivfpq_scan_all_ex",
     "ivfpq_radius_model_create", "ivfpq_radius_model_destroy", "ivfpq_query_radii",
-    "ivfpq_search_noalloc",
+    "ivfpq_search_noalloc", "ivfpq_search_workspace_bytes_ex",
 ]
 
 SCORE_DISTANCE, SCORE_HIT_COUNT, SCORE_HIT_REWARD = 0, 1, 2
+SCAN_AUTO, SCAN_QUERY_MAJOR, SCAN_LIST_MAJOR = 0, 1, 2
 METRIC_L2, METRIC_IP = 0, 1
 
 OK, ERR_INVALID_ARGUMENT, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5
@@ -48,7 +49,7 @@ class _Desc(ctypes.Structure):
 
 
 class _Scoring(ctypes.Structure):
-    _fields_ = [("mode", ctypes.c_int32), ("d_query_radii", ctypes.c_void_p)]
+    _fields_ = [("mode", ctypes.c_int32), ("d_query_radii", ctypes.c_void_p), ("strategy", ctypes.c_int32)]
 
 
 class _Info(ctypes.Structure):
@@ -72,6 +73,8 @@ def load_library():
     lib.ivfpq_index_destroy.restype = None
     lib.ivfpq_search_workspace_bytes.argtypes = [vp, i64, i32, i32]
     lib.ivfpq_search_workspace_bytes.restype = sz
+    lib.ivfpq_search_workspace_bytes_ex.argtypes = [vp, i64, i32, i32, ctypes.POINTER(_Scoring)]
+    lib.ivfpq_search_workspace_bytes_ex.restype = sz
     lib.ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.ivfpq_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
     lib.ivfpq_coarse.argtypes = [vp, vp, i64, i32, vp, vp, vp, sz, vp]
@@ -143,7 +146,7 @@ def _radii(radii, M: int) -> np.ndarray:
     return r
 
 
-def _scoring(mode: int, query_radii: Optional[torch.Tensor], radii, Q: int, M: int):
+def _scoring(mode: int, query_radii: Optional[torch.Tensor], radii, Q: int, M: int, strategy: int = SCAN_AUTO):
     """(host radii pointer or None, ctypes scoring struct or None, objects to keep alive)."""
     keep = []
     qr_ptr = None
@@ -157,8 +160,8 @@ def _scoring(mode: int, query_radii: Optional[torch.Tensor], radii, Q: int, M: i
         r_ptr = r.ctypes.data
         keep.append(r)
     sc = None
-    if mode != SCORE_DISTANCE or qr_ptr is not None:
-        sc = _Scoring(mode=int(mode), d_query_radii=qr_ptr)
+    if mode != SCORE_DISTANCE or qr_ptr is not None or strategy != SCAN_AUTO:
+        sc = _Scoring(mode=int(mode), d_query_radii=qr_ptr, strategy=int(strategy))
         keep.append(sc)
     return r_ptr, (ctypes.byref(sc) if sc is not None else None), keep
 
@@ -260,20 +263,21 @@ class IvfPqIndex:
             pass
 
     # ---- search-side calls -------------------------------------------------
-    def workspace_bytes(self, Q: int, nprobe: int, k: int) -> int:
-        return int(load_library().ivfpq_search_workspace_bytes(self._h, Q, nprobe, k))
+    def workspace_bytes(self, Q: int, nprobe: int, k: int, strategy: int = SCAN_AUTO) -> int:
+        sc = _Scoring(mode=SCORE_DISTANCE, d_query_radii=None, strategy=int(strategy))
+        return int(load_library().ivfpq_search_workspace_bytes_ex(self._h, Q, nprobe, k, ctypes.byref(sc)))
 
-    def workspace(self, Q: int, nprobe: int, k: int) -> torch.Tensor:
-        n = max(256, self.workspace_bytes(Q, nprobe, k))
+    def workspace(self, Q: int, nprobe: int, k: int, strategy: int = SCAN_AUTO) -> torch.Tensor:
+        n = max(256, self.workspace_bytes(Q, nprobe, k, strategy))
         return torch.empty(n, dtype=torch.uint8, device="cuda")
 
     def search(self, queries: torch.Tensor, nprobe: int, k: int, radii, workspace: Optional[torch.Tensor] = None,
                out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, mode: int = SCORE_DISTANCE,
-               query_radii: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+               query_radii: Optional[torch.Tensor] = None, strategy: int = SCAN_AUTO) -> Tuple[torch.Tensor, torch.Tensor]:
         q = self._queries(queries)
         Q = q.shape[0]
-        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
-        ws = self._workspace(workspace, Q, nprobe, k)
+        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M, strategy)
+        ws = self._workspace(workspace, Q, nprobe, k, strategy)
         ids, dist = self._outputs(out, Q, k, q.device)
         lib = load_library()
         if sc is None:
@@ -292,9 +296,9 @@ class IvfPqIndex:
     def _probes(self, probe_ids, Q: int) -> torch.Tensor:
         return _dev(probe_ids, torch.int32, (Q, None), self.device, "probe_ids")
 
-    def _workspace(self, workspace, Q: int, nprobe: int, k: int) -> torch.Tensor:
+    def _workspace(self, workspace, Q: int, nprobe: int, k: int, strategy: int = SCAN_AUTO) -> torch.Tensor:
         if workspace is None:
-            return self.workspace(Q, nprobe, k)
+            return self.workspace(Q, nprobe, k, strategy)
         return _dev(workspace, torch.uint8, (None,), self.device, "workspace")
 
     def _outputs(self, out, Q: int, k: int, device):
@@ -360,12 +364,12 @@ class IvfPqIndex:
     def scan_topk(self, queries: torch.Tensor, probe_ids: torch.Tensor, k: int, radii,
                   workspace: Optional[torch.Tensor] = None, mode: int = SCORE_DISTANCE,
                   query_radii: Optional[torch.Tensor] = None,
-                  out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+                  out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, strategy: int = SCAN_AUTO):
         q = self._queries(queries)
         pid = self._probes(probe_ids, q.shape[0])
         Q, nprobe = pid.shape
-        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M)
-        ws = self._workspace(workspace, Q, nprobe, k)
+        r_ptr, sc, keep = _scoring(mode, query_radii, radii, Q, self.M, strategy)
+        ws = self._workspace(workspace, Q, nprobe, k, strategy)
         ids, dist = self._outputs(out, Q, k, q.device)
         _check(load_library().ivfpq_scan_topk_ex(self._h, q.data_ptr(), Q, nprobe, pid.data_ptr(), k, r_ptr, sc,
                                                  ids.data_ptr(), dist.data_ptr(), ws.data_ptr(), ws.numel(),

@@ -144,8 +144,8 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_ablate")) {
-    if (value & ~(8 | 32 | 64)) {
-      set_error("set_option: scan_ablate accepts the bits 8, 32 and 64 only");
+    if (value & ~(8 | 16 | 32 | 64)) {
+      set_error("set_option: scan_ablate accepts the bits 8, 16, 32 and 64 only");
       return IVFPQ_ERR_INVALID_ARGUMENT;
     }
     set_scan_ablate(value);
@@ -154,6 +154,16 @@ int ivfpq_set_option(const char *name, int value) {
   if (name && !strcmp(name, "scan_loads")) {
     if (value < 0 || value > 3) { set_error("set_option: scan_loads must be 0, 1, 2 or 3"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_scan_variant(value);
+    return IVFPQ_OK;
+  }
+  if (name && !strcmp(name, "lm_first")) {
+    if (value < 1 || value > 64) { set_error("set_option: lm_first must be in [1, 64]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    set_lm_first(value);
+    return IVFPQ_OK;
+  }
+  if (name && !strcmp(name, "lm_cap")) {
+    if (value < 64 || value > 65536) { set_error("set_option: lm_cap must be in [64, 65536]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    set_lm_cap(value);
     return IVFPQ_OK;
   }
   set_error("set_option: unknown option");
@@ -423,6 +433,16 @@ size_t ivfpq_search_workspace_bytes(const ivfpq_index *ix, int64_t Q, int32_t np
   return w.total < 256 ? 256 : w.total;
 }
 
+size_t ivfpq_search_workspace_bytes_ex(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k,
+                                       const ivfpq_scoring *sc) {
+  size_t n = ivfpq_search_workspace_bytes(ix, Q, nprobe, k);
+  if (n && sc && sc->strategy == IVFPQ_SCAN_LIST_MAJOR && list_major_supported(ix, nprobe, k)) {
+    const Workspace w = plan_workspace(ix, Q, nprobe, k);
+    n = align256(w.total) + plan_list_major(ix, Q, nprobe).total;
+  }
+  return n;
+}
+
 int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                  int32_t *d_probe_ids, float *d_probe_dist, void *ws, size_t ws_bytes, void *stream) {
   const char *fn = "coarse";
@@ -440,22 +460,44 @@ int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32
 
 // scoring defaults (distances, shared radii) when the caller passes none
 static int unpack_scoring(const ivfpq_index *ix, const ivfpq_scoring *sc, const float *radii, RadiiSq *r2,
-                          int32_t *mode, const float **d_query_radii, const char *fn) {
+                          int32_t *mode, const float **d_query_radii, const char *fn,
+                          int32_t *strategy = nullptr) {
   *mode = IVFPQ_SCORE_DISTANCE;
   *d_query_radii = nullptr;
+  if (strategy) *strategy = IVFPQ_SCAN_QUERY_MAJOR;
   if (sc) {
     if (sc->mode < IVFPQ_SCORE_DISTANCE || sc->mode > IVFPQ_SCORE_HIT_REWARD) {
       set_error("%s: scoring mode %d unknown", fn, sc->mode);
       return IVFPQ_ERR_INVALID_ARGUMENT;
     }
+    if (sc->strategy < IVFPQ_SCAN_AUTO || sc->strategy > IVFPQ_SCAN_LIST_MAJOR) {
+      set_error("%s: scan strategy %d unknown", fn, sc->strategy);
+      return IVFPQ_ERR_INVALID_ARGUMENT;
+    }
     *mode = sc->mode;
     *d_query_radii = sc->d_query_radii;
+    if (strategy && sc->strategy == IVFPQ_SCAN_LIST_MAJOR) *strategy = IVFPQ_SCAN_LIST_MAJOR;
   }
   if (*d_query_radii) {  // per-query radii replace the shared ones
     memset(r2, 0, sizeof *r2);
     return IVFPQ_OK;
   }
   return make_radii(ix, radii, r2, fn);
+}
+
+// Stages 2-4 list-major: the usual workspace, then the list-major part behind it.
+static int scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                           const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t mode, const float *qr,
+                           int64_t *d_out_ids, float *d_out_dist, const Workspace &w, void *ws, size_t ws_bytes,
+                           hipStream_t s, const char *fn) {
+  const LmWorkspace lw = plan_list_major(ix, Q, nprobe);
+  Workspace both = w;
+  both.total = align256(w.total) + lw.total;
+  if (int rc = check_workspace(both, ws, ws_bytes, fn)) return rc;
+  char *base = static_cast<char *>(ws);
+  return launch_scan_list_major(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, mode, qr,
+                                reinterpret_cast<float *>(base + w.probe_dist), d_out_ids, d_out_dist, lw,
+                                base + align256(w.total), s);
 }
 
 int ivfpq_build_lut_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
@@ -489,14 +531,17 @@ int ivfpq_scan_topk_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q,
   if (rc) return rc;
   if ((rc = check_k(k, fn))) return rc;
   RadiiSq r2;
-  int32_t mode;
+  int32_t mode, strategy;
   const float *qr;
-  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn))) return rc;
+  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn, &strategy))) return rc;
   if (Q == 0) return IVFPQ_OK;
   if (!d_probe_ids || !d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
-  if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
   char *base = static_cast<char *>(ws);
+  if (strategy == IVFPQ_SCAN_LIST_MAJOR && list_major_supported(ix, nprobe, k))
+    return scan_list_major(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, ws,
+                           ws_bytes, static_cast<hipStream_t>(stream), fn);
+  if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
   return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, w.nsplit,
                      reinterpret_cast<uint32_t *>(base + w.part_d),
                      reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
@@ -590,12 +635,24 @@ int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
   if (rc) return rc;
   if ((rc = check_k(k, fn))) return rc;
   RadiiSq r2;
-  int32_t mode;
+  int32_t mode, strategy;
   const float *qr;
-  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn))) return rc;
+  if ((rc = unpack_scoring(ix, scoring, radii, &r2, &mode, &qr, fn, &strategy))) return rc;
   if (Q == 0) return IVFPQ_OK;
   if (!d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
+  if (strategy == IVFPQ_SCAN_LIST_MAJOR && list_major_supported(ix, nprobe, k)) {
+    Workspace both = w;
+    both.total = align256(w.total) + plan_list_major(ix, Q, nprobe).total;
+    if ((rc = check_workspace(both, ws, ws_bytes, fn))) return rc;   // before anything is enqueued
+    char *base = static_cast<char *>(ws);
+    int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
+    rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr, reinterpret_cast<float *>(base + w.coarse_dist),
+                       w.q_chunk, w.nlist_pad, static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+    return scan_list_major(ix, d_queries, Q, nprobe, probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, ws,
+                           ws_bytes, static_cast<hipStream_t>(stream), fn);
+  }
   if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
   return search_in_workspace(ix, d_queries, Q, nprobe, k, r2, mode, qr, d_out_ids, d_out_dist, w,
                              static_cast<char *>(ws), static_cast<hipStream_t>(stream));

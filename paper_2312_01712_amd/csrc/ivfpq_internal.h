@@ -89,12 +89,42 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
 int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                      const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
                      int32_t mode, const float *d_query_radii, hipStream_t s);
+// Which part of the probe table a scan launch covers, and for which queries (NULL: all of it).
+struct ScanView {
+  int32_t probe_stride;  // row stride of d_probe_ids / d_probe_lb when only the first nprobe of a longer row are scanned (0: nprobe)
+  const int32_t *qmap;   // device [Q] or NULL: queries with a negative entry are left out
+  bool bounds_ready;     // d_probe_lb already holds the list-level bounds of every row
+};
 int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,
                 uint32_t *d_part_d, int64_t *d_part_id, int64_t *d_out_ids, float *d_out_dist,
                 const int64_t *d_cand_offsets, float *d_all_dist, int64_t *d_all_ids,
                 int32_t *d_errors, int32_t mode, const float *d_query_radii, float *d_probe_lb,
-                hipStream_t s);
+                hipStream_t s, const ScanView *view = nullptr);
+int launch_probe_bounds(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                        const int32_t *d_probe_ids, const RadiiSq &r2, int32_t mode, const float *d_query_radii,
+                        float *d_probe_lb, hipStream_t s);
+// ---- list-major batched scan (scan_lm.hip) --------------------------------------------------
+struct LmWorkspace {      // offsets into the list-major part of the workspace, 256-byte aligned
+  size_t cnt, cur, base;  // [nlist], [nlist], [nlist+1] int32
+  size_t pairs;           // [pairs_cap] (query, list) int32 pairs bucketed by list
+  size_t gcnt, qmap;      // [Q] uint32 / int32
+  size_t cand;            // [Q][cap] (distance bits, row) candidates of the list-major scan
+  size_t total;
+  int64_t pairs_cap;
+  int32_t first;          // probed lists per query that are scanned query-major first
+  int32_t cap;            // candidate slots per query
+};
+bool list_major_supported(const ivfpq_index *ix, int32_t nprobe, int32_t k);
+LmWorkspace plan_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe);
+int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                           const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t mode,
+                           const float *d_query_radii, float *d_probe_lb, int64_t *d_out_ids, float *d_out_dist,
+                           const LmWorkspace &w, char *lm_base, hipStream_t s);
+void set_lm_first(int v);  // lists per query scanned query-major before the list-major scan (1 .. 64)
+void set_lm_cap(int v);    // candidate slots per query of the list-major scan (64 .. 65536)
+int get_scan_ablate();
+
 int launch_query_radii(const ivfpq_index *ix, const ivfpq_radius_model *md, const float *d_queries,
                        int64_t Q, const int32_t *d_probe_ids, int32_t nprobe, float scale,
                        float *d_radii, hipStream_t s);

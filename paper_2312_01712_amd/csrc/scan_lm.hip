@@ -1,0 +1,553 @@
+// List-major batched scan: the queries that probe the same inverted list are served
+// together, two at a time, from ONE pass over the list's codes.
+//
+// Paper Sec. 5.2 / Algorithm 1 builds an inverted entry -> points map per list so that the
+// distance calculation (Sec. 5.3) touches a list's points once per hit entry.  On CDNA4 the
+// dense code stream is the better carrier, and what the map buys -- work shared inside a list
+// -- is had by turning the loop nest around: the outer loop runs over lists, the queries that
+// selected a list (Sec. 2.1 step A) are grouped, and the group shares the list's code stream
+// and ONE table look-up per (point, subspace): the tables of the two queries of a group are
+// interleaved entry by entry, so a single 8-byte LDS read returns both queries' values for a
+// point's code.  The LDS gather rate, which bounds the query-major scan on data where
+// nothing can be pruned, is per lane-address and not per byte, so two queries cost what one
+// did.  Sums keep the subspace order of the plain loop: results are bit for bit those of the
+// query-major scan.
+//
+// A query's lists are now scanned by different workgroups at different times, so the running
+// k-th distance is not at hand.  Instead:
+//   A  the query-major kernel scans the first few probed lists of every query (the nearest
+//      ones) and leaves each query's top-k of those; tau_q = its k-th distance bounds the
+//      final k-th distance from above;
+//   B  (query, list) pairs of the remaining probes whose list-level lower bound exceeds tau_q
+//      are dropped; the others are bucketed by list (count, offsets, fill);
+//   C  the list-major scan appends every point with distance <= tau_q to the query's
+//      candidate buffer (a few hundred per query: anything above tau_q cannot be in the
+//      result);
+//   D  one wavefront per query merges its buffer into the top-k of phase A by (distance, id).
+// A query whose buffer overflows is redone by the query-major kernel, so the result is
+// always that of the plain loop.
+
+#include "scan_device.h"
+
+namespace {
+
+constexpr int LM_G = 2;        // queries per group (interleaved tables, 8-byte look-ups)
+constexpr int LM_NW = 8;       // wavefronts per workgroup: one workgroup per CU (the table fills most of its LDS), 2 per SIMD, 256 registers each
+constexpr int LM_QUEUE = 64;   // accepted candidates a wavefront holds per query before it appends them
+
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+struct LmArgs {
+  const float *queries;         // [Q][D]
+  const int32_t *probe_ids;     // [Q][nprobe]
+  const float *probe_lb;        // [Q][nprobe] list-level lower bounds, or NULL
+  const float *centroids;       // [nlist][D]
+  const float *codebooks;       // [M][256][dsub]
+  const int64_t *list_offsets;  // [nlist+1]
+  const int64_t *list_blocks;   // [nlist+1]
+  const uint8_t *codes;         // interleaved blocks
+  const int64_t *ids;           // [N]
+  int64_t *out_ids;             // [Q][k]: phase A's top-k on entry to the merge, the result after it
+  float *out_dist;              // [Q][k]
+  int32_t *cnt;                 // [nlist] pairs per list
+  int32_t *cur;                 // [nlist] fill cursors
+  int32_t *base;                // [nlist+1] first pair slot of a list (ranges padded to LM_G); [nlist] = slots in use
+  int2 *pairs;                  // [Q*(nprobe-first) + nlist] (query, list); query -1 pads a list's range
+  uint32_t *gcnt;               // [Q] candidates appended (may run past cap: the query then counts as overflowed)
+  uint2 *cand;                  // [Q][cap] (distance bits, row in the index)
+  int32_t *qmap;                // [Q] out: q for a query to be redone query-major, -1 otherwise
+  const float *query_radii;     // [Q][M] or NULL
+  int64_t Q;
+  int32_t D, M, dsub, Mp, nlist, nprobe, first, k, cap, mode;
+};
+
+// tau_q as the bit pattern of a non-negative float (orders like the value; +inf when phase A
+// found fewer than k points)
+__device__ inline uint32_t lm_tau_bits(const LmArgs &a, int64_t q) {
+  return __float_as_uint(a.out_dist[q * a.k + a.k - 1]);
+}
+
+// One thread per (query, probe >= first).  fill == 0: count the surviving pairs of every list
+// (and clear the query's candidate count); fill == 1: write them to the list's slot range.
+// Both passes evaluate the same predicate on the same data.
+__global__ __launch_bounds__(256) void lm_pairs_kernel(LmArgs a, int fill) {
+  const int np2 = a.nprobe - a.first;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= a.Q * np2) return;
+  const int64_t q = idx / np2;
+  const int p = a.first + (int)(idx % np2);
+  if (!fill && p == a.first) a.gcnt[q] = 0u;
+  const int32_t c = a.probe_ids[q * a.nprobe + p];
+  if ((uint32_t)c >= (uint32_t)a.nlist) return;
+  if (a.list_offsets[c + 1] - a.list_offsets[c] <= 0) return;
+  if (a.probe_lb) {
+    // no point of the list can reach the k-th distance that phase A already guarantees
+    const float tau = a.out_dist[q * a.k + a.k - 1];
+    if (a.probe_lb[q * a.nprobe + p] > tau) return;
+  }
+  if (!fill) {
+    atomicAdd(&a.cnt[c], 1);
+  } else {
+    const int slot = a.base[c] + atomicAdd(&a.cur[c], 1);
+    a.pairs[slot] = make_int2((int)q, c);
+  }
+}
+
+// Slot ranges of the lists: base[c] = sum over c' < c of cnt[c'] rounded up to LM_G.  The
+// padding slot of an odd range is marked (query -1), the cursors are cleared.  One workgroup.
+__global__ __launch_bounds__(1024) void lm_offsets_kernel(LmArgs a) {
+  __shared__ int part[1024];
+  const int tid = threadIdx.x;
+  const int chunk = (a.nlist + 1023) / 1024;
+  const int lo = tid * chunk < a.nlist ? tid * chunk : a.nlist;
+  const int hi = lo + chunk < a.nlist ? lo + chunk : a.nlist;
+  int sum = 0;
+  for (int c = lo; c < hi; ++c) sum += (a.cnt[c] + LM_G - 1) / LM_G * LM_G;
+  part[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int v = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = part[tid] - sum;
+  for (int c = lo; c < hi; ++c) {
+    const int n = a.cnt[c], padded = (n + LM_G - 1) / LM_G * LM_G;
+    a.base[c] = run;
+    for (int j = n; j < padded; ++j) a.pairs[run + j] = make_int2(-1, c);
+    run += padded;
+    a.cur[c] = 0;
+  }
+  if (tid == 1023) a.base[a.nlist] = part[1023];
+}
+
+// 8-byte look-up of a point's code in an interleaved table row (2 KiB per row): the byte
+// select of the sub-dword addressing form extracts the code and scales it by 8.
+__device__ __forceinline__ uint32_t code_offset8(uint32_t w, int j) {
+  uint32_t a;
+  const uint32_t three = 3u;
+  switch (j) {
+    case 0: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(a) : "s"(three), "v"(w)); break;
+    case 1: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(a) : "s"(three), "v"(w)); break;
+    case 2: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(a) : "s"(three), "v"(w)); break;
+    default: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(a) : "s"(three), "v"(w)); break;
+  }
+  return a;
+}
+
+// d0 += table value of query 0, d1 += that of query 1, for subspaces [h, h1) in subspace order;
+// the look-ups of a group are issued together and added afterwards (see lookup_group).
+template <int MT>
+__device__ __forceinline__ void lookup_group2(const CodeRegs<((MT + 3) / 4 * 4) / 4> &r, int h, int h1, float &d0,
+                                              float &d1) {
+  floatx2 t[LOOKUP_GROUP];
+#pragma unroll
+  for (int j = 0; j < LOOKUP_GROUP; ++j) {
+    const int m = h + j;
+    if (m < h1) {
+      // the table starts at LDS address 0 (no static LDS: checked when the kernel is prepared)
+      const uint32_t off = code_offset8(r.w[m >> 2], m & 3);
+      t[j] = *(const LDS floatx2 *)(uintptr_t)(uint32_t)(m * 2048 + off);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < LOOKUP_GROUP; ++j)
+    if (h + j < h1) {
+      d0 += t[j][0];
+      d1 += t[j][1];
+    }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Append a wavefront's queued candidates of one query to the query's buffer: `slot` is where
+// the buffer's counter stood when the wavefront reserved its n entries.
+__device__ __forceinline__ void lm_store(const LmArgs &a, int64_t q, uint32_t slot, LDS uint32_t *qd,
+                                         LDS uint32_t *qrow, int n, int lane) {
+  // past the capacity nothing is stored; the counter has grown all the same, which marks the
+  // query as overflowed
+  if (slot + (uint32_t)n <= (uint32_t)a.cap && lane < n)
+    a.cand[q * a.cap + slot + lane] = make_uint2(qd[lane], qrow[lane]);
+}
+
+__device__ __forceinline__ void lm_flush(const LmArgs &a, int64_t q, LDS uint32_t *qd, LDS uint32_t *qrow, int n,
+                                         int lane) {
+  uint32_t slot = 0;
+  if (lane == 0) slot = atomicAdd(&a.gcnt[q], (uint32_t)n);
+  slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)slot);
+  lm_store(a, q, slot, qd, qrow, n, lane);
+}
+
+// Offer a block's distances for one query: every valid point with distance <= tau is queued.
+__device__ __forceinline__ void lm_offer(const LmArgs &a, int64_t q, float dist, bool valid, uint32_t tau,
+                                         uint32_t row, LDS uint32_t *qd, LDS uint32_t *qrow, int &qcount, int lane) {
+  const uint32_t bits = __float_as_uint(dist);
+  const bool pass = valid && bits <= tau;
+  const unsigned long long bal = __ballot(pass);
+  if (bal == 0) return;
+  const int n = __popcll(bal);
+  if (qcount + n > LM_QUEUE) {
+    lm_flush(a, q, qd, qrow, qcount, lane);
+    qcount = 0;
+  }
+  if (pass) {
+    const int slot = qcount + __popcll(bal & ((1ull << lane) - 1ull));
+    qd[slot] = bits;
+    qrow[slot] = row;
+  }
+  qcount += n;
+}
+
+// One task: a list and the (up to) LM_G queries of a group that probe it.
+struct LmTask {
+  int32_t c;
+  int64_t q0, q1;      // q1 == q0 when the group is half empty (has1 false): its copy is dropped
+  bool has1;
+  int64_t row0;
+  int32_t len, nb;
+  const uint8_t *base;
+  uint32_t tau0, tau1;
+};
+
+// Persistent workgroups, one per CU.  Tasks are sorted by list; in every round the grid takes
+// the next gridDim.x tasks, and within a round the workgroups of one XCD (workgroup b runs on
+// XCD b % 8) take a run of consecutive tasks, so that the tasks which stream the same list's
+// codes share an L2.  Everything a task needs from global memory -- its pair entries, the
+// list's metadata, the two query rows, the centroid, the first code block -- is requested
+// while the task before it is still being scanned, so that a workgroup (the only one on its
+// CU: the interleaved table fills most of the LDS) does not sit idle through a chain of
+// dependent loads at every task boundary.
+template <int MT, int DSUB>
+__global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_NW / 4))) void lm_scan_kernel(LmArgs a, RadiiSq r2) {
+  constexpr int NW = LM_NW;
+  constexpr int MPT = (MT + 3) / 4 * 4;
+  constexpr int ITER = (MT + NW - 1) / NW;
+  constexpr int NCH = MPT / 16 + (MPT % 16) / 4;
+  extern __shared__ __align__(16) unsigned char smem[];
+  LDS unsigned char *smem3 = (LDS unsigned char *)smem;
+  const int D = a.D;   // LM_G * D <= NT and LM_G * MT <= NT: one element per thread (checked by the launcher)
+  const int dpad = (D + 3) & ~3;
+  // LDS carve: interleaved table [MT][256][2] | residuals [2][dpad] | r_m^2 [2][MAX_M] | queues
+  LDS float *lut = (LDS float *)smem3;
+  LDS float *sres = (LDS float *)(smem3 + MT * 2048);
+  LDS float *sr2 = sres + LM_G * dpad;
+  LDS uint32_t *queue = (LDS uint32_t *)(sr2 + LM_G * IVFPQ_MAX_M);  // [NW][G][2][LM_QUEUE]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  LDS uint32_t *qd0 = queue + (wave * LM_G + 0) * 2 * LM_QUEUE, *qrow0 = qd0 + LM_QUEUE;
+  LDS uint32_t *qd1 = queue + (wave * LM_G + 1) * 2 * LM_QUEUE, *qrow1 = qd1 + LM_QUEUE;
+
+  // this wavefront's codebook rows (rows wave, wave + NW, ...) stay in registers for the whole kernel
+  float4 cbr[ITER][DSUB];
+#pragma unroll
+  for (int it = 0; it < ITER; ++it) {
+    const int m = wave + it * NW;
+    const int mc = m < MT ? m : MT - 1;
+    const uint8_t *cb = uniform_ptr(reinterpret_cast<const uint8_t *>(a.codebooks + (int64_t)mc * 256 * DSUB));
+#pragma unroll
+    for (int x = 0; x < DSUB; ++x)
+      cbr[it][x] = *reinterpret_cast<const float4 *>(cb + (uint32_t)(lane * 16 * DSUB + 16 * x));
+  }
+
+  const int ntasks = a.base[a.nlist] / LM_G;
+  const int nwg = gridDim.x, b = blockIdx.x;
+  const int in_round = (nwg & 7) == 0 ? (b & 7) * (nwg >> 3) + (b >> 3) : b;
+
+  // what this thread contributes to a task's residuals and radii: element tid of [2][D] / [2][MT]
+  const int rg = tid >= D ? 1 : 0, rd = tid - rg * D;
+  const bool r_on = tid < LM_G * D;
+  const int mg = tid >= MT ? 1 : 0, mm = tid - mg * MT;
+  const bool m_on = tid < LM_G * MT;
+
+  // the pair entries of a task (scalar loads; consumed by fetch_task)
+  auto fetch_pairs = [&](int t, int2 &p0, int2 &p1) __attribute__((always_inline)) {
+    p0 = a.pairs[(int64_t)t * LM_G];
+    p1 = a.pairs[(int64_t)t * LM_G + 1];
+  };
+  // everything else a task needs, requested together: metadata, bounds, this thread's residual
+  // and radius element, the wavefront's first code block
+  auto fetch_task = [&](const int2 &p0, const int2 &p1, LmTask &tk, float &qv, float &cv, float &rv,
+                        CodeRegs<MPT / 4> &first) __attribute__((always_inline)) {
+    tk.c = __builtin_amdgcn_readfirstlane(p0.y);
+    tk.q0 = __builtin_amdgcn_readfirstlane(p0.x);
+    tk.has1 = __builtin_amdgcn_readfirstlane(p1.x) >= 0;
+    tk.q1 = tk.has1 ? __builtin_amdgcn_readfirstlane(p1.x) : tk.q0;
+    tk.row0 = a.list_offsets[tk.c];
+    tk.len = (int)(a.list_offsets[tk.c + 1] - tk.row0);
+    tk.nb = (tk.len + 63) >> 6;
+    tk.base = a.codes + a.list_blocks[tk.c] * ivfpq_block_bytes(MPT);
+    tk.tau0 = lm_tau_bits(a, tk.q0);
+    tk.tau1 = lm_tau_bits(a, tk.q1);
+    qv = cv = 0.0f;
+    if (r_on) {
+      qv = a.queries[(rg ? tk.q1 : tk.q0) * D + rd];
+      cv = a.centroids[(int64_t)tk.c * D + rd];
+    }
+    rv = 0.0f;
+    if (m_on) {
+      rv = r2.v[mm];
+      if (a.query_radii) {
+        const float r = a.query_radii[(mg ? tk.q1 : tk.q0) * MT + mm];
+        rv = r * r;
+      }
+    }
+    const int b0 = wave < tk.nb ? wave : tk.nb - 1;   // nb >= 1: only non-empty lists have tasks
+    load_chunks<MPT, 0, NCH>(tk.base, tk.nb, b0, lane, first);
+  };
+
+  LmTask tk;
+  float qv, cv, rv;
+  CodeRegs<MPT / 4> nxt;
+  int t = in_round;
+  if (t >= ntasks) return;
+  {
+    int2 p0, p1;
+    fetch_pairs(t, p0, p1);
+    fetch_task(p0, p1, tk, qv, cv, rv, nxt);
+  }
+  for (;;) {
+    if (r_on) sres[rg * dpad + rd] = qv - cv;
+    if (m_on) sr2[mg * IVFPQ_MAX_M + mm] = rv;
+    __syncthreads();
+    // ---- the two tables, interleaved: row m holds (query 0, query 1) of entry 0, of entry 1, ... ----
+    auto build_rows = [&](auto mode_tag) __attribute__((always_inline)) {
+      constexpr int MODE = decltype(mode_tag)::value;
+#pragma unroll
+      for (int it = 0; it < ITER; ++it) {
+        const int m = wave + it * NW;
+        if (m < MT) {
+          float res0[DSUB], res1[DSUB];
+#pragma unroll
+          for (int j = 0; j < DSUB; ++j) {
+            res0[j] = sres[m * DSUB + j];
+            res1[j] = sres[dpad + m * DSUB + j];
+          }
+          const float4 v0 = lut_entry4<DSUB, MODE>(res0, cbr[it], sr2[m]);
+          const float4 v1 = lut_entry4<DSUB, MODE>(res1, cbr[it], sr2[IVFPQ_MAX_M + m]);
+          LDS floatx4 *dst = (LDS floatx4 *)(lut + m * 512 + 8 * lane);
+          dst[0] = floatx4{v0.x, v1.x, v0.y, v1.y};
+          dst[1] = floatx4{v0.z, v1.z, v0.w, v1.w};
+        }
+      }
+    };
+    if (a.mode == 0) build_rows(std::integral_constant<int, 0>{});
+    else if (a.mode == 1) build_rows(std::integral_constant<int, 1>{});
+    else build_rows(std::integral_constant<int, 2>{});
+    // the next task's pair entries are on their way while this one is scanned
+    const int tn = t + nwg;
+    const bool more = tn < ntasks;
+    int2 np0 = make_int2(0, 0), np1 = make_int2(0, 0);
+    if (more) fetch_pairs(tn, np0, np1);
+    __syncthreads();
+    // ---- one pass over the list's codes serves both queries ----
+    int qc0 = 0, qc1 = 0;
+    const int last = tk.nb - 1;
+    for (int blk = wave; blk < tk.nb; blk += NW) {
+      CodeRegs<MPT / 4> cur = nxt;
+      const int bn = blk + NW < last ? blk + NW : last;
+      load_chunks<MPT, 0, NCH>(tk.base, tk.nb, bn, lane, nxt);   // past the end: re-reads the last block, in bounds
+      float d0 = 0.0f, d1 = 0.0f;
+#pragma unroll
+      for (int h = 0; h < MT; h += LOOKUP_GROUP) lookup_group2<MT>(cur, h, cmin(h + LOOKUP_GROUP, MT), d0, d1);
+      const int i = blk * 64 + lane;
+      const bool valid = i < tk.len;
+      const uint32_t row = (uint32_t)(tk.row0 + i);
+      lm_offer(a, tk.q0, d0, valid, tk.tau0, row, qd0, qrow0, qc0, lane);
+      if (tk.has1) lm_offer(a, tk.q1, d1, valid, tk.tau1, row, qd1, qrow1, qc1, lane);
+    }
+    // the rest of the next task's inputs is requested before this task's candidates are
+    // appended: both wait on the memory system at the same time
+    const LmTask done = tk;
+    if (more) fetch_task(np0, np1, tk, qv, cv, rv, nxt);
+    {
+      // one atomic instruction reserves the space of both queues: lane g for query g
+      uint32_t slot = 0;
+      const int n_mine = lane == 0 ? qc0 : (lane == 1 ? qc1 : 0);
+      if (n_mine > 0) slot = atomicAdd(&a.gcnt[lane == 0 ? done.q0 : done.q1], (uint32_t)n_mine);
+      const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)slot, 0);
+      const uint32_t s1 = (uint32_t)__builtin_amdgcn_readlane((int)slot, 1);
+      if (qc0 > 0) lm_store(a, done.q0, s0, qd0, qrow0, qc0, lane);
+      if (qc1 > 0) lm_store(a, done.q1, s1, qd1, qrow1, qc1, lane);
+    }
+    if (!more) break;
+    t = tn;
+    __syncthreads();  // every wavefront is done with the table and the residuals before the next task rewrites them
+  }
+}
+
+// One wavefront per query: the candidates of the list-major scan are merged into the top-k of
+// the first lists by (distance, id).  Queries whose buffer overflowed are handed to the
+// query-major kernel through qmap.
+__global__ __launch_bounds__(256) void lm_merge_kernel(LmArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (q >= a.Q) return;
+  const uint32_t n = a.gcnt[q];
+  const bool overflow = n > (uint32_t)a.cap;
+  if (lane == 0) a.qmap[q] = overflow ? (int32_t)q : -1;
+  if (overflow || n == 0) return;   // redone elsewhere / phase A's result stands
+  const int k = a.k;
+  Key L0, L1;
+  {
+    const int64_t o = q * k;
+    const bool in0 = lane < k, in1 = 64 + lane < k;
+    const int64_t id0 = in0 ? a.out_ids[o + lane] : -1, id1 = in1 ? a.out_ids[o + 64 + lane] : -1;
+    L0.d = id0 >= 0 ? __float_as_uint(a.out_dist[o + lane]) : SENT_D;
+    L0.id = id0 >= 0 ? id0 : SENT_ID;
+    L1.d = id1 >= 0 ? __float_as_uint(a.out_dist[o + 64 + lane]) : SENT_D;
+    L1.id = id1 >= 0 ? id1 : SENT_ID;
+  }
+  Key tau;
+  {
+    const Key t0 = bcast_key(L0, (k - 1) & 63), t1 = bcast_key(L1, (k - 1) & 63);
+    tau = (k - 1) < 64 ? t0 : t1;
+  }
+  for (uint32_t off = 0; off < n; off += 64) {
+    Key c;
+    c.d = SENT_D;
+    c.id = SENT_ID;
+    if (off + lane < n) {
+      const uint2 e = a.cand[q * a.cap + off + lane];
+      c.d = e.x;
+      c.id = a.ids[e.y];
+    }
+    const bool pass = kless(c, tau);
+    if (__ballot(pass) == 0) continue;
+    if (!pass) {
+      c.d = SENT_D;
+      c.id = SENT_ID;
+    }
+    wave_sort_desc<true>(c, lane);
+    wave_merge<true>(L0, L1, c, lane);
+    const Key t0 = bcast_key(L0, (k - 1) & 63), t1 = bcast_key(L1, (k - 1) & 63);
+    tau = (k - 1) < 64 ? t0 : t1;
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const Key e = h ? L1 : L0;
+    const int i = h * 64 + lane;
+    if (i < k) {
+      const bool real = e.d != SENT_D;
+      a.out_ids[q * k + i] = real ? e.id : -1;
+      a.out_dist[q * k + i] = real ? __uint_as_float(e.d) : __builtin_inff();
+    }
+  }
+}
+
+std::atomic<int> g_lm_first{2};     // lists per query that phase A scans query-major
+std::atomic<int> g_lm_cap{4096};    // candidate slots per query
+
+size_t lm_scan_lds(int M, int D) {
+  const int dpad = (D + 3) & ~3;
+  return (size_t)M * 2048 + (size_t)LM_G * dpad * 4 + (size_t)LM_G * IVFPQ_MAX_M * 4 +
+         (size_t)LM_NW * LM_G * 2 * LM_QUEUE * 4;
+}
+
+template <int MT, int DSUB>
+int launch_lm_scan_t(const LmArgs &a, const RadiiSq &r2, int grid, hipStream_t s) {
+  auto kern = lm_scan_kernel<MT, DSUB>;
+  static std::atomic<uint64_t> prepared;
+  if (int rc = prepare_kernel(kern, prepared)) return rc;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(LM_NW * 64), lm_scan_lds(MT, a.D), s, a, r2);
+  return IVFPQ_OK;
+}
+
+}  // namespace
+
+namespace ivfpq {
+
+void set_lm_first(int v) { g_lm_first.store(v, std::memory_order_relaxed); }
+void set_lm_cap(int v) { g_lm_cap.store(v, std::memory_order_relaxed); }
+
+bool list_major_supported(const ivfpq_index *ix, int32_t nprobe, int32_t k) {
+  if (ix->metric != IVFPQ_METRIC_L2 || k > KP) return false;
+  const bool shape = (ix->M == 48 && ix->dsub == 2) || (ix->M == 64 && ix->dsub == 2) || (ix->M == 16 && ix->dsub == 4);
+  if (!shape || lm_scan_lds(ix->M, ix->D) > (size_t)LDS_PER_CU || LM_G * ix->D > LM_NW * 64 || LM_G * ix->M > LM_NW * 64) return false;
+  return nprobe > g_lm_first.load(std::memory_order_relaxed);
+}
+
+static size_t lm_align(size_t v) { return (v + 255) & ~(size_t)255; }
+
+LmWorkspace plan_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe) {
+  LmWorkspace w;
+  w.first = g_lm_first.load(std::memory_order_relaxed);
+  w.cap = g_lm_cap.load(std::memory_order_relaxed);
+  w.pairs_cap = Q * (nprobe - w.first) + ix->nlist;
+  size_t off = 0;
+  w.cnt = off;   off += lm_align((size_t)ix->nlist * 4);
+  w.cur = off;   off += lm_align((size_t)ix->nlist * 4);
+  w.base = off;  off += lm_align(((size_t)ix->nlist + 1) * 4);
+  w.pairs = off; off += lm_align((size_t)w.pairs_cap * 8);
+  w.gcnt = off;  off += lm_align((size_t)Q * 4);
+  w.qmap = off;  off += lm_align((size_t)Q * 4);
+  w.cand = off;  off += lm_align((size_t)Q * w.cap * 8);
+  w.total = off;
+  return w;
+}
+
+int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                           const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t mode,
+                           const float *d_query_radii, float *d_probe_lb, int64_t *d_out_ids, float *d_out_dist,
+                           const LmWorkspace &w, char *lm_base, hipStream_t s) {
+  if (Q * (int64_t)nprobe > 0x7FFFFFFFll || w.pairs_cap > 0x7FFFFFFFll) {
+    set_error("scan (list-major): %lld (query, probe) pairs exceed 2^31", (long long)(Q * (int64_t)nprobe));
+    return IVFPQ_ERR_UNSUPPORTED;
+  }
+  // list-level lower bounds of every (query, probe), then phase A over the first lists of every query
+  int rc = launch_probe_bounds(ix, d_queries, Q, nprobe, d_probe_ids, r2, mode, d_query_radii, d_probe_lb, s);
+  if (rc) return rc;
+  ScanView head = {nprobe, nullptr, true};
+  rc = launch_scan(ix, d_queries, Q, w.first, d_probe_ids, k, r2, 1, nullptr, nullptr, d_out_ids, d_out_dist,
+                   nullptr, nullptr, nullptr, nullptr, mode, d_query_radii, d_probe_lb, s, &head);
+  if (rc) return rc;
+
+  LmArgs a;
+  a.queries = d_queries;
+  a.probe_ids = d_probe_ids;
+  a.probe_lb = (get_scan_ablate() & 64) ? nullptr : d_probe_lb;
+  a.centroids = ix->d_centroids;
+  a.codebooks = ix->d_codebooks;
+  a.list_offsets = ix->d_list_offsets;
+  a.list_blocks = ix->d_list_blocks;
+  a.codes = ix->d_codes;
+  a.ids = ix->d_ids;
+  a.out_ids = d_out_ids;
+  a.out_dist = d_out_dist;
+  a.cnt = reinterpret_cast<int32_t *>(lm_base + w.cnt);
+  a.cur = reinterpret_cast<int32_t *>(lm_base + w.cur);
+  a.base = reinterpret_cast<int32_t *>(lm_base + w.base);
+  a.pairs = reinterpret_cast<int2 *>(lm_base + w.pairs);
+  a.gcnt = reinterpret_cast<uint32_t *>(lm_base + w.gcnt);
+  a.cand = reinterpret_cast<uint2 *>(lm_base + w.cand);
+  a.qmap = reinterpret_cast<int32_t *>(lm_base + w.qmap);
+  a.query_radii = d_query_radii;
+  a.Q = Q;
+  a.D = ix->D; a.M = ix->M; a.dsub = ix->dsub; a.Mp = ix->Mp; a.nlist = ix->nlist;
+  a.nprobe = nprobe; a.first = w.first; a.k = k; a.cap = w.cap; a.mode = mode;
+
+  rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);
+  if (rc) return rc;
+  const int64_t npairs = Q * (nprobe - w.first);
+  const unsigned pair_grid = (unsigned)((npairs + 255) / 256);
+  hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 0);
+  hipLaunchKernelGGL(lm_offsets_kernel, dim3(1), dim3(1024), 0, s, a);
+  hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 1);
+  int dev = 0, cus = 0;
+  IVFPQ_HIP_TRY(hipGetDevice(&dev));
+  IVFPQ_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  if (cus < 1) cus = 1;
+  if (ix->M == 48) rc = launch_lm_scan_t<48, 2>(a, r2, cus, s);
+  else if (ix->M == 64) rc = launch_lm_scan_t<64, 2>(a, r2, cus, s);
+  else rc = launch_lm_scan_t<16, 4>(a, r2, cus, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(lm_merge_kernel, dim3((unsigned)((Q + 3) / 4)), dim3(256), 0, s, a);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  // queries whose candidate buffer overflowed: the query-major kernel over all of their probes
+  ScanView redo = {0, a.qmap, true};
+  return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, 1, nullptr, nullptr, d_out_ids, d_out_dist,
+                     nullptr, nullptr, nullptr, nullptr, mode, d_query_radii, d_probe_lb, s, &redo);
+}
+
+}  // namespace ivfpq

@@ -136,11 +136,16 @@ static void search_arguments() {
   REQUIRE(ivfpq_scan_topk(&ix, q, 4, 2, nullptr, 5, radii, ids, dist, ws_mem, need, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_scan_topk(&ix, q, 4, 2, pid, 5, radii, ids, nullptr, ws_mem, need, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_build_lut(&ix, q, 4, 2, pid, radii, nullptr, nullptr, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
-  { ivfpq_scoring sc = {7, nullptr};
+  { ivfpq_scoring sc = {7, nullptr, 0};
     REQUIRE(ivfpq_search_ex(&ix, q, 4, 2, 5, radii, &sc, ids, dist, ws_mem, need, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT); }
+  { ivfpq_scoring sc = {0, nullptr, 5};
+    REQUIRE(ivfpq_search_ex(&ix, q, 4, 2, 5, radii, &sc, ids, dist, ws_mem, need, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT); }
+  REQUIRE(ivfpq_set_option("lm_first", 0) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_set_option("lm_cap", 8) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_set_option("lm_first", 2) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK);
   REQUIRE(ivfpq_scan_all(&ix, q, 4, 2, pid, radii, nullptr, nullptr, nullptr, nullptr, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_ablate", 1) == IVFPQ_ERR_INVALID_ARGUMENT);   // result-changing bits are gone
-  REQUIRE(ivfpq_set_option("scan_ablate", 8 | 32 | 64) == IVFPQ_OK);
+  REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("scan_ablate", 0) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("scan_loads", 4) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_waves", 5) == IVFPQ_ERR_INVALID_ARGUMENT);

@@ -18,7 +18,7 @@ int launch_build_lut(const ivfpq_index *, const float *, int64_t, int32_t, const
                      float *, uint64_t *, int32_t, const float *, hipStream_t) { return reached("build_lut"); }
 int launch_scan(const ivfpq_index *, const float *, int64_t, int32_t, const int32_t *, int32_t, const RadiiSq &,
                 int32_t, uint32_t *, int64_t *, int64_t *, float *, const int64_t *, float *, int64_t *,
-                int32_t *, int32_t, const float *, float *, hipStream_t) { return reached("scan"); }
+                int32_t *, int32_t, const float *, float *, hipStream_t, const ScanView *) { return reached("scan"); }
 int launch_query_radii(const ivfpq_index *, const ivfpq_radius_model *, const float *, int64_t, const int32_t *,
                        int32_t, float, float *, hipStream_t) { return reached("query_radii"); }
 int launch_relayout(const ivfpq_index *, const uint8_t *, hipStream_t) { return reached("relayout"); }
@@ -26,6 +26,13 @@ int launch_list_boxes(const ivfpq_index *, const uint8_t *, hipStream_t) { retur
 int launch_iota(int64_t *, int64_t, hipStream_t) { return reached("iota"); }
 int launch_fill_i32(int32_t *, int64_t, int32_t, hipStream_t) { return reached("fill_i32"); }
 int coarse_fallbacks(int, unsigned int *out) { *out = 0; return IVFPQ_OK; }
+bool list_major_supported(const ivfpq_index *, int32_t, int32_t) { return false; }
+LmWorkspace plan_list_major(const ivfpq_index *, int64_t, int32_t) { return LmWorkspace(); }
+int launch_scan_list_major(const ivfpq_index *, const float *, int64_t, int32_t, const int32_t *, int32_t,
+                           const RadiiSq &, int32_t, const float *, float *, int64_t *, float *, const LmWorkspace &,
+                           char *, hipStream_t) { return reached("scan_list_major"); }
+void set_lm_first(int) {}
+void set_lm_cap(int) {}
 void set_scan_ablate(int) {}
 void set_scan_variant(int) {}
 void set_scan_waves(int) {}

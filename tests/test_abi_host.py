@@ -88,7 +88,7 @@ def test_header_is_plain_c():
         with open(src, "w") as f:
             f.write('#include "ivfpq.h"\n'
                     "int probe(const ivfpq_index *ix, const float *q, void *ws, size_t n) {\n"
-                    "  ivfpq_scoring sc = {IVFPQ_SCORE_DISTANCE, 0};\n"
+                    "  ivfpq_scoring sc = {IVFPQ_SCORE_DISTANCE, 0, IVFPQ_SCAN_AUTO};\n"
                     "  ivfpq_radius_model_desc md = {0};\n"
                     "  (void)md;\n"
                     "  return ivfpq_search_ex(ix, q, 1, 1, 1, 0, &sc, 0, 0, ws, n, 0);\n"

@@ -675,7 +675,7 @@ def test_pruning_switches_do_not_change_results(lib, shape):
         o_ids, o_dist = oracle.search(q, idx, nprobe, w.k, radii, threads=8)
         gi = b.IvfPqIndex.from_index(idx)
         try:
-            for ablate in (0, 8, 32, 64, 104):
+            for ablate in (0, 8, 16, 32, 64, 104, 88):
                 for loads in (0, 1, 2, 3):
                     b.set_option("scan_ablate", ablate)
                     b.set_option("scan_loads", loads)
@@ -776,6 +776,120 @@ def test_c1_full(lib):
     full_check(w, idx, q, radii, stages=False)
 
 
+def _lm_options(b, first=2, cap=4096):
+    b.set_option("lm_first", first)
+    b.set_option("lm_cap", cap)
+
+
+@pytest.mark.parametrize("family,D,M,sigma", [("sift", 128, 64, 20.0), ("deep", 96, 48, 0.1), ("gauss", 64, 16, 0.15)])
+def test_list_major_scan_matches_oracle(lib, family, D, M, sigma):
+    """The list-major batched scan (queries that probe a list share one pass over its codes,
+    two per interleaved table) returns the oracle's ids and distance bits: every shape it is
+    built for, thresholded and unthresholded, all three scorings, shared and per-query radii,
+    1 / 2 / 5 lists scanned query-major first, a candidate buffer so small that queries overflow
+    and are redone query-major, probe lists with invalid ids and empty lists (scan_topk), odd and
+    even numbers of queries per list, and batches down to one query."""
+    b = _binding()
+    w = wl.Workload(f"lm_{family}", 40_000, D, 48, M, 301, 12, 100, family, 96, sigma)
+    idx, centres = wl.train_index(w)
+    q = wl.queries(w, centres).numpy()
+    dq = _cuda(q)
+    gi = b.IvfPqIndex.from_index(idx)
+    LM = b.SCAN_LIST_MAJOR
+    try:
+        for radii in (wl.calibrate_radii(w, idx, centres, 0.25), np.full(M, np.inf, np.float32)):
+            o_ids, o_dist = oracle.search(q, idx, w.nprobe, w.k, radii, threads=8)
+            for first, cap in ((2, 2048), (1, 2048), (5, 4096), (2, 64)):
+                _lm_options(b, first, cap)
+                ids, dist = gi.search(dq, w.nprobe, w.k, radii, strategy=LM)
+                torch.cuda.synchronize()
+                assert np.array_equal(ids.cpu().numpy(), o_ids), (family, first, cap)
+                assert_same_float(dist.cpu().numpy(), o_dist, f"list-major {family} first={first} cap={cap}")
+            _lm_options(b)
+            # smaller batches (a single query: every task is half empty), other k
+            for Q, k in ((1, 100), (2, 7), (77, 128)):
+                ok_ids, ok_dist = oracle.search(q[:Q], idx, w.nprobe, k, radii, threads=8)
+                ids, dist = gi.search(_cuda(q[:Q]), w.nprobe, k, radii, strategy=LM)
+                assert np.array_equal(ids.cpu().numpy(), ok_ids), (family, Q, k)
+                assert_same_float(dist.cpu().numpy(), ok_dist, f"list-major {family} Q={Q} k={k}")
+        # hit-count scorings and per-query radii
+        shared = wl.calibrate_radii(w, idx, centres, 0.25)
+        rq = per_query_radii(w, idx, centres, q, 0.25)
+        for mode in (1, 2, 0):
+            for radii, d_rq in ((shared, None), (rq, _cuda(rq))):
+                o_ids, o_dist = oracle.search(q, idx, w.nprobe, w.k, radii, threads=8, mode=mode)
+                ids, dist = gi.search(dq, w.nprobe, w.k, shared if d_rq is None else None, mode=mode,
+                                      query_radii=d_rq, strategy=LM)
+                assert np.array_equal(ids.cpu().numpy(), o_ids), (family, mode, d_rq is not None)
+                assert_same_float(dist.cpu().numpy(), o_dist, f"list-major {family} mode {mode}")
+        # given probe lists: ids outside the index and empty lists count as empty probes; nprobe not above
+        # the lists scanned first falls back to the query-major scan
+        rng = np.random.default_rng(9)
+        pid = rng.integers(0, idx.nlist, size=(q.shape[0], 9)).astype(np.int32)
+        for row in pid:                       # distinct lists per row, as the filtering stage gives them
+            row[:] = rng.choice(idx.nlist, 9, replace=False)
+        ref = gi.scan_topk(dq, _cuda(pid), 50, shared)
+        pid_bad = pid.copy()
+        pid_bad[::3, 4] = -1
+        pid_bad[1::3, 7] = idx.nlist + 5
+        ref_bad = gi.scan_topk(dq, _cuda(pid_bad), 50, shared)
+        for p_arr, r in ((pid, ref), (pid_bad, ref_bad)):
+            got = gi.scan_topk(dq, _cuda(p_arr), 50, shared, strategy=LM)
+            assert torch.equal(got[0], r[0]) and torch.equal(got[1].view(torch.int32), r[1].view(torch.int32))
+        got = gi.scan_topk(dq, _cuda(pid[:, :2].copy()), 50, shared, strategy=LM)
+        r2 = gi.scan_topk(dq, _cuda(pid[:, :2].copy()), 50, shared)
+        assert torch.equal(got[0], r2[0]) and torch.equal(got[1].view(torch.int32), r2[1].view(torch.int32))
+        # run twice: bitwise identical (the order in which pairs and candidates land is not fixed, the result is)
+        a1 = gi.search(dq, w.nprobe, w.k, shared, strategy=LM)
+        a2 = gi.search(dq, w.nprobe, w.k, shared, strategy=LM)
+        assert torch.equal(a1[0], a2[0]) and torch.equal(a1[1], a2[1])
+        # a workspace sized for the query-major scan is refused before anything runs
+        small = gi.workspace(q.shape[0], w.nprobe, w.k)
+        with pytest.raises(b.IvfpqError) as e:
+            gi.search(dq, w.nprobe, w.k, shared, workspace=small, strategy=LM)
+        assert e.value.status == b.ERR_WORKSPACE
+    finally:
+        _lm_options(b)
+        gi.close()
+
+
+def test_list_major_request_on_unsupported_shapes_is_served_query_major(lib):
+    """Inner-product indexes, k above 128 and shapes the list-major kernel is not built for
+    take the query-major path whatever the strategy says; results are the oracle's."""
+    b = _binding()
+    rng = np.random.default_rng(21)
+    sizes = [0, 1, 63, 64, 65, 0, 130, 700, 5, 1500, 64 * 9, 0, 333, 2, 127, 129]
+    for M, D, metric, k in ((100, 200, 0, 50), (12, 12, 0, 50), (64, 128, 1, 50), (64, 128, 0, 200)):
+        idx = _random_index(rng, 0, D, len(sizes), M, sizes)
+        q = rng.normal(size=(33, D)).astype(np.float32)
+        r = np.full(M, 0.9 * np.sqrt(D / M), dtype=np.float32)
+        gi = b.IvfPqIndex.from_index(idx, metric=metric)
+        o_ids, o_dist = oracle.search(q, idx, 6, k, r, threads=8, metric=metric)
+        ids, dist = gi.search(_cuda(q), 6, k, r, strategy=b.SCAN_LIST_MAJOR)
+        assert np.array_equal(ids.cpu().numpy(), o_ids), (M, D, metric, k)
+        assert_same_float(dist.cpu().numpy(), o_dist, f"M={M} metric={metric} k={k}")
+        gi.close()
+
+
+def test_list_major_ragged_lists(lib):
+    """Hand-made list sizes (empty, one point, one block, a block and a point, long), every list
+    probed, so that tasks see every block count; 64- and 48-subspace shapes."""
+    b = _binding()
+    for M, D in ((64, 128), (48, 96), (16, 64)):
+        rng = np.random.default_rng(M)
+        sizes = [0, 1, 63, 64, 65, 0, 130, 700, 5, 1500, 64 * 9, 0, 333, 2, 127, 129, 64 * 17 + 1]
+        idx = _random_index(rng, 0, D, len(sizes), M, sizes)
+        q = rng.normal(size=(45, D)).astype(np.float32)
+        gi = b.IvfPqIndex.from_index(idx)
+        for r in (np.full(M, 0.9 * np.sqrt(D / M), dtype=np.float32), np.full(M, np.inf, np.float32)):
+            for nprobe, k in ((idx.nlist, 128), (6, 100), (3, 1)):
+                o_ids, o_dist = oracle.search(q, idx, nprobe, k, r, threads=8)
+                ids, dist = gi.search(_cuda(q), nprobe, k, r, strategy=b.SCAN_LIST_MAJOR)
+                assert np.array_equal(ids.cpu().numpy(), o_ids), (M, nprobe, k)
+                assert_same_float(dist.cpu().numpy(), o_dist, f"ragged M={M} nprobe={nprobe} k={k}")
+        gi.close()
+
+
 ORACLE_THREADS = 16   # the GPU box gives a job 16 host cores
 
 
@@ -804,6 +918,11 @@ def test_full_size_configs_sampled_queries(lib, name):
         assert np.array_equal(ids.cpu().numpy()[sample], o_ids), (name, frac)
         assert_same_float(dist.cpu().numpy()[sample], o_dist, f"{name} keep={frac}")
         say(f"  {name} keep={frac}: {len(sample)} sampled queries match the oracle")
+        if name in ("C2", "C3"):   # the list-major scan of the same batch: the same bits
+            ids_l, dist_l = gi.search(dq, w.nprobe, w.k, radii, strategy=b.SCAN_LIST_MAJOR)
+            torch.cuda.synchronize()
+            assert torch.equal(ids_l, ids) and torch.equal(dist_l.view(torch.int32), dist.view(torch.int32)), (name, frac)
+            say(f"  {name} keep={frac}: the list-major scan gives the same {w.Q} x {w.k} results")
     # properties that hold for every query at full size
     ids_np, dist_np = ids.cpu().numpy(), dist.cpu().numpy()
     assert np.all(np.diff(dist_np, axis=1) >= 0) and ids_np.min() >= 0 and ids_np.max() < w.N
