@@ -96,7 +96,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
 
     Q, nprobe, k = w.Q, w.nprobe, (args.k or w.k)
     passes = (k + 127) // 128   # the scan kernel keeps 128 keys per query and launch
-    strategy = binding.SCAN_LIST_MAJOR if args.strategy == "list-major" else binding.SCAN_AUTO
+    strategy = {"auto": binding.SCAN_AUTO, "query-major": binding.SCAN_QUERY_MAJOR, "list-major": binding.SCAN_LIST_MAJOR}[args.strategy]
     ws = gi.workspace(Q, nprobe, k, strategy)
     pid = torch.empty((Q, nprobe), dtype=torch.int32, device="cuda")
     out = (torch.empty((Q, k), dtype=torch.int64, device="cuda"), torch.empty((Q, k), dtype=torch.float32, device="cuda"))
@@ -164,7 +164,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
         out_p = (torch.empty_like(out[0]), torch.empty_like(out[1]))
         binding.set_option("scan_ablate", PLAIN_SCAN)
         binding.set_option("scan_loads", 1)
-        plain_strategy[0] = binding.SCAN_AUTO
+        plain_strategy[0] = binding.SCAN_QUERY_MAJOR
         try:
             step(outputs=out_p)
             _, plain_ms, _ = timed(plain_steps, out_p)
@@ -269,9 +269,10 @@ def main():
     ap.add_argument("--radius-target", choices=["top", "keep"], default="top",
                     help="what the offline polynomial is fitted to: the radius that contains the entries of the true "
                          "top-100 neighbours (the paper's), or the radius that keeps --keep of the entries")
-    ap.add_argument("--strategy", choices=["query-major", "list-major"], default="query-major",
+    ap.add_argument("--strategy", choices=["auto", "query-major", "list-major"], default="auto",
                     help="how stages 2-4 walk the (query, list) pairs; list-major: queries that probe a list share "
-                         "one pass over its codes (for data without cluster structure, e.g. C3)")
+                         "one pass over its codes; auto (default): the library's choice (list-major on the "
+                         "1M- and 10M-point workloads, query-major on the 100M-point one)")
     ap.add_argument("--lm-first", type=int, default=0, help="list-major: lists per query scanned query-major first (0: the library's default)")
     ap.add_argument("--lm-cap", type=int, default=0, help="list-major: candidate slots per query (0: the library's default)")
     ap.add_argument("--scan-waves", type=int, default=0)
@@ -326,7 +327,7 @@ def main():
 
     # The second half of the metric -- the ADC scan's HBM rate against the peak -- is quoted on the
     # 100M-point workload (6.4 GB of codes: the only one that no cache holds).  The default run adds it.
-    default_run = (args.workload == "C2" and args.strategy == "query-major" and not args.no_c5 and k == 100 and not metric and args.score_mode == 0
+    default_run = (args.workload == "C2" and args.strategy == "auto" and not args.no_c5 and k == 100 and not metric and args.score_mode == 0
                    and not args.dynamic_radii and not args.scan_loads and not args.scan_ablate and not args.scan_waves)
     if default_run:
         r5 = run_workload(args, "C5", 5, 2, 0.0 if args.no_cpu_baseline else 4.0, 3)

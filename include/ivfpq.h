@@ -109,7 +109,8 @@ int ivfpq_index_create(const ivfpq_index_desc *desc, ivfpq_index **out);
 void ivfpq_index_destroy(ivfpq_index *index);
 
 /* Bytes of device workspace the search-side calls need for a batch of Q
- * queries (0 on invalid arguments).  The workspace must be 256-byte aligned. */
+ * queries (0 on invalid arguments), with the scan strategy left to the library.
+ * The workspace must be 256-byte aligned. */
 size_t ivfpq_search_workspace_bytes(const ivfpq_index *index, int64_t Q, int32_t nprobe, int32_t k);
 
 /* The whole search path (stages 1-4) for a batch.
@@ -207,22 +208,27 @@ typedef enum {
 
 /* How stages 2-4 walk the (query, probed list) pairs.  Results do not depend on it.
  *   IVFPQ_SCAN_QUERY_MAJOR  one workgroup per query scans the query's lists nearest first and
- *     prunes against its running k-th distance (the default; best where lists differ in
- *     how much they can contribute, i.e. on clustered data).
+ *     prunes against its running k-th distance (per list, per block of 64 points, per partial
+ *     sum).  Best on long lists.
  *   IVFPQ_SCAN_LIST_MAJOR   the CDNA4 counterpart of the paper's entry -> points map
  *     (Sec. 5.2, Algorithm 1; Sec. 5.3): the queries that selected a list are served together,
  *     two per pass over the list's codes, with their tables interleaved so that one look-up
- *     serves both; the first lists of a query are still scanned query-major and give the
- *     bound that filters the rest.  Best where nothing can be pruned (no cluster structure).
+ *     serves both.  The nearest list of every query is ranked first (its k-th distance is the
+ *     bound that filters the query's other lists).  Best where the per-query fixed costs or
+ *     the look-up rate dominate: short lists, data without cluster structure.
  *     Needs the L2 metric, k <= 128 and an (M, dsub) of (48, 2), (64, 2) or (16, 4); any other
- *     call is served query-major.  Takes a larger workspace: size it with
- *     ivfpq_search_workspace_bytes_ex. */
+ *     call is served query-major.  Takes a larger workspace.
+ *   IVFPQ_SCAN_AUTO         the library chooses: list-major where it is available, for
+ *     distance scoring, when the batch has at least 16 384 (query, list) pairs and the index's
+ *     mean list length is at most 4096; query-major otherwise.
+ * ivfpq_search_workspace_bytes sizes the workspace for AUTO with distance scoring;
+ * ivfpq_search_workspace_bytes_ex for the scoring actually passed. */
 typedef enum { IVFPQ_SCAN_AUTO = 0, IVFPQ_SCAN_QUERY_MAJOR = 1, IVFPQ_SCAN_LIST_MAJOR = 2 } ivfpq_scan_strategy;
 
 typedef struct {
   int32_t mode;               /* an ivfpq_score_mode                              */
   const float *d_query_radii; /* device [Q][M], or NULL for the shared host radii */
-  int32_t strategy;           /* an ivfpq_scan_strategy; AUTO is QUERY_MAJOR       */
+  int32_t strategy;           /* an ivfpq_scan_strategy                            */
 } ivfpq_scoring;
 
 /* Workspace bytes for the *_ex calls with this scoring (the strategy decides). */
@@ -318,8 +324,10 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  *                  subspaces) of a block ahead and the rest only when the block needs it, whole
  *                  blocks once pruning has been switched off for a query; 1 always whole blocks;
  *                  2 / 3 always the first half / the first chunk ahead.
- *   "lm_first"     list-major scan: probed lists per query that are scanned query-major first
- *                  (1 .. 64, default 2); they give the bound that filters the other lists.
+ *   "lm_first"     list-major scan: probed lists per query that are ranked first (1 .. 64,
+ *                  default 1); their k-th distance is the bound that filters the other lists.
+ *                  1: the nearest list is ranked list-major as well (queries that share it
+ *                  share its pass); more: those lists are scanned query-major.
  *   "lm_cap"       list-major scan: candidate slots per query (64 .. 65536, default 4096); a
  *                  query that overflows them is redone query-major.  Set both before sizing
  *                  the workspace.

@@ -126,6 +126,20 @@ static int check_workspace(const Workspace &w, const void *ws, size_t bytes, con
   return IVFPQ_OK;
 }
 
+// Which way stages 2-4 run.  A request for the list-major scan is honoured where that scan is
+// built (L2, k <= 128, the specialised shapes), anything else runs query-major.  Left to the
+// library (AUTO), the list-major scan serves distance scoring on batches with enough (query,
+// list) pairs to group, over indexes whose lists are short: there the per-query fixed costs
+// of the query-major kernel dominate, while long lists (the 100M-point configuration) gain
+// more from its per-block pruning.  Measured: faster on every 1M-point workload and on the
+// 10M-point one, four times slower on the 100M-point one.
+static bool use_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k, int32_t mode,
+                           int32_t requested) {
+  if (requested == IVFPQ_SCAN_QUERY_MAJOR || !list_major_supported(ix, nprobe, k)) return false;
+  if (requested == IVFPQ_SCAN_LIST_MAJOR) return true;
+  return mode == IVFPQ_SCORE_DISTANCE && Q * (int64_t)nprobe >= 16384 && ix->N <= (int64_t)4096 * ix->nlist;
+}
+
 }  // namespace ivfpq
 
 using namespace ivfpq;
@@ -428,19 +442,17 @@ int ivfpq_query_radii(const ivfpq_index *ix, const ivfpq_radius_model *md, const
 }
 
 size_t ivfpq_search_workspace_bytes(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k) {
-  if (!ix || Q < 0 || nprobe < 1 || nprobe > ix->nlist || k < 1) return 0;
-  const Workspace w = plan_workspace(ix, Q, nprobe, k);
-  return w.total < 256 ? 256 : w.total;
+  return ivfpq_search_workspace_bytes_ex(ix, Q, nprobe, k, nullptr);
 }
 
 size_t ivfpq_search_workspace_bytes_ex(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k,
                                        const ivfpq_scoring *sc) {
-  size_t n = ivfpq_search_workspace_bytes(ix, Q, nprobe, k);
-  if (n && sc && sc->strategy == IVFPQ_SCAN_LIST_MAJOR && list_major_supported(ix, nprobe, k)) {
-    const Workspace w = plan_workspace(ix, Q, nprobe, k);
+  if (!ix || Q < 0 || nprobe < 1 || nprobe > ix->nlist || k < 1) return 0;
+  const Workspace w = plan_workspace(ix, Q, nprobe, k);
+  size_t n = w.total;
+  if (use_list_major(ix, Q, nprobe, k, sc ? sc->mode : IVFPQ_SCORE_DISTANCE, sc ? sc->strategy : IVFPQ_SCAN_AUTO))
     n = align256(w.total) + plan_list_major(ix, Q, nprobe).total;
-  }
-  return n;
+  return n < 256 ? 256 : n;
 }
 
 int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
@@ -464,7 +476,7 @@ static int unpack_scoring(const ivfpq_index *ix, const ivfpq_scoring *sc, const 
                           int32_t *strategy = nullptr) {
   *mode = IVFPQ_SCORE_DISTANCE;
   *d_query_radii = nullptr;
-  if (strategy) *strategy = IVFPQ_SCAN_QUERY_MAJOR;
+  if (strategy) *strategy = IVFPQ_SCAN_AUTO;
   if (sc) {
     if (sc->mode < IVFPQ_SCORE_DISTANCE || sc->mode > IVFPQ_SCORE_HIT_REWARD) {
       set_error("%s: scoring mode %d unknown", fn, sc->mode);
@@ -476,7 +488,7 @@ static int unpack_scoring(const ivfpq_index *ix, const ivfpq_scoring *sc, const 
     }
     *mode = sc->mode;
     *d_query_radii = sc->d_query_radii;
-    if (strategy && sc->strategy == IVFPQ_SCAN_LIST_MAJOR) *strategy = IVFPQ_SCAN_LIST_MAJOR;
+    if (strategy) *strategy = sc->strategy;
   }
   if (*d_query_radii) {  // per-query radii replace the shared ones
     memset(r2, 0, sizeof *r2);
@@ -538,7 +550,7 @@ int ivfpq_scan_topk_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q,
   if (!d_probe_ids || !d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
   char *base = static_cast<char *>(ws);
-  if (strategy == IVFPQ_SCAN_LIST_MAJOR && list_major_supported(ix, nprobe, k))
+  if (use_list_major(ix, Q, nprobe, k, mode, strategy))
     return scan_list_major(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, ws,
                            ws_bytes, static_cast<hipStream_t>(stream), fn);
   if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
@@ -641,7 +653,7 @@ int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
   if (Q == 0) return IVFPQ_OK;
   if (!d_out_ids || !d_out_dist) { set_error("%s: NULL pointer", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   const Workspace w = plan_workspace(ix, Q, nprobe, k);
-  if (strategy == IVFPQ_SCAN_LIST_MAJOR && list_major_supported(ix, nprobe, k)) {
+  if (use_list_major(ix, Q, nprobe, k, mode, strategy)) {
     Workspace both = w;
     both.total = align256(w.total) + plan_list_major(ix, Q, nprobe).total;
     if ((rc = check_workspace(both, ws, ws_bytes, fn))) return rc;   // before anything is enqueued

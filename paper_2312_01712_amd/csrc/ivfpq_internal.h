@@ -109,6 +109,7 @@ struct LmWorkspace {      // offsets into the list-major part of the workspace, 
   size_t cnt, cur, base;  // [nlist], [nlist], [nlist+1] int32
   size_t pairs;           // [pairs_cap] (query, list) int32 pairs bucketed by list
   size_t gcnt, qmap;      // [Q] uint32 / int32
+  size_t qmap_head;       // [Q] int32
   size_t cand;            // [Q][cap] (distance bits, row) candidates of the list-major scan
   size_t total;
   int64_t pairs_cap;

@@ -34,6 +34,9 @@ namespace {
 constexpr int LM_G = 2;        // queries per group (interleaved tables, 8-byte look-ups)
 constexpr int LM_NW = 8;       // wavefronts per workgroup: one workgroup per CU (the table fills most of its LDS), 2 per SIMD, 256 registers each
 constexpr int LM_QUEUE = 64;   // accepted candidates a wavefront holds per query before it appends them
+constexpr int LM_SEL_WORDS = 16;     // head pass: small LDS block of selection state
+constexpr int LM_BINS = 2048;        // head pass: bins of the selection histogram
+constexpr int LM_COLLECT = 128;      // head pass: candidates a query may collect (the sorted list of a wavefront)
 
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
@@ -56,6 +59,8 @@ struct LmArgs {
   uint32_t *gcnt;               // [Q] candidates appended (may run past cap: the query then counts as overflowed)
   uint2 *cand;                  // [Q][cap] (distance bits, row in the index)
   int32_t *qmap;                // [Q] out: q for a query to be redone query-major, -1 otherwise
+  int32_t *qmap_head;           // [Q] head pass: q for a query whose nearest list is left to the query-major kernel, else -1
+  int32_t head_max;             // head pass: longest list (points) whose distances fit the workgroup's LDS
   const float *query_radii;     // [Q][M] or NULL
   int64_t Q;
   int32_t D, M, dsub, Mp, nlist, nprobe, first, k, cap, mode;
@@ -70,17 +75,26 @@ __device__ inline uint32_t lm_tau_bits(const LmArgs &a, int64_t q) {
 // One thread per (query, probe >= first).  fill == 0: count the surviving pairs of every list
 // (and clear the query's candidate count); fill == 1: write them to the list's slot range.
 // Both passes evaluate the same predicate on the same data.
-__global__ __launch_bounds__(256) void lm_pairs_kernel(LmArgs a, int fill) {
-  const int np2 = a.nprobe - a.first;
+// head == 1 (the head pass): one thread per query, the pair is (query, its nearest list); a
+// query whose nearest list is missing, empty or too long for the head pass is handed to the
+// query-major kernel through qmap_head instead.
+__global__ __launch_bounds__(256) void lm_pairs_kernel(LmArgs a, int fill, int head) {
+  const int np2 = head ? 1 : a.nprobe - a.first;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= a.Q * np2) return;
   const int64_t q = idx / np2;
-  const int p = a.first + (int)(idx % np2);
-  if (!fill && p == a.first) a.gcnt[q] = 0u;
+  const int p = head ? 0 : a.first + (int)(idx % np2);
+  if (!head && !fill && p == a.first) a.gcnt[q] = 0u;
   const int32_t c = a.probe_ids[q * a.nprobe + p];
-  if ((uint32_t)c >= (uint32_t)a.nlist) return;
-  if (a.list_offsets[c + 1] - a.list_offsets[c] <= 0) return;
-  if (a.probe_lb) {
+  const bool exists = (uint32_t)c < (uint32_t)a.nlist;
+  const int64_t len = exists ? a.list_offsets[c + 1] - a.list_offsets[c] : 0;
+  if (head) {
+    const bool ok = len > 0 && len <= a.head_max;
+    if (!fill) a.qmap_head[q] = ok ? -1 : (int32_t)q;
+    if (!ok) return;
+  }
+  if (len <= 0) return;
+  if (!head && a.probe_lb) {
     // no point of the list can reach the k-th distance that phase A already guarantees
     const float tau = a.out_dist[q * a.k + a.k - 1];
     if (a.probe_lb[q * a.nprobe + p] > tau) return;
@@ -199,6 +213,50 @@ __device__ __forceinline__ void lm_offer(const LmArgs &a, int64_t q, float dist,
   qcount += n;
 }
 
+// ---- head pass: exact top-k of ONE list per query, without a bound to filter by ----------
+// The nearest list of a query has to be ranked in full.  Its distances (bit patterns of
+// non-negative floats, which order like the values) are kept in LDS; a histogram of 2048
+// bins over the range they span finds the bin of the k-th smallest, everything up to that
+// bin is collected (k keys plus the few that share the last bin) and a rank sort over the
+// collected keys puts them in (distance, id) order.  More than LM_COLLECT collected keys
+// (masses of equal distances) hand the query to the query-major kernel.
+
+// bin b of a histogram lives at word (b % 32) * 64 + b / 32, so that lane l, which owns the 32
+// consecutive bins 32 l .. 32 l + 31, reads them without bank conflicts
+__device__ __forceinline__ uint32_t lds_add(LDS uint32_t *p) {   // LDS atomic increment, returns the old value
+  return __hip_atomic_fetch_add(p, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ int lm_hidx(uint32_t bin) { return (int)(((bin & 31u) << 6) | (bin >> 5)); }
+
+// One wavefront: the bin that holds the need-th smallest key (need >= 1, at most the number
+// of keys counted) and the number of keys in the bins below it.
+__device__ inline void lm_find_bin(const LDS uint32_t *hist, uint32_t need, int lane, uint32_t &bin, uint32_t &below) {
+  uint32_t sum = 0;
+  for (int j = 0; j < 32; ++j) sum += hist[j * 64 + lane];
+  uint32_t incl = sum;
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
+    if (lane >= off) incl += v;
+  }
+  const uint32_t excl = incl - sum;
+  const bool mine = excl < need && need <= incl;   // exactly one lane
+  uint32_t b = 0, bl = 0, run = excl;
+  if (mine) {
+    for (int j = 0; j < 32; ++j) {
+      const uint32_t c = hist[j * 64 + lane];
+      if (run < need && need <= run + c) {
+        b = 32u * lane + j;
+        bl = run;
+      }
+      run += c;
+    }
+  }
+  const unsigned long long bal = __ballot(mine);
+  const int src = bal ? __ffsll((long long)bal) - 1 : 0;
+  bin = (uint32_t)__shfl((int)b, src);
+  below = (uint32_t)__shfl((int)bl, src);
+}
+
 // One task: a list and the (up to) LM_G queries of a group that probe it.
 struct LmTask {
   int32_t c;
@@ -218,7 +276,10 @@ struct LmTask {
 // while the task before it is still being scanned, so that a workgroup (the only one on its
 // CU: the interleaved table fills most of the LDS) does not sit idle through a chain of
 // dependent loads at every task boundary.
-template <int MT, int DSUB>
+// HEAD: the head pass -- a task's list is the nearest list of its queries; no bound exists yet,
+// every distance is kept (in LDS) and the exact top-k of the list is selected per query and
+// written to the query's output row, where the main pass and the merge find it.
+template <int MT, int DSUB, bool HEAD>
 __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_NW / 4))) void lm_scan_kernel(LmArgs a, RadiiSq r2) {
   constexpr int NW = LM_NW;
   constexpr int MPT = (MT + 3) / 4 * 4;
@@ -232,24 +293,36 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   LDS float *lut = (LDS float *)smem3;
   LDS float *sres = (LDS float *)(smem3 + MT * 2048);
   LDS float *sr2 = sres + LM_G * dpad;
-  LDS uint32_t *queue = (LDS uint32_t *)(sr2 + LM_G * IVFPQ_MAX_M);  // [NW][G][2][LM_QUEUE]
+  LDS uint32_t *queue = (LDS uint32_t *)(sr2 + LM_G * IVFPQ_MAX_M);  // main pass: [NW][G][2][LM_QUEUE]
+  // head pass: selection state, then the distances [2][head_max]; the histograms and the
+  // collected keys use the table's LDS once the list has been scanned
+  LDS uint32_t *ssel = queue;                      // [LM_SEL_WORDS]
+  LDS uint32_t *sdist = queue + LM_SEL_WORDS;      // [2][head_max]
+  LDS uint32_t *hist = (LDS uint32_t *)smem3;      // [2][LM_BINS]
+  LDS uint32_t *coll_d = hist + LM_G * LM_BINS;    // [2][LM_COLLECT] collected keys: distance bits ...
+  LDS uint32_t *coll_rank = coll_d + LM_G * LM_COLLECT;   // ... their positions in sorted order ...
+  LDS int64_t *coll_id = (LDS int64_t *)(coll_rank + LM_G * LM_COLLECT);   // ... and ids
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   LDS uint32_t *qd0 = queue + (wave * LM_G + 0) * 2 * LM_QUEUE, *qrow0 = qd0 + LM_QUEUE;
   LDS uint32_t *qd1 = queue + (wave * LM_G + 1) * 2 * LM_QUEUE, *qrow1 = qd1 + LM_QUEUE;
 
-  // this wavefront's codebook rows (rows wave, wave + NW, ...) stay in registers for the whole kernel
-  float4 cbr[ITER][DSUB];
-#pragma unroll
-  for (int it = 0; it < ITER; ++it) {
+  // this wavefront's codebook rows (rows wave, wave + NW, ...) stay in registers for the whole
+  // kernel; the head pass at 64 subspaces has no registers left for the last two of its eight
+  // rows and fetches those (from the L2) when a task's table is built
+  constexpr int RES = (HEAD && ITER > 6) ? 6 : ITER;
+  float4 cbr[RES][DSUB];
+  auto load_row = [&](int it, float4 (&row)[DSUB]) __attribute__((always_inline)) {
     const int m = wave + it * NW;
     const int mc = m < MT ? m : MT - 1;
     const uint8_t *cb = uniform_ptr(reinterpret_cast<const uint8_t *>(a.codebooks + (int64_t)mc * 256 * DSUB));
 #pragma unroll
     for (int x = 0; x < DSUB; ++x)
-      cbr[it][x] = *reinterpret_cast<const float4 *>(cb + (uint32_t)(lane * 16 * DSUB + 16 * x));
-  }
+      row[x] = *reinterpret_cast<const float4 *>(cb + (uint32_t)(lane * 16 * DSUB + 16 * x));
+  };
+#pragma unroll
+  for (int it = 0; it < RES; ++it) load_row(it, cbr[it]);
 
   const int ntasks = a.base[a.nlist] / LM_G;
   const int nwg = gridDim.x, b = blockIdx.x;
@@ -278,8 +351,8 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     tk.len = (int)(a.list_offsets[tk.c + 1] - tk.row0);
     tk.nb = (tk.len + 63) >> 6;
     tk.base = a.codes + a.list_blocks[tk.c] * ivfpq_block_bytes(MPT);
-    tk.tau0 = lm_tau_bits(a, tk.q0);
-    tk.tau1 = lm_tau_bits(a, tk.q1);
+    tk.tau0 = HEAD ? 0u : lm_tau_bits(a, tk.q0);
+    tk.tau1 = HEAD ? 0u : lm_tau_bits(a, tk.q1);
     qv = cv = 0.0f;
     if (r_on) {
       qv = a.queries[(rg ? tk.q1 : tk.q0) * D + rd];
@@ -310,22 +383,28 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   for (;;) {
     if (r_on) sres[rg * dpad + rd] = qv - cv;
     if (m_on) sr2[mg * IVFPQ_MAX_M + mm] = rv;
+    if (HEAD && tid < LM_SEL_WORDS)   // [0..1] keys collected, [2..3] bin of the k-th key, [4..5] smallest key, [6..7] largest key
+      ssel[tid] = (tid == 4 || tid == 5) ? 0xFFFFFFFFu : 0u;
     __syncthreads();
     // ---- the two tables, interleaved: row m holds (query 0, query 1) of entry 0, of entry 1, ... ----
     auto build_rows = [&](auto mode_tag) __attribute__((always_inline)) {
       constexpr int MODE = decltype(mode_tag)::value;
+      float4 cbs[ITER > RES ? ITER - RES : 1][DSUB];   // streamed rows, requested together
+#pragma unroll
+      for (int it = RES; it < ITER; ++it) load_row(it, cbs[it - RES]);
 #pragma unroll
       for (int it = 0; it < ITER; ++it) {
         const int m = wave + it * NW;
         if (m < MT) {
+          const float4 *row = it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0];
           float res0[DSUB], res1[DSUB];
 #pragma unroll
           for (int j = 0; j < DSUB; ++j) {
             res0[j] = sres[m * DSUB + j];
             res1[j] = sres[dpad + m * DSUB + j];
           }
-          const float4 v0 = lut_entry4<DSUB, MODE>(res0, cbr[it], sr2[m]);
-          const float4 v1 = lut_entry4<DSUB, MODE>(res1, cbr[it], sr2[IVFPQ_MAX_M + m]);
+          const float4 v0 = lut_entry4<DSUB, MODE>(res0, row, sr2[m]);
+          const float4 v1 = lut_entry4<DSUB, MODE>(res1, row, sr2[IVFPQ_MAX_M + m]);
           LDS floatx4 *dst = (LDS floatx4 *)(lut + m * 512 + 8 * lane);
           dst[0] = floatx4{v0.x, v1.x, v0.y, v1.y};
           dst[1] = floatx4{v0.z, v1.z, v0.w, v1.w};
@@ -343,6 +422,7 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     __syncthreads();
     // ---- one pass over the list's codes serves both queries ----
     int qc0 = 0, qc1 = 0;
+    uint32_t mn0 = 0xFFFFFFFFu, mn1 = 0xFFFFFFFFu, mx0 = 0u, mx1 = 0u;   // head pass: key range of this wavefront's points
     const int last = tk.nb - 1;
     for (int blk = wave; blk < tk.nb; blk += NW) {
       CodeRegs<MPT / 4> cur = nxt;
@@ -354,14 +434,125 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
       const int i = blk * 64 + lane;
       const bool valid = i < tk.len;
       const uint32_t row = (uint32_t)(tk.row0 + i);
-      lm_offer(a, tk.q0, d0, valid, tk.tau0, row, qd0, qrow0, qc0, lane);
-      if (tk.has1) lm_offer(a, tk.q1, d1, valid, tk.tau1, row, qd1, qrow1, qc1, lane);
+      if constexpr (HEAD) {
+        if (valid) {
+          const uint32_t k0 = __float_as_uint(d0), k1 = __float_as_uint(d1);
+          sdist[i] = k0;
+          sdist[a.head_max + i] = k1;
+          mn0 = k0 < mn0 ? k0 : mn0;
+          mx0 = k0 > mx0 ? k0 : mx0;
+          mn1 = k1 < mn1 ? k1 : mn1;
+          mx1 = k1 > mx1 ? k1 : mx1;
+        }
+      } else {
+        lm_offer(a, tk.q0, d0, valid, tk.tau0, row, qd0, qrow0, qc0, lane);
+        if (tk.has1) lm_offer(a, tk.q1, d1, valid, tk.tau1, row, qd1, qrow1, qc1, lane);
+      }
     }
     // the rest of the next task's inputs is requested before this task's candidates are
     // appended: both wait on the memory system at the same time
     const LmTask done = tk;
     if (more) fetch_task(np0, np1, tk, qv, cv, rv, nxt);
-    {
+    if constexpr (HEAD) {
+      const int L = done.len, k = a.k;
+      const int ng = done.has1 ? 2 : 1;
+      // smallest and largest key of each query's list (this wavefront's share first)
+      for (int g = 0; g < ng; ++g) {
+        uint32_t lo = g ? mn1 : mn0, hi = g ? mx1 : mx0;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+          const uint32_t ol = (uint32_t)__shfl_xor((int)lo, off), oh = (uint32_t)__shfl_xor((int)hi, off);
+          lo = ol < lo ? ol : lo;
+          hi = oh > hi ? oh : hi;
+        }
+        if (lane == 0) {
+          __hip_atomic_fetch_min(&ssel[4 + g], lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          __hip_atomic_fetch_max(&ssel[6 + g], hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
+      __syncthreads();   // the list is scanned: every distance is in LDS and the table's LDS is free
+      // One histogram level over a window fitted to the keys: bin = (key - min) >> shift with the
+      // smallest shift that maps the largest key below LM_BINS.  A bin is 1/2048 of the range of
+      // the list's distances wide, so beyond the k keys wanted only a few more are collected.
+      uint32_t kmin[2], shift[2];
+      for (int g = 0; g < 2; ++g) {
+        kmin[g] = ssel[4 + g];
+        const uint32_t span = ssel[6 + g] - kmin[g];
+        const int bits = 32 - __clz((int)(span | 1u));
+        shift[g] = bits > 11 ? (uint32_t)(bits - 11) : 0u;
+      }
+      uint32_t top[2] = {LM_BINS, LM_BINS};   // collect keys whose bin is <= top (everything when the list is short)
+      if (L > LM_COLLECT) {                    // uniform; then k <= LM_COLLECT < L: the k-th smallest exists
+        for (int i = tid; i < LM_G * LM_BINS; i += NW * 64) hist[i] = 0u;
+        __syncthreads();
+        for (int i = tid; i < L; i += NW * 64)
+          for (int g = 0; g < ng; ++g)
+            lds_add(&hist[g * LM_BINS + lm_hidx((sdist[g * a.head_max + i] - kmin[g]) >> shift[g])]);
+        __syncthreads();
+        if (wave < ng) {                       // wavefront g ranks query g's histogram
+          uint32_t bin, below;
+          lm_find_bin(hist + wave * LM_BINS, (uint32_t)k, lane, bin, below);
+          if (lane == 0) ssel[2 + wave] = bin;
+        }
+        __syncthreads();
+        top[0] = ssel[2];
+        top[1] = ssel[3];
+      }
+      for (int i = tid; i < L; i += NW * 64)
+        for (int g = 0; g < ng; ++g) {
+          const uint32_t key = sdist[g * a.head_max + i];
+          if (((key - kmin[g]) >> shift[g]) <= top[g]) {
+            const uint32_t slot = lds_add(&ssel[g]);
+            if (slot < (uint32_t)LM_COLLECT) {
+              coll_d[g * LM_COLLECT + slot] = key;
+              coll_id[g * LM_COLLECT + slot] = a.ids[done.row0 + i];
+            }
+          }
+        }
+      if (tid < LM_G * LM_COLLECT) coll_rank[tid] = 0u;
+      __syncthreads();
+      // Rank sort, all wavefronts: thread (query g, key i, half h) counts the keys of half h of
+      // query g's collected keys that precede key i in (distance, id) order; the two halves add
+      // up to the key's position in the sorted order.  Keys are distinct, so are the positions.
+      {
+        const int g = tid >> 8, i = tid & (LM_COLLECT - 1), h = (tid >> 7) & 1;
+        const uint32_t n = ssel[g];
+        const bool live = g < ng && n <= (uint32_t)LM_COLLECT;
+        Key me;
+        me.d = SENT_D;
+        me.id = SENT_ID;
+        if (live && (uint32_t)i < n) {
+          me.d = coll_d[g * LM_COLLECT + i];
+          me.id = coll_id[g * LM_COLLECT + i];
+          uint32_t before = 0;
+          const int j0 = h * (LM_COLLECT / 2);
+          const int j1 = j0 + LM_COLLECT / 2 < (int)n ? j0 + LM_COLLECT / 2 : (int)n;
+          for (int j = j0; j < j1; ++j) {
+            Key o;
+            o.d = coll_d[g * LM_COLLECT + j];
+            o.id = coll_id[g * LM_COLLECT + j];
+            before += kless(o, me) ? 1u : 0u;
+          }
+          if (before) __hip_atomic_fetch_add(&coll_rank[g * LM_COLLECT + i], before, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        __syncthreads();
+        const int64_t q = g ? done.q1 : done.q0;
+        if (g < ng && h == 0) {
+          if (n > (uint32_t)LM_COLLECT) {
+            if (i == 0) a.qmap_head[q] = (int32_t)q;   // too many equal distances: left to the query-major kernel
+          } else if ((uint32_t)i < n) {
+            const uint32_t r = coll_rank[g * LM_COLLECT + i];
+            if (r < (uint32_t)k) {
+              a.out_ids[q * k + r] = me.id;
+              a.out_dist[q * k + r] = __uint_as_float(me.d);
+            }
+          } else if (i < k) {                           // fewer than k points in the list
+            a.out_ids[q * k + i] = -1;
+            a.out_dist[q * k + i] = __builtin_inff();
+          }
+        }
+      }
+    } else {
       // one atomic instruction reserves the space of both queues: lane g for query g
       uint32_t slot = 0;
       const int n_mine = lane == 0 ? qc0 : (lane == 1 ? qc1 : 0);
@@ -436,22 +627,38 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(LmArgs a) {
   }
 }
 
-std::atomic<int> g_lm_first{2};     // lists per query that phase A scans query-major
+std::atomic<int> g_lm_first{1};     // lists per query that are ranked first (their k-th distance filters the rest)
 std::atomic<int> g_lm_cap{4096};    // candidate slots per query
 
-size_t lm_scan_lds(int M, int D) {
+size_t lm_fixed_lds(int M, int D) {   // table, residuals, radii
   const int dpad = (D + 3) & ~3;
-  return (size_t)M * 2048 + (size_t)LM_G * dpad * 4 + (size_t)LM_G * IVFPQ_MAX_M * 4 +
-         (size_t)LM_NW * LM_G * 2 * LM_QUEUE * 4;
+  return (size_t)M * 2048 + (size_t)LM_G * dpad * 4 + (size_t)LM_G * IVFPQ_MAX_M * 4;
 }
+size_t lm_scan_lds(int M, int D) { return lm_fixed_lds(M, D) + (size_t)LM_NW * LM_G * 2 * LM_QUEUE * 4; }
+// head pass: the distances of the list's points for both queries live in LDS next to the table
+int lm_head_max(int M, int D) {
+  const int64_t spare = (int64_t)LDS_PER_CU - (int64_t)lm_fixed_lds(M, D) - LM_SEL_WORDS * 4;
+  int64_t n = spare / (LM_G * 4);
+  n &= ~(int64_t)63;
+  return (int)(n > 8192 ? 8192 : (n < 0 ? 0 : n));
+}
+size_t lm_head_lds(int M, int D) { return lm_fixed_lds(M, D) + (size_t)LM_G * lm_head_max(M, D) * 4 + LM_SEL_WORDS * 4; }
 
-template <int MT, int DSUB>
+template <int MT, int DSUB, bool HEAD>
 int launch_lm_scan_t(const LmArgs &a, const RadiiSq &r2, int grid, hipStream_t s) {
-  auto kern = lm_scan_kernel<MT, DSUB>;
+  auto kern = lm_scan_kernel<MT, DSUB, HEAD>;
   static std::atomic<uint64_t> prepared;
   if (int rc = prepare_kernel(kern, prepared)) return rc;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(LM_NW * 64), lm_scan_lds(MT, a.D), s, a, r2);
+  const size_t lds = HEAD ? lm_head_lds(MT, a.D) : lm_scan_lds(MT, a.D);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(LM_NW * 64), lds, s, a, r2);
   return IVFPQ_OK;
+}
+
+template <bool HEAD>
+int launch_lm_scan(const ivfpq_index *ix, const LmArgs &a, const RadiiSq &r2, int grid, hipStream_t s) {
+  if (ix->M == 48) return launch_lm_scan_t<48, 2, HEAD>(a, r2, grid, s);
+  if (ix->M == 64) return launch_lm_scan_t<64, 2, HEAD>(a, r2, grid, s);
+  return launch_lm_scan_t<16, 4, HEAD>(a, r2, grid, s);
 }
 
 }  // namespace
@@ -474,7 +681,7 @@ LmWorkspace plan_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe) {
   LmWorkspace w;
   w.first = g_lm_first.load(std::memory_order_relaxed);
   w.cap = g_lm_cap.load(std::memory_order_relaxed);
-  w.pairs_cap = Q * (nprobe - w.first) + ix->nlist;
+  w.pairs_cap = Q * (nprobe - w.first > 1 ? nprobe - w.first : 1) + ix->nlist;   // also holds the head pass's Q pairs
   size_t off = 0;
   w.cnt = off;   off += lm_align((size_t)ix->nlist * 4);
   w.cur = off;   off += lm_align((size_t)ix->nlist * 4);
@@ -482,6 +689,7 @@ LmWorkspace plan_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe) {
   w.pairs = off; off += lm_align((size_t)w.pairs_cap * 8);
   w.gcnt = off;  off += lm_align((size_t)Q * 4);
   w.qmap = off;  off += lm_align((size_t)Q * 4);
+  w.qmap_head = off; off += lm_align((size_t)Q * 4);
   w.cand = off;  off += lm_align((size_t)Q * w.cap * 8);
   w.total = off;
   return w;
@@ -495,12 +703,8 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
     set_error("scan (list-major): %lld (query, probe) pairs exceed 2^31", (long long)(Q * (int64_t)nprobe));
     return IVFPQ_ERR_UNSUPPORTED;
   }
-  // list-level lower bounds of every (query, probe), then phase A over the first lists of every query
+  // list-level lower bounds of every (query, probe)
   int rc = launch_probe_bounds(ix, d_queries, Q, nprobe, d_probe_ids, r2, mode, d_query_radii, d_probe_lb, s);
-  if (rc) return rc;
-  ScanView head = {nprobe, nullptr, true};
-  rc = launch_scan(ix, d_queries, Q, w.first, d_probe_ids, k, r2, 1, nullptr, nullptr, d_out_ids, d_out_dist,
-                   nullptr, nullptr, nullptr, nullptr, mode, d_query_radii, d_probe_lb, s, &head);
   if (rc) return rc;
 
   LmArgs a;
@@ -522,25 +726,48 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   a.gcnt = reinterpret_cast<uint32_t *>(lm_base + w.gcnt);
   a.cand = reinterpret_cast<uint2 *>(lm_base + w.cand);
   a.qmap = reinterpret_cast<int32_t *>(lm_base + w.qmap);
+  a.qmap_head = reinterpret_cast<int32_t *>(lm_base + w.qmap_head);
+  a.head_max = lm_head_max(ix->M, ix->D);
   a.query_radii = d_query_radii;
   a.Q = Q;
   a.D = ix->D; a.M = ix->M; a.dsub = ix->dsub; a.Mp = ix->Mp; a.nlist = ix->nlist;
   a.nprobe = nprobe; a.first = w.first; a.k = k; a.cap = w.cap; a.mode = mode;
 
-  rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);
-  if (rc) return rc;
-  const int64_t npairs = Q * (nprobe - w.first);
-  const unsigned pair_grid = (unsigned)((npairs + 255) / 256);
-  hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 0);
-  hipLaunchKernelGGL(lm_offsets_kernel, dim3(1), dim3(1024), 0, s, a);
-  hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 1);
   int dev = 0, cus = 0;
   IVFPQ_HIP_TRY(hipGetDevice(&dev));
   IVFPQ_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   if (cus < 1) cus = 1;
-  if (ix->M == 48) rc = launch_lm_scan_t<48, 2>(a, r2, cus, s);
-  else if (ix->M == 64) rc = launch_lm_scan_t<64, 2>(a, r2, cus, s);
-  else rc = launch_lm_scan_t<16, 4>(a, r2, cus, s);
+
+  // ---- the first lists of every query: they give the bound tau_q that filters the rest ----
+  // One list per query under distance scoring: the head pass ranks it list-major (queries that
+  // share a nearest list share its table pass); the query-major kernel serves what the head
+  // pass leaves out (qmap_head).  Otherwise (several first lists, or the hit-count scorings,
+  // whose masses of equal scores the head pass's selection is not made for): query-major.
+  const bool head_pass = w.first == 1 && mode == IVFPQ_SCORE_DISTANCE && a.head_max >= 64;
+  if (head_pass) {
+    rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);
+    if (rc) return rc;
+    const unsigned qgrid = (unsigned)((Q + 255) / 256);
+    hipLaunchKernelGGL(lm_pairs_kernel, dim3(qgrid), dim3(256), 0, s, a, 0, 1);
+    hipLaunchKernelGGL(lm_offsets_kernel, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(lm_pairs_kernel, dim3(qgrid), dim3(256), 0, s, a, 1, 1);
+    rc = launch_lm_scan<true>(ix, a, r2, cus, s);
+    if (rc) return rc;
+  }
+  ScanView head = {nprobe, head_pass ? a.qmap_head : nullptr, true};
+  rc = launch_scan(ix, d_queries, Q, w.first, d_probe_ids, k, r2, 1, nullptr, nullptr, d_out_ids, d_out_dist,
+                   nullptr, nullptr, nullptr, nullptr, mode, d_query_radii, d_probe_lb, s, &head);
+  if (rc) return rc;
+
+  // ---- the other lists, list-major: pairs bucketed by list, scan, merge ----
+  rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);
+  if (rc) return rc;
+  const int64_t npairs = Q * (nprobe - w.first);
+  const unsigned pair_grid = (unsigned)((npairs + 255) / 256);
+  hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 0, 0);
+  hipLaunchKernelGGL(lm_offsets_kernel, dim3(1), dim3(1024), 0, s, a);
+  hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 1, 0);
+  rc = launch_lm_scan<false>(ix, a, r2, cus, s);
   if (rc) return rc;
   hipLaunchKernelGGL(lm_merge_kernel, dim3((unsigned)((Q + 3) / 4)), dim3(256), 0, s, a);
   IVFPQ_HIP_TRY(hipGetLastError());

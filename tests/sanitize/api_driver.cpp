@@ -142,7 +142,7 @@ static void search_arguments() {
     REQUIRE(ivfpq_search_ex(&ix, q, 4, 2, 5, radii, &sc, ids, dist, ws_mem, need, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT); }
   REQUIRE(ivfpq_set_option("lm_first", 0) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("lm_cap", 8) == IVFPQ_ERR_INVALID_ARGUMENT);
-  REQUIRE(ivfpq_set_option("lm_first", 2) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK);
+  REQUIRE(ivfpq_set_option("lm_first", 1) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK);
   REQUIRE(ivfpq_scan_all(&ix, q, 4, 2, pid, radii, nullptr, nullptr, nullptr, nullptr, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_ablate", 1) == IVFPQ_ERR_INVALID_ARGUMENT);   // result-changing bits are gone
   REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64) == IVFPQ_OK);

@@ -776,7 +776,7 @@ def test_c1_full(lib):
     full_check(w, idx, q, radii, stages=False)
 
 
-def _lm_options(b, first=2, cap=4096):
+def _lm_options(b, first=1, cap=4096):
     b.set_option("lm_first", first)
     b.set_option("lm_cap", cap)
 
@@ -799,7 +799,7 @@ def test_list_major_scan_matches_oracle(lib, family, D, M, sigma):
     try:
         for radii in (wl.calibrate_radii(w, idx, centres, 0.25), np.full(M, np.inf, np.float32)):
             o_ids, o_dist = oracle.search(q, idx, w.nprobe, w.k, radii, threads=8)
-            for first, cap in ((2, 2048), (1, 2048), (5, 4096), (2, 64)):
+            for first, cap in ((1, 4096), (2, 2048), (5, 4096), (2, 64), (1, 64)):
                 _lm_options(b, first, cap)
                 ids, dist = gi.search(dq, w.nprobe, w.k, radii, strategy=LM)
                 torch.cuda.synchronize()
@@ -877,9 +877,17 @@ def test_list_major_ragged_lists(lib):
     b = _binding()
     for M, D in ((64, 128), (48, 96), (16, 64)):
         rng = np.random.default_rng(M)
-        sizes = [0, 1, 63, 64, 65, 0, 130, 700, 5, 1500, 64 * 9, 0, 333, 2, 127, 129, 64 * 17 + 1]
+        # 5000 points: longer than the head pass takes at 64 subspaces (those queries' nearest list is
+        # ranked by the query-major kernel), within it at 48 and 16
+        sizes = [0, 1, 63, 64, 65, 0, 130, 700, 5, 1500, 64 * 9, 0, 333, 2, 127, 129, 64 * 17 + 1, 5000]
         idx = _random_index(rng, 0, D, len(sizes), M, sizes)
+        # the list of 700 points holds 400 copies of one code: more equal distances than the head
+        # pass's selection collects, so its queries fall back too; ids decide among the copies
+        lo = int(idx.list_offsets[7])
+        idx.codes[lo + 100:lo + 500] = idx.codes[lo + 100]
         q = rng.normal(size=(45, D)).astype(np.float32)
+        # queries sitting on centroids, so that every list is some query's nearest one
+        q[:len(sizes)] = idx.centroids + 0.01 * rng.normal(size=idx.centroids.shape).astype(np.float32)
         gi = b.IvfPqIndex.from_index(idx)
         for r in (np.full(M, 0.9 * np.sqrt(D / M), dtype=np.float32), np.full(M, np.inf, np.float32)):
             for nprobe, k in ((idx.nlist, 128), (6, 100), (3, 1)):
@@ -918,11 +926,12 @@ def test_full_size_configs_sampled_queries(lib, name):
         assert np.array_equal(ids.cpu().numpy()[sample], o_ids), (name, frac)
         assert_same_float(dist.cpu().numpy()[sample], o_dist, f"{name} keep={frac}")
         say(f"  {name} keep={frac}: {len(sample)} sampled queries match the oracle")
-        if name in ("C2", "C3"):   # the list-major scan of the same batch: the same bits
-            ids_l, dist_l = gi.search(dq, w.nprobe, w.k, radii, strategy=b.SCAN_LIST_MAJOR)
+        # the strategy is the library's choice above; forced either way the whole batch has the same bits
+        for st in (b.SCAN_QUERY_MAJOR, b.SCAN_LIST_MAJOR):
+            ids_s, dist_s = gi.search(dq, w.nprobe, w.k, radii, strategy=st)
             torch.cuda.synchronize()
-            assert torch.equal(ids_l, ids) and torch.equal(dist_l.view(torch.int32), dist.view(torch.int32)), (name, frac)
-            say(f"  {name} keep={frac}: the list-major scan gives the same {w.Q} x {w.k} results")
+            assert torch.equal(ids_s, ids) and torch.equal(dist_s.view(torch.int32), dist.view(torch.int32)), (name, frac, st)
+        say(f"  {name} keep={frac}: query-major and list-major scans give the same {w.Q} x {w.k} results")
     # properties that hold for every query at full size
     ids_np, dist_np = ids.cpu().numpy(), dist.cpu().numpy()
     assert np.all(np.diff(dist_np, axis=1) >= 0) and ids_np.min() >= 0 and ids_np.max() < w.N
