@@ -46,7 +46,7 @@ Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32
   if (ns > 64) ns = 64;
   if (ns < 1) ns = 1;
   w.nsplit = (int32_t)ns;
-  size_t fixed = 2 * align256((size_t)Q * nprobe * 4);
+  size_t fixed = 2 * align256((size_t)Q * nprobe * 4) + align256((size_t)Q * 4);
   if (w.nsplit > 1) fixed += align256((size_t)Q * w.nsplit * 128 * 4) + align256((size_t)Q * w.nsplit * 128 * 8);
   const size_t row_bytes = (size_t)w.nlist_pad * 4;
   int64_t qc = ((int64_t)1 << 30) / (int64_t)row_bytes;
@@ -66,6 +66,7 @@ Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32
   w.coarse_dist = off; off += align256((size_t)w.q_chunk * row_bytes);
   w.probe_ids = off;   off += align256((size_t)Q * nprobe * 4);
   w.probe_dist = off;  off += align256((size_t)Q * nprobe * 4);
+  w.coarse_flags = off; off += align256((size_t)Q * 4);
   if (w.nsplit > 1) {
     w.part_d = off;    off += align256((size_t)Q * w.nsplit * 128 * 4);
     w.part_id = off;   off += align256((size_t)Q * w.nsplit * 128 * 8);
@@ -467,7 +468,7 @@ int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32
   char *base = static_cast<char *>(ws);
   return launch_coarse(ix, d_queries, Q, nprobe, d_probe_ids, d_probe_dist,
                        reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad,
-                       static_cast<hipStream_t>(stream));
+                       reinterpret_cast<int32_t *>(base + w.coarse_flags), static_cast<hipStream_t>(stream));
 }
 
 // scoring defaults (distances, shared radii) when the caller passes none
@@ -606,7 +607,8 @@ static int search_in_workspace(const ivfpq_index *ix, const float *d_queries, in
                                float *d_out_dist, const Workspace &w, char *base, hipStream_t s) {
   int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
   int rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr,
-                         reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad, s);
+                         reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad,
+                         reinterpret_cast<int32_t *>(base + w.coarse_flags), s);
   if (rc) return rc;
   return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
                      reinterpret_cast<uint32_t *>(base + w.part_d),
@@ -660,7 +662,8 @@ int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
     char *base = static_cast<char *>(ws);
     int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
     rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr, reinterpret_cast<float *>(base + w.coarse_dist),
-                       w.q_chunk, w.nlist_pad, static_cast<hipStream_t>(stream));
+                       w.q_chunk, w.nlist_pad, reinterpret_cast<int32_t *>(base + w.coarse_flags),
+                       static_cast<hipStream_t>(stream));
     if (rc) return rc;
     return scan_list_major(ix, d_queries, Q, nprobe, probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, ws,
                            ws_bytes, static_cast<hipStream_t>(stream), fn);

@@ -232,10 +232,14 @@ __device__ inline unsigned long long row_key(const float *row, int c) {
 // of the kprop-th key when a level is too coarse; at width 1 a bin holds one key, so
 // the loop ends).  The selected lists get their distances in the reference order,
 // are sorted by (distance, list id), and the first nprobe are emitted.
+// With `flags` (device [qn]) a workgroup serves the queries of its group of `group` consecutive
+// queries whose flag is set, one after the other, and nothing else: the second line behind
+// coarse_select_wave_kernel, launched with few workgroups because it usually finds no work.
 __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4))) void coarse_select_kernel(
     float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int nlist,
     int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm, int ip,
-    int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
+    int32_t *__restrict__ out_ids, float *__restrict__ out_dist, const int32_t *__restrict__ flags, int qn,
+    int group) {
   extern __shared__ float sq[];  // [D]
   __shared__ uint32_t hist[NBINS];
   __shared__ uint32_t tmp[2 * SEL_THREADS];
@@ -247,7 +251,11 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4))
   __shared__ float red[SEL_THREADS / 64];
 
   const int tid = threadIdx.x;
-  const int64_t q = blockIdx.x;
+  for (int gq = 0; gq < group; ++gq) {
+  const int64_t q = (int64_t)blockIdx.x * group + gq;
+  if (q >= qn) break;
+  if (flags && flags[q] == 0) continue;   // uniform over the workgroup
+  __syncthreads();                         // the shared arrays are free of the query before
   float *row = rows + q * ldo;
   const float *qv = Qm + q * D;
 
@@ -431,6 +439,164 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4))
     out_ids[q * nprobe + p] = (int32_t)(uint32_t)key;
     if (out_dist) out_dist[q * nprobe + p] = unorderable((uint32_t)(key >> 32));
   }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same selection with one WAVEFRONT per query and no workgroup barrier: a histogram of
+// 1024 bins over the range of the row's proposal values finds the bin of the kprop-th
+// smallest, the lists up to that bin are collected (kprop plus the few that share the last
+// bin), get their reference-order distances (one list per lane) and are put in (distance,
+// list) order by a rank sort.  The proposal is accepted under the same rounding bound as
+// above.  Whatever does not fit -- more than CS_CAND lists up to the bin (masses of equal
+// proposal values), a proposal that the bound does not accept -- is flagged and left to
+// coarse_select_kernel, so the result is that of the reference order in every case.
+
+#define LDS __attribute__((address_space(3)))
+constexpr int CS_BINS = 1024;   // histogram bins; bin b lives at word (b % 16) * 64 + b / 16 (lane l owns bins 16 l .. 16 l + 15)
+constexpr int CS_CAND = 256;    // lists a query may collect
+constexpr int CS_WAVES = 4;     // queries per workgroup
+
+__device__ __forceinline__ int cs_hidx(uint32_t bin) { return (int)(((bin & 15u) << 6) | (bin >> 4)); }
+
+__global__ __launch_bounds__(CS_WAVES * 64) void coarse_select_wave_kernel(
+    const float *__restrict__ rows, const float *__restrict__ Qm, const float *__restrict__ cent, int qn, int nlist,
+    int D, int ldo, int nprobe, int kprop, float err_scale, float max_cnorm, int ip,
+    int32_t *__restrict__ out_ids, float *__restrict__ out_dist, int32_t *__restrict__ flags) {
+  extern __shared__ __align__(16) unsigned char cs_smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t q = (int64_t)blockIdx.x * CS_WAVES + wave;
+  if (q >= qn) return;   // no workgroup barrier anywhere in this kernel
+  const int dpad = (D + 3) & ~3;
+  const size_t per_wave = (size_t)CS_BINS * 4 + (size_t)CS_CAND * 8 + (size_t)dpad * 4;
+  LDS unsigned char *mine = (LDS unsigned char *)cs_smem + wave * per_wave;
+  LDS uint32_t *hist = (LDS uint32_t *)mine;
+  LDS unsigned long long *cand = (LDS unsigned long long *)(mine + CS_BINS * 4);
+  LDS float *sq = (LDS float *)(mine + CS_BINS * 4 + CS_CAND * 8);
+  const float *row = rows + q * ldo;
+  const float *qv = Qm + q * D;
+
+  float part = 0.0f;
+  for (int i = lane; i < D; i += 64) {
+    const float x = qv[i];
+    sq[i] = x;
+    part += x * x;
+  }
+  for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+  const float qq = part;
+
+  // range of the row's proposal values (as integers that order like the values)
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  for (int c = lane; c < nlist; c += 64) {
+    const uint32_t k = orderable(row[c]);
+    kmin = k < kmin ? k : kmin;
+    kmax = k > kmax ? k : kmax;
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t a = (uint32_t)__shfl_xor((int)kmin, off), b = (uint32_t)__shfl_xor((int)kmax, off);
+    kmin = a < kmin ? a : kmin;
+    kmax = b > kmax ? b : kmax;
+  }
+  const int bits = 32 - __clz((int)((kmax - kmin) | 1u));
+  const uint32_t shift = bits > 10 ? (uint32_t)(bits - 10) : 0u;   // (kmax - kmin) >> shift < CS_BINS
+
+  for (int i = lane; i < CS_BINS; i += 64) hist[i] = 0u;
+  for (int c = lane; c < nlist; c += 64)
+    __hip_atomic_fetch_add(&hist[cs_hidx((orderable(row[c]) - kmin) >> shift)], 1u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  // bin of the kprop-th smallest value: lane l owns bins 16 l .. 16 l + 15
+  uint32_t top;
+  {
+    uint32_t sum = 0;
+    for (int j = 0; j < 16; ++j) sum += hist[j * 64 + lane];
+    uint32_t incl = sum;
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
+      if (lane >= off) incl += v;
+    }
+    const uint32_t excl = incl - sum, need = (uint32_t)kprop;
+    const bool hit = excl < need && need <= incl;   // exactly one lane (kprop <= nlist)
+    uint32_t b = 0, run = excl;
+    if (hit)
+      for (int j = 0; j < 16; ++j) {
+        const uint32_t n = hist[j * 64 + lane];
+        if (run < need && need <= run + n) b = 16u * lane + j;
+        run += n;
+      }
+    const unsigned long long bal = __ballot(hit);
+    top = (uint32_t)__shfl((int)b, bal ? __ffsll((long long)bal) - 1 : 0);
+  }
+  // collect the lists up to that bin
+  uint32_t count = 0;
+  for (int c0 = 0; c0 < nlist; c0 += 64) {
+    const int c = c0 + lane;
+    const bool take = c < nlist && ((orderable(row[c]) - kmin) >> shift) <= top;
+    const unsigned long long bal = __ballot(take);
+    if (take) {
+      const uint32_t slot = count + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+      if (slot < (uint32_t)CS_CAND) cand[slot] = (uint32_t)c;
+    }
+    count += (uint32_t)__popcll(bal);
+  }
+  bool ok = count <= (uint32_t)CS_CAND;
+  const int n = ok ? (int)count : 0;
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  // reference-order distances, one list per lane and round; keys (distance, list) back to LDS
+  constexpr int ROUNDS = CS_CAND / 64;
+  unsigned long long key[ROUNDS];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    key[r] = ~0ull;
+    const int i = r * 64 + lane;
+    if (r * 64 < n) {   // uniform
+      if (i < n) {
+        const int c = (int)(uint32_t)cand[i];
+        const float d = exact_score((const float *)sq, cent + (int64_t)c * D, D, ip);
+        key[r] = ((unsigned long long)orderable(d) << 32) | (uint32_t)c;
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r)
+    if (r * 64 + lane < n) cand[r * 64 + lane] = key[r];
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  // rank sort: position of a key = number of keys below it (keys are distinct)
+  uint32_t rank[ROUNDS];
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) rank[r] = 0;
+  for (int j = 0; j < n; ++j) {
+    const unsigned long long o = cand[j];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) rank[r] += o < key[r] ? 1u : 0u;
+  }
+  // the nprobe-th reference distance, for the acceptance test
+  float tau = 0.0f;
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r) {
+    const bool has = r * 64 + lane < n && rank[r] == (uint32_t)nprobe - 1u;
+    const unsigned long long bal = __ballot(has);
+    if (bal) tau = unorderable((uint32_t)(__shfl((unsigned long long)key[r], __ffsll((long long)bal) - 1) >> 32));
+  }
+  if (ok && n < nlist) {
+    // every list that was not collected has a proposal value of at least the next bin's lower
+    // edge; accept if that clears the nprobe-th reference distance by more than the rounding
+    // bound of the matrix product
+    const unsigned long long edge = (unsigned long long)kmin + (((unsigned long long)top + 1ull) << shift);
+    const float t_prop = unorderable(edge > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)edge) + (ip ? 0.0f : qq);
+    const float bound = err_scale * (qq + max_cnorm);
+    ok = (t_prop - tau) > bound;   // false for NaN
+  }
+  ok = ok && n >= nprobe;
+  if (lane == 0) flags[q] = ok ? 0 : 1;
+  if (!ok) return;
+#pragma unroll
+  for (int r = 0; r < ROUNDS; ++r)
+    if (r * 64 + lane < n && rank[r] < (uint32_t)nprobe) {
+      out_ids[q * nprobe + rank[r]] = (int32_t)(uint32_t)key[r];
+      if (out_dist) out_dist[q * nprobe + rank[r]] = unorderable((uint32_t)(key[r] >> 32));
+    }
 }
 
 int pow2ceil(int v) {
@@ -454,7 +620,7 @@ int coarse_fallbacks(int reset, unsigned int *out) {
 
 int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                   int32_t *d_probe_ids, float *d_probe_dist, float *d_scratch, int64_t q_chunk,
-                  int32_t nlist_pad, hipStream_t s) {
+                  int32_t nlist_pad, int32_t *d_flags, hipStream_t s) {
   const int D = ix->D, nlist = ix->nlist;
   int slack = nprobe / 4;
   if (slack < 16) slack = 16;
@@ -472,10 +638,27 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
     dim3 grid((nlist + BN - 1) / BN, (qn + BM - 1) / BM);
     hipLaunchKernelGGL(coarse_gemm_kernel, grid, dim3(256), 0, s, qm, ix->d_centroids, ix->d_cnorm,
                        d_scratch, qn, nlist, D, nlist_pad, vec, ix->metric == IVFPQ_METRIC_IP);
-    hipLaunchKernelGGL(coarse_select_kernel, dim3(qn), dim3(SEL_THREADS), (size_t)D * sizeof(float), s,
-                       d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe, kprop,
-                       err_scale, ix->max_cnorm, ix->metric == IVFPQ_METRIC_IP, d_probe_ids + q0 * nprobe,
-                       d_probe_dist ? d_probe_dist + q0 * nprobe : nullptr);
+    const int ip = ix->metric == IVFPQ_METRIC_IP;
+    int32_t *ids = d_probe_ids + q0 * nprobe;
+    float *dist = d_probe_dist ? d_probe_dist + q0 * nprobe : nullptr;
+    // One wavefront per query where the proposal is small enough for it; the workgroup-per-query
+    // kernel then only serves the queries the wavefront kernel flags (16 queries per workgroup,
+    // so that the usual case of no flag costs a few hundred idle workgroups).
+    const size_t wave_lds = CS_WAVES * ((size_t)CS_BINS * 4 + (size_t)CS_CAND * 8 + (size_t)((D + 3) & ~3) * 4);
+    const bool by_wave = d_flags && kprop <= CS_CAND / 2 && wave_lds <= 64 * 1024;
+    if (by_wave) {
+      hipLaunchKernelGGL(coarse_select_wave_kernel, dim3((qn + CS_WAVES - 1) / CS_WAVES), dim3(CS_WAVES * 64), wave_lds,
+                         s, d_scratch, qm, ix->d_centroids, qn, nlist, D, nlist_pad, nprobe, kprop, err_scale,
+                         ix->max_cnorm, ip, ids, dist, d_flags + q0);
+      const int group = 16;
+      hipLaunchKernelGGL(coarse_select_kernel, dim3((qn + group - 1) / group), dim3(SEL_THREADS),
+                         (size_t)D * sizeof(float), s, d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe,
+                         kprop, err_scale, ix->max_cnorm, ip, ids, dist, d_flags + q0, qn, group);
+    } else {
+      hipLaunchKernelGGL(coarse_select_kernel, dim3(qn), dim3(SEL_THREADS), (size_t)D * sizeof(float), s,
+                         d_scratch, qm, ix->d_centroids, nlist, D, nlist_pad, nprobe, kprop, err_scale,
+                         ix->max_cnorm, ip, ids, dist, nullptr, qn, 1);
+    }
   }
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;

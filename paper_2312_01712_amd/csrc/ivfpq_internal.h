@@ -73,6 +73,7 @@ struct Workspace {
   size_t coarse_dist;   // [Qc][nlist_pad] fp32 approximate distances of one query chunk
   size_t probe_ids;     // [Q][nprobe] int32
   size_t probe_dist;    // [Q][nprobe] fp32: list-level lower bounds for the scan
+  size_t coarse_flags;  // [Q] int32: queries the one-wavefront selection of the filtering stage leaves to the workgroup one
   size_t part_d;        // [Q][nsplit][128] uint32 (only when nsplit > 1)
   size_t part_id;       // [Q][nsplit][128] int64
   size_t total;
@@ -85,7 +86,7 @@ Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32
 // ---- launchers (enqueue only) -------------------------------------------------
 int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                   int32_t *d_probe_ids, float *d_probe_dist, float *d_scratch, int64_t q_chunk,
-                  int32_t nlist_pad, hipStream_t s);
+                  int32_t nlist_pad, int32_t *d_flags, hipStream_t s);
 int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                      const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
                      int32_t mode, const float *d_query_radii, hipStream_t s);

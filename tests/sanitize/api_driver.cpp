@@ -46,10 +46,11 @@ static void sweep_workspace() {
         // regions in order, 256-byte aligned, inside the total
         const size_t ends[] = {w.coarse_dist + (size_t)w.q_chunk * w.nlist_pad * 4,
                                w.probe_ids + (size_t)Q * nprobe * 4, w.probe_dist + (size_t)Q * nprobe * 4};
-        REQUIRE(w.coarse_dist % 256 == 0 && w.probe_ids % 256 == 0 && w.probe_dist % 256 == 0);
-        REQUIRE(ends[0] <= w.probe_ids && ends[1] <= w.probe_dist && ends[2] <= w.total);
+        REQUIRE(w.coarse_dist % 256 == 0 && w.probe_ids % 256 == 0 && w.probe_dist % 256 == 0 && w.coarse_flags % 256 == 0);
+        REQUIRE(ends[0] <= w.probe_ids && ends[1] <= w.probe_dist && ends[2] <= w.coarse_flags);
+        REQUIRE(w.coarse_flags + (size_t)Q * 4 <= w.total);
         if (w.nsplit > 1) {
-          REQUIRE(w.part_d % 256 == 0 && w.part_id % 256 == 0 && ends[2] <= w.part_d);
+          REQUIRE(w.part_d % 256 == 0 && w.part_id % 256 == 0 && w.coarse_flags + (size_t)Q * 4 <= w.part_d);
           REQUIRE(w.part_d + (size_t)Q * w.nsplit * 128 * 4 <= w.part_id);
           REQUIRE(w.part_id + (size_t)Q * w.nsplit * 128 * 8 <= w.total);
         }

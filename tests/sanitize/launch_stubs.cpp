@@ -13,7 +13,7 @@ static int reached(const char *what) {
   return IVFPQ_ERR_HIP;
 }
 int launch_coarse(const ivfpq_index *, const float *, int64_t, int32_t, int32_t *, float *, float *, int64_t,
-                  int32_t, hipStream_t) { return reached("coarse"); }
+                  int32_t, int32_t *, hipStream_t) { return reached("coarse"); }
 int launch_build_lut(const ivfpq_index *, const float *, int64_t, int32_t, const int32_t *, const RadiiSq &,
                      float *, uint64_t *, int32_t, const float *, hipStream_t) { return reached("build_lut"); }
 int launch_scan(const ivfpq_index *, const float *, int64_t, int32_t, const int32_t *, int32_t, const RadiiSq &,
