@@ -443,12 +443,12 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4))
 }
 
 // ---------------------------------------------------------------------------
-// The same selection with one WAVEFRONT per query and no workgroup barrier: a histogram of
-// 1024 bins over the range of the row's proposal values finds the bin of the kprop-th
-// smallest, the lists up to that bin are collected (kprop plus the few that share the last
-// bin), get their reference-order distances (one list per lane) and are put in (distance,
-// list) order by a rank sort.  The proposal is accepted under the same rounding bound as
-// above.  Whatever does not fit -- more than CS_CAND lists up to the bin (masses of equal
+// The same selection with one WAVEFRONT per query and no workgroup barrier, for rows of up
+// to 4096 lists: a histogram of 1024 bins over the range of the row's proposal values finds
+// the bin of the kprop-th smallest, the lists up to that bin (and far enough past the
+// nprobe-th for the acceptance test) are collected, get their reference-order distances (one
+// list per lane) and are put in (distance, list) order by a rank sort.  The proposal is
+// accepted under the same rounding bound as above.  Whatever does not fit -- more than CS_CAND lists up to the bin (masses of equal
 // proposal values), a proposal that the bound does not accept -- is flagged and left to
 // coarse_select_kernel, so the result is that of the reference order in every case.
 
@@ -485,53 +485,69 @@ __global__ __launch_bounds__(CS_WAVES * 64) void coarse_select_wave_kernel(
   for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
   const float qq = part;
 
-  // range of the row's proposal values (as integers that order like the values)
-  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  // range of the row's proposal values
+  float vmin = __builtin_inff(), vmax = -__builtin_inff();
   for (int c = lane; c < nlist; c += 64) {
-    const uint32_t k = orderable(row[c]);
-    kmin = k < kmin ? k : kmin;
-    kmax = k > kmax ? k : kmax;
+    const float v = row[c];
+    vmin = fminf(vmin, v);
+    vmax = fmaxf(vmax, v);
   }
   for (int off = 32; off > 0; off >>= 1) {
-    const uint32_t a = (uint32_t)__shfl_xor((int)kmin, off), b = (uint32_t)__shfl_xor((int)kmax, off);
-    kmin = a < kmin ? a : kmin;
-    kmax = b > kmax ? b : kmax;
+    vmin = fminf(vmin, __shfl_xor(vmin, off));
+    vmax = fmaxf(vmax, __shfl_xor(vmax, off));
   }
-  const int bits = 32 - __clz((int)((kmax - kmin) | 1u));
-  const uint32_t shift = bits > 10 ? (uint32_t)(bits - 10) : 0u;   // (kmax - kmin) >> shift < CS_BINS
-
+  // bins of equal width in value: bin(v) is monotone in v whatever the roundings, which is all
+  // the selection needs (NaN and a degenerate range go to bin 0 / the last bin)
+  const float scale = (float)CS_BINS / (vmax - vmin);
+  auto bin_of = [&](float v) __attribute__((always_inline)) {
+    const float x = (v - vmin) * scale;
+    return x >= (float)(CS_BINS - 1) ? (uint32_t)(CS_BINS - 1) : (x > 0.0f ? (uint32_t)x : 0u);
+  };
   for (int i = lane; i < CS_BINS; i += 64) hist[i] = 0u;
   for (int c = lane; c < nlist; c += 64)
-    __hip_atomic_fetch_add(&hist[cs_hidx((orderable(row[c]) - kmin) >> shift)], 1u, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __hip_atomic_fetch_add(&hist[cs_hidx(bin_of(row[c]))], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-  // bin of the kprop-th smallest value: lane l owns bins 16 l .. 16 l + 15
-  uint32_t top;
-  {
-    uint32_t sum = 0;
-    for (int j = 0; j < 16; ++j) sum += hist[j * 64 + lane];
-    uint32_t incl = sum;
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
-      if (lane >= off) incl += v;
-    }
-    const uint32_t excl = incl - sum, need = (uint32_t)kprop;
-    const bool hit = excl < need && need <= incl;   // exactly one lane (kprop <= nlist)
-    uint32_t b = 0, run = excl;
-    if (hit)
-      for (int j = 0; j < 16; ++j) {
-        const uint32_t n = hist[j * 64 + lane];
-        if (run < need && need <= run + n) b = 16u * lane + j;
-        run += n;
-      }
-    const unsigned long long bal = __ballot(hit);
-    top = (uint32_t)__shfl((int)b, bal ? __ffsll((long long)bal) - 1 : 0);
+  // bin of the need-th smallest value: lane l owns bins 16 l .. 16 l + 15
+  uint32_t own[16], sum = 0;
+  for (int j = 0; j < 16; ++j) {
+    own[j] = hist[j * 64 + lane];
+    sum += own[j];
   }
-  // collect the lists up to that bin
+  uint32_t incl = sum;
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
+    if (lane >= off) incl += v;
+  }
+  const uint32_t excl = incl - sum;
+  auto bin_of_rank = [&](uint32_t need) __attribute__((always_inline)) {   // 1 <= need <= nlist
+    const bool hit = excl < need && need <= incl;   // exactly one lane
+    uint32_t b = 0, run = excl;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (hit && run < need && need <= run + own[j]) b = 16u * lane + j;
+      run += own[j];
+    }
+    const unsigned long long bal = __ballot(hit);
+    return (uint32_t)__shfl((int)b, bal ? __ffsll((long long)bal) - 1 : 0);
+  };
+  // The cut: the bin of the kprop-th smallest proposal, and far enough beyond the bin of the
+  // nprobe-th for the acceptance test below to hold (twice the rounding bound past that bin's
+  // upper edge), whichever is later.
+  const float bound = err_scale * (qq + max_cnorm);
+  uint32_t top = bin_of_rank((uint32_t)kprop);
+  {
+    const float reach = (float)(bin_of_rank((uint32_t)nprobe) + 2u) + 2.0f * bound * scale;
+    const uint32_t top2 = reach >= (float)(CS_BINS - 1) ? (uint32_t)(CS_BINS - 1) : (reach > 0.0f ? (uint32_t)reach : 0u);
+    top = top2 > top ? top2 : top;
+  }
+  // collect the lists up to that bin; the smallest proposal among the others bounds them all
   uint32_t count = 0;
+  float rest_min = __builtin_inff();
   for (int c0 = 0; c0 < nlist; c0 += 64) {
     const int c = c0 + lane;
-    const bool take = c < nlist && ((orderable(row[c]) - kmin) >> shift) <= top;
+    const float v = c < nlist ? row[c] : __builtin_inff();
+    const bool take = c < nlist && bin_of(v) <= top;
+    if (!take) rest_min = fminf(rest_min, v);
     const unsigned long long bal = __ballot(take);
     if (take) {
       const uint32_t slot = count + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
@@ -539,6 +555,7 @@ __global__ __launch_bounds__(CS_WAVES * 64) void coarse_select_wave_kernel(
     }
     count += (uint32_t)__popcll(bal);
   }
+  for (int off = 32; off > 0; off >>= 1) rest_min = fminf(rest_min, __shfl_xor(rest_min, off));
   bool ok = count <= (uint32_t)CS_CAND;
   const int n = ok ? (int)count : 0;
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
@@ -580,12 +597,10 @@ __global__ __launch_bounds__(CS_WAVES * 64) void coarse_select_wave_kernel(
     if (bal) tau = unorderable((uint32_t)(__shfl((unsigned long long)key[r], __ffsll((long long)bal) - 1) >> 32));
   }
   if (ok && n < nlist) {
-    // every list that was not collected has a proposal value of at least the next bin's lower
-    // edge; accept if that clears the nprobe-th reference distance by more than the rounding
-    // bound of the matrix product
-    const unsigned long long edge = (unsigned long long)kmin + (((unsigned long long)top + 1ull) << shift);
-    const float t_prop = unorderable(edge > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)edge) + (ip ? 0.0f : qq);
-    const float bound = err_scale * (qq + max_cnorm);
+    // every list that was not collected has a proposal value of at least rest_min; accept if
+    // that clears the nprobe-th reference distance by more than the rounding bound of the
+    // matrix product
+    const float t_prop = rest_min + (ip ? 0.0f : qq);
     ok = (t_prop - tau) > bound;   // false for NaN
   }
   ok = ok && n >= nprobe;
@@ -645,7 +660,7 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
     // kernel then only serves the queries the wavefront kernel flags (16 queries per workgroup,
     // so that the usual case of no flag costs a few hundred idle workgroups).
     const size_t wave_lds = CS_WAVES * ((size_t)CS_BINS * 4 + (size_t)CS_CAND * 8 + (size_t)((D + 3) & ~3) * 4);
-    const bool by_wave = d_flags && kprop <= CS_CAND / 2 && wave_lds <= 64 * 1024;
+    const bool by_wave = d_flags && kprop <= CS_CAND / 2 && nlist <= 4096 && wave_lds <= 64 * 1024;
     if (by_wave) {
       hipLaunchKernelGGL(coarse_select_wave_kernel, dim3((qn + CS_WAVES - 1) / CS_WAVES), dim3(CS_WAVES * 64), wave_lds,
                          s, d_scratch, qm, ix->d_centroids, qn, nlist, D, nlist_pad, nprobe, kprop, err_scale,
