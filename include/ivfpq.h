@@ -218,9 +218,9 @@ typedef enum {
  *     the look-up rate dominate: short lists, data without cluster structure.
  *     Needs the L2 metric, k <= 128 and an (M, dsub) of (48, 2), (64, 2) or (16, 4); any other
  *     call is served query-major.  Takes a larger workspace.
- *   IVFPQ_SCAN_AUTO         the library chooses: list-major where it is available, for
- *     distance scoring, when the batch has at least 16 384 (query, list) pairs and the index's
- *     mean list length is at most 4096; query-major otherwise.
+ *   IVFPQ_SCAN_AUTO         the library chooses: list-major where it is available, when the
+ *     batch has at least 16 384 (query, list) pairs and the index's mean list length is at
+ *     most 4096; query-major otherwise.
  * ivfpq_search_workspace_bytes sizes the workspace for AUTO with distance scoring;
  * ivfpq_search_workspace_bytes_ex for the scoring actually passed. */
 typedef enum { IVFPQ_SCAN_AUTO = 0, IVFPQ_SCAN_QUERY_MAJOR = 1, IVFPQ_SCAN_LIST_MAJOR = 2 } ivfpq_scan_strategy;
@@ -337,7 +337,8 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  *                  to by itself for queries whose blocks rarely end early), 32 that switch,
  *                  64 the list-level bound that skips a list before its table is built.
  *                  8 | 16 | 64 with "scan_loads" 1 is the plain scan: every code byte of every
- *                  probed list is read and looked up. */
+ *                  probed list is read and looked up.  128: the hit-count scorings use the
+ *                  float table of the distance scoring instead of their byte table. */
 int ivfpq_set_option(const char *name, int value);
 
 /* Text for the most recent failure on this thread ("" if none). */

@@ -129,16 +129,17 @@ static int check_workspace(const Workspace &w, const void *ws, size_t bytes, con
 
 // Which way stages 2-4 run.  A request for the list-major scan is honoured where that scan is
 // built (L2, k <= 128, the specialised shapes), anything else runs query-major.  Left to the
-// library (AUTO), the list-major scan serves distance scoring on batches with enough (query,
-// list) pairs to group, over indexes whose lists are short: there the per-query fixed costs
-// of the query-major kernel dominate, while long lists (the 100M-point configuration) gain
-// more from its per-block pruning.  Measured: faster on every 1M-point workload and on the
-// 10M-point one, four times slower on the 100M-point one.
+// library (AUTO), the list-major scan serves batches with enough (query, list) pairs to group,
+// over indexes whose lists are short: there the per-query fixed costs of the query-major
+// kernel dominate, while long lists (the 100M-point configuration) gain more from its
+// per-block pruning.  Measured: faster on every 1M-point workload and on the 10M-point one,
+// four times slower on the 100M-point one.
 static bool use_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k, int32_t mode,
                            int32_t requested) {
   if (requested == IVFPQ_SCAN_QUERY_MAJOR || !list_major_supported(ix, nprobe, k)) return false;
   if (requested == IVFPQ_SCAN_LIST_MAJOR) return true;
-  return mode == IVFPQ_SCORE_DISTANCE && Q * (int64_t)nprobe >= 16384 && ix->N <= (int64_t)4096 * ix->nlist;
+  (void)mode;
+  return Q * (int64_t)nprobe >= 16384 && ix->N <= (int64_t)4096 * ix->nlist;
 }
 
 }  // namespace ivfpq
@@ -159,8 +160,8 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "scan_ablate")) {
-    if (value & ~(8 | 16 | 32 | 64)) {
-      set_error("set_option: scan_ablate accepts the bits 8, 16, 32 and 64 only");
+    if (value & ~(8 | 16 | 32 | 64 | 128)) {
+      set_error("set_option: scan_ablate accepts the bits 8, 16, 32, 64 and 128 only");
       return IVFPQ_ERR_INVALID_ARGUMENT;
     }
     set_scan_ablate(value);

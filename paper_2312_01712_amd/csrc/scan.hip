@@ -29,9 +29,12 @@
 
 namespace {
 
-template <int MT, int DSUB, int NW, bool DUMP>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wpe(MT, NW)))) void scan_kernel(ScanArgs a, RadiiSq r2) {
+// BYTE: the hit-count scorings with a byte table (one byte per entry, 256 bytes per row,
+// integer sums) instead of the float table; the sums are the same small integers either way.
+template <int MT, int DSUB, int NW, bool DUMP, bool BYTE = false>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wpe(BYTE ? (MT + 3) / 4 : MT, NW)))) void scan_kernel(ScanArgs a, RadiiSq r2) {
   constexpr int NT = NW * 64;
+  using Acc = std::conditional_t<BYTE, uint32_t, float>;
   constexpr int MPT = (MT + 3) / 4 * 4;
   extern __shared__ __align__(16) unsigned char smem[];
   const int M = MT > 0 ? MT : a.M;
@@ -39,7 +42,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   const int D = a.D;
   const int dsub = DSUB > 0 ? DSUB : a.dsub;
   // LDS carve: table | merge staging (aliases the table) | query | queues | tau
-  const int lut_bytes = M * 1024;
+  const int lut_bytes = M * (BYTE ? 256 : 1024);
   const int stage_bytes = NW * KP * 12;
   const int region0 = lut_bytes > stage_bytes ? lut_bytes : stage_bytes;
   LDS unsigned char *smem3 = (LDS unsigned char *)smem;
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   constexpr bool VEC = MT > 0 && (DSUB == 2 || DSUB == 4);
   constexpr int ITER = VEC ? (MT + NW - 1) / NW : 1;
   constexpr int DS4 = VEC ? DSUB : 1;
-  constexpr int WPE = scan_wpe(MT, NW);
+  constexpr int WPE = scan_wpe(BYTE ? (MT + 3) / 4 : MT, NW);
   // (a dsub = 4 row takes 16 registers and its table arithmetic more temporaries: with resident
   // rows the kernel spilled up to 198 registers, so those rows are all streamed)
   constexpr int RES_REGS = DS4 == 4 ? 0 : res_regs(WPE), RES_MAX_TOTAL = res_max_total(WPE);
@@ -301,7 +304,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
 #pragma unroll
             for (int j = 0; j < DS4; ++j) res[j] = sres[m * DSUB + j];
             const float4 v = lut_entry4<DSUB, MODE>(res, it < RES ? cbr[it < RES ? it : 0] : cbs[it >= RES ? it - RES : 0], sr2[m]);
-            *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
+            if constexpr (BYTE)   // penalties 0, 1, 2: four entries in one dword
+              *((LDS uint32_t *)lut + m * 64 + lane) = (uint32_t)v.x | ((uint32_t)v.y << 8) | ((uint32_t)v.z << 16) | ((uint32_t)v.w << 24);
+            else
+              *(LDS floatx4 *)(lut + m * 256 + 4 * lane) = floatx4{v.x, v.y, v.z, v.w};
             if (!DUMP)
               lo[it >> 3][it & 7] = umin32(umin32(__float_as_uint(v.x), __float_as_uint(v.y)),
                                            umin32(__float_as_uint(v.z), __float_as_uint(v.w)));
@@ -382,7 +388,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
           const int i = b * 64 + lane;
           const bool valid = i < len;
           if (DUMP) {
-            const float dist = adc_sum<MT>(lut, cur);
+            const float dist = BYTE ? adc_sum_bytes<MT>(lut, cur) : adc_sum<MT>(lut, cur);
             if (valid) {
               a.all_dist[dump_pos + i] = dist;
               a.all_ids[dump_pos + i] = a.ids[row0 + i];
@@ -392,7 +398,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             const uint32_t pref = (a.ablate & 8) ? SENT_D : (shared < st.tau.d ? shared : st.tau.d);
             // bound on the k-th smallest distance, enlarged as adc_part_exit needs it
             const float tauf = pref == SENT_D ? __builtin_inff() : __uint_as_float(pref) * 1.0001220703125f;
-            float dist = 0.0f;
+            Acc dist = 0;
             ++blocks;
             // no point of this list can reach the bound any more (it only tightens): the
             // wavefront is done with the list, and requests no further blocks of it
@@ -413,7 +419,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             if (HALF_OK && depth >= 1) load_chunks<MPT, HCH, NCH>(base, nb, b, lane, cur);
             if (!adc_part_exit<MT, HALF_OK ? MH : 0, MT>(lut, cur, ssuf, tauf, prune, valid, dist)) continue;
             ++full;
-            wave_offer(st, dist, valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
+            wave_offer(st, acc_value(dist), valid, row0 + i, a.ids, qd, qid, lane, a.k, sh);
           }
         }
         tot_blocks += blocks;
@@ -1050,9 +1056,9 @@ std::atomic<int> g_scan_waves{0};    // 0 = choose from the shape
 std::atomic<int> g_scan_ablate{0};   // pruning switches: 8 | 32 | 64
 std::atomic<int> g_scan_variant{0};  // code loads: 0 = default (first chunk ahead while pruning), 1 = always whole blocks, 2 = always the first half ahead, 3 = always the first chunk ahead
 
-template <int MT, int DSUB, int NW>
+template <int MT, int DSUB, int NW, bool BYTE = false>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
-  const int lut_bytes = a.M * 1024, stage = NW * KP * 12;
+  const int lut_bytes = a.M * (BYTE ? 256 : 1024), stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
                      (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 28 + 5 * IVFPQ_MAX_M * 4 +
                      (size_t)NW * SUF_SLOTS * 4 + 16;
@@ -1060,7 +1066,7 @@ int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump,
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
     return IVFPQ_ERR_UNSUPPORTED;
   }
-  auto kern = dump ? scan_kernel<MT, DSUB, NW, true> : scan_kernel<MT, DSUB, NW, false>;
+  auto kern = dump ? scan_kernel<MT, DSUB, NW, true, BYTE> : scan_kernel<MT, DSUB, NW, false, BYTE>;
   static std::atomic<uint64_t> prepared[2];
   if (int rc = prepare_kernel(kern, prepared[dump ? 1 : 0])) return rc;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds, s, a, r2);
@@ -1074,6 +1080,8 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
   // wavefronts with twice the registers, the run-time-M kernel (few registers) runs 16.
   // Tables of at most 32 KiB leave room for four workgroups per CU: 4 wavefronts each, so that
   // a workgroup's serial phases (table, barriers, final merge) overlap with three others'.
+  // hit-count scorings on a specialised shape: the byte table (8 wavefronts, whatever M)
+  if (MT > 0 && a.mode != 0 && !(a.ablate & 128) && (nw == 0 || nw == 8)) return launch_scan_t<MT, DSUB, 8, true>(a, r2, grid, dump, s);
   if (nw == 0) nw = (MT == 0 && a.M > 72) ? 16 : (a.M <= 32 ? 4 : 8);
   if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
   if (nw >= 8) return launch_scan_t<MT, DSUB, 8>(a, r2, grid, dump, s);

@@ -289,7 +289,8 @@ struct ScanArgs {
   int32_t load_mode;  // 0 default policy, 1 whole blocks, 2 always the first half of the chunks ahead, 3 always the first chunk
   int32_t ablate;  // pruning switches (results do not depend on them): 8 disables the early exit of the
                    // distance sums, 16 scans plainly from the first list on (no row minima, no checks),
-                   // 32 disables the switch to plain scanning, 64 the list-level bound
+                   // 32 disables the switch to plain scanning, 64 the list-level bound, 128 the byte
+                   // table of the hit-count scorings
 };
 
 // Codes of one point (the lane's) in registers.
@@ -380,6 +381,31 @@ __device__ __forceinline__ void lookup_group(const LDS float *lut, const CodeReg
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// The same for a BYTE table (hit-count scorings, paper Sec. 5.4: an entry stores its penalty
+// 0, 1 or 2 in one byte; a row is 256 bytes, one dword per LDS bank, so a wavefront's look-ups
+// of a row never conflict): acc += penalty of the point's code, as an integer.
+template <int MT>
+__device__ __forceinline__ void lookup_group(const LDS float *, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
+                                             int h, int h1, uint32_t &acc) {
+  uint32_t t[LOOKUP_GROUP];
+#pragma unroll
+  for (int j = 0; j < LOOKUP_GROUP; ++j) {
+    const int m = h + j;
+    if (m < h1) {
+      const uint32_t code = (r.w[m >> 2] >> (8 * (m & 3))) & 0xFFu;
+      t[j] = *(const LDS unsigned char *)(uintptr_t)(uint32_t)(m * 256 + code);   // the table starts at LDS address 0
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < LOOKUP_GROUP; ++j)
+    if (h + j < h1) acc += t[j];
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ float acc_value(float a) { return a; }
+__device__ __forceinline__ float acc_value(uint32_t a) { return (float)a; }   // exact: sums of at most 2 M
+
 template <int MT>
 __device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
                                 float start = 0.0f) {
@@ -387,6 +413,13 @@ __device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) /
 #pragma unroll
   for (int h = 0; h < MT; h += LOOKUP_GROUP) lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, MT), dist);
   return dist;
+}
+template <int MT>
+__device__ inline float adc_sum_bytes(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r) {
+  uint32_t acc = 0;
+#pragma unroll
+  for (int h = 0; h < MT; h += LOOKUP_GROUP) lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, MT), acc);
+  return (float)acc;
 }
 
 // Same sum, over subspaces [M0, M1), with early exit.  Table values are >= 0 and fp32
@@ -399,9 +432,10 @@ __device__ inline float adc_sum(const LDS float *lut, const CodeRegs<((MT + 3) /
 // Every 8 subspaces the wavefront checks whether any of its points can still reach the
 // bound; if none can, the rest of the block is skipped and false returned.  Points that
 // survive get exactly the sum adc_sum computes.  With `checks` off it is the plain sum.
-template <int MT, int M0, int M1>
+// (ACC: float for a table of distances, uint32_t for a byte table of penalties.)
+template <int MT, int M0, int M1, typename ACC>
 __device__ inline bool adc_part_exit(const LDS float *lut, const CodeRegs<((MT + 3) / 4 * 4) / 4> &r,
-                                     const LDS float *suf, float tauf, bool checks, bool valid, float &dist) {
+                                     const LDS float *suf, float tauf, bool checks, bool valid, ACC &dist) {
 #pragma unroll
   for (int g = M0; g < M1; g += 8) {
     // requested ahead of the look-ups, so that it has arrived when they have
@@ -411,7 +445,7 @@ __device__ inline bool adc_part_exit(const LDS float *lut, const CodeRegs<((MT +
     for (int h = g; h < cmin(g + 8, M1); h += LOOKUP_GROUP)
       lookup_group<MT>(lut, r, h, cmin(h + LOOKUP_GROUP, cmin(g + 8, M1)), dist);
     if (checks && cmin(g + 8, M1) < MT) {  // `checks` is uniform: off, a check costs a scalar branch
-      if (__ballot(valid && dist + rest <= tauf) == 0) return false;
+      if (__ballot(valid && acc_value(dist) + rest <= tauf) == 0) return false;
     }
   }
   return true;

@@ -146,7 +146,7 @@ static void search_arguments() {
   REQUIRE(ivfpq_set_option("lm_first", 1) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK);
   REQUIRE(ivfpq_scan_all(&ix, q, 4, 2, pid, radii, nullptr, nullptr, nullptr, nullptr, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_ablate", 1) == IVFPQ_ERR_INVALID_ARGUMENT);   // result-changing bits are gone
-  REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64) == IVFPQ_OK);
+  REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64 | 128) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("scan_ablate", 0) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("scan_loads", 4) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_waves", 5) == IVFPQ_ERR_INVALID_ARGUMENT);

@@ -18,6 +18,8 @@ from helpers import per_query_radii  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
+ORACLE_THREADS = 16   # the GPU box gives a job 16 host cores
+
 REL_TOL = 1e-4
 
 
@@ -485,13 +487,23 @@ def test_hit_count_scoring_1m(lib):
     radii = wl.calibrate_radii(w, idx, centres, 0.25)
     rq = per_query_radii(w, idx, centres, q, 0.25)
     gi = b.IvfPqIndex.from_index(idx)
-    sample = np.random.default_rng(2).choice(w.Q, 32, replace=False)
+    sample = np.sort(np.random.default_rng(2).choice(w.Q, 256, replace=False))
     for mode, r, d_rq in ((1, radii, None), (2, radii, None), (0, rq, _cuda(rq)), (2, rq, _cuda(rq))):
         ids, dist = gi.search(_cuda(q), w.nprobe, w.k, radii if d_rq is None else None, mode=mode, query_radii=d_rq)
         rs = r if d_rq is None else r[sample]
-        o_ids, o_dist = oracle.search(q[sample], idx, w.nprobe, w.k, rs, threads=8, mode=mode)
+        o_ids, o_dist = oracle.search(q[sample], idx, w.nprobe, w.k, rs, threads=ORACLE_THREADS, mode=mode)
         assert np.array_equal(ids.cpu().numpy()[sample], o_ids), (mode, d_rq is not None)
         assert_same_float(dist.cpu().numpy()[sample], o_dist, f"C2 mode {mode}")
+        if mode:   # the byte table (default) and the float table give the same scores; so does the list-major scan
+            try:
+                b.set_option("scan_ablate", 128)
+                ids_f, dist_f = gi.search(_cuda(q), w.nprobe, w.k, radii if d_rq is None else None, mode=mode, query_radii=d_rq)
+            finally:
+                b.set_option("scan_ablate", 0)
+            ids_l, dist_l = gi.search(_cuda(q), w.nprobe, w.k, radii if d_rq is None else None, mode=mode,
+                                      query_radii=d_rq, strategy=b.SCAN_LIST_MAJOR)
+            for other_ids, other_dist in ((ids_f, dist_f), (ids_l, dist_l)):
+                assert torch.equal(other_ids, ids) and torch.equal(other_dist.view(torch.int32), dist.view(torch.int32)), mode
     gi.close()
 
 
@@ -898,7 +910,6 @@ def test_list_major_ragged_lists(lib):
         gi.close()
 
 
-ORACLE_THREADS = 16   # the GPU box gives a job 16 host cores
 
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5_10M", "C5"])
