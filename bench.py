@@ -12,7 +12,7 @@ index and the queries resident in HBM.  Prints ONE JSON line:
                 asserted equal): algorithmic code bytes per launch / its mean duration
                 (HIP events on the launch stream).  The default kernel skips most of those
                 bytes by exact pruning, so its algorithmic rate is not an efficiency; it is
-                reported beside the plain scan as `pruned`, with the speed-up.
+                reported beside the plain scan as `default_path`, with the speed-up.
   c5            (default run only) the same figures for the 100M-point workload, the one
                 whose 6.4 GB of codes do not fit any cache: the HBM test proper
   cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same queries
@@ -41,12 +41,14 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+KERNEL_SOURCES = ("coarse.hip", "ivfpq_internal.h", "scan.hip", "scan_device.h", "scan_lm.hip")
+
+
 def csrc_sha256() -> str:
-    """Hash of the kernel sources (every .hip and .h under csrc/, in name order)."""
+    """Hash of the sources that hold the kernels of the search path (csrc/api.hip has none)."""
     h = hashlib.sha256()
-    for name in sorted(os.listdir(CSRC)):
-        if name.endswith((".hip", ".h")):
-            h.update(name.encode() + b"\0" + open(os.path.join(CSRC, name), "rb").read())
+    for name in KERNEL_SOURCES:
+        h.update(name.encode() + b"\0" + open(os.path.join(CSRC, name), "rb").read())
     return h.hexdigest()
 
 
@@ -98,6 +100,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
     passes = (k + 127) // 128   # the scan kernel keeps 128 keys per query and launch
     strategy = {"auto": binding.SCAN_AUTO, "query-major": binding.SCAN_QUERY_MAJOR, "list-major": binding.SCAN_LIST_MAJOR}[args.strategy]
     ws = gi.workspace(Q, nprobe, k, strategy)
+    gi_strategy = gi.resolve_strategy(Q, nprobe, k, args.score_mode, strategy)
     pid = torch.empty((Q, nprobe), dtype=torch.int32, device="cuda")
     out = (torch.empty((Q, k), dtype=torch.int64, device="cuda"), torch.empty((Q, k), dtype=torch.float32, device="cuda"))
     d_rq = rmodel = model_arrays = None
@@ -187,16 +190,22 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
         "value": Q * steps / elapsed, "ms_per_step": elapsed / steps * 1e3,
         "config": {"workload": f"{w.name}: N={w.N} D={w.D} nlist={w.nlist} M={w.M} Q={Q} nprobe={nprobe} k={k}",
                    "family": w.family, "similarity": args.metric, "keep_fraction": args.keep, "score_mode": args.score_mode,
-                   "scan_strategy": args.strategy,
+                   "scan_strategy": args.strategy + (" -> " + ("list-major" if gi_strategy == binding.SCAN_LIST_MAJOR else "query-major") if args.strategy == "auto" else ""),
                    "radii": f"per-query (density map, fitted to {args.radius_target}, scale {args.radius_scale})" if args.dynamic_radii else "per-subspace",
                    "keep_fraction_note": "with exact pruning on, the radius sets recall, not throughput",
                    "recall_at_k": recall, "recall_truth_k": min(k, 100), "r1_at_k": r1,
                    "coarse_ms": coarse_ms, "scan_ms": scan_ms, "coarse_exact_fallbacks_per_step": fallbacks},
     }
     default_traffic = measured_traffic(w.name, args.keep, "default") if (args.score_mode == 0 and not args.dynamic_radii and k == w.k and not metric and not plain_only) else None
-    pruned = {"kernel": "probe_bound_kernel + scan_kernel as shipped (list-level bound, early exit of the sums, chunked loads: bytes that cannot change the result are not read)",
+    resolved = gi_strategy
+    pruned = {"strategy": "list-major" if resolved == binding.SCAN_LIST_MAJOR else "query-major",
+              "kernel": ("probe_bound_kernel + lm_pairs / lm_offsets + lm_scan_kernel (head pass: every query's nearest list, "
+                         "ranked list-major; main pass: the other lists that the list-level bound does not rule out, two "
+                         "queries per table pass) + lm_merge_kernel, as shipped") if resolved == binding.SCAN_LIST_MAJOR else
+                        "probe_bound_kernel + scan_kernel as shipped (list-level bound, early exit of the sums, chunked loads: "
+                        "bytes that cannot change the result are not read)",
               "avg_launch_ms": launch_ms, "algorithmic_rate": algo_bytes / (launch_ms * 1e-3) / 1e9, "unit": "GB/s",
-              "note": "algorithmic bytes over time: exceeds the HBM peak when pruning skips bytes; not an efficiency",
+              "note": "algorithmic bytes over time: exceeds the HBM peak when exact pruning skips bytes; not an efficiency",
               "traffic": default_traffic,
               "hbm_rate_from_traffic": (default_traffic / (launch_ms * 1e-3) / 1e9) if default_traffic else None}
     if plain is not None:
@@ -205,7 +214,7 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
                            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                            "traffic": measured_traffic(w.name, args.keep, "plain") if (args.score_mode == 0 and not args.dynamic_radii and k == w.k and not metric) else None,
                            "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": plain,
-                           "pruned": dict(pruned, speedup_over_plain=plain / launch_ms)}
+                           "default_path": dict(pruned, speedup_over_plain=plain / launch_ms)}
     else:   # a run with the switches set by hand: the timed kernel is whatever they select
         achieved = algo_bytes / (launch_ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "kernel": f"scan_kernel with scan_ablate {args.scan_ablate}, scan_loads {args.scan_loads}",

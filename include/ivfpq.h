@@ -235,6 +235,11 @@ typedef struct {
 size_t ivfpq_search_workspace_bytes_ex(const ivfpq_index *index, int64_t Q, int32_t nprobe, int32_t k,
                                        const ivfpq_scoring *scoring);
 
+/* The strategy such a call will run with: IVFPQ_SCAN_QUERY_MAJOR or IVFPQ_SCAN_LIST_MAJOR
+ * (scoring NULL: AUTO, distance scoring); a negative ivfpq_status on invalid arguments. */
+int ivfpq_resolve_strategy(const ivfpq_index *index, int64_t Q, int32_t nprobe, int32_t k,
+                           const ivfpq_scoring *scoring);
+
 int ivfpq_search_ex(const ivfpq_index *index, const float *d_queries, int64_t Q, int32_t nprobe,
                     int32_t k, const float *radii, const ivfpq_scoring *scoring, int64_t *d_out_ids,
                     float *d_out_dist, void *d_workspace, size_t workspace_bytes, void *hip_stream);

@@ -25,7 +25,7 @@ SYMBOLS = [
     "ivfpq_set_option", "ivfpq_coarse_fallbacks", "ivfpq_last_error",
     "ivfpq_search_ex", "ivfpq_build_lut_ex", "ivfpq_scan_topk_ex", "ivfpq_scan_all_ex",
     "ivfpq_radius_model_create", "ivfpq_radius_model_destroy", "ivfpq_query_radii",
-    "ivfpq_search_noalloc", "ivfpq_search_workspace_bytes_ex",
+    "ivfpq_search_noalloc", "ivfpq_search_workspace_bytes_ex", "ivfpq_resolve_strategy",
 ]
 
 SCORE_DISTANCE, SCORE_HIT_COUNT, SCORE_HIT_REWARD = 0, 1, 2
@@ -75,6 +75,7 @@ def load_library():
     lib.ivfpq_search_workspace_bytes.restype = sz
     lib.ivfpq_search_workspace_bytes_ex.argtypes = [vp, i64, i32, i32, ctypes.POINTER(_Scoring)]
     lib.ivfpq_search_workspace_bytes_ex.restype = sz
+    lib.ivfpq_resolve_strategy.argtypes = [vp, i64, i32, i32, ctypes.POINTER(_Scoring)]
     lib.ivfpq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.ivfpq_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
     lib.ivfpq_coarse.argtypes = [vp, vp, i64, i32, vp, vp, vp, sz, vp]
@@ -266,6 +267,14 @@ class IvfPqIndex:
     def workspace_bytes(self, Q: int, nprobe: int, k: int, strategy: int = SCAN_AUTO) -> int:
         sc = _Scoring(mode=SCORE_DISTANCE, d_query_radii=None, strategy=int(strategy))
         return int(load_library().ivfpq_search_workspace_bytes_ex(self._h, Q, nprobe, k, ctypes.byref(sc)))
+
+    def resolve_strategy(self, Q: int, nprobe: int, k: int, mode: int = SCORE_DISTANCE, strategy: int = SCAN_AUTO) -> int:
+        """SCAN_QUERY_MAJOR or SCAN_LIST_MAJOR: what a call of this shape runs with."""
+        sc = _Scoring(mode=int(mode), d_query_radii=None, strategy=int(strategy))
+        rc = int(load_library().ivfpq_resolve_strategy(self._h, Q, nprobe, k, ctypes.byref(sc)))
+        if rc < 0:
+            _check(rc)
+        return rc
 
     def workspace(self, Q: int, nprobe: int, k: int, strategy: int = SCAN_AUTO) -> torch.Tensor:
         n = max(256, self.workspace_bytes(Q, nprobe, k, strategy))

@@ -457,6 +457,19 @@ size_t ivfpq_search_workspace_bytes_ex(const ivfpq_index *ix, int64_t Q, int32_t
   return n < 256 ? 256 : n;
 }
 
+int ivfpq_resolve_strategy(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32_t k, const ivfpq_scoring *sc) {
+  if (!ix || Q < 0 || nprobe < 1 || nprobe > ix->nlist || k < 1) {
+    set_error("resolve_strategy: invalid argument");
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  if (sc && (sc->strategy < IVFPQ_SCAN_AUTO || sc->strategy > IVFPQ_SCAN_LIST_MAJOR)) {
+    set_error("resolve_strategy: scan strategy %d unknown", sc->strategy);
+    return IVFPQ_ERR_INVALID_ARGUMENT;
+  }
+  return use_list_major(ix, Q, nprobe, k, sc ? sc->mode : IVFPQ_SCORE_DISTANCE, sc ? sc->strategy : IVFPQ_SCAN_AUTO)
+             ? IVFPQ_SCAN_LIST_MAJOR : IVFPQ_SCAN_QUERY_MAJOR;
+}
+
 int ivfpq_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                  int32_t *d_probe_ids, float *d_probe_dist, void *ws, size_t ws_bytes, void *stream) {
   const char *fn = "coarse";

@@ -108,7 +108,8 @@ __global__ __launch_bounds__(256) void lm_pairs_kernel(LmArgs a, int fill, int h
 }
 
 // Slot ranges of the lists: base[c] = sum over c' < c of cnt[c'] rounded up to LM_G.  The
-// padding slot of an odd range is marked (query -1), the cursors are cleared.  One workgroup.
+// padding slot of an odd range is marked (query -1), the cursors and the counts are cleared.
+// One workgroup.
 __global__ __launch_bounds__(1024) void lm_offsets_kernel(LmArgs a) {
   __shared__ int part[1024];
   const int tid = threadIdx.x;
@@ -132,6 +133,7 @@ __global__ __launch_bounds__(1024) void lm_offsets_kernel(LmArgs a) {
     for (int j = n; j < padded; ++j) a.pairs[run + j] = make_int2(-1, c);
     run += padded;
     a.cur[c] = 0;
+    a.cnt[c] = 0;   // left clear for the next pass over this workspace
   }
   if (tid == 1023) a.base[a.nlist] = part[1023];
 }
@@ -524,15 +526,18 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
         if (live && (uint32_t)i < n) {
           me.d = coll_d[g * LM_COLLECT + i];
           me.id = coll_id[g * LM_COLLECT + i];
-          uint32_t before = 0;
+          // distances first; ids only where a distance ties (rare: the slow loop usually does not run)
+          uint32_t before = 0, ties = 0;
           const int j0 = h * (LM_COLLECT / 2);
           const int j1 = j0 + LM_COLLECT / 2 < (int)n ? j0 + LM_COLLECT / 2 : (int)n;
           for (int j = j0; j < j1; ++j) {
-            Key o;
-            o.d = coll_d[g * LM_COLLECT + j];
-            o.id = coll_id[g * LM_COLLECT + j];
-            before += kless(o, me) ? 1u : 0u;
+            const uint32_t od = coll_d[g * LM_COLLECT + j];
+            before += od < me.d ? 1u : 0u;
+            ties += od == me.d ? 1u : 0u;
           }
+          if (ties > ((i >= j0 && i < j1) ? 1u : 0u))
+            for (int j = j0; j < j1; ++j)
+              before += (coll_d[g * LM_COLLECT + j] == me.d && coll_id[g * LM_COLLECT + j] < me.id) ? 1u : 0u;
           if (before) __hip_atomic_fetch_add(&coll_rank[g * LM_COLLECT + i], before, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         __syncthreads();
@@ -744,9 +749,9 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   // pass leaves out (qmap_head).  Otherwise (several first lists, or the hit-count scorings,
   // whose masses of equal scores the head pass's selection is not made for): query-major.
   const bool head_pass = w.first == 1 && mode == IVFPQ_SCORE_DISTANCE && a.head_max >= 64;
+  rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);   // the per-list counts start at zero; lm_offsets_kernel leaves them so
+  if (rc) return rc;
   if (head_pass) {
-    rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);
-    if (rc) return rc;
     const unsigned qgrid = (unsigned)((Q + 255) / 256);
     hipLaunchKernelGGL(lm_pairs_kernel, dim3(qgrid), dim3(256), 0, s, a, 0, 1);
     hipLaunchKernelGGL(lm_offsets_kernel, dim3(1), dim3(1024), 0, s, a);
@@ -760,8 +765,6 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   if (rc) return rc;
 
   // ---- the other lists, list-major: pairs bucketed by list, scan, merge ----
-  rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);
-  if (rc) return rc;
   const int64_t npairs = Q * (nprobe - w.first);
   const unsigned pair_grid = (unsigned)((npairs + 255) / 256);
   hipLaunchKernelGGL(lm_pairs_kernel, dim3(pair_grid), dim3(256), 0, s, a, 0, 0);
