@@ -97,7 +97,9 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
     log(f"[{w.name}] index built in {time.time() - t0:.1f}s; code bytes on device {gi.info()['code_bytes']}")
 
     Q, nprobe, k = w.Q, w.nprobe, (args.k or w.k)
-    passes = (k + 127) // 128   # the scan kernel keeps 128 keys per query and launch
+    # a wavefront's list holds 128 keys: more neighbours take one pass with per-query slots
+    # (L2 distances) or ceil(k / 128) passes (inner product, hit counts)
+    passes = 1 if (metric == 0 and args.score_mode == 0 and args.wide_cap != 0) else (k + 127) // 128
     strategy = {"auto": binding.SCAN_AUTO, "query-major": binding.SCAN_QUERY_MAJOR, "list-major": binding.SCAN_LIST_MAJOR}[args.strategy]
     ws = gi.workspace(Q, nprobe, k, strategy)
     gi_strategy = gi.resolve_strategy(Q, nprobe, k, args.score_mode, strategy)
@@ -284,6 +286,7 @@ def main():
                          "1M- and 10M-point workloads, query-major on the 100M-point one)")
     ap.add_argument("--lm-first", type=int, default=0, help="list-major: lists per query scanned query-major first (0: the library's default)")
     ap.add_argument("--lm-cap", type=int, default=0, help="list-major: candidate slots per query (0: the library's default)")
+    ap.add_argument("--wide-cap", type=int, default=-1, help="k above 128: slots per query of the one-pass selection (0: off, pass by pass)")
     ap.add_argument("--scan-waves", type=int, default=0)
     ap.add_argument("--scan-loads", type=int, default=0, help="code loads: 0 default (first chunk ahead while pruning), 1 whole blocks, 2 / 3 always first half / first chunk")
     ap.add_argument("--scan-ablate", type=int, default=0, help="exact-pruning switches to turn off: 8 | 16 | 32 | 64 (results unchanged)")
@@ -314,6 +317,8 @@ def main():
         binding.set_option("lm_first", args.lm_first)
     if args.lm_cap:
         binding.set_option("lm_cap", args.lm_cap)
+    if args.wide_cap >= 0:
+        binding.set_option("wide_cap", args.wide_cap)
     if args.scan_waves:
         binding.set_option("scan_waves", args.scan_waves)
     if args.scan_loads:

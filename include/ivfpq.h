@@ -110,7 +110,11 @@ void ivfpq_index_destroy(ivfpq_index *index);
 
 /* Bytes of device workspace the search-side calls need for a batch of Q
  * queries (0 on invalid arguments), with the scan strategy left to the library.
- * The workspace must be 256-byte aligned. */
+ * The workspace must be 256-byte aligned.  For 128 < k <= 1024 with L2 distances
+ * the figure includes the per-query slots ("wide_cap" below, 12 bytes each, for
+ * at most 1 GiB at a time) that let one pass over the lists produce all k
+ * neighbours; a workspace sized for k = 128 is accepted too, and the call then
+ * takes ceil(k / 128) passes.  Results are the same either way. */
 size_t ivfpq_search_workspace_bytes(const ivfpq_index *index, int64_t Q, int32_t nprobe, int32_t k);
 
 /* The whole search path (stages 1-4) for a batch.
@@ -336,6 +340,11 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  *   "lm_cap"       list-major scan: candidate slots per query (64 .. 65536, default 4096); a
  *                  query that overflows them is redone query-major.  Set both before sizing
  *                  the workspace.
+ *   "wide_cap"     128 < k <= 1024: slots per query for the keys within the running bound on the
+ *                  k-th distance (1024 .. 65536, default 8192).  Between lists the bound, which
+ *                  only tightens, clears the slots it has overtaken; a query that still runs
+ *                  out of slots is redone pass by pass.  0: no slots, every query pass by
+ *                  pass (128 neighbours per pass).  Set before sizing the workspace.
  *   "scan_ablate"  bit mask that switches exact pruning off, to measure what it saves: 8 the
  *                  early exit of the distance sums, 16 all of the per-block pruning from the
  *                  first list on (no row minima, no checks: what the kernel otherwise switches

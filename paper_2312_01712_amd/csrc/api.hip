@@ -75,6 +75,30 @@ Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32
   return w;
 }
 
+static std::atomic<int> g_wide_cap{8192};  // slots per query of the wide selection
+
+void set_wide_cap(int v) { g_wide_cap.store(v, std::memory_order_relaxed); }
+
+WideWorkspace plan_wide(const ivfpq_index *ix, int64_t Q, int32_t k, int32_t mode) {
+  WideWorkspace w = {};
+  if (ix->metric != IVFPQ_METRIC_L2 || mode != 0 || k <= 128 || k > 8 * 128 || Q < 1) return w;
+  w.cap = g_wide_cap.load(std::memory_order_relaxed);
+  if (w.cap == 0) return w;  // switched off: pass by pass
+  // the slot arrays take at most 1 GiB: larger batches go through them in chunks
+  int64_t qc = ((int64_t)1 << 30) / ((int64_t)w.cap * 12);
+  if (qc < 1024) qc = 1024;
+  w.q_chunk = qc < Q ? qc : Q;
+  auto a256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  size_t off = 0;
+  w.d = off;     off += a256((size_t)w.q_chunk * w.cap * 4);
+  w.id = off;    off += a256((size_t)w.q_chunk * w.cap * 8);
+  w.n = off;     off += a256((size_t)w.q_chunk * 4);
+  w.bound = off; off += a256((size_t)w.q_chunk * 4);
+  w.qmap = off;  off += a256((size_t)w.q_chunk * 4);
+  w.total = off;
+  return w;
+}
+
 static int check_common(const ivfpq_index *ix, const void *q, int64_t Q, int32_t nprobe, const char *fn) {
   if (!ix) { set_error("%s: index is NULL", fn); return IVFPQ_ERR_INVALID_ARGUMENT; }
   if (Q < 0) { set_error("%s: Q = %lld is negative", fn, (long long)Q); return IVFPQ_ERR_INVALID_ARGUMENT; }
@@ -180,6 +204,11 @@ int ivfpq_set_option(const char *name, int value) {
   if (name && !strcmp(name, "lm_cap")) {
     if (value < 64 || value > 65536) { set_error("set_option: lm_cap must be in [64, 65536]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_lm_cap(value);
+    return IVFPQ_OK;
+  }
+  if (name && !strcmp(name, "wide_cap")) {
+    if (value != 0 && (value < 1024 || value > 65536)) { set_error("set_option: wide_cap must be 0 or in [1024, 65536]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    set_wide_cap(value);
     return IVFPQ_OK;
   }
   set_error("set_option: unknown option");
@@ -454,6 +483,8 @@ size_t ivfpq_search_workspace_bytes_ex(const ivfpq_index *ix, int64_t Q, int32_t
   size_t n = w.total;
   if (use_list_major(ix, Q, nprobe, k, sc ? sc->mode : IVFPQ_SCORE_DISTANCE, sc ? sc->strategy : IVFPQ_SCAN_AUTO))
     n = align256(w.total) + plan_list_major(ix, Q, nprobe).total;
+  else if (const size_t wide = plan_wide(ix, Q, k, sc ? sc->mode : IVFPQ_SCORE_DISTANCE).total)
+    n = align256(w.total) + wide;
   return n < 256 ? 256 : n;
 }
 
@@ -510,6 +541,24 @@ static int unpack_scoring(const ivfpq_index *ix, const ivfpq_scoring *sc, const 
     return IVFPQ_OK;
   }
   return make_radii(ix, radii, r2, fn);
+}
+
+// Stages 2-4 query-major.  For k above 128 the slots of the wide selection lie behind the usual
+// workspace; a workspace without room for them still serves the call, pass by pass.
+static int scan_query_major(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
+                            const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t mode, const float *qr,
+                            int64_t *d_out_ids, float *d_out_dist, const Workspace &w, char *base, size_t ws_bytes,
+                            hipStream_t s) {
+  const WideWorkspace ww = plan_wide(ix, Q, k, mode);
+  ScanView view = {0, nullptr, false, nullptr, nullptr};
+  if (ww.total > 0 && ws_bytes >= align256(w.total) + ww.total) {
+    view.wide = &ww;
+    view.wide_base = base + align256(w.total);
+  }
+  return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, w.nsplit,
+                     reinterpret_cast<uint32_t *>(base + w.part_d), reinterpret_cast<int64_t *>(base + w.part_id),
+                     d_out_ids, d_out_dist, nullptr, nullptr, nullptr, nullptr, mode, qr,
+                     reinterpret_cast<float *>(base + w.probe_dist), s, &view);
 }
 
 // Stages 2-4 list-major: the usual workspace, then the list-major part behind it.
@@ -569,11 +618,8 @@ int ivfpq_scan_topk_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q,
     return scan_list_major(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, ws,
                            ws_bytes, static_cast<hipStream_t>(stream), fn);
   if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
-  return launch_scan(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, w.nsplit,
-                     reinterpret_cast<uint32_t *>(base + w.part_d),
-                     reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, mode, qr, reinterpret_cast<float *>(base + w.probe_dist),
-                     static_cast<hipStream_t>(stream));
+  return scan_query_major(ix, d_queries, Q, nprobe, d_probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, base,
+                          ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int ivfpq_scan_topk(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
@@ -618,16 +664,14 @@ static int scratch_address(void **out, const char *fn) {
 // Stages 1-4 with the workspace `base` carved as `w` says.
 static int search_in_workspace(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                                int32_t k, const RadiiSq &r2, int32_t mode, const float *qr, int64_t *d_out_ids,
-                               float *d_out_dist, const Workspace &w, char *base, hipStream_t s) {
+                               float *d_out_dist, const Workspace &w, char *base, size_t ws_bytes, hipStream_t s) {
   int32_t *probe_ids = reinterpret_cast<int32_t *>(base + w.probe_ids);
   int rc = launch_coarse(ix, d_queries, Q, nprobe, probe_ids, nullptr,
                          reinterpret_cast<float *>(base + w.coarse_dist), w.q_chunk, w.nlist_pad,
                          reinterpret_cast<int32_t *>(base + w.coarse_flags), s);
   if (rc) return rc;
-  return launch_scan(ix, d_queries, Q, nprobe, probe_ids, k, r2, w.nsplit,
-                     reinterpret_cast<uint32_t *>(base + w.part_d),
-                     reinterpret_cast<int64_t *>(base + w.part_id), d_out_ids, d_out_dist, nullptr,
-                     nullptr, nullptr, nullptr, mode, qr, reinterpret_cast<float *>(base + w.probe_dist), s);
+  return scan_query_major(ix, d_queries, Q, nprobe, probe_ids, k, r2, mode, qr, d_out_ids, d_out_dist, w, base,
+                          ws_bytes, s);
 }
 
 int ivfpq_search_noalloc(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
@@ -652,7 +696,8 @@ int ivfpq_search_noalloc(const ivfpq_index *ix, const float *d_queries, int64_t 
   // Nothing in the workspace has to start at zero: every region is written in full (for the
   // rows and probes of this call) before it is read, so the previous call's contents do not matter.
   return search_in_workspace(ix, d_queries, Q, nprobe, k, r2, IVFPQ_SCORE_DISTANCE, nullptr, d_out_ids,
-                             d_out_dist, w, static_cast<char *>(base), static_cast<hipStream_t>(stream));
+                             d_out_dist, w, static_cast<char *>(base), IVFPQ_NOALLOC_SCRATCH_BYTES,
+                             static_cast<hipStream_t>(stream));
 }
 
 int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,
@@ -684,7 +729,7 @@ int ivfpq_search_ex(const ivfpq_index *ix, const float *d_queries, int64_t Q, in
   }
   if ((rc = check_workspace(w, ws, ws_bytes, fn))) return rc;
   return search_in_workspace(ix, d_queries, Q, nprobe, k, r2, mode, qr, d_out_ids, d_out_dist, w,
-                             static_cast<char *>(ws), static_cast<hipStream_t>(stream));
+                             static_cast<char *>(ws), ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int ivfpq_search(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe, int32_t k,

@@ -90,11 +90,27 @@ int launch_coarse(const ivfpq_index *ix, const float *d_queries, int64_t Q, int3
 int launch_build_lut(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                      const int32_t *d_probe_ids, const RadiiSq &r2, float *d_lut, uint64_t *d_mask,
                      int32_t mode, const float *d_query_radii, hipStream_t s);
+// Workspace of the wide selection (more than 128 neighbours per query in one pass of the
+// query-major scan): offsets into its part of the workspace, 256-byte aligned.
+struct WideWorkspace {
+  size_t d, id;      // [q_chunk][cap] distance keys / rows within the bound
+  size_t n, bound;   // [q_chunk] slots in use (-1: overflow) / final bound
+  size_t qmap;       // [q_chunk] int32: 0 for the queries left to the pass-by-pass path, else -1
+  size_t total;      // 0: the wide selection does not apply
+  int64_t q_chunk;   // queries that share the slot arrays at a time
+  int32_t cap;       // slots per query
+};
+// total == 0 unless the wide selection serves this call (L2 distances, 128 < k <= 1024).
+WideWorkspace plan_wide(const ivfpq_index *ix, int64_t Q, int32_t k, int32_t mode);
+void set_wide_cap(int v);  // slots per query of the wide selection (1024 .. 65536)
+
 // Which part of the probe table a scan launch covers, and for which queries (NULL: all of it).
 struct ScanView {
   int32_t probe_stride;  // row stride of d_probe_ids / d_probe_lb when only the first nprobe of a longer row are scanned (0: nprobe)
   const int32_t *qmap;   // device [Q] or NULL: queries with a negative entry are left out
   bool bounds_ready;     // d_probe_lb already holds the list-level bounds of every row
+  const WideWorkspace *wide;  // NULL: k above 128 is produced pass by pass
+  char *wide_base;            // device base of the wide selection's part of the workspace
 };
 int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                 const int32_t *d_probe_ids, int32_t k, const RadiiSq &r2, int32_t nsplit,

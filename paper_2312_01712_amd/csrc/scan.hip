@@ -56,7 +56,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   // per-probe list metadata of up to META probes, staged once per chunk of probes so
   // that a probe does not start with a chain of dependent scalar loads
   constexpr int META = 64;
-  const int tau_bytes = (4 * (NW + 1) + 15) & ~15;
+  const int tau_bytes = (4 * (2 * NW + 4) + 15) & ~15;  // bound | ranks [NW] | wide: slots taken, overflow | wide: counts [NW]
   LDS int64_t *meta_row0 = (LDS int64_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12 + tau_bytes);
   LDS int64_t *meta_blk = meta_row0 + META;
   LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
@@ -104,12 +104,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   const int mode = a.mode;
   if (tid <= NW) tau_words[tid] = SENT_D;
   if (tid < 2) stat[tid] = 0u;
+  const bool wide = !DUMP && a.wide_cap > 0;
+  if (tid < 2) tau_words[NW + 1 + tid] = 0u;
   SharedTau sh;
   sh.bound = tau_words;
   sh.rank = tau_words + 1;
   sh.nw = NW;
   sh.wave = wave;
-  sh.jrank = (a.k + NW - 1) / NW;
+  // wide selection: the bound is on the k_out-th distance, from ceil(k_out / NW) keys per wavefront
+  sh.jrank = ((wide ? a.k_out : a.k) + NW - 1) / NW;
+  sh.wide = wide ? tau_words + NW + 1 : nullptr;
+  sh.wide_d = wide ? a.wide_d + q * a.wide_cap : nullptr;
+  sh.wide_id = wide ? a.wide_id + q * a.wide_cap : nullptr;
+  sh.wide_cap = a.wide_cap;
 
   WaveTop st;
   init_wave_top<false, DUMP>(st, a, q);
@@ -247,6 +254,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
       else load_chunks<MPT, 0, HALF_OK ? 1 : NCH>(base, nb, b0, lane, nxt);
     }
     __syncthreads();  // previous list fully scanned (and sq written) before the table changes
+    if (!DUMP && wide && sh.wide[0] > (uint32_t)(a.wide_cap >> 2) && sh.wide[1] == 0u)
+      wide_compact<NW>(sh, tau_words + NW + 3, tid, lane, wave);
     if (VEC && !DUMP && !decided && p - p_begin >= PROBE_LISTS) {  // every wavefront has pushed its counts
       decided = true;
       if (!(a.ablate & 32)) {
@@ -395,7 +404,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
             }
           } else {
             const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
-            const uint32_t pref = (a.ablate & 8) ? SENT_D : (shared < st.tau.d ? shared : st.tau.d);
+            const uint32_t pref = (a.ablate & 8) ? SENT_D : ((wide || shared < st.tau.d) ? shared : st.tau.d);
             // bound on the k-th smallest distance, enlarged as adc_part_exit needs it
             const float tauf = pref == SENT_D ? __builtin_inff() : __uint_as_float(pref) * 1.0001220703125f;
             Acc dist = 0;
@@ -445,7 +454,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(scan_wp
   }
   if (DUMP) return;
 
-  finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
+  if (wide) finish_wide(st, qd, qid, lane, tid, sh, a, q);
+  else finish_topk<NW>(st, qd, qid, lane, wave, sh, smem3, a, q, split);
 }
 
 
@@ -557,7 +567,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   LDS int64_t *queue_id = (LDS int64_t *)(smem3 + region0 + sq_bytes);
   LDS uint32_t *queue_d = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 8);
   LDS uint32_t *tau_words = (LDS uint32_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12);
-  const int tau_bytes = (4 * (NW + 1) + 15) & ~15;
+  const int tau_bytes = (4 * (2 * NW + 4) + 15) & ~15;  // bound | ranks [NW] | wide: slots taken, overflow | wide: counts [NW]
   LDS int64_t *meta_row0 = (LDS int64_t *)(smem3 + region0 + sq_bytes + NW * 64 * 12 + tau_bytes);
   LDS int64_t *meta_blk = meta_row0 + META;
   LDS int32_t *meta_len = (LDS int32_t *)(meta_blk + META);
@@ -612,6 +622,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
   sh.nw = NW;
   sh.wave = wave;
   sh.jrank = (a.k + NW - 1) / NW;
+  sh.wide = nullptr;  // the inner-product scan produces k above KP pass by pass
+  sh.wide_d = nullptr;
+  sh.wide_id = nullptr;
+  sh.wide_cap = 0;
   WaveTop st;
   init_wave_top<true, DUMP>(st, a, q);
   LDS uint32_t *qd = queue_d + wave * 64;
@@ -882,6 +896,87 @@ __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restric
   }
 }
 
+// ---------------------------------------------------------------------------
+// Wide selection, second step: the keys a query's workgroup kept (all within its final
+// bound on the k-th distance, plus those the bound overtook after they were stored) are
+// filtered by that bound, given their ids, sorted by (distance, id) in LDS and the first k
+// written out.
+// A query whose slots overflowed, or that has more than WIDE_SORT keys within the bound
+// (long runs of equal distances), gets map[q] = 0 and is served pass by pass afterwards;
+// every other query gets map[q] = -1.
+constexpr int WIDE_SORT = 2048;
+
+__global__ __launch_bounds__(256) void wide_select_kernel(const uint32_t *__restrict__ wd, const int64_t *__restrict__ wid,
+                                                          const int32_t *__restrict__ wn,
+                                                          const uint32_t *__restrict__ wbound,
+                                                          const int64_t *__restrict__ ids, int cap, int k,
+                                                          int64_t *__restrict__ out_ids, float *__restrict__ out_dist,
+                                                          int32_t *__restrict__ map) {
+  __shared__ uint32_t sd[WIDE_SORT];
+  __shared__ int64_t sid[WIDE_SORT];
+  __shared__ uint32_t cnt;
+  const int tid = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  const int n = wn[q];
+  if (n < 0) {
+    if (tid == 0) map[q] = 0;
+    return;
+  }
+  const uint32_t bound = wbound[q];
+  if (tid == 0) cnt = 0u;
+  __syncthreads();
+  const uint32_t *d = wd + q * cap;
+  const int64_t *id = wid + q * cap;
+  for (int i = tid; i < n; i += 256) {
+    const uint32_t v = d[i];
+    if (v <= bound) {
+      const uint32_t slot = __hip_atomic_fetch_add(&cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (slot < (uint32_t)WIDE_SORT) {
+        sd[slot] = v;
+        sid[slot] = ids[id[i]];  // the slots hold rows
+      }
+    }
+  }
+  __syncthreads();
+  const int m = (int)cnt;
+  if (m > WIDE_SORT) {
+    if (tid == 0) map[q] = 0;
+    return;
+  }
+  if (tid == 0) map[q] = -1;
+  int P = 2;
+  while (P < m) P <<= 1;
+  for (int i = m + tid; i < P; i += 256) {
+    sd[i] = SENT_D;
+    sid[i] = SENT_ID;
+  }
+  __syncthreads();
+  for (int k2 = 2; k2 <= P; k2 <<= 1) {
+    for (int j = k2 >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (P >> 1); t += 256) {
+        const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+        const uint32_t a0 = sd[lo], a1 = sd[hi];
+        const bool greater = a0 != a1 ? a0 > a1 : sid[lo] > sid[hi];
+        const bool asc = (lo & k2) == 0;  // direction of this pair's run
+        if (greater == asc) {
+          const int64_t i0 = sid[lo], i1 = sid[hi];
+          sd[lo] = a1;
+          sd[hi] = a0;
+          sid[lo] = i1;
+          sid[hi] = i0;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int i = tid; i < k; i += 256) {
+    const bool real = i < m;
+    out_ids[q * k + i] = real ? sid[i] : -1;
+    out_dist[q * k + i] = real ? key_dist<false>(sd[i]) : __builtin_inff();
+  }
+}
+
+
 // Merge the probe groups' partial lists of a query (one wavefront per query).
 __global__ __launch_bounds__(64) void merge_kernel(const uint32_t *__restrict__ part_d,
                                                    const int64_t *__restrict__ part_id, int nsplit,
@@ -1060,7 +1155,7 @@ template <int MT, int DSUB, int NW, bool BYTE = false>
 int launch_scan_t(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump, hipStream_t s) {
   const int lut_bytes = a.M * (BYTE ? 256 : 1024), stage = NW * KP * 12;
   const size_t lds = (size_t)(lut_bytes > stage ? lut_bytes : stage) + 2 * ((a.D * 4 + 15) & ~15) +
-                     (size_t)NW * 64 * 12 + ((4 * (NW + 1) + 15) & ~15) + 64 * 28 + 5 * IVFPQ_MAX_M * 4 +
+                     (size_t)NW * 64 * 12 + ((4 * (2 * NW + 4) + 15) & ~15) + 64 * 28 + 5 * IVFPQ_MAX_M * 4 +
                      (size_t)NW * SUF_SLOTS * 4 + 16;
   if (lds > (size_t)LDS_PER_CU) {
     ivfpq::set_error("scan: %zu bytes of LDS needed, 163840 available", lds);
@@ -1083,6 +1178,7 @@ int launch_scan_nw(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
   // hit-count scorings on a specialised shape: the byte table (8 wavefronts, whatever M)
   if (MT > 0 && a.mode != 0 && !(a.ablate & 128) && (nw == 0 || nw == 8)) return launch_scan_t<MT, DSUB, 8, true>(a, r2, grid, dump, s);
   if (nw == 0) nw = (MT == 0 && a.M > 72) ? 16 : (a.M <= 32 ? 4 : 8);
+  if (a.wide_cap > 0 && nw * KP < a.k_out) nw = 8;  // the bound takes ceil(k_out / nw) <= KP keys of every wavefront
   if (nw >= 16) return launch_scan_t<MT, DSUB, 16>(a, r2, grid, dump, s);
   if (nw >= 8) return launch_scan_t<MT, DSUB, 8>(a, r2, grid, dump, s);
   return launch_scan_t<MT, DSUB, 4>(a, r2, grid, dump, s);
@@ -1162,6 +1258,11 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
   a.mode = mode;
   a.query_radii = d_query_radii;
   a.load_mode = g_scan_variant.load(std::memory_order_relaxed);
+  a.wide_d = nullptr;
+  a.wide_id = nullptr;
+  a.wide_n = nullptr;
+  a.wide_bound = nullptr;
+  a.wide_cap = 0;
   const bool dump = d_all_dist != nullptr;
   const int64_t grid = Q * nsplit;
   if (grid > 0x7FFFFFFFll) {
@@ -1176,26 +1277,68 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
         return rc;
     a.probe_lb = d_probe_lb;
   }
+  auto dispatch = [&](const ScanArgs &x, int64_t g) -> int {
+    if (ip) {
+      if (M == 64) return launch_scan_ip<64>(x, r2, g, dump, s);
+      if (M == 48) return launch_scan_ip<48>(x, r2, g, dump, s);
+      if (M == 100) return launch_scan_ip<100>(x, r2, g, dump, s);
+      if (M == 16) return launch_scan_ip<16>(x, r2, g, dump, s);
+      return launch_scan_ip<0>(x, r2, g, dump, s);
+    }
+    if (M == 64 && ds == 2) return launch_scan_nw<64, 2>(x, r2, g, dump, s);
+    if (M == 48 && ds == 2) return launch_scan_nw<48, 2>(x, r2, g, dump, s);
+    if (M == 100 && ds == 2) return launch_scan_nw<100, 2>(x, r2, g, dump, s);
+    if (M == 16 && ds == 4) return launch_scan_nw<16, 4>(x, r2, g, dump, s);
+    return launch_scan_nw<0, 0>(x, r2, g, dump, s);
+  };
+  a.k_out = k;
+  // k above KP in one pass (wide selection): chunks of queries share the slot arrays; each
+  // chunk is scanned once with every key within the bound kept, sorted by wide_select_kernel,
+  // and the queries that kernel could not finish go through the passes below.
+  const WideWorkspace *ww = view ? view->wide : nullptr;
+  if (ww && ww->total > 0 && k > KP && k <= 8 * KP && !dump && !ip && mode == 0 && !a.qmap) {
+    char *wb = view->wide_base;
+    for (int64_t q0 = 0; q0 < Q; q0 += ww->q_chunk) {
+      const int64_t qc = Q - q0 < ww->q_chunk ? Q - q0 : ww->q_chunk;
+      ScanArgs c = a;
+      c.queries = d_queries + q0 * ix->D;
+      c.probe_ids = d_probe_ids + q0 * a.probe_stride;
+      if (a.probe_lb) c.probe_lb = a.probe_lb + q0 * a.probe_stride;
+      if (d_query_radii) c.query_radii = d_query_radii + q0 * ix->M;
+      c.out_ids = d_out_ids + q0 * k;
+      c.out_dist = d_out_dist + q0 * k;
+      c.nsplit = 1;
+      c.k = KP;
+      c.k_off = 0;
+      c.wide_d = reinterpret_cast<uint32_t *>(wb + ww->d);
+      c.wide_id = reinterpret_cast<int64_t *>(wb + ww->id);
+      c.wide_n = reinterpret_cast<int32_t *>(wb + ww->n);
+      c.wide_bound = reinterpret_cast<uint32_t *>(wb + ww->bound);
+      c.wide_cap = ww->cap;
+      int32_t *map = reinterpret_cast<int32_t *>(wb + ww->qmap);
+      if (int rc = dispatch(c, qc)) return rc;
+      hipLaunchKernelGGL(wide_select_kernel, dim3((unsigned)qc), dim3(256), 0, s, c.wide_d, c.wide_id, c.wide_n,
+                         c.wide_bound, ix->d_ids, ww->cap, k, c.out_ids, c.out_dist, map);
+      ScanView rest;
+      rest.probe_stride = a.probe_stride;
+      rest.qmap = map;
+      rest.bounds_ready = true;
+      rest.wide = nullptr;
+      rest.wide_base = nullptr;
+      if (int rc = launch_scan(ix, c.queries, qc, nprobe, c.probe_ids, k, r2, 1, nullptr, nullptr, c.out_ids, c.out_dist,
+                               nullptr, nullptr, nullptr, nullptr, mode, c.query_radii,
+                               a.probe_lb ? d_probe_lb + q0 * a.probe_stride : nullptr, s, &rest))
+        return rc;
+    }
+    IVFPQ_HIP_TRY(hipGetLastError());
+    return IVFPQ_OK;
+  }
   // A wavefront's sorted list holds KP keys, so k > KP takes ceil(k / KP) passes over the
   // lists; pass j keeps the keys above the last key pass j - 1 wrote.
-  a.k_out = k;
   for (int32_t off = 0; off == 0 || off < k; off += KP) {
     a.k_off = off;
     a.k = k - off < KP ? k - off : KP;
-    int rc;
-    if (ip) {
-      if (M == 64) rc = launch_scan_ip<64>(a, r2, grid, dump, s);
-      else if (M == 48) rc = launch_scan_ip<48>(a, r2, grid, dump, s);
-      else if (M == 100) rc = launch_scan_ip<100>(a, r2, grid, dump, s);
-      else if (M == 16) rc = launch_scan_ip<16>(a, r2, grid, dump, s);
-      else rc = launch_scan_ip<0>(a, r2, grid, dump, s);
-    } else
-    if (M == 64 && ds == 2) rc = launch_scan_nw<64, 2>(a, r2, grid, dump, s);
-    else if (M == 48 && ds == 2) rc = launch_scan_nw<48, 2>(a, r2, grid, dump, s);
-    else if (M == 100 && ds == 2) rc = launch_scan_nw<100, 2>(a, r2, grid, dump, s);
-    else if (M == 16 && ds == 4) rc = launch_scan_nw<16, 4>(a, r2, grid, dump, s);
-    else rc = launch_scan_nw<0, 0>(a, r2, grid, dump, s);
-    if (rc != IVFPQ_OK) return rc;
+    if (int rc = dispatch(a, grid)) return rc;
     if (dump) break;
     if (nsplit > 1)
       hipLaunchKernelGGL(merge_kernel, dim3((unsigned)Q), dim3(64), 0, s, d_part_d, d_part_id, nsplit, a.k,

@@ -291,6 +291,14 @@ struct ScanArgs {
                    // distance sums, 16 scans plainly from the first list on (no row minima, no checks),
                    // 32 disables the switch to plain scanning, 64 the list-level bound, 128 the byte
                    // table of the hit-count scorings
+  // Wide selection (k_out above KP in one pass, wide_cap > 0): every candidate within the
+  // workgroup's bound on the k_out-th distance goes to the query's slots; wide_select_kernel
+  // sorts them afterwards.  The wavefronts' own lists (KP keys each) only feed the bound.
+  uint32_t *wide_d;      // [Q][wide_cap] distance keys
+  int64_t *wide_id;      // [Q][wide_cap] rows (positions in the index, not ids)
+  int32_t *wide_n;       // [Q] slots in use, or -1: they did not suffice
+  uint32_t *wide_bound;  // [Q] the bound at the end of the scan
+  int32_t wide_cap;
 };
 
 // Codes of one point (the lane's) in registers.
@@ -484,6 +492,11 @@ struct SharedTau {
   LDS uint32_t *bound;
   LDS uint32_t *rank;  // [NW]
   int nw, wave, jrank;
+  // wide selection: [0] slots taken so far, [1] set when they ran out; NULL otherwise
+  LDS uint32_t *wide;
+  uint32_t *wide_d;    // this query's slots
+  int64_t *wide_id;
+  int wide_cap;
 };
 
 // Fold the queued keys into the sorted list and refresh the bounds.  Two rules
@@ -508,7 +521,8 @@ __device__ __forceinline__ void wave_flush(WaveTop &st, LDS uint32_t *qd, LDS in
   const uint32_t j0 = (uint32_t)__shfl((int)st.L0.d, jr & 63), j1 = (uint32_t)__shfl((int)st.L1.d, jr & 63);
   volatile LDS uint32_t *rank = sh.rank;
   if (lane == 0) {
-    if (st.tau.d != SENT_D) __hip_atomic_fetch_min(sh.bound, st.tau.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    // (rule (i) needs a list that can hold k keys: not so in the wide selection)
+    if (!sh.wide && st.tau.d != SENT_D) __hip_atomic_fetch_min(sh.bound, st.tau.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     rank[sh.wave] = jr < 64 ? j0 : j1;
   }
   uint32_t mx = lane < sh.nw ? rank[lane] : 0u;
@@ -527,12 +541,31 @@ __device__ __forceinline__ void wave_offer(WaveTop &st, float dist, bool valid, 
                                   int lane, int k, const SharedTau &sh) {
   const uint32_t bits = dist_key<SGN>(dist);
   const uint32_t shared = *(volatile LDS uint32_t *)sh.bound;
-  const uint32_t pref = shared < st.tau.d ? shared : st.tau.d;
+  const uint32_t pref = (sh.wide || shared < st.tau.d) ? shared : st.tau.d;
   bool pass = valid && bits <= pref;
   if (__ballot(pass) == 0) return;
   Key c;
   c.d = bits;
-  c.id = pass ? ids[row] : SENT_ID;
+  // (wide selection: the wavefront's list only feeds the bound, which is a distance, so the
+  // row number breaks ties as well as the id would, and no id is fetched during the scan)
+  c.id = sh.wide ? row : (pass ? ids[row] : SENT_ID);
+  if (sh.wide) {
+    // every key within the bound is kept: one slot range per wavefront and block
+    const unsigned long long wb = __ballot(pass);
+    const uint32_t wn = (uint32_t)__popcll(wb);
+    uint32_t pos = 0;
+    if (lane == 0) pos = __hip_atomic_fetch_add(sh.wide, wn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    pos = (uint32_t)__builtin_amdgcn_readfirstlane((int)pos);
+    if (pos + wn <= (uint32_t)sh.wide_cap) {
+      if (pass) {
+        const uint32_t slot = pos + (uint32_t)__popcll(wb & ((1ull << lane) - 1ull));
+        sh.wide_d[slot] = c.d;
+        sh.wide_id[slot] = c.id;
+      }
+    } else if (lane == 0) {
+      sh.wide[1] = 1u;
+    }
+  }
   pass = pass && kless(c, st.tau) && kless(st.floor, c);
   unsigned long long bal = __ballot(pass);
   int n = __popcll(bal);
@@ -628,6 +661,63 @@ __device__ __forceinline__ void finish_topk(WaveTop &st, LDS uint32_t *qd, LDS i
         }
       }
     }
+  }
+}
+
+// Wide selection, between two lists (nobody scans): drop the slots whose key the bound has
+// since ruled out.  Chunks of NT slots are read, counted and written back in order; a key
+// never moves to a higher slot, so the chunk being written never reaches the one read next.
+// `wcnt` holds NW words.  Ends with a barrier.
+template <int NW>
+__device__ inline void wide_compact(const SharedTau &sh, LDS uint32_t *wcnt, int tid, int lane, int wave) {
+  constexpr int NT = NW * 64;
+  const uint32_t taken = sh.wide[0];
+  const uint32_t n = taken < (uint32_t)sh.wide_cap ? taken : (uint32_t)sh.wide_cap;
+  const uint32_t bound = *(volatile LDS uint32_t *)sh.bound;
+  uint32_t out = 0;
+  for (uint32_t base = 0; base < n; base += NT) {
+    const uint32_t i = base + tid;
+    uint32_t d = SENT_D;
+    int64_t id = SENT_ID;
+    if (i < n) {
+      d = sh.wide_d[i];
+      id = sh.wide_id[i];
+    }
+    const bool keep = i < n && d <= bound;
+    const unsigned long long bal = __ballot(keep);
+    if (lane == 0) wcnt[wave] = (uint32_t)__popcll(bal);
+    __syncthreads();  // the counts are there, and every read of this chunk has completed
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const uint32_t c = wcnt[w];
+      total += c;
+      if (w < wave) before += c;
+    }
+    if (keep) {
+      const uint32_t pos = out + before + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+      sh.wide_d[pos] = d;
+      sh.wide_id[pos] = id;
+    }
+    out += total;
+    __syncthreads();  // counts free for the next chunk
+  }
+  if (tid == 0) sh.wide[0] = out;
+  __syncthreads();
+}
+
+// End of a workgroup's work in the wide selection: the final bound and the slot count go to
+// global memory for wide_select_kernel; a query whose slots ran out is marked -1 and served
+// by the pass-by-pass path afterwards.
+__device__ inline void finish_wide(WaveTop &st, LDS uint32_t *qd, LDS int64_t *qid, int lane, int tid,
+                                   const SharedTau &sh, const ScanArgs &a, int64_t q) {
+  if (st.qcount > 0) wave_flush<true>(st, qd, qid, lane, a.k, sh);
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t taken = sh.wide[0];
+    const bool over = sh.wide[1] != 0u || taken > (uint32_t)sh.wide_cap;
+    a.wide_n[q] = over ? -1 : (int32_t)taken;
+    a.wide_bound[q] = *(volatile LDS uint32_t *)sh.bound;
   }
 }
 

@@ -56,6 +56,21 @@ static void sweep_workspace() {
         }
         const size_t pub = ivfpq_search_workspace_bytes(&ix, Q, nprobe, 100);
         REQUIRE(pub >= w.total && pub >= 256);
+        // k above 128: the slots of the one-pass selection lie behind the usual workspace
+        REQUIRE(Q > 0 || ivfpq::plan_wide(&ix, Q, 1000, 0).total == 0);
+        for (int k : {129, 1000, 1024}) {
+          if (Q == 0) break;
+          const ivfpq::WideWorkspace ww = ivfpq::plan_wide(&ix, Q, k, 0);
+          REQUIRE(ww.total > 0 && ww.cap == 8192 && ww.q_chunk >= 1 && ww.q_chunk <= Q);
+          REQUIRE(ww.q_chunk == Q || (size_t)ww.q_chunk * ww.cap * 12 <= ((size_t)1 << 30));
+          REQUIRE(ww.d % 256 == 0 && ww.id % 256 == 0 && ww.n % 256 == 0 && ww.bound % 256 == 0 && ww.qmap % 256 == 0);
+          REQUIRE(ww.d + (size_t)ww.q_chunk * ww.cap * 4 <= ww.id && ww.id + (size_t)ww.q_chunk * ww.cap * 8 <= ww.n);
+          REQUIRE(ww.n + (size_t)ww.q_chunk * 4 <= ww.bound && ww.bound + (size_t)ww.q_chunk * 4 <= ww.qmap);
+          REQUIRE(ww.qmap + (size_t)ww.q_chunk * 4 <= ww.total);
+          const size_t pubk = ivfpq_search_workspace_bytes(&ix, Q, nprobe, k);
+          REQUIRE(pubk >= ((ivfpq::plan_workspace(&ix, Q, nprobe, k).total + 255) & ~(size_t)255) + ww.total);
+        }
+        REQUIRE(ivfpq::plan_wide(&ix, Q, 128, 0).total == 0 && ivfpq::plan_wide(&ix, Q, 1000, 1).total == 0);
         ++n;
       }
   std::printf("api_driver: workspace planner clean on %d shapes\n", n);
@@ -144,6 +159,9 @@ static void search_arguments() {
   REQUIRE(ivfpq_set_option("lm_first", 0) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("lm_cap", 8) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("lm_first", 1) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK);
+  REQUIRE(ivfpq_set_option("wide_cap", 512) == IVFPQ_ERR_INVALID_ARGUMENT && ivfpq_set_option("wide_cap", 1 << 17) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_set_option("wide_cap", 0) == IVFPQ_OK && ivfpq_search_workspace_bytes(&ix, 4, 2, 1000) == ivfpq_search_workspace_bytes(&ix, 4, 2, 100));
+  REQUIRE(ivfpq_set_option("wide_cap", 8192) == IVFPQ_OK && ivfpq_search_workspace_bytes(&ix, 4, 2, 1000) > ivfpq_search_workspace_bytes(&ix, 4, 2, 100));
   REQUIRE(ivfpq_scan_all(&ix, q, 4, 2, pid, radii, nullptr, nullptr, nullptr, nullptr, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_ablate", 1) == IVFPQ_ERR_INVALID_ARGUMENT);   // result-changing bits are gone
   REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64 | 128) == IVFPQ_OK);

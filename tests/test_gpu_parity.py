@@ -274,6 +274,52 @@ def test_more_than_128_neighbours(lib, M, D):
     gi.close()
 
 
+@pytest.mark.parametrize("M,D", [(64, 128), (16, 64), (6, 12)])
+def test_wide_selection_paths(lib, M, D):
+    """k above 128 in one pass of the query-major scan (every key within the workgroup's bound
+    kept in per-query slots, then sorted): the default slot count, few slots (the bound-driven
+    compaction between lists runs, and queries that still overflow fall back to the pass-by-pass
+    path), many slots (the batch goes through the slot arrays in chunks), and the pass-by-pass
+    path alone when the caller's workspace has no room for slots.  All against the oracle."""
+    b = _binding()
+    rng = np.random.default_rng(177 + M)
+    nlist = 20
+    sizes = rng.integers(200, 1500, size=nlist)
+    sizes[5] = 0
+    sizes[7] = 3000          # one long list: more keys than the small slot counts hold
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    r = np.full(M, 0.8 * np.sqrt(D / M), dtype=np.float32)
+    q = rng.normal(size=(2100, D)).astype(np.float32)
+    gi = b.IvfPqIndex.from_index(idx)
+    assert gi.workspace(600, 8, 1000).numel() > gi.workspace(600, 8, 128).numel(), "no slots planned for k = 1000"
+    cases = [(600, 8, 1000, 8192), (600, 8, 1000, 1024), (600, 8, 600, 2048), (300, 12, 1024, 4096),
+             (2100, 6, 300, 65536), (40, 8, 129, 8192), (300, 8, 1000, 0)]
+    try:
+        for Q, nprobe, k, cap in cases:
+            say(f"  wide selection: M={M} Q={Q} nprobe={nprobe} k={k} slots={cap}")
+            if cap:
+                b.set_option("wide_cap", cap)
+            dq = _cuda(q[:Q])
+            o_ids, o_dist = oracle.search(q[:Q], idx, nprobe, k, r, threads=ORACLE_THREADS)
+            # cap 0: a workspace sized for k = 128 has no room for the slots
+            ws = gi.workspace(Q, nprobe, k if cap else 128)
+            ids, dist = gi.search(dq, nprobe, k, r, workspace=ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(ids.cpu().numpy(), o_ids), (Q, nprobe, k, cap)
+            assert_same_float(dist.cpu().numpy(), o_dist, f"wide selection k={k} slots={cap}")
+        # every candidate at distance 0: more equal keys within the bound than the sort takes
+        dq = _cuda(q[:50])
+        zero = np.zeros(M, np.float32)
+        b.set_option("wide_cap", 8192)
+        o_ids, o_dist = oracle.search(q[:50], idx, 8, 700, zero, threads=ORACLE_THREADS)
+        ids, dist = gi.search(dq, 8, 700, zero)
+        assert np.array_equal(ids.cpu().numpy(), o_ids)
+        assert_same_float(dist.cpu().numpy(), o_dist, "wide selection, all keys equal")
+    finally:
+        b.set_option("wide_cap", 8192)
+        gi.close()
+
+
 def test_fewer_candidates_than_k_and_empty_probes(lib):
     rng = np.random.default_rng(11)
     sizes = [0, 3, 0, 0, 40, 0, 0, 2]
