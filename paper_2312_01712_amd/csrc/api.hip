@@ -48,12 +48,16 @@ Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32
   w.nsplit = (int32_t)ns;
   size_t fixed = 2 * align256((size_t)Q * nprobe * 4) + align256((size_t)Q * 4);
   if (w.nsplit > 1) fixed += align256((size_t)Q * w.nsplit * 128 * 4) + align256((size_t)Q * w.nsplit * 128 * 8);
-  const size_t row_bytes = (size_t)w.nlist_pad * 4;
+  // scratch of the filtering stage per query: a row of the product, or (many lists) the keys
+  // the product keeps plus a sixteenth of a row for the queries that need every distance
+  const int32_t nkeys = coarse_fused_keys(ix->nlist, nprobe, ix->D);
+  const size_t row_bytes = nkeys > 0 ? (size_t)nkeys * 4 + (size_t)w.nlist_pad / 4 + 1 : (size_t)w.nlist_pad * 4;
   int64_t qc = ((int64_t)1 << 30) / (int64_t)row_bytes;
   qc &= ~(int64_t)127;
   if (qc < 128) qc = 128;
   if (budget > 0) {
-    const int64_t fit = fixed + 256 <= budget ? (int64_t)((budget - fixed - 256) / row_bytes) : 0;
+    const size_t spare = 256 + (nkeys > 0 ? (size_t)(FB_SLOTS + 1) * w.nlist_pad * 4 + 1024 : 0);   // fixed part and rounding of the scratch size
+    const int64_t fit = fixed + spare <= budget ? (int64_t)((budget - fixed - spare) / row_bytes) : 0;
     if (fit < qc) qc = fit >= Q ? fit : (fit & ~(int64_t)127);
     if (qc < 1 || (qc < 128 && qc < Q)) {
       w.total = SIZE_MAX;
@@ -63,7 +67,7 @@ Workspace plan_workspace(const ivfpq_index *ix, int64_t Q, int32_t nprobe, int32
   if (qc > Q) qc = Q;
   w.q_chunk = qc < 1 ? 1 : qc;
   size_t off = 0;
-  w.coarse_dist = off; off += align256((size_t)w.q_chunk * row_bytes);
+  w.coarse_dist = off; off += align256(coarse_scratch_floats(w.nlist_pad, nkeys, w.q_chunk) * 4);
   w.probe_ids = off;   off += align256((size_t)Q * nprobe * 4);
   w.probe_dist = off;  off += align256((size_t)Q * nprobe * 4);
   w.coarse_flags = off; off += align256((size_t)Q * 4);

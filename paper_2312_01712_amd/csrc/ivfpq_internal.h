@@ -68,9 +68,33 @@ int hip_fail(hipError_t e, const char *what);
     if (_e != hipSuccess) return ivfpq::hip_fail(_e, #expr); \
   } while (0)
 
+// ---- filtering stage with many lists ---------------------------------------------------------
+// There the matrix product does not write its rows: per query and group of 64 lists it keeps
+// the COARSE_FT smallest values as keys (coarse_gemm_top_kernel).  Keys per query, or 0 where
+// rows are written (few lists: a group would hold several of a query's nearest lists, and the
+// bound on what it left out would reject the proposal).
+constexpr int COARSE_FT = 6;
+inline int32_t coarse_fused_keys(int32_t nlist, int32_t nprobe, int32_t D) {
+  int slack = nprobe / 4;
+  if (slack < 16) slack = 16;
+  const int64_t kprop = (int64_t)nprobe + slack;
+  const int64_t groups = 2 * (((int64_t)nlist + 127) / 128);
+  const int64_t keys = groups * COARSE_FT;
+  if (kprop > 128 || keys > 16384 || groups < 3 * kprop || D > 2048) return 0;
+  return (int32_t)keys;
+}
+// Floats of scratch the filtering stage takes for a chunk of qc queries: rows of the product,
+// or keys, then reference-order rows for the queries that need every distance (one per 16
+// queries and FB_SLOTS more), then the list of the first FB_SLOTS such queries.
+constexpr int FB_SLOTS = 64;
+inline size_t coarse_scratch_floats(int32_t nlist_pad, int32_t nkeys, int64_t qc) {
+  if (nkeys <= 0) return (size_t)qc * nlist_pad;
+  return (((size_t)qc * nkeys + 63) & ~(size_t)63) + (size_t)((qc + 15) / 16 + FB_SLOTS) * nlist_pad + FB_SLOTS + 64;
+}
+
 // ---- workspace carving (all offsets 256-byte aligned) -----------------------
 struct Workspace {
-  size_t coarse_dist;   // [Qc][nlist_pad] fp32 approximate distances of one query chunk
+  size_t coarse_dist;   // scratch of the filtering stage for one query chunk (coarse_scratch_floats)
   size_t probe_ids;     // [Q][nprobe] int32
   size_t probe_dist;    // [Q][nprobe] fp32: list-level lower bounds for the scan
   size_t coarse_flags;  // [Q] int32: queries the one-wavefront selection of the filtering stage leaves to the workgroup one

@@ -42,9 +42,14 @@ static void sweep_workspace() {
         ivfpq_index ix = fake_index(1000, 128, nlist, 64);
         const ivfpq::Workspace w = ivfpq::plan_workspace(&ix, Q, nprobe, 100);
         REQUIRE(w.q_chunk >= 1 && w.nsplit >= 1 && w.nsplit <= nprobe && w.nlist_pad >= nlist);
-        REQUIRE((size_t)w.q_chunk * w.nlist_pad * 4 <= ((size_t)1 << 30) + (size_t)128 * w.nlist_pad * 4);
+        // scratch of the filtering stage: rows of the product, or keys + reference-order rows (many lists)
+        const int nkeys = ivfpq::coarse_fused_keys(nlist, nprobe, 128);
+        REQUIRE((nkeys > 0) == (nlist >= 16384 && nprobe <= 64));   // of the shapes swept here
+        const size_t scratch = ivfpq::coarse_scratch_floats(w.nlist_pad, nkeys, w.q_chunk) * 4;
+        REQUIRE(scratch <= ((size_t)1 << 30) + (size_t)(128 + ivfpq::FB_SLOTS) * w.nlist_pad * 4 + 1024);
+        REQUIRE(nkeys == 0 || Q < 2000 || scratch < (size_t)Q * w.nlist_pad * 4 / 4);   // no full rows any more
         // regions in order, 256-byte aligned, inside the total
-        const size_t ends[] = {w.coarse_dist + (size_t)w.q_chunk * w.nlist_pad * 4,
+        const size_t ends[] = {w.coarse_dist + scratch,
                                w.probe_ids + (size_t)Q * nprobe * 4, w.probe_dist + (size_t)Q * nprobe * 4};
         REQUIRE(w.coarse_dist % 256 == 0 && w.probe_ids % 256 == 0 && w.probe_dist % 256 == 0 && w.coarse_flags % 256 == 0);
         REQUIRE(ends[0] <= w.probe_ids && ends[1] <= w.probe_dist && ends[2] <= w.coarse_flags);
@@ -191,7 +196,7 @@ static void search_arguments() {
         if (w.total == SIZE_MAX) continue;
         REQUIRE(w.total <= IVFPQ_NOALLOC_SCRATCH_BYTES);
         REQUIRE(w.q_chunk >= 1 && (w.q_chunk == Q || w.q_chunk % 128 == 0) && w.q_chunk <= Q);
-        REQUIRE(w.coarse_dist + (size_t)w.q_chunk * w.nlist_pad * 4 <= w.probe_ids);
+        REQUIRE(w.coarse_dist + ivfpq::coarse_scratch_floats(w.nlist_pad, ivfpq::coarse_fused_keys(nl, np, 16), w.q_chunk) * 4 <= w.probe_ids);
       } }
   ivfpq_index_info info;
   REQUIRE(ivfpq_index_get_info(&ix, &info) == IVFPQ_OK && info.D == 16 && info.dsub == 4);

@@ -320,6 +320,47 @@ def test_wide_selection_paths(lib, M, D):
         gi.close()
 
 
+@pytest.mark.parametrize("metric", [0, 1])
+def test_filtering_stage_many_lists(lib, metric):
+    """Indexes with thousands of lists: the matrix product keeps, per query and group of 64
+    lists, its six smallest values instead of writing rows, and the selection works on those.
+    Random centroids (the usual case: no query flagged), a list count that is no multiple of the
+    tile, and centroids sorted along a line, where a query's nearest lists are neighbours in list
+    order, so that groups fill up and the flagged queries take the reference-order path."""
+    b = _binding()
+    rng = np.random.default_rng(4100 + metric)
+    D, M = 32, 4
+    cases = [("random", 9000, 16, 700), ("ragged tile", 16384 + 77, 64, 300), ("sorted line", 8192, 20, 200),
+             ("zero centroids", 7000, 12, 50), ("60 000 lists", 60000, 32, 100)]
+    for name, nlist, nprobe, Q in cases:
+        sizes = np.zeros(nlist, dtype=np.int64)
+        sizes[rng.integers(0, nlist, size=50)] = 3
+        idx = _random_index(rng, 0, D, nlist, M, sizes)
+        q = rng.normal(size=(Q, D)).astype(np.float32)
+        if name == "sorted line":
+            idx.centroids[:] = 0.0
+            idx.centroids[:, 0] = np.arange(nlist, dtype=np.float32) * 0.01
+            q[:, 0] = rng.uniform(5.0, 70.0, size=Q).astype(np.float32)
+            q[:, 1:] *= 0.01
+        if name == "zero centroids":     # proposal values of exactly 0 and equal values everywhere
+            idx.centroids[: nlist // 2] = 0.0
+            q[:10] = 0.0
+        say(f"  filtering, many lists ({name}): nlist={nlist} nprobe={nprobe} Q={Q} metric={metric}")
+        gi = b.IvfPqIndex.from_index(idx, metric=metric)
+        b.coarse_fallbacks(reset=True)
+        pid, pd = gi.coarse(_cuda(q), nprobe)
+        torch.cuda.synchronize()
+        fb = b.coarse_fallbacks()
+        o_pid, o_pd = oracle.coarse(q, idx.centroids, nprobe, metric=metric)
+        assert np.array_equal(pid.cpu().numpy(), o_pid), f"probe lists differ ({name})"
+        assert_same_float(pd.cpu().numpy(), o_pd, f"probe distances ({name})")
+        if name == "random":
+            assert fb <= Q // 50, f"{fb} of {Q} queries took the reference-order path"
+        if name == "sorted line" and metric == 0:
+            assert fb >= Q // 2, f"only {fb} of {Q} queries took the reference-order path"
+        gi.close()
+
+
 def test_fewer_candidates_than_k_and_empty_probes(lib):
     rng = np.random.default_rng(11)
     sizes = [0, 3, 0, 0, 40, 0, 0, 2]
