@@ -35,7 +35,7 @@ constexpr int LM_G = 2;        // queries per group (interleaved tables, 8-byte 
 constexpr int LM_NW = 8;       // wavefronts per workgroup: one workgroup per CU (the table fills most of its LDS), 2 per SIMD, 256 registers each
 constexpr int LM_QUEUE = 64;   // accepted candidates a wavefront holds per query before it appends them
 constexpr int LM_SEL_WORDS = 16;     // head pass: small LDS block of selection state
-constexpr int LM_BINS = 2048;        // head pass: bins of the selection histogram
+constexpr int LM_BINS = 1024;        // head pass: bins of the selection histogram
 constexpr int LM_COLLECT = 128;      // head pass: candidates a query may collect (the sorted list of a wavefront)
 
 typedef float floatx2 __attribute__((ext_vector_type(2)));
@@ -64,6 +64,7 @@ struct LmArgs {
   const float *query_radii;     // [Q][M] or NULL
   int64_t Q;
   int32_t D, M, dsub, Mp, nlist, nprobe, first, k, cap, mode;
+  int32_t head_done;            // the head pass has run: queries it left out (qmap_head) have no first-list result yet
 };
 
 // tau_q as the bit pattern of a non-negative float (orders like the value; +inf when phase A
@@ -85,6 +86,9 @@ __global__ __launch_bounds__(256) void lm_pairs_kernel(LmArgs a, int fill, int h
   const int64_t q = idx / np2;
   const int p = head ? 0 : a.first + (int)(idx % np2);
   if (!head && !fill && p == a.first) a.gcnt[q] = 0u;
+  // a query the head pass left out has no bound yet: it takes no part here and is redone
+  // query-major over all of its lists (lm_merge_kernel puts it on that list)
+  if (!head && a.head_done && a.qmap_head[q] >= 0) return;
   const int32_t c = a.probe_ids[q * a.nprobe + p];
   const bool exists = (uint32_t)c < (uint32_t)a.nlist;
   const int64_t len = exists ? a.list_offsets[c + 1] - a.list_offsets[c] : 0;
@@ -217,24 +221,24 @@ __device__ __forceinline__ void lm_offer(const LmArgs &a, int64_t q, float dist,
 
 // ---- head pass: exact top-k of ONE list per query, without a bound to filter by ----------
 // The nearest list of a query has to be ranked in full.  Its distances (bit patterns of
-// non-negative floats, which order like the values) are kept in LDS; a histogram of 2048
-// bins over the range they span finds the bin of the k-th smallest, everything up to that
-// bin is collected (k keys plus the few that share the last bin) and a rank sort over the
-// collected keys puts them in (distance, id) order.  More than LM_COLLECT collected keys
-// (masses of equal distances) hand the query to the query-major kernel.
+// non-negative floats, which order like the values) are kept in LDS; a histogram of 1024 bins
+// of equal width finds the bin of the k-th smallest, everything up to that bin is collected (k keys plus the few that share the last bin) and one wavefront per query
+// sorts the collected keys by (distance, id).  More than LM_COLLECT collected keys (masses of
+// equal distances) hand the query to the query-major kernel.
 
-// bin b of a histogram lives at word (b % 32) * 64 + b / 32, so that lane l, which owns the 32
-// consecutive bins 32 l .. 32 l + 31, reads them without bank conflicts
+// bin b of a histogram lives at word (b % 16) * 64 + b / 16, so that lane l, which owns the 16
+// consecutive bins 16 l .. 16 l + 15, reads them without bank conflicts
 __device__ __forceinline__ uint32_t lds_add(LDS uint32_t *p) {   // LDS atomic increment, returns the old value
   return __hip_atomic_fetch_add(p, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-__device__ __forceinline__ int lm_hidx(uint32_t bin) { return (int)(((bin & 31u) << 6) | (bin >> 5)); }
+constexpr int LM_BPL = LM_BINS / 64;   // bins per lane
+__device__ __forceinline__ int lm_hidx(uint32_t bin) { return (int)(((bin % LM_BPL) << 6) | (bin / LM_BPL)); }
 
 // One wavefront: the bin that holds the need-th smallest key (need >= 1, at most the number
 // of keys counted) and the number of keys in the bins below it.
 __device__ inline void lm_find_bin(const LDS uint32_t *hist, uint32_t need, int lane, uint32_t &bin, uint32_t &below) {
   uint32_t sum = 0;
-  for (int j = 0; j < 32; ++j) sum += hist[j * 64 + lane];
+  for (int j = 0; j < LM_BPL; ++j) sum += hist[j * 64 + lane];
   uint32_t incl = sum;
   for (int off = 1; off < 64; off <<= 1) {
     const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
@@ -244,10 +248,10 @@ __device__ inline void lm_find_bin(const LDS uint32_t *hist, uint32_t need, int 
   const bool mine = excl < need && need <= incl;   // exactly one lane
   uint32_t b = 0, bl = 0, run = excl;
   if (mine) {
-    for (int j = 0; j < 32; ++j) {
+    for (int j = 0; j < LM_BPL; ++j) {
       const uint32_t c = hist[j * 64 + lane];
       if (run < need && need <= run + c) {
-        b = 32u * lane + j;
+        b = (uint32_t)LM_BPL * lane + j;
         bl = run;
       }
       run += c;
@@ -296,14 +300,14 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   LDS float *sres = (LDS float *)(smem3 + MT * 2048);
   LDS float *sr2 = sres + LM_G * dpad;
   LDS uint32_t *queue = (LDS uint32_t *)(sr2 + LM_G * IVFPQ_MAX_M);  // main pass: [NW][G][2][LM_QUEUE]
-  // head pass: selection state, then the distances [2][head_max]; the histograms and the
+  // head pass: selection state, the histograms, then the distances [2][head_max]; the
   // collected keys use the table's LDS once the list has been scanned
   LDS uint32_t *ssel = queue;                      // [LM_SEL_WORDS]
-  LDS uint32_t *sdist = queue + LM_SEL_WORDS;      // [2][head_max]
-  LDS uint32_t *hist = (LDS uint32_t *)smem3;      // [2][LM_BINS]
-  LDS uint32_t *coll_d = hist + LM_G * LM_BINS;    // [2][LM_COLLECT] collected keys: distance bits ...
-  LDS uint32_t *coll_rank = coll_d + LM_G * LM_COLLECT;   // ... their positions in sorted order ...
-  LDS int64_t *coll_id = (LDS int64_t *)(coll_rank + LM_G * LM_COLLECT);   // ... and ids
+  LDS uint32_t *hist = queue + LM_SEL_WORDS;       // [2][LM_BINS]
+  LDS uint32_t *sdist = hist + LM_G * LM_BINS;     // [2][head_max]
+  LDS uint32_t *coll_d = (LDS uint32_t *)smem3;    // [2][LM_COLLECT] collected keys: distance bits ...
+  LDS uint32_t *coll_pos = coll_d + LM_G * LM_COLLECT;    // ... their positions in the list ...
+  LDS uint32_t *coll_rank = coll_pos + LM_G * LM_COLLECT;  // ... and in sorted order
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -313,7 +317,7 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   // this wavefront's codebook rows (rows wave, wave + NW, ...) stay in registers for the whole
   // kernel; the head pass at 64 subspaces has no registers left for the last two of its eight
   // rows and fetches those (from the L2) when a task's table is built
-  constexpr int RES = (HEAD && ITER > 6) ? 6 : ITER;
+  constexpr int RES = (HEAD && ITER > 6) ? 5 : ITER;
   float4 cbr[RES][DSUB];
   auto load_row = [&](int it, float4 (&row)[DSUB]) __attribute__((always_inline)) {
     const int m = wave + it * NW;
@@ -387,6 +391,8 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     if (m_on) sr2[mg * IVFPQ_MAX_M + mm] = rv;
     if (HEAD && tid < LM_SEL_WORDS)   // [0..1] keys collected, [2..3] bin of the k-th key, [4..5] smallest key, [6..7] largest key
       ssel[tid] = (tid == 4 || tid == 5) ? 0xFFFFFFFFu : 0u;
+    if constexpr (HEAD)
+      for (int i = tid; i < LM_G * LM_BINS; i += NW * 64) hist[i] = 0u;
     __syncthreads();
     // ---- the two tables, interleaved: row m holds (query 0, query 1) of entry 0, of entry 1, ... ----
     auto build_rows = [&](auto mode_tag) __attribute__((always_inline)) {
@@ -425,6 +431,29 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     // ---- one pass over the list's codes serves both queries ----
     int qc0 = 0, qc1 = 0;
     uint32_t mn0 = 0xFFFFFFFFu, mn1 = 0xFFFFFFFFu, mx0 = 0u, mx1 = 0u;   // head pass: key range of this wavefront's points
+    // Head pass: the histogram's window.  No table entry exceeds its row's r_m^2, so a distance
+    // lies in [0, sum of the r_m^2]: with finite radii the window is known before the scan and
+    // every distance is counted as it is produced.  Otherwise (infinite radii) the window is
+    // the range the distances turn out to span, and they are counted in a pass of their own.
+    // Bins have equal width in value; bin_of is monotone in the distance, which is all the
+    // selection needs.
+    float wlo[2] = {0.0f, 0.0f}, wscale[2] = {0.0f, 0.0f};
+    bool window_known = false;
+    if constexpr (HEAD) {
+      float s0 = lane < MT ? sr2[lane] : 0.0f, s1 = lane < MT ? sr2[IVFPQ_MAX_M + lane] : 0.0f;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        s0 += __shfl_xor(s0, off);
+        s1 += __shfl_xor(s1, off);
+      }
+      window_known = s0 > 0.0f && s0 < __builtin_inff() && s1 > 0.0f && s1 < __builtin_inff();   // same in every wavefront
+      wscale[0] = (float)LM_BINS / s0;
+      wscale[1] = (float)LM_BINS / s1;
+    }
+    auto bin_of = [&](int g, uint32_t key) __attribute__((always_inline)) {
+      const float x = (__uint_as_float(key) - wlo[g]) * wscale[g];
+      return x >= (float)(LM_BINS - 1) ? (uint32_t)(LM_BINS - 1) : (x > 0.0f ? (uint32_t)x : 0u);
+    };
     const int last = tk.nb - 1;
     for (int blk = wave; blk < tk.nb; blk += NW) {
       CodeRegs<MPT / 4> cur = nxt;
@@ -441,10 +470,15 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
           const uint32_t k0 = __float_as_uint(d0), k1 = __float_as_uint(d1);
           sdist[i] = k0;
           sdist[a.head_max + i] = k1;
-          mn0 = k0 < mn0 ? k0 : mn0;
-          mx0 = k0 > mx0 ? k0 : mx0;
-          mn1 = k1 < mn1 ? k1 : mn1;
-          mx1 = k1 > mx1 ? k1 : mx1;
+          if (window_known) {
+            lds_add(&hist[lm_hidx(bin_of(0, k0))]);
+            lds_add(&hist[LM_BINS + lm_hidx(bin_of(1, k1))]);
+          } else {
+            mn0 = k0 < mn0 ? k0 : mn0;
+            mx0 = k0 > mx0 ? k0 : mx0;
+            mn1 = k1 < mn1 ? k1 : mn1;
+            mx1 = k1 > mx1 ? k1 : mx1;
+          }
         }
       } else {
         lm_offer(a, tk.q0, d0, valid, tk.tau0, row, qd0, qrow0, qc0, lane);
@@ -458,39 +492,38 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     if constexpr (HEAD) {
       const int L = done.len, k = a.k;
       const int ng = done.has1 ? 2 : 1;
-      // smallest and largest key of each query's list (this wavefront's share first)
-      for (int g = 0; g < ng; ++g) {
-        uint32_t lo = g ? mn1 : mn0, hi = g ? mx1 : mx0;
+      // window not known: smallest and largest key of each query's list (this wavefront's share first)
+      if (!window_known)
+        for (int g = 0; g < ng; ++g) {
+          uint32_t lo = g ? mn1 : mn0, hi = g ? mx1 : mx0;
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-          const uint32_t ol = (uint32_t)__shfl_xor((int)lo, off), oh = (uint32_t)__shfl_xor((int)hi, off);
-          lo = ol < lo ? ol : lo;
-          hi = oh > hi ? oh : hi;
+          for (int off = 32; off > 0; off >>= 1) {
+            const uint32_t ol = (uint32_t)__shfl_xor((int)lo, off), oh = (uint32_t)__shfl_xor((int)hi, off);
+            lo = ol < lo ? ol : lo;
+            hi = oh > hi ? oh : hi;
+          }
+          if (lane == 0) {
+            __hip_atomic_fetch_min(&ssel[4 + g], lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_max(&ssel[6 + g], hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
         }
-        if (lane == 0) {
-          __hip_atomic_fetch_min(&ssel[4 + g], lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          __hip_atomic_fetch_max(&ssel[6 + g], hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-      }
       __syncthreads();   // the list is scanned: every distance is in LDS and the table's LDS is free
-      // One histogram level over a window fitted to the keys: bin = (key - min) >> shift with the
-      // smallest shift that maps the largest key below LM_BINS.  A bin is 1/2048 of the range of
-      // the list's distances wide, so beyond the k keys wanted only a few more are collected.
-      uint32_t kmin[2], shift[2];
-      for (int g = 0; g < 2; ++g) {
-        kmin[g] = ssel[4 + g];
-        const uint32_t span = ssel[6 + g] - kmin[g];
-        const int bits = 32 - __clz((int)(span | 1u));
-        shift[g] = bits > 11 ? (uint32_t)(bits - 11) : 0u;
-      }
       uint32_t top[2] = {LM_BINS, LM_BINS};   // collect keys whose bin is <= top (everything when the list is short)
+      if (tid < LM_G * LM_COLLECT) {           // empty slots: the sentinel, and rank 0
+        coll_d[tid] = SENT_D;
+        coll_rank[tid] = 0u;
+      }
+      if (L <= LM_COLLECT) __syncthreads();    // (else the barriers of the histogram come before the slots are filled)
       if (L > LM_COLLECT) {                    // uniform; then k <= LM_COLLECT < L: the k-th smallest exists
-        for (int i = tid; i < LM_G * LM_BINS; i += NW * 64) hist[i] = 0u;
-        __syncthreads();
-        for (int i = tid; i < L; i += NW * 64)
-          for (int g = 0; g < ng; ++g)
-            lds_add(&hist[g * LM_BINS + lm_hidx((sdist[g * a.head_max + i] - kmin[g]) >> shift[g])]);
-        __syncthreads();
+        if (!window_known) {
+          for (int g = 0; g < 2; ++g) {
+            wlo[g] = __uint_as_float(ssel[4 + g]);
+            wscale[g] = (float)LM_BINS / (__uint_as_float(ssel[6 + g]) - wlo[g]);   // one value only: every key in bin 0
+          }
+          for (int i = tid; i < L; i += NW * 64)
+            for (int g = 0; g < ng; ++g) lds_add(&hist[g * LM_BINS + lm_hidx(bin_of(g, sdist[g * a.head_max + i]))]);
+          __syncthreads();
+        }
         if (wave < ng) {                       // wavefront g ranks query g's histogram
           uint32_t bin, below;
           lm_find_bin(hist + wave * LM_BINS, (uint32_t)k, lane, bin, below);
@@ -500,44 +533,58 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
         top[0] = ssel[2];
         top[1] = ssel[3];
       }
-      for (int i = tid; i < L; i += NW * 64)
+      // collect (distance, position in the list) of the keys up to that bin; a wavefront reserves
+      // the slots of its keys with one atomic operation
+      for (int i0 = wave * 64; i0 < L; i0 += NW * 64) {
+        const int i = i0 + lane;
         for (int g = 0; g < ng; ++g) {
-          const uint32_t key = sdist[g * a.head_max + i];
-          if (((key - kmin[g]) >> shift[g]) <= top[g]) {
-            const uint32_t slot = lds_add(&ssel[g]);
-            if (slot < (uint32_t)LM_COLLECT) {
-              coll_d[g * LM_COLLECT + slot] = key;
-              coll_id[g * LM_COLLECT + slot] = a.ids[done.row0 + i];
-            }
+          const uint32_t key = i < L ? sdist[g * a.head_max + i] : 0u;
+          const bool take = i < L && bin_of(g, key) <= top[g];
+          const unsigned long long bal = __ballot(take);
+          if (bal == 0ull) continue;
+          uint32_t first = 0;
+          if (lane == 0) first = __hip_atomic_fetch_add(&ssel[g], (uint32_t)__popcll(bal), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          first = (uint32_t)__builtin_amdgcn_readfirstlane((int)first);
+          const uint32_t slot = first + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+          if (take && slot < (uint32_t)LM_COLLECT) {
+            coll_d[g * LM_COLLECT + slot] = key;
+            coll_pos[g * LM_COLLECT + slot] = (uint32_t)i;
           }
         }
-      if (tid < LM_G * LM_COLLECT) coll_rank[tid] = 0u;
+      }
       __syncthreads();
       // Rank sort, all wavefronts: thread (query g, key i, half h) counts the keys of half h of
       // query g's collected keys that precede key i in (distance, id) order; the two halves add
-      // up to the key's position in the sorted order.  Keys are distinct, so are the positions.
+      // up to the key's position in the sorted order.  Unused slots hold the sentinel, which
+      // precedes nothing, so the count runs over a fixed 64 slots, four per LDS read.  The id of
+      // a key is requested before the count and only needed after it; where distances tie (rare)
+      // the ids of the tying keys are fetched on the spot.
       {
+        typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
         const int g = tid >> 8, i = tid & (LM_COLLECT - 1), h = (tid >> 7) & 1;
         const uint32_t n = ssel[g];
-        const bool live = g < ng && n <= (uint32_t)LM_COLLECT;
-        Key me;
-        me.d = SENT_D;
-        me.id = SENT_ID;
-        if (live && (uint32_t)i < n) {
-          me.d = coll_d[g * LM_COLLECT + i];
-          me.id = coll_id[g * LM_COLLECT + i];
-          // distances first; ids only where a distance ties (rare: the slow loop usually does not run)
-          uint32_t before = 0, ties = 0;
-          const int j0 = h * (LM_COLLECT / 2);
-          const int j1 = j0 + LM_COLLECT / 2 < (int)n ? j0 + LM_COLLECT / 2 : (int)n;
-          for (int j = j0; j < j1; ++j) {
-            const uint32_t od = coll_d[g * LM_COLLECT + j];
-            before += od < me.d ? 1u : 0u;
-            ties += od == me.d ? 1u : 0u;
+        const bool live = g < ng && n <= (uint32_t)LM_COLLECT && (uint32_t)i < n;
+        const uint32_t md = live ? coll_d[g * LM_COLLECT + i] : SENT_D;
+        const uint32_t mpos = live ? coll_pos[g * LM_COLLECT + i] : 0u;
+        int64_t mid = SENT_ID;
+        if (live) mid = a.ids[done.row0 + mpos];
+        uint32_t before = 0, ties = 0;
+        const LDS uintx4 *half = (const LDS uintx4 *)(coll_d + g * LM_COLLECT + h * (LM_COLLECT / 2));
+#pragma unroll
+        for (int j = 0; j < LM_COLLECT / 8; ++j) {
+          const uintx4 od = half[j];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            before += od[x] < md ? 1u : 0u;
+            ties += od[x] == md ? 1u : 0u;
           }
-          if (ties > ((i >= j0 && i < j1) ? 1u : 0u))
-            for (int j = j0; j < j1; ++j)
-              before += (coll_d[g * LM_COLLECT + j] == me.d && coll_id[g * LM_COLLECT + j] < me.id) ? 1u : 0u;
+        }
+        if (live) {
+          if (ties > ((i >> 6) == h ? 1u : 0u)) {
+            const int j0 = h * (LM_COLLECT / 2);
+            for (int j = j0; j < j0 + LM_COLLECT / 2 && j < (int)n; ++j)
+              if (coll_d[g * LM_COLLECT + j] == md && a.ids[done.row0 + coll_pos[g * LM_COLLECT + j]] < mid) ++before;
+          }
           if (before) __hip_atomic_fetch_add(&coll_rank[g * LM_COLLECT + i], before, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         __syncthreads();
@@ -548,8 +595,8 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
           } else if ((uint32_t)i < n) {
             const uint32_t r = coll_rank[g * LM_COLLECT + i];
             if (r < (uint32_t)k) {
-              a.out_ids[q * k + r] = me.id;
-              a.out_dist[q * k + r] = __uint_as_float(me.d);
+              a.out_ids[q * k + r] = mid;
+              a.out_dist[q * k + r] = __uint_as_float(md);
             }
           } else if (i < k) {                           // fewer than k points in the list
             a.out_ids[q * k + i] = -1;
@@ -581,7 +628,7 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(LmArgs a) {
   const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (q >= a.Q) return;
   const uint32_t n = a.gcnt[q];
-  const bool overflow = n > (uint32_t)a.cap;
+  const bool overflow = n > (uint32_t)a.cap || (a.head_done && a.qmap_head[q] >= 0);
   if (lane == 0) a.qmap[q] = overflow ? (int32_t)q : -1;
   if (overflow || n == 0) return;   // redone elsewhere / phase A's result stands
   const int k = a.k;
@@ -642,12 +689,12 @@ size_t lm_fixed_lds(int M, int D) {   // table, residuals, radii
 size_t lm_scan_lds(int M, int D) { return lm_fixed_lds(M, D) + (size_t)LM_NW * LM_G * 2 * LM_QUEUE * 4; }
 // head pass: the distances of the list's points for both queries live in LDS next to the table
 int lm_head_max(int M, int D) {
-  const int64_t spare = (int64_t)LDS_PER_CU - (int64_t)lm_fixed_lds(M, D) - LM_SEL_WORDS * 4;
+  const int64_t spare = (int64_t)LDS_PER_CU - (int64_t)lm_fixed_lds(M, D) - LM_SEL_WORDS * 4 - LM_G * LM_BINS * 4;
   int64_t n = spare / (LM_G * 4);
   n &= ~(int64_t)63;
   return (int)(n > 8192 ? 8192 : (n < 0 ? 0 : n));
 }
-size_t lm_head_lds(int M, int D) { return lm_fixed_lds(M, D) + (size_t)LM_G * lm_head_max(M, D) * 4 + LM_SEL_WORDS * 4; }
+size_t lm_head_lds(int M, int D) { return lm_fixed_lds(M, D) + (size_t)LM_G * lm_head_max(M, D) * 4 + LM_SEL_WORDS * 4 + LM_G * LM_BINS * 4; }
 
 template <int MT, int DSUB, bool HEAD>
 int launch_lm_scan_t(const LmArgs &a, const RadiiSq &r2, int grid, hipStream_t s) {
@@ -737,6 +784,7 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   a.Q = Q;
   a.D = ix->D; a.M = ix->M; a.dsub = ix->dsub; a.Mp = ix->Mp; a.nlist = ix->nlist;
   a.nprobe = nprobe; a.first = w.first; a.k = k; a.cap = w.cap; a.mode = mode;
+  a.head_done = 0;
 
   int dev = 0, cus = 0;
   IVFPQ_HIP_TRY(hipGetDevice(&dev));
@@ -745,8 +793,8 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
 
   // ---- the first lists of every query: they give the bound tau_q that filters the rest ----
   // One list per query under distance scoring: the head pass ranks it list-major (queries that
-  // share a nearest list share its table pass); the query-major kernel serves what the head
-  // pass leaves out (qmap_head).  Otherwise (several first lists, or the hit-count scorings,
+  // share a nearest list share its table pass); what the head pass leaves out (qmap_head) skips
+  // the list-major scan and is redone query-major at the end.  Otherwise (several first lists, or the hit-count scorings,
   // whose masses of equal scores the head pass's selection is not made for): query-major.
   const bool head_pass = w.first == 1 && mode == IVFPQ_SCORE_DISTANCE && a.head_max >= 64;
   rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);   // the per-list counts start at zero; lm_offsets_kernel leaves them so
@@ -759,10 +807,13 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
     rc = launch_lm_scan<true>(ix, a, r2, cus, s);
     if (rc) return rc;
   }
-  ScanView head = {nprobe, head_pass ? a.qmap_head : nullptr, true};
-  rc = launch_scan(ix, d_queries, Q, w.first, d_probe_ids, k, r2, 1, nullptr, nullptr, d_out_ids, d_out_dist,
-                   nullptr, nullptr, nullptr, nullptr, mode, d_query_radii, d_probe_lb, s, &head);
-  if (rc) return rc;
+  a.head_done = head_pass ? 1 : 0;
+  if (!head_pass) {
+    ScanView head = {nprobe, nullptr, true};
+    rc = launch_scan(ix, d_queries, Q, w.first, d_probe_ids, k, r2, 1, nullptr, nullptr, d_out_ids, d_out_dist,
+                     nullptr, nullptr, nullptr, nullptr, mode, d_query_radii, d_probe_lb, s, &head);
+    if (rc) return rc;
+  }
 
   // ---- the other lists, list-major: pairs bucketed by list, scan, merge ----
   const int64_t npairs = Q * (nprobe - w.first);
