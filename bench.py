@@ -41,11 +41,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-KERNEL_SOURCES = ("coarse.hip", "ivfpq_internal.h", "scan.hip", "scan_device.h", "scan_lm.hip")
+KERNEL_SOURCES = ("ivfpq_internal.h", "scan.hip", "scan_device.h", "scan_lm.hip")
 
 
 def csrc_sha256() -> str:
-    """Hash of the sources that hold the kernels of the search path (csrc/api.hip has none)."""
+    """Hash of the sources that hold the kernels of stages 2-4, whose traffic
+    profiles/traffic.json records (the filtering stage's coarse.hip is not part of it)."""
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
         h.update(name.encode() + b"\0" + open(os.path.join(CSRC, name), "rb").read())
@@ -206,6 +207,9 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
                          "queries per table pass) + lm_merge_kernel, as shipped") if resolved == binding.SCAN_LIST_MAJOR else
                         "probe_bound_kernel + scan_kernel as shipped (list-level bound, early exit of the sums, chunked loads: "
                         "bytes that cannot change the result are not read)",
+              "bound": ("lds + per-task phases: one workgroup per CU alternates between building the interleaved table "
+                        "(vector ALU) and 8-byte LDS gathers") if resolved == binding.SCAN_LIST_MAJOR else
+                       "alu where most lists are ruled out (the tables of the lists that remain), lds gathers where nothing is",
               "avg_launch_ms": launch_ms, "algorithmic_rate": algo_bytes / (launch_ms * 1e-3) / 1e9, "unit": "GB/s",
               "note": "algorithmic bytes over time: exceeds the HBM peak when exact pruning skips bytes; not an efficiency",
               "traffic": default_traffic,

@@ -676,23 +676,23 @@ __global__ __launch_bounds__(CS_WAVES * 64) void coarse_select_wave_kernel(
   LDS float *sq = (LDS float *)(mine + CS_BINS * 4 + CS_CAND * 8);
   const float *row = rows + q * ldo;
   const float *qv = Qm + q * D;
-  // The row's entries, raw: key rows of up to 64 * ROW_REGS keys are read once, with all loads
-  // in flight together, and stay in registers for the three passes below; longer rows (and the
-  // product's own rows) are read by each pass.  `each(fn)` calls fn(position, raw entry) for
+  // The row's entries, raw: rows of up to 64 * ROW_REGS entries are read once, with all loads
+  // in flight together, and stay in registers for the three passes below; longer rows are read
+  // by each pass.  `each(fn)` calls fn(position, raw entry) for
   // the whole row, every lane in every call (positions past the end included).
   constexpr int ROW_REGS = 24;
   const uint32_t *raw_row = reinterpret_cast<const uint32_t *>(row);
-  const bool in_regs = FUSED && nrow <= 64 * ROW_REGS;
-  uint32_t kreg[FUSED ? ROW_REGS : 1];
+  const bool in_regs = nrow <= 64 * ROW_REGS;
+  uint32_t kreg[ROW_REGS];
   if (in_regs) {
 #pragma unroll
-    for (int j = 0; j < ROW_REGS; ++j) kreg[FUSED ? j : 0] = j * 64 + lane < nrow ? raw_row[j * 64 + lane] : 0u;
+    for (int j = 0; j < ROW_REGS; ++j) kreg[j] = j * 64 + lane < nrow ? raw_row[j * 64 + lane] : 0u;
   }
   auto each = [&](auto fn) __attribute__((always_inline)) {
     if (in_regs) {
 #pragma unroll
       for (int j = 0; j < ROW_REGS; ++j)
-        if (j * 64 < nrow) fn(j * 64 + lane, kreg[FUSED ? j : 0]);
+        if (j * 64 < nrow) fn(j * 64 + lane, kreg[j]);
     } else {
       for (int c0 = 0; c0 < nrow; c0 += 64) fn(c0 + lane, c0 + lane < nrow ? raw_row[c0 + lane] : 0u);
     }
