@@ -352,7 +352,11 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  *                  64 the list-level bound that skips a list before its table is built.
  *                  8 | 16 | 64 with "scan_loads" 1 is the plain scan: every code byte of every
  *                  probed list is read and looked up.  128: the hit-count scorings use the
- *                  float table of the distance scoring instead of their byte table. */
+ *                  float table of the distance scoring instead of their byte table.
+ *   "bound_grid"   the list-level bound (two-dimensional subspaces, L2) can add, to the per-list
+ *                  boxes, a per-subspace grid of distances to the nearest codebook entry: 0
+ *                  (default) on indexes with more than 4096 points per list, where a list that
+ *                  slips through the bound costs most; 1 always; 2 never. */
 int ivfpq_set_option(const char *name, int value);
 
 /* Text for the most recent failure on this thread ("" if none). */

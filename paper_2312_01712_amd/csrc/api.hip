@@ -210,6 +210,11 @@ int ivfpq_set_option(const char *name, int value) {
     set_lm_cap(value);
     return IVFPQ_OK;
   }
+  if (name && !strcmp(name, "bound_grid")) {
+    if (value < 0 || value > 2) { set_error("set_option: bound_grid must be 0, 1 or 2"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    set_bound_grid(value);
+    return IVFPQ_OK;
+  }
   if (name && !strcmp(name, "wide_cap")) {
     if (value != 0 && (value < 1024 || value > 65536)) { set_error("set_option: wide_cap must be 0 or in [1024, 65536]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_wide_cap(value);
@@ -230,6 +235,8 @@ void ivfpq_index_destroy(ivfpq_index *ix) {
   (void)hipFree(ix->d_centroids);
   (void)hipFree(ix->d_cnorm);
   (void)hipFree(ix->d_box);
+  (void)hipFree(ix->d_grid);
+  (void)hipFree(ix->d_grid_par);
   (void)hipFree(ix->d_codebooks);
   (void)hipFree(ix->d_list_offsets);
   (void)hipFree(ix->d_list_blocks);
@@ -344,6 +351,16 @@ int ivfpq_index_create(const ivfpq_index_desc *d, ivfpq_index **out) {
     // below from the codes; an empty list keeps the all-zero box)
     TRY_OR_FAIL(hipMalloc(&ix->d_box, (size_t)d->nlist * d->D * 2 * 4));
     TRY_OR_FAIL(hipMemset(ix->d_box, 0, (size_t)d->nlist * d->D * 2 * 4));
+    // two-dimensional subspaces, L2: a grid per subspace with, for every cell, a lower bound on
+    // the squared distance from any point of the cell to the nearest entry (the second
+    // ingredient of the list-level bound, see probe_bound_kernel)
+    if (ix->dsub == 2 && d->metric == IVFPQ_METRIC_L2) {
+      TRY_OR_FAIL(hipMalloc(&ix->d_grid, (size_t)d->M * GRID_G * GRID_G * 4));
+      TRY_OR_FAIL(hipMalloc(&ix->d_grid_par, (size_t)d->M * 8 * 4));
+      rc = launch_codebook_grid(ix, nullptr);
+      if (rc != IVFPQ_OK) goto fail;
+      TRY_OR_FAIL(hipDeviceSynchronize());
+    }
     if (d->N > 0) {
       bool codes_dev = false;
       if (hipPointerGetAttributes(&attr, d->codes) == hipSuccess) codes_dev = attr.type == hipMemoryTypeDevice;

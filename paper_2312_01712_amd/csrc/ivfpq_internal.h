@@ -17,6 +17,8 @@ struct ivfpq_index {
   float *d_centroids;       // [nlist][D]
   float *d_cnorm;           // [nlist] squared norms (only used to propose probe lists)
   float *d_box;             // [nlist][M][2][dsub] per list and subspace: bounding box (low corner, high corner) of the entries its points use
+  float *d_grid;            // dsub == 2, L2 metric: [M][GRID_G * GRID_G] lower bound on the squared distance from any point of a grid cell to the subspace's nearest entry; else NULL
+  float *d_grid_par;        // [M][8]: low corner (x, y), high corner (x, y), cells per unit (x, y), 0, 0
   float *d_codebooks;       // [M][256][dsub]
   int64_t *d_list_offsets;  // [nlist+1] in points
   int64_t *d_list_blocks;   // [nlist+1] in 64-point blocks of the interleaved layout
@@ -172,11 +174,14 @@ int launch_query_radii(const ivfpq_index *ix, const ivfpq_radius_model *md, cons
                        float *d_radii, hipStream_t s);
 int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
 int launch_list_boxes(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s);
+constexpr int GRID_G = 64;   // cells per side of the per-subspace grid of nearest-entry bounds
+int launch_codebook_grid(const ivfpq_index *ix, hipStream_t s);
 int launch_iota(int64_t *d, int64_t n, hipStream_t s);
 int coarse_fallbacks(int reset, unsigned int *out);
 int launch_fill_i32(int32_t *d, int64_t n, int32_t v, hipStream_t s);
 void set_scan_ablate(int bits);   // pruning switches 8 | 32 | 64 (results unchanged)
 void set_scan_variant(int v);     // code loads: 0 adaptive, 1 whole blocks, 2 first half + rest on demand
 void set_scan_waves(int nw);  // wavefronts per scan workgroup: 0 (auto), 4, 8 or 16
+void set_bound_grid(int v);   // nearest-entry grid in the list-level bound: 0 (long lists only), 1 always, 2 never
 
 }  // namespace ivfpq

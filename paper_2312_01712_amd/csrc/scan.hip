@@ -29,6 +29,8 @@
 
 namespace {
 
+using ivfpq::GRID_G;
+
 // BYTE: the hit-count scorings with a byte table (one byte per entry, 256 bytes per row,
 // integer sums) instead of the float table; the sums are the same small integers either way.
 template <int MT, int DSUB, int NW, bool DUMP, bool BYTE = false>
@@ -820,7 +822,9 @@ constexpr int BOUND_PAIRS = 2;  // (query, probe) pairs per wavefront: their loa
 __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
                                                           const int32_t *__restrict__ probe_ids,
                                                           const float *__restrict__ centroids,
-                                                          const float *__restrict__ box, int D, int M, int dsub,
+                                                          const float *__restrict__ box,
+                                                          const float *__restrict__ grid,
+                                                          const float *__restrict__ grid_par, int D, int M, int dsub,
                                                           int nlist, int64_t total, int nprobe, RadiiSq r2,
                                                           const float *__restrict__ query_radii, int mode,
                                                           float *__restrict__ out) {
@@ -851,12 +855,30 @@ __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restric
         cv[i] = *reinterpret_cast<const float2 *>(centroids + (int64_t)cs[i] * D + 2 * m);
         v[i] = reinterpret_cast<const float4 *>(box + (int64_t)cs[i] * D * 2)[m];
       }
+      float4 gp0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      float2 gp1 = make_float2(0.0f, 0.0f);
+      if (grid) {
+        gp0 = reinterpret_cast<const float4 *>(grid_par)[2 * m];
+        gp1 = reinterpret_cast<const float2 *>(grid_par)[4 * m + 2];
+      }
 #pragma unroll
       for (int i = 0; i < BOUND_PAIRS; ++i) {
         const float x0 = qv[i].x - cv[i].x, x1 = qv[i].y - cv[i].y;
         const float t0 = fmaxf(fmaxf(v[i].x - x0, x0 - v[i].z), 0.0f);
         const float t1 = fmaxf(fmaxf(v[i].y - x1, x1 - v[i].w), 0.0f);
         best[i] = fmaf(t1, t1, t0 * t0);
+        if (grid) {
+          // Second bound: every entry of the subspace (used by this list or not) lies in the
+          // grid's rectangle.  Inside it, the cell of the residual projection holds a lower
+          // bound on the squared distance to the nearest entry; outside, the projection p' onto
+          // the rectangle satisfies |p - e|^2 >= |p - p'|^2 + |p' - e|^2 for every e in it.
+          const float fx = fminf(fmaxf((x0 - gp0.x) * gp1.x, 0.0f), (float)(GRID_G - 1));
+          const float fy = fminf(fmaxf((x1 - gp0.y) * gp1.y, 0.0f), (float)(GRID_G - 1));
+          const float cell = grid[(int64_t)m * (GRID_G * GRID_G) + (int)fy * GRID_G + (int)fx];
+          const float o0 = fmaxf(fmaxf(gp0.x - x0, x0 - gp0.z), 0.0f);
+          const float o1 = fmaxf(fmaxf(gp0.y - x1, x1 - gp0.w), 0.0f);
+          best[i] = fmaxf(best[i], cell + fmaf(o1, o1, o0 * o0));
+        }
       }
     } else {
 #pragma unroll
@@ -1135,6 +1157,69 @@ __global__ __launch_bounds__(256) void relayout_kernel(const uint8_t *__restrict
   }
 }
 
+// Index build, two-dimensional subspaces: one workgroup per subspace lays a GRID_G x GRID_G
+// grid over the bounding rectangle of the subspace's 256 entries (one cell of margin all
+// round) and stores, per cell, min over the entries of the squared distance from the entry to
+// the cell -- the cell enlarged by 1/256 of its size on every side, so that a point whose cell
+// index is off by a rounding is still covered.  par[m] = (low x, low y, high x, high y,
+// cells per unit x, cells per unit y, 0, 0).
+__global__ __launch_bounds__(256) void codebook_grid_kernel(const float *__restrict__ codebooks, float *__restrict__ grid,
+                                                            float *__restrict__ par) {
+  __shared__ float ex[256], ey[256];
+  __shared__ float red[4][4];
+  const int m = blockIdx.x, tid = threadIdx.x;
+  const float x = codebooks[((int64_t)m * 256 + tid) * 2], y = codebooks[((int64_t)m * 256 + tid) * 2 + 1];
+  ex[tid] = x;
+  ey[tid] = y;
+  float lox = x, hix = x, loy = y, hiy = y;
+  for (int off = 32; off > 0; off >>= 1) {
+    lox = fminf(lox, __shfl_xor(lox, off));
+    hix = fmaxf(hix, __shfl_xor(hix, off));
+    loy = fminf(loy, __shfl_xor(loy, off));
+    hiy = fmaxf(hiy, __shfl_xor(hiy, off));
+  }
+  if ((tid & 63) == 0) {
+    red[tid >> 6][0] = lox;
+    red[tid >> 6][1] = hix;
+    red[tid >> 6][2] = loy;
+    red[tid >> 6][3] = hiy;
+  }
+  __syncthreads();
+  lox = fminf(fminf(red[0][0], red[1][0]), fminf(red[2][0], red[3][0]));
+  hix = fmaxf(fmaxf(red[0][1], red[1][1]), fmaxf(red[2][1], red[3][1]));
+  loy = fminf(fminf(red[0][2], red[1][2]), fminf(red[2][2], red[3][2]));
+  hiy = fmaxf(fmaxf(red[0][3], red[1][3]), fmaxf(red[2][3], red[3][3]));
+  // a degenerate extent (all entries equal in a coordinate) gets an arbitrary positive one
+  float wx = hix - lox, wy = hiy - loy;
+  if (!(wx > 0.0f)) wx = 1.0f;
+  if (!(wy > 0.0f)) wy = 1.0f;
+  const float cx = wx / (float)(GRID_G - 2), cy = wy / (float)(GRID_G - 2);   // cell size: the entries span G - 2 cells
+  const float gx0 = lox - cx, gy0 = loy - cy;
+  const float gx1 = gx0 + cx * (float)GRID_G, gy1 = gy0 + cy * (float)GRID_G;
+  if (tid == 0) {
+    float *o = par + (int64_t)m * 8;
+    o[0] = gx0;
+    o[1] = gy0;
+    o[2] = fmaxf(gx1, hix);   // the rectangle must hold every entry whatever the sums above round to
+    o[3] = fmaxf(gy1, hiy);
+    o[4] = 1.0f / cx;
+    o[5] = 1.0f / cy;
+    o[6] = o[7] = 0.0f;
+  }
+  for (int c = tid; c < GRID_G * GRID_G; c += 256) {
+    const int ix = c % GRID_G, iy = c / GRID_G;
+    const float eps = 1.0f / 256.0f;
+    const float ax = gx0 + cx * ((float)ix - eps), bx = gx0 + cx * ((float)(ix + 1) + eps);
+    const float ay = gy0 + cy * ((float)iy - eps), by = gy0 + cy * ((float)(iy + 1) + eps);
+    float best = __builtin_inff();
+    for (int e = 0; e < 256; ++e) {
+      const float dx = fmaxf(fmaxf(ax - ex[e], ex[e] - bx), 0.0f), dy = fmaxf(fmaxf(ay - ey[e], ey[e] - by), 0.0f);
+      best = fminf(best, fmaf(dy, dy, dx * dx));
+    }
+    grid[(int64_t)m * (GRID_G * GRID_G) + c] = best;
+  }
+}
+
 __global__ void iota_kernel(int64_t *d, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) d[i] = i;
@@ -1149,6 +1234,7 @@ __global__ void fill_i32_kernel(int32_t *d, int64_t n, int32_t v) {
 // on one host thread while another enqueues a search; a launch reads each switch once.
 std::atomic<int> g_scan_waves{0};    // 0 = choose from the shape
 std::atomic<int> g_scan_ablate{0};   // pruning switches: 8 | 32 | 64
+std::atomic<int> g_bound_grid{0};    // list-level bound: 0 = the nearest-entry grid on long lists only, 1 = always, 2 = never
 std::atomic<int> g_scan_variant{0};  // code loads: 0 = default (first chunk ahead while pruning), 1 = always whole blocks, 2 = always the first half ahead, 3 = always the first chunk ahead
 
 template <int MT, int DSUB, int NW, bool BYTE = false>
@@ -1216,6 +1302,7 @@ int launch_scan_ip(const ScanArgs &a, const RadiiSq &r2, int64_t grid, bool dump
 namespace ivfpq {
 
 void set_scan_waves(int nw) { g_scan_waves.store(nw, std::memory_order_relaxed); }
+void set_bound_grid(int v) { g_bound_grid.store(v, std::memory_order_relaxed); }
 void set_scan_ablate(int bits) { g_scan_ablate.store(bits, std::memory_order_relaxed); }
 void set_scan_variant(int v) { g_scan_variant.store(v, std::memory_order_relaxed); }
 int get_scan_ablate() { return g_scan_ablate.load(std::memory_order_relaxed); }
@@ -1353,13 +1440,21 @@ int launch_probe_bounds(const ivfpq_index *ix, const float *d_queries, int64_t Q
                         float *d_probe_lb, hipStream_t s) {
   const int64_t total = Q * nprobe;
   if (total == 0) return IVFPQ_OK;
+  // The grid of nearest-entry distances tightens the bound (on the 100M-point configuration it
+  // rules out 59.4 instead of 55.9 of a query's 64 lists, and the tables built per query drop
+  // from 8.1 to 4.6) at the price of a slower bound kernel (three more loads per pair and
+  // subspace, one of them a gather): it pays where a list that slips through is expensive,
+  // i.e. on long lists (measured: 4 % faster there, 7-14 % slower on the 1M-point ones).
+  const int grid_mode = g_bound_grid.load(std::memory_order_relaxed);
+  const bool use_grid = ix->d_grid && grid_mode != 2 && (grid_mode == 1 || ix->N > (int64_t)4096 * ix->nlist);
   const int64_t per_block = 4 * BOUND_PAIRS;
   if ((total + per_block - 1) / per_block > 0x7FFFFFFFll) {
     set_error("scan: %lld (query, probe) pairs exceed the grid limit of the bound kernel", (long long)total);
     return IVFPQ_ERR_UNSUPPORTED;
   }
   hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + per_block - 1) / per_block)), dim3(256), 0, s,
-                     d_queries, d_probe_ids, ix->d_centroids, ix->d_box, ix->D, ix->M, ix->dsub, ix->nlist, total,
+                     d_queries, d_probe_ids, ix->d_centroids, ix->d_box,
+                     use_grid ? ix->d_grid : nullptr, ix->d_grid_par, ix->D, ix->M, ix->dsub, ix->nlist, total,
                      nprobe, r2, d_query_radii, mode, d_probe_lb);
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;
@@ -1392,6 +1487,13 @@ int launch_relayout(const ivfpq_index *ix, const uint8_t *d_rows, hipStream_t s)
   const int64_t grid = (ix->total_blocks + 3) / 4;
   hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(256), 0, s, d_rows, ix->d_list_offsets,
                      ix->d_list_blocks, ix->nlist, ix->M, ix->Mp, ix->total_blocks, ix->d_codes);
+  IVFPQ_HIP_TRY(hipGetLastError());
+  return IVFPQ_OK;
+}
+
+int launch_codebook_grid(const ivfpq_index *ix, hipStream_t s) {
+  hipLaunchKernelGGL(codebook_grid_kernel, dim3((unsigned)ix->M), dim3(256), 0, s, ix->d_codebooks, ix->d_grid,
+                     ix->d_grid_par);
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;
 }

@@ -386,6 +386,17 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     fetch_pairs(t, p0, p1);
     fetch_task(p0, p1, tk, qv, cv, rv, nxt);
   }
+  // main pass: the candidates of the task before, queued in LDS, and where they go
+  uint32_t pend_slot = 0;
+  int64_t pend_q0 = 0, pend_q1 = 0;
+  int pend_c0 = 0, pend_c1 = 0;
+  auto drain_pending = [&]() __attribute__((always_inline)) {
+    const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)pend_slot, 0);
+    const uint32_t s1 = (uint32_t)__builtin_amdgcn_readlane((int)pend_slot, 1);
+    if (pend_c0 > 0) lm_store(a, pend_q0, s0, qd0, qrow0, pend_c0, lane);
+    if (pend_c1 > 0) lm_store(a, pend_q1, s1, qd1, qrow1, pend_c1, lane);
+    pend_c0 = pend_c1 = 0;
+  };
   for (;;) {
     if (r_on) sres[rg * dpad + rd] = qv - cv;
     if (m_on) sr2[mg * IVFPQ_MAX_M + mm] = rv;
@@ -427,6 +438,7 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     const bool more = tn < ntasks;
     int2 np0 = make_int2(0, 0), np1 = make_int2(0, 0);
     if (more) fetch_pairs(tn, np0, np1);
+    if constexpr (!HEAD) drain_pending();   // the queues are free again before this task fills them
     __syncthreads();
     // ---- one pass over the list's codes serves both queries ----
     int qc0 = 0, qc1 = 0;
@@ -605,16 +617,22 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
         }
       }
     } else {
-      // one atomic instruction reserves the space of both queues: lane g for query g
-      uint32_t slot = 0;
+      // One atomic instruction reserves the space of both queues: lane g for query g.  Its
+      // result is not waited for here: the queued candidates are written to the reserved slots
+      // after the next task's table is built (drain_pending), so the round trip of the atomic
+      // is hidden behind that work.
+      pend_slot = 0;
       const int n_mine = lane == 0 ? qc0 : (lane == 1 ? qc1 : 0);
-      if (n_mine > 0) slot = atomicAdd(&a.gcnt[lane == 0 ? done.q0 : done.q1], (uint32_t)n_mine);
-      const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)slot, 0);
-      const uint32_t s1 = (uint32_t)__builtin_amdgcn_readlane((int)slot, 1);
-      if (qc0 > 0) lm_store(a, done.q0, s0, qd0, qrow0, qc0, lane);
-      if (qc1 > 0) lm_store(a, done.q1, s1, qd1, qrow1, qc1, lane);
+      if (n_mine > 0) pend_slot = atomicAdd(&a.gcnt[lane == 0 ? done.q0 : done.q1], (uint32_t)n_mine);
+      pend_q0 = done.q0;
+      pend_q1 = done.q1;
+      pend_c0 = qc0;
+      pend_c1 = qc1;
     }
-    if (!more) break;
+    if (!more) {
+      if constexpr (!HEAD) drain_pending();
+      break;
+    }
     t = tn;
     __syncthreads();  // every wavefront is done with the table and the residuals before the next task rewrites them
   }

@@ -169,7 +169,8 @@ static void search_arguments() {
   REQUIRE(ivfpq_set_option("wide_cap", 8192) == IVFPQ_OK && ivfpq_search_workspace_bytes(&ix, 4, 2, 1000) > ivfpq_search_workspace_bytes(&ix, 4, 2, 100));
   REQUIRE(ivfpq_scan_all(&ix, q, 4, 2, pid, radii, nullptr, nullptr, nullptr, nullptr, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_ablate", 1) == IVFPQ_ERR_INVALID_ARGUMENT);   // result-changing bits are gone
-  REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64 | 128) == IVFPQ_OK);
+  REQUIRE(ivfpq_set_option("scan_ablate", 8 | 16 | 32 | 64 | 128) == IVFPQ_OK && ivfpq_set_option("scan_ablate", 256) == IVFPQ_ERR_INVALID_ARGUMENT);
+  REQUIRE(ivfpq_set_option("bound_grid", 3) == IVFPQ_ERR_INVALID_ARGUMENT && ivfpq_set_option("bound_grid", 1) == IVFPQ_OK && ivfpq_set_option("bound_grid", 0) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("scan_ablate", 0) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("scan_loads", 4) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("scan_waves", 5) == IVFPQ_ERR_INVALID_ARGUMENT);

@@ -23,6 +23,7 @@ int launch_query_radii(const ivfpq_index *, const ivfpq_radius_model *, const fl
                        int32_t, float, float *, hipStream_t) { return reached("query_radii"); }
 int launch_relayout(const ivfpq_index *, const uint8_t *, hipStream_t) { return reached("relayout"); }
 int launch_list_boxes(const ivfpq_index *, const uint8_t *, hipStream_t) { return reached("list_boxes"); }
+int launch_codebook_grid(const ivfpq_index *, hipStream_t) { return reached("codebook_grid"); }
 int launch_iota(int64_t *, int64_t, hipStream_t) { return reached("iota"); }
 int launch_fill_i32(int32_t *, int64_t, int32_t, hipStream_t) { return reached("fill_i32"); }
 int coarse_fallbacks(int, unsigned int *out) { *out = 0; return IVFPQ_OK; }
@@ -35,5 +36,6 @@ void set_lm_first(int) {}
 void set_lm_cap(int) {}
 void set_scan_ablate(int) {}
 void set_scan_variant(int) {}
+void set_bound_grid(int) {}
 void set_scan_waves(int) {}
 }  // namespace ivfpq

@@ -361,6 +361,45 @@ def test_filtering_stage_many_lists(lib, metric):
         gi.close()
 
 
+def test_list_level_bound_on_odd_codebooks(lib):
+    """The list-level bound uses, per two-dimensional subspace, a grid of nearest-entry distances
+    over the bounding rectangle of the entries.  Codebooks that strain it: a subspace whose
+    entries all coincide, one whose entries lie on a line, one with a huge offset and a tiny
+    spread, one with a huge spread; queries on entries, on centroids, far outside every
+    rectangle; radii small enough and k small enough for the bound to rule lists out.  With the
+    grid forced on and forced off (option bound_grid), query-major and list-major: the oracle's answer."""
+    b = _binding()
+    rng = np.random.default_rng(2024)
+    M, D, nlist = 16, 32, 40
+    sizes = rng.integers(100, 600, size=nlist)
+    idx = _random_index(rng, 0, D, nlist, M, sizes)
+    cb = idx.codebooks                                   # [M][256][2]
+    cb[0] = 0.25                                         # all entries equal
+    cb[1, :, 1] = 0.0                                    # on a line
+    cb[2] = 1.0e6 + 1.0e-2 * rng.normal(size=(256, 2))   # huge offset, tiny spread
+    cb[3] = 1.0e4 * rng.normal(size=(256, 2))            # huge spread
+    cb[4, :, 0] = cb[4, 0, 0]                            # a vertical line
+    q = np.concatenate([idx.centroids[:8],                                         # residual 0
+                        idx.centroids[8:16] + np.tile(cb[:, 7, :].reshape(-1), (8, 1)),   # on an entry of every subspace
+                        1.0e3 * rng.normal(size=(8, D)),                          # far outside
+                        rng.normal(size=(400, D))]).astype(np.float32)
+    gi = b.IvfPqIndex.from_index(idx)
+    try:
+        for r in (np.full(M, 0.5, np.float32), np.full(M, 3.0, np.float32), np.full(M, np.inf, np.float32)):
+            for nprobe, k in ((12, 5), (40, 100)):
+                o_ids, o_dist = oracle.search(q, idx, nprobe, k, r, threads=ORACLE_THREADS)
+                for grid in (1, 2):
+                    for strategy in (b.SCAN_QUERY_MAJOR, b.SCAN_LIST_MAJOR):
+                        b.set_option("bound_grid", grid)
+                        ids, dist = gi.search(_cuda(q), nprobe, k, r, strategy=strategy)
+                        torch.cuda.synchronize()
+                        assert np.array_equal(ids.cpu().numpy(), o_ids), (float(r[0]), nprobe, k, grid, strategy)
+                        assert_same_float(dist.cpu().numpy(), o_dist, f"odd codebooks r={r[0]} grid={grid}")
+    finally:
+        b.set_option("bound_grid", 0)
+        gi.close()
+
+
 def test_fewer_candidates_than_k_and_empty_probes(lib):
     rng = np.random.default_rng(11)
     sizes = [0, 3, 0, 0, 40, 0, 0, 2]
@@ -781,9 +820,18 @@ def test_pruning_switches_do_not_change_results(lib, shape):
                     ids, dist = gi.search(_cuda(q), nprobe, w.k, radii)
                     assert np.array_equal(ids.cpu().numpy(), o_ids), (ablate, loads)
                     assert_same_float(dist.cpu().numpy(), o_dist, f"ablate {ablate} loads {loads}")
+            b.set_option("scan_ablate", 0)
+            b.set_option("scan_loads", 0)
+            for grid in (1, 2):       # the list-level bound with and without the nearest-entry grid
+                for strategy in (b.SCAN_QUERY_MAJOR, b.SCAN_LIST_MAJOR):
+                    b.set_option("bound_grid", grid)
+                    ids, dist = gi.search(_cuda(q), nprobe, w.k, radii, strategy=strategy)
+                    assert np.array_equal(ids.cpu().numpy(), o_ids), ("grid", grid, strategy)
+                    assert_same_float(dist.cpu().numpy(), o_dist, f"bound_grid {grid}")
         finally:
             b.set_option("scan_ablate", 0)
             b.set_option("scan_loads", 0)
+            b.set_option("bound_grid", 0)
             gi.close()
     # the inner-product kernel has its own early exit, list skip and list-level bound
     radii = _ip_radii(idx, q, 0.25)
