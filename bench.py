@@ -226,6 +226,14 @@ def run_workload(args, name: str, steps: int, warmup: int, cpu_seconds: float, p
                            "traffic": measured_traffic(w.name, args.keep, "plain") if (args.score_mode == 0 and not args.dynamic_radii and k == w.k and not metric) else None,
                            "algorithmic_bytes_per_launch": algo_bytes, "avg_launch_ms": plain,
                            "default_path": dict(pruned, speedup_over_plain=plain / launch_ms)}
+        if plain_lm:   # the code bytes of a list are read from HBM once and served to its many pairs from the L2 and LDS
+            res["roofline"]["note"] = ("list-major: queries that probe a list share its code stream, so the HBM traffic is a few percent of the "
+                                       "algorithmic bytes and the 8-byte LDS gathers bound the pass, not HBM; the HBM test proper is the "
+                                       "100M-point workload (c5)")
+    elif not plain_only:   # the plain scan was skipped (--plain-steps 0): no roofline figure, only the default path's record
+        res["roofline"] = {"bound": "hbm", "kernel": "plain scan not timed in this run", "achieved": None, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": None, "traffic": None, "algorithmic_bytes_per_launch": algo_bytes,
+                           "avg_launch_ms": None, "default_path": pruned}
     else:   # a run with the switches set by hand: the timed kernel is whatever they select
         achieved = algo_bytes / (launch_ms * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "kernel": f"scan_kernel with scan_ablate {args.scan_ablate}, scan_loads {args.scan_loads}",

@@ -146,7 +146,7 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
                 hipStream_t s, const ScanView *view = nullptr);
 int launch_probe_bounds(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                         const int32_t *d_probe_ids, const RadiiSq &r2, int32_t mode, const float *d_query_radii,
-                        float *d_probe_lb, hipStream_t s);
+                        float *d_probe_lb, hipStream_t s, int32_t *d_zero = nullptr, int64_t zero_n = 0);
 // ---- list-major batched scan (scan_lm.hip) --------------------------------------------------
 struct LmWorkspace {      // offsets into the list-major part of the workspace, 256-byte aligned
   size_t cnt, cur, base;  // [nlist], [nlist], [nlist+1] int32

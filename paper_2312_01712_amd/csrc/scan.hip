@@ -816,7 +816,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) vo
 // residual is the same fp32 value q - c the table uses).  For the hit-count scorings the bound
 // of a subspace is the penalty that every such entry gets when the whole box lies outside the
 // (inner) sphere, decided with the same margin.  One wavefront per BOUND_PAIRS (query, probe)
-// pairs, lane = subspace.
+// pairs, lane = subspace.  zero[0 .. zero_n) is set to 0 by the same launch (the list-major
+// scan's per-list counters).
 constexpr int BOUND_PAIRS = 2;  // (query, probe) pairs per wavefront: their loads are issued together
 
 __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restrict__ queries,
@@ -827,8 +828,11 @@ __global__ __launch_bounds__(256) void probe_bound_kernel(const float *__restric
                                                           const float *__restrict__ grid_par, int D, int M, int dsub,
                                                           int nlist, int64_t total, int nprobe, RadiiSq r2,
                                                           const float *__restrict__ query_radii, int mode,
-                                                          float *__restrict__ out) {
+                                                          float *__restrict__ out, int32_t *__restrict__ zero,
+                                                          int64_t zero_n) {
   const int lane = threadIdx.x & 63;
+  // (on the side: clear the caller's counters, so that they need no launch of their own)
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < zero_n; i += (int64_t)gridDim.x * 256) zero[i] = 0;
   const int64_t qp0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * BOUND_PAIRS;
   if (qp0 >= total) return;
   int64_t qs[BOUND_PAIRS];
@@ -1437,9 +1441,9 @@ int launch_scan(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_
 
 int launch_probe_bounds(const ivfpq_index *ix, const float *d_queries, int64_t Q, int32_t nprobe,
                         const int32_t *d_probe_ids, const RadiiSq &r2, int32_t mode, const float *d_query_radii,
-                        float *d_probe_lb, hipStream_t s) {
+                        float *d_probe_lb, hipStream_t s, int32_t *d_zero, int64_t zero_n) {
   const int64_t total = Q * nprobe;
-  if (total == 0) return IVFPQ_OK;
+  if (total == 0) return zero_n > 0 ? launch_fill_i32(d_zero, zero_n, 0, s) : IVFPQ_OK;
   // The grid of nearest-entry distances tightens the bound (on the 100M-point configuration it
   // rules out 59.4 instead of 55.9 of a query's 64 lists, and the tables built per query drop
   // from 8.1 to 4.6) at the price of a slower bound kernel (three more loads per pair and
@@ -1455,7 +1459,7 @@ int launch_probe_bounds(const ivfpq_index *ix, const float *d_queries, int64_t Q
   hipLaunchKernelGGL(probe_bound_kernel, dim3((unsigned)((total + per_block - 1) / per_block)), dim3(256), 0, s,
                      d_queries, d_probe_ids, ix->d_centroids, ix->d_box,
                      use_grid ? ix->d_grid : nullptr, ix->d_grid_par, ix->D, ix->M, ix->dsub, ix->nlist, total,
-                     nprobe, r2, d_query_radii, mode, d_probe_lb);
+                     nprobe, r2, d_query_radii, mode, d_probe_lb, d_zero, d_zero ? zero_n : 0);
   IVFPQ_HIP_TRY(hipGetLastError());
   return IVFPQ_OK;
 }

@@ -773,9 +773,6 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
     set_error("scan (list-major): %lld (query, probe) pairs exceed 2^31", (long long)(Q * (int64_t)nprobe));
     return IVFPQ_ERR_UNSUPPORTED;
   }
-  // list-level lower bounds of every (query, probe)
-  int rc = launch_probe_bounds(ix, d_queries, Q, nprobe, d_probe_ids, r2, mode, d_query_radii, d_probe_lb, s);
-  if (rc) return rc;
 
   LmArgs a;
   a.queries = d_queries;
@@ -804,6 +801,12 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   a.nprobe = nprobe; a.first = w.first; a.k = k; a.cap = w.cap; a.mode = mode;
   a.head_done = 0;
 
+  // list-level lower bounds of every (query, probe); the same launch clears the per-list counts
+  // (lm_offsets_kernel leaves them clear for the pass after it)
+  int rc = launch_probe_bounds(ix, d_queries, Q, nprobe, d_probe_ids, r2, mode, d_query_radii, d_probe_lb, s, a.cnt,
+                               ix->nlist);
+  if (rc) return rc;
+
   int dev = 0, cus = 0;
   IVFPQ_HIP_TRY(hipGetDevice(&dev));
   IVFPQ_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
@@ -815,8 +818,6 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   // the list-major scan and is redone query-major at the end.  Otherwise (several first lists, or the hit-count scorings,
   // whose masses of equal scores the head pass's selection is not made for): query-major.
   const bool head_pass = w.first == 1 && mode == IVFPQ_SCORE_DISTANCE && a.head_max >= 64;
-  rc = launch_fill_i32(a.cnt, ix->nlist, 0, s);   // the per-list counts start at zero; lm_offsets_kernel leaves them so
-  if (rc) return rc;
   if (head_pass) {
     const unsigned qgrid = (unsigned)((Q + 255) / 256);
     hipLaunchKernelGGL(lm_pairs_kernel, dim3(qgrid), dim3(256), 0, s, a, 0, 1);

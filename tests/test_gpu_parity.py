@@ -1045,8 +1045,6 @@ def test_list_major_ragged_lists(lib):
         gi.close()
 
 
-
-
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5_10M", "C5"])
 def test_full_size_configs_sampled_queries(lib, name):
     """The full-size indexes -- the three 1M-point configurations, the 100M-point one, and a
