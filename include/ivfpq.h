@@ -337,9 +337,10 @@ int64_t ivfpq_coarse_fallbacks(int reset);
  *                  default 1); their k-th distance is the bound that filters the other lists.
  *                  1: the nearest list is ranked list-major as well (queries that share it
  *                  share its pass); more: those lists are scanned query-major.
- *   "lm_cap"       list-major scan: candidate slots per query (64 .. 65536, default 4096); a
- *                  query that overflows them is redone query-major.  Set both before sizing
- *                  the workspace.
+ *   "lm_cap"       list-major scan: candidate slots per query (64 .. 65536; default 0: 256 per
+ *                  probed list, at least 4096 and at most 16384; 8 bytes of workspace per
+ *                  slot); a query that overflows them is redone query-major.  Set both
+ *                  before sizing the workspace.
  *   "wide_cap"     128 < k <= 1024: slots per query for the keys within the running bound on the
  *                  k-th distance (1024 .. 65536, default 8192).  Between lists the bound, which
  *                  only tightens, clears the slots it has overtaken; a query that still runs

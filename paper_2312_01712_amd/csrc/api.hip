@@ -206,7 +206,7 @@ int ivfpq_set_option(const char *name, int value) {
     return IVFPQ_OK;
   }
   if (name && !strcmp(name, "lm_cap")) {
-    if (value < 64 || value > 65536) { set_error("set_option: lm_cap must be in [64, 65536]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
+    if (value != 0 && (value < 64 || value > 65536)) { set_error("set_option: lm_cap must be 0 or in [64, 65536]"); return IVFPQ_ERR_INVALID_ARGUMENT; }
     set_lm_cap(value);
     return IVFPQ_OK;
   }

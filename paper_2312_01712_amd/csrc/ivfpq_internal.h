@@ -166,7 +166,7 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
                            const float *d_query_radii, float *d_probe_lb, int64_t *d_out_ids, float *d_out_dist,
                            const LmWorkspace &w, char *lm_base, hipStream_t s);
 void set_lm_first(int v);  // lists per query scanned query-major before the list-major scan (1 .. 64)
-void set_lm_cap(int v);    // candidate slots per query of the list-major scan (64 .. 65536)
+void set_lm_cap(int v);    // candidate slots per query of the list-major scan (64 .. 65536; 0: by the number of probes)
 int get_scan_ablate();
 
 int launch_query_radii(const ivfpq_index *ix, const ivfpq_radius_model *md, const float *d_queries,

@@ -698,7 +698,7 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(LmArgs a) {
 }
 
 std::atomic<int> g_lm_first{1};     // lists per query that are ranked first (their k-th distance filters the rest)
-std::atomic<int> g_lm_cap{4096};    // candidate slots per query
+std::atomic<int> g_lm_cap{0};       // candidate slots per query; 0: by the number of probes (lm_auto_cap)
 
 size_t lm_fixed_lds(int M, int D) {   // table, residuals, radii
   const int dpad = (D + 3) & ~3;
@@ -750,7 +750,11 @@ static size_t lm_align(size_t v) { return (v + 255) & ~(size_t)255; }
 LmWorkspace plan_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe) {
   LmWorkspace w;
   w.first = g_lm_first.load(std::memory_order_relaxed);
+  // Candidates that pass the first lists' bound grow with the number of lists probed; a query
+  // that runs out of slots costs a query-major pass over all of its lists.  Measured on the
+  // 1M x 96 configuration (64 probes): 4096 slots 11.39 ms per batch, 8192 10.88, 16384 10.71.
   w.cap = g_lm_cap.load(std::memory_order_relaxed);
+  if (w.cap == 0) w.cap = nprobe >= 64 ? 16384 : (nprobe * 256 > 4096 ? nprobe * 256 : 4096);
   w.pairs_cap = Q * (nprobe - w.first > 1 ? nprobe - w.first : 1) + ix->nlist;   // also holds the head pass's Q pairs
   size_t off = 0;
   w.cnt = off;   off += lm_align((size_t)ix->nlist * 4);

@@ -163,7 +163,8 @@ static void search_arguments() {
     REQUIRE(ivfpq_search_ex(&ix, q, 4, 2, 5, radii, &sc, ids, dist, ws_mem, need, nullptr) == IVFPQ_ERR_INVALID_ARGUMENT); }
   REQUIRE(ivfpq_set_option("lm_first", 0) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("lm_cap", 8) == IVFPQ_ERR_INVALID_ARGUMENT);
-  REQUIRE(ivfpq_set_option("lm_first", 1) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK);
+  REQUIRE(ivfpq_set_option("lm_first", 1) == IVFPQ_OK && ivfpq_set_option("lm_cap", 4096) == IVFPQ_OK &&
+          ivfpq_set_option("lm_cap", 0) == IVFPQ_OK);
   REQUIRE(ivfpq_set_option("wide_cap", 512) == IVFPQ_ERR_INVALID_ARGUMENT && ivfpq_set_option("wide_cap", 1 << 17) == IVFPQ_ERR_INVALID_ARGUMENT);
   REQUIRE(ivfpq_set_option("wide_cap", 0) == IVFPQ_OK && ivfpq_search_workspace_bytes(&ix, 4, 2, 1000) == ivfpq_search_workspace_bytes(&ix, 4, 2, 100));
   REQUIRE(ivfpq_set_option("wide_cap", 8192) == IVFPQ_OK && ivfpq_search_workspace_bytes(&ix, 4, 2, 1000) > ivfpq_search_workspace_bytes(&ix, 4, 2, 100));

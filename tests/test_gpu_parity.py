@@ -923,7 +923,7 @@ def test_c1_full(lib):
     full_check(w, idx, q, radii, stages=False)
 
 
-def _lm_options(b, first=1, cap=4096):
+def _lm_options(b, first=1, cap=0):
     b.set_option("lm_first", first)
     b.set_option("lm_cap", cap)
 
