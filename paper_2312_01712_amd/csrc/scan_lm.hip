@@ -67,12 +67,6 @@ struct LmArgs {
   int32_t head_done;            // the head pass has run: queries it left out (qmap_head) have no first-list result yet
 };
 
-// tau_q as the bit pattern of a non-negative float (orders like the value; +inf when phase A
-// found fewer than k points)
-__device__ inline uint32_t lm_tau_bits(const LmArgs &a, int64_t q) {
-  return __float_as_uint(a.out_dist[q * a.k + a.k - 1]);
-}
-
 // One thread per (query, probe >= first).  fill == 0: count the surviving pairs of every list
 // (and clear the query's candidate count); fill == 1: write them to the list's slot range.
 // Both passes evaluate the same predicate on the same data.
@@ -271,7 +265,7 @@ struct LmTask {
   int64_t row0;
   int32_t len, nb;
   const uint8_t *base;
-  uint32_t tau0, tau1;
+  float tauv;          // main pass: lane 0 holds tau of q0, the other lanes tau of q1 (a vector load, like the metadata)
 };
 
 // Persistent workgroups, one per CU.  Tasks are sorted by list; in every round the grid takes
@@ -315,9 +309,10 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   LDS uint32_t *qd1 = queue + (wave * LM_G + 1) * 2 * LM_QUEUE, *qrow1 = qd1 + LM_QUEUE;
 
   // this wavefront's codebook rows (rows wave, wave + NW, ...) stay in registers for the whole
-  // kernel; the head pass at 64 subspaces has no registers left for the last two of its eight
-  // rows and fetches those (from the L2) when a task's table is built
-  constexpr int RES = (HEAD && ITER > 6) ? 5 : ITER;
+  // kernel; the head pass at 64 subspaces has registers for three of its eight rows and fetches
+  // the others (from the L2) when a task's table is built (four and five resident rows spill 2
+  // and 6 registers; the batch takes the same time with 3 and 4)
+  constexpr int RES = (HEAD && ITER > 6) ? 3 : ITER;
   float4 cbr[RES][DSUB];
   auto load_row = [&](int it, float4 (&row)[DSUB]) __attribute__((always_inline)) {
     const int m = wave + it * NW;
@@ -340,25 +335,37 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   const int mg = tid >= MT ? 1 : 0, mm = tid - mg * MT;
   const bool m_on = tid < LM_G * MT;
 
-  // the pair entries of a task (scalar loads; consumed by fetch_task)
-  auto fetch_pairs = [&](int t, int2 &p0, int2 &p1) __attribute__((always_inline)) {
-    p0 = a.pairs[(int64_t)t * LM_G];
-    p1 = a.pairs[(int64_t)t * LM_G + 1];
+  // A task's pair entries and its list's metadata are requested with VECTOR loads (a lane each:
+  // even lanes the first pair entry, odd lanes the second; lanes 0 and 1 the list's row range,
+  // the others its first block), although every lane of the wavefront wants the same values:
+  // scalar loads share their counter with the LDS, so a scalar load in flight makes the next
+  // LDS read of the scan wait for it, whereas vector loads complete in order behind the code
+  // stream and cost nothing when they are consumed a scan later.
+  auto fetch_pairs = [&](int t) __attribute__((always_inline)) { return a.pairs[(int64_t)t * LM_G + (lane & 1)]; };
+  auto fetch_meta = [&](const int2 &pv) __attribute__((always_inline)) {
+    const int c = __builtin_amdgcn_readlane(pv.y, 0);
+    const int64_t *src = lane < 2 ? a.list_offsets + c + lane : a.list_blocks + c;
+    return *src;
   };
-  // everything else a task needs, requested together: metadata, bounds, this thread's residual
-  // and radius element, the wavefront's first code block
-  auto fetch_task = [&](const int2 &p0, const int2 &p1, LmTask &tk, float &qv, float &cv, float &rv,
+  auto lane64 = [&](int64_t v, int l) __attribute__((always_inline)) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+  };
+  // everything else a task needs, requested together: bounds, this thread's residual and radius
+  // element, the wavefront's first code block
+  auto fetch_task = [&](const int2 &pv, int64_t mv, LmTask &tk, float &qv, float &cv, float &rv,
                         CodeRegs<MPT / 4> &first) __attribute__((always_inline)) {
-    tk.c = __builtin_amdgcn_readfirstlane(p0.y);
-    tk.q0 = __builtin_amdgcn_readfirstlane(p0.x);
-    tk.has1 = __builtin_amdgcn_readfirstlane(p1.x) >= 0;
-    tk.q1 = tk.has1 ? __builtin_amdgcn_readfirstlane(p1.x) : tk.q0;
-    tk.row0 = a.list_offsets[tk.c];
-    tk.len = (int)(a.list_offsets[tk.c + 1] - tk.row0);
+    tk.c = __builtin_amdgcn_readlane(pv.y, 0);
+    tk.q0 = __builtin_amdgcn_readlane(pv.x, 0);
+    tk.has1 = __builtin_amdgcn_readlane(pv.x, 1) >= 0;
+    tk.q1 = tk.has1 ? __builtin_amdgcn_readlane(pv.x, 1) : tk.q0;
+    tk.row0 = lane64(mv, 0);
+    tk.len = (int)(lane64(mv, 1) - tk.row0);
     tk.nb = (tk.len + 63) >> 6;
-    tk.base = a.codes + a.list_blocks[tk.c] * ivfpq_block_bytes(MPT);
-    tk.tau0 = HEAD ? 0u : lm_tau_bits(a, tk.q0);
-    tk.tau1 = HEAD ? 0u : lm_tau_bits(a, tk.q1);
+    tk.base = a.codes + lane64(mv, 2) * ivfpq_block_bytes(MPT);
+    tk.tauv = 0.0f;
+    if constexpr (!HEAD) tk.tauv = a.out_dist[(lane == 0 ? tk.q0 : tk.q1) * a.k + a.k - 1];
     qv = cv = 0.0f;
     if (r_on) {
       qv = a.queries[(rg ? tk.q1 : tk.q0) * D + rd];
@@ -381,10 +388,11 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
   CodeRegs<MPT / 4> nxt;
   int t = in_round;
   if (t >= ntasks) return;
+  int2 npv = make_int2(0, 0);   // pair entries of the next task
   {
-    int2 p0, p1;
-    fetch_pairs(t, p0, p1);
-    fetch_task(p0, p1, tk, qv, cv, rv, nxt);
+    const int2 pv = fetch_pairs(t);
+    if (t + nwg < ntasks) npv = fetch_pairs(t + nwg);
+    fetch_task(pv, fetch_meta(pv), tk, qv, cv, rv, nxt);
   }
   // main pass: the candidates of the task before, queued in LDS, and where they go
   uint32_t pend_slot = 0;
@@ -433,11 +441,14 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
     if (a.mode == 0) build_rows(std::integral_constant<int, 0>{});
     else if (a.mode == 1) build_rows(std::integral_constant<int, 1>{});
     else build_rows(std::integral_constant<int, 2>{});
-    // the next task's pair entries are on their way while this one is scanned
+    // on their way while this task is scanned: the next task's list metadata, the pair
+    // entries of the task after it
     const int tn = t + nwg;
     const bool more = tn < ntasks;
-    int2 np0 = make_int2(0, 0), np1 = make_int2(0, 0);
-    if (more) fetch_pairs(tn, np0, np1);
+    int64_t nmv = 0;
+    int2 nnv = make_int2(0, 0);
+    if (more) nmv = fetch_meta(npv);
+    if (tn + nwg < ntasks) nnv = fetch_pairs(tn + nwg);
     if constexpr (!HEAD) drain_pending();   // the queues are free again before this task fills them
     __syncthreads();
     // ---- one pass over the list's codes serves both queries ----
@@ -466,6 +477,10 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
       const float x = (__uint_as_float(key) - wlo[g]) * wscale[g];
       return x >= (float)(LM_BINS - 1) ? (uint32_t)(LM_BINS - 1) : (x > 0.0f ? (uint32_t)x : 0u);
     };
+    // tau_q as the bit pattern of a non-negative float (orders like the value; +inf when the
+    // first lists held fewer than k points)
+    const uint32_t tau0 = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(tk.tauv), 0);
+    const uint32_t tau1 = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(tk.tauv), 1);
     const int last = tk.nb - 1;
     for (int blk = wave; blk < tk.nb; blk += NW) {
       CodeRegs<MPT / 4> cur = nxt;
@@ -493,14 +508,17 @@ __global__ __launch_bounds__(LM_NW * 64) __attribute__((amdgpu_waves_per_eu(LM_N
           }
         }
       } else {
-        lm_offer(a, tk.q0, d0, valid, tk.tau0, row, qd0, qrow0, qc0, lane);
-        if (tk.has1) lm_offer(a, tk.q1, d1, valid, tk.tau1, row, qd1, qrow1, qc1, lane);
+        lm_offer(a, tk.q0, d0, valid, tau0, row, qd0, qrow0, qc0, lane);
+        if (tk.has1) lm_offer(a, tk.q1, d1, valid, tau1, row, qd1, qrow1, qc1, lane);
       }
     }
     // the rest of the next task's inputs is requested before this task's candidates are
     // appended: both wait on the memory system at the same time
     const LmTask done = tk;
-    if (more) fetch_task(np0, np1, tk, qv, cv, rv, nxt);
+    if (more) {
+      fetch_task(npv, nmv, tk, qv, cv, rv, nxt);
+      npv = nnv;
+    }
     if constexpr (HEAD) {
       const int L = done.len, k = a.k;
       const int ng = done.has1 ? 2 : 1;
