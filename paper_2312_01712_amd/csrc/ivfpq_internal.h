@@ -149,8 +149,9 @@ int launch_probe_bounds(const ivfpq_index *ix, const float *d_queries, int64_t Q
                         float *d_probe_lb, hipStream_t s, int32_t *d_zero = nullptr, int64_t zero_n = 0);
 // ---- list-major batched scan (scan_lm.hip) --------------------------------------------------
 struct LmWorkspace {      // offsets into the list-major part of the workspace, 256-byte aligned
-  size_t cnt, cur, base;  // [nlist], [nlist], [nlist+1] int32
+  size_t cnt, base;       // [nlist], [nlist+1] int32
   size_t pairs;           // [pairs_cap] (query, list) int32 pairs bucketed by list
+  size_t rank;            // [pairs_cap] int32: a pair's position among the pairs of its list
   size_t gcnt, qmap;      // [Q] uint32 / int32
   size_t qmap_head;       // [Q] int32
   size_t cand;            // [Q][cap] (distance bits, row) candidates of the list-major scan

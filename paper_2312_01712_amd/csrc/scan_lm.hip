@@ -53,7 +53,7 @@ struct LmArgs {
   int64_t *out_ids;             // [Q][k]: phase A's top-k on entry to the merge, the result after it
   float *out_dist;              // [Q][k]
   int32_t *cnt;                 // [nlist] pairs per list
-  int32_t *cur;                 // [nlist] fill cursors
+  int32_t *rank;                // [max(Q, Q*(nprobe-first))] position of a pair among its list's pairs, -1: no pair
   int32_t *base;                // [nlist+1] first pair slot of a list (ranges padded to LM_G); [nlist] = slots in use
   int2 *pairs;                  // [Q*(nprobe-first) + nlist] (query, list); query -1 pads a list's range
   uint32_t *gcnt;               // [Q] candidates appended (may run past cap: the query then counts as overflowed)
@@ -68,8 +68,10 @@ struct LmArgs {
 };
 
 // One thread per (query, probe >= first).  fill == 0: count the surviving pairs of every list
-// (and clear the query's candidate count); fill == 1: write them to the list's slot range.
-// Both passes evaluate the same predicate on the same data.
+// (and clear the query's candidate count); the value the count returns is the pair's position
+// among its list's pairs and is kept (rank, -1 for a pair that takes no part), so that
+// fill == 1 only has to write the pair to that position of the list's slot range: no second
+// evaluation of the predicate and no second atomic operation on the per-list words.
 // head == 1 (the head pass): one thread per query, the pair is (query, its nearest list); a
 // query whose nearest list is missing, empty or too long for the head pass is handed to the
 // query-major kernel through qmap_head instead.
@@ -79,34 +81,35 @@ __global__ __launch_bounds__(256) void lm_pairs_kernel(LmArgs a, int fill, int h
   if (idx >= a.Q * np2) return;
   const int64_t q = idx / np2;
   const int p = head ? 0 : a.first + (int)(idx % np2);
-  if (!head && !fill && p == a.first) a.gcnt[q] = 0u;
+  const int32_t c = a.probe_ids[q * a.nprobe + p];
+  if (fill) {
+    const int32_t r = a.rank[idx];
+    if (r >= 0) a.pairs[a.base[c] + r] = make_int2((int)q, c);
+    return;
+  }
+  if (!head && p == a.first) a.gcnt[q] = 0u;
+  bool take = true;
   // a query the head pass left out has no bound yet: it takes no part here and is redone
   // query-major over all of its lists (lm_merge_kernel puts it on that list)
-  if (!head && a.head_done && a.qmap_head[q] >= 0) return;
-  const int32_t c = a.probe_ids[q * a.nprobe + p];
+  if (!head && a.head_done && a.qmap_head[q] >= 0) take = false;
   const bool exists = (uint32_t)c < (uint32_t)a.nlist;
   const int64_t len = exists ? a.list_offsets[c + 1] - a.list_offsets[c] : 0;
   if (head) {
     const bool ok = len > 0 && len <= a.head_max;
-    if (!fill) a.qmap_head[q] = ok ? -1 : (int32_t)q;
-    if (!ok) return;
+    a.qmap_head[q] = ok ? -1 : (int32_t)q;
+    take = ok;
   }
-  if (len <= 0) return;
-  if (!head && a.probe_lb) {
+  if (len <= 0) take = false;
+  if (take && !head && a.probe_lb) {
     // no point of the list can reach the k-th distance that phase A already guarantees
     const float tau = a.out_dist[q * a.k + a.k - 1];
-    if (a.probe_lb[q * a.nprobe + p] > tau) return;
+    if (a.probe_lb[q * a.nprobe + p] > tau) take = false;
   }
-  if (!fill) {
-    atomicAdd(&a.cnt[c], 1);
-  } else {
-    const int slot = a.base[c] + atomicAdd(&a.cur[c], 1);
-    a.pairs[slot] = make_int2((int)q, c);
-  }
+  a.rank[idx] = take ? atomicAdd(&a.cnt[c], 1) : -1;
 }
 
 // Slot ranges of the lists: base[c] = sum over c' < c of cnt[c'] rounded up to LM_G.  The
-// padding slot of an odd range is marked (query -1), the cursors and the counts are cleared.
+// padding slot of an odd range is marked (query -1), the counts are cleared.
 // One workgroup.
 __global__ __launch_bounds__(1024) void lm_offsets_kernel(LmArgs a) {
   __shared__ int part[1024];
@@ -130,7 +133,6 @@ __global__ __launch_bounds__(1024) void lm_offsets_kernel(LmArgs a) {
     a.base[c] = run;
     for (int j = n; j < padded; ++j) a.pairs[run + j] = make_int2(-1, c);
     run += padded;
-    a.cur[c] = 0;
     a.cnt[c] = 0;   // left clear for the next pass over this workspace
   }
   if (tid == 1023) a.base[a.nlist] = part[1023];
@@ -690,7 +692,7 @@ __global__ __launch_bounds__(256) void lm_merge_kernel(LmArgs a) {
     if (off + lane < n) {
       const uint2 e = a.cand[q * a.cap + off + lane];
       c.d = e.x;
-      c.id = a.ids[e.y];
+      if (e.x <= tau.d) c.id = a.ids[e.y];   // a larger distance fails the test below whatever its id: no id fetched
     }
     const bool pass = kless(c, tau);
     if (__ballot(pass) == 0) continue;
@@ -776,9 +778,9 @@ LmWorkspace plan_list_major(const ivfpq_index *ix, int64_t Q, int32_t nprobe) {
   w.pairs_cap = Q * (nprobe - w.first > 1 ? nprobe - w.first : 1) + ix->nlist;   // also holds the head pass's Q pairs
   size_t off = 0;
   w.cnt = off;   off += lm_align((size_t)ix->nlist * 4);
-  w.cur = off;   off += lm_align((size_t)ix->nlist * 4);
   w.base = off;  off += lm_align(((size_t)ix->nlist + 1) * 4);
   w.pairs = off; off += lm_align((size_t)w.pairs_cap * 8);
+  w.rank = off;  off += lm_align((size_t)w.pairs_cap * 4);
   w.gcnt = off;  off += lm_align((size_t)Q * 4);
   w.qmap = off;  off += lm_align((size_t)Q * 4);
   w.qmap_head = off; off += lm_align((size_t)Q * 4);
@@ -809,7 +811,7 @@ int launch_scan_list_major(const ivfpq_index *ix, const float *d_queries, int64_
   a.out_ids = d_out_ids;
   a.out_dist = d_out_dist;
   a.cnt = reinterpret_cast<int32_t *>(lm_base + w.cnt);
-  a.cur = reinterpret_cast<int32_t *>(lm_base + w.cur);
+  a.rank = reinterpret_cast<int32_t *>(lm_base + w.rank);
   a.base = reinterpret_cast<int32_t *>(lm_base + w.base);
   a.pairs = reinterpret_cast<int2 *>(lm_base + w.pairs);
   a.gcnt = reinterpret_cast<uint32_t *>(lm_base + w.gcnt);
