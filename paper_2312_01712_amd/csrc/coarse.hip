@@ -861,12 +861,6 @@ __global__ __launch_bounds__(CS_WAVES * 64) void coarse_select_wave_kernel(
     }
 }
 
-int pow2ceil(int v) {
-  int p = 1;
-  while (p < v) p <<= 1;
-  return p;
-}
-
 }  // namespace
 
 namespace ivfpq {
